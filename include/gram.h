@@ -1,0 +1,159 @@
+/*
+ * gram.h -- C ABI of the MI355X (gfx950) library for GRAM's data-parallel hot
+ * path: the item-deduplicated encode / gradient-accumulate step of
+ * content-based collaborative filtering (Section 4, Algorithm 1 of the paper).
+ *
+ * One training step over a mini-batch of M = B*L item-ID positions:
+ *
+ *   gram_unique           the set B_I of unique items of the batch (Table 1;
+ *                         "for all i in B_I" in Algorithm 1), ascending, with
+ *                         the inverse index and multiplicities
+ *   gram_encode_gather    step 1, Eq. 4: one representation per unique item
+ *                         (dense linear stand-in for the encoder, E = X[uniq].W),
+ *                         gathered back to every position
+ *   gram_grad_accumulate  step 3, Eq. 6: dL/dH summed per unique item into the
+ *                         buffer that persists over the N mini-batches of a
+ *                         Multi-step window (Section 4.2)
+ *   gram_encoder_wgrad    step 4, Eq. 7/9: encoder weight gradient once per
+ *                         unique item, dW = X[items]^T . G
+ *   gram_flush            end of the window ("t mod N"): export and empty the
+ *                         buffer
+ *
+ * Memory.  Every pointer marked DEVICE is memory of the current HIP device,
+ * owned by the caller (the library never frees, reallocates or keeps it beyond
+ * the call unless stated).  Pointers marked HOST are ordinary host memory.
+ * gram_create allocates all workspace once; no later call allocates.
+ *
+ * Streams.  `stream` is a hipStream_t passed as void* (NULL = default
+ * stream).  Calls only enqueue work; they synchronise with the host only where
+ * a HOST out-pointer is non-NULL, and in gram_check.  One context serves one
+ * stream at a time and is not re-entrant.
+ *
+ * Layouts.  All matrices are dense row-major.  ids/uniq/inverse/counts are
+ * int32.  X[N,d_in] and W[d_in,d] have the context's xw_dtype; E, H, dH, G and
+ * dW are float32 (the paper does not state a precision; sums are taken in
+ * float32 in a fixed order, so results are bit-reproducible run to run).
+ *
+ * Errors.  Functions return GRAM_OK (0) or a negative gram_status and leave a
+ * message for gram_last_error.  Errors the device detects (an ID outside
+ * [0,N), buffer capacity exceeded) are latched in a device flag and returned
+ * by the next call that synchronises (a HOST out-pointer, or gram_check);
+ * an out-of-range ID is processed as the padding ID (0 if there is none) so no
+ * kernel reads out of bounds, and the outputs of that step are unspecified.
+ */
+#ifndef GRAM_H
+#define GRAM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gram_ctx gram_ctx; /* opaque: workspace + persistent gradient buffer */
+
+typedef enum gram_status {
+    GRAM_OK = 0,
+    GRAM_ERR_ARG = -1,           /* NULL / negative / unsupported argument            */
+    GRAM_ERR_CAPACITY = -2,      /* m > max_positions, or the window touched more
+                                    unique items than u_total_cap                     */
+    GRAM_ERR_SEQUENCE = -3,      /* call order violated (see each function)           */
+    GRAM_ERR_RANGE = -4,         /* an ID outside [0, vocab_n)                        */
+    GRAM_ERR_HIP = -5,           /* HIP runtime error; text in gram_last_error        */
+    GRAM_ERR_UNIMPLEMENTED = -6
+} gram_status;
+
+typedef enum gram_dtype { GRAM_F32 = 0, GRAM_BF16 = 1 } gram_dtype;
+
+typedef struct gram_config {
+    int32_t vocab_n;       /* N: IDs are valid in [0,N); row r of X belongs to ID r    */
+    int32_t d_in;          /* content-feature width; multiple of 8                     */
+    int32_t d;             /* representation width; multiple of 4                      */
+    int64_t max_positions; /* capacity M_max = B*L of one step                         */
+    int32_t k_steps;       /* N of Algorithm 1 (accumulation period), >= 1             */
+    int32_t pad_id;        /* padding ID (0 in the paper-shaped workloads); < 0: none  */
+    int64_t u_total_cap;   /* rows of the persistent buffer; 0 => min(K*M_max, N)      */
+    int32_t xw_dtype;      /* gram_dtype of X and W                                    */
+} gram_config;
+
+/* Bytes of device memory gram_create would allocate for cfg (0 if cfg is invalid). */
+int64_t gram_workspace_bytes(const gram_config* cfg);
+
+/* Create a context on the current device.  Allocates the workspace and the
+ * persistent buffer (hipMalloc) and initialises them on the default stream,
+ * then synchronises.  *out is NULL on failure. */
+int gram_create(gram_ctx** out, const gram_config* cfg);
+
+/* Frees everything gram_create allocated.  Synchronises the device first. */
+int gram_destroy(gram_ctx* ctx);
+
+/* Unique items of a batch (Table 1, B_I; Eq. 4 ranges over it).
+ *   ids      DEVICE [m]            item IDs, row-major [B,L]; padding = cfg.pad_id
+ *   m        0 <= m <= max_positions
+ *   uniq     DEVICE [>= min(m,N)]  out: distinct IDs ascending (padding included
+ *                                  when present); entries >= U untouched
+ *   inverse  DEVICE [m]            out: uniq[inverse[p]] == ids[p]
+ *   counts   DEVICE [>= min(m,N)]  out: occurrences of uniq[j]; sums to m
+ *   u_dev    DEVICE [1], nullable  out: U
+ *   u_host   HOST   [1], nullable  out: U; non-NULL makes the call synchronise
+ *                                  and return latched device errors
+ * The context keeps the sort order of this batch for the next
+ * gram_encode_gather / gram_grad_accumulate; a new gram_unique replaces it. */
+int gram_unique(gram_ctx* ctx, const int32_t* ids, int64_t m, int32_t* uniq, int32_t* inverse,
+                int32_t* counts, int32_t* u_dev, int32_t* u_host, void* stream);
+
+/* Encode once per unique item and gather to positions (Algorithm 1 step 1).
+ *   X        DEVICE [N,d_in]   item content features (xw_dtype)
+ *   W        DEVICE [d_in,d]   encoder weight (xw_dtype)
+ *   uniq, inverse, u_dev       the outputs of the preceding gram_unique (DEVICE)
+ *   m        the m of that gram_unique
+ *   E        DEVICE [>= min(m,N), d], nullable   out: E[j,:] = X[uniq[j],:].W,
+ *            zero row for the padding ID; NULL keeps E in the workspace
+ *   H        DEVICE [m,d]      out: H[p,:] = E[inverse[p],:] (zero at padding)
+ * Requires a preceding gram_unique on this context (GRAM_ERR_SEQUENCE). */
+int gram_encode_gather(gram_ctx* ctx, const void* X, const void* W, const int32_t* uniq,
+                       const int32_t* inverse, const int32_t* u_dev, int64_t m, float* E, float* H,
+                       void* stream);
+
+/* Per-unique-item gradient (Algorithm 1 step 3): for the batch of the last
+ * gram_unique, G[item] += sum over the item's positions p (ascending) of
+ * dH[p,:], into the persistent buffer.  Padding positions are not read.
+ *   dH       DEVICE [m,d]  upstream gradient dL/dH
+ *   m        must equal the m of the last gram_unique
+ *   step_k   0-based step of the window; must equal the number of steps
+ *            accumulated since the last gram_flush and be < k_steps
+ * No float atomics are used: every buffer row has one writer and a fixed
+ * summation order. */
+int gram_grad_accumulate(gram_ctx* ctx, const float* dH, int64_t m, int32_t step_k, void* stream);
+
+/* Encoder weight gradient over all items accumulated in the window
+ * (Algorithm 1 step 4): dW[i,c] = sum_items X[item,i] * G[item,c].
+ *   X        DEVICE [N,d_in]
+ *   dW       DEVICE [d_in,d]  out (overwritten)
+ * Requires at least one accumulated step (GRAM_ERR_SEQUENCE).  Call before
+ * gram_flush.  With bf16 features G is rounded to bf16 (nearest-even) as it
+ * enters the matrix cores; products are summed in float32. */
+int gram_encoder_wgrad(gram_ctx* ctx, const void* X, float* dW, void* stream);
+
+/* End of the accumulation window: export the buffer in ascending ID order,
+ * then empty it and reset the step counter.
+ *   uniq_total    DEVICE [>= u_total_cap], nullable  out: IDs seen in the window
+ *   counts_total  DEVICE [>= u_total_cap], nullable  out: their total occurrences
+ *   G_total       DEVICE [>= u_total_cap, d], nullable  out: their gradient rows
+ *   u_total_dev   DEVICE [1], nullable  out: number of IDs exported
+ *   u_total_host  HOST   [1], nullable  out: same; non-NULL synchronises and
+ *                                       returns latched device errors */
+int gram_flush(gram_ctx* ctx, int32_t* uniq_total, int32_t* counts_total, float* G_total,
+               int32_t* u_total_dev, int32_t* u_total_host, void* stream);
+
+/* Synchronise `stream` and return (and clear) any latched device error. */
+int gram_check(gram_ctx* ctx, void* stream);
+
+/* Message of the last failing call on ctx (or of the last failing gram_create
+ * when ctx is NULL).  The string is owned by the library. */
+const char* gram_last_error(const gram_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRAM_H */

@@ -1,0 +1,327 @@
+// C ABI of libgram (see include/gram.h): argument checks, call-order checks,
+// workspace layout, kernel sequencing.  No arithmetic of the method lives here.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include <new>
+
+#include "gram_internal.h"
+
+using namespace gram;
+
+namespace {
+
+std::string g_create_error;
+
+int fail(Ctx* c, int code, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (c) c->last_error = buf; else g_create_error = buf;
+    return code;
+}
+
+int hip_fail(Ctx* c, hipError_t e, const char* what)
+{
+    return fail(c, GRAM_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+int bits_for(int32_t vocab_n)
+{
+    int b = 1;
+    while (b < 31 && ((int64_t)1 << b) < (int64_t)vocab_n) ++b;
+    return b;
+}
+
+int64_t table_elems_for(int64_t n_sort_max)
+{
+    int64_t nw = (n_sort_max + 4095) / 4096;
+    if (nw < 256) nw = 256;
+    return ((int64_t)1 << kMaxDigitBits) * nw;
+}
+
+struct Derived {
+    int64_t cap_u, cap_total, n_sort_max, tiles_scan, tiles_seg;
+    int splits;
+};
+
+const char* validate(const gram_config* cfg, Derived* dv)
+{
+    if (!cfg) return "cfg is NULL";
+    if (cfg->vocab_n < 1) return "vocab_n must be >= 1";
+    if (cfg->xw_dtype != GRAM_F32 && cfg->xw_dtype != GRAM_BF16) return "xw_dtype must be GRAM_F32 or GRAM_BF16";
+    if (cfg->d_in < 1 || (cfg->xw_dtype == GRAM_BF16 && cfg->d_in % 8 != 0))
+        return "d_in must be positive (a multiple of 8 for bf16)";
+    if (cfg->d < 4 || cfg->d % 4 != 0) return "d must be a positive multiple of 4";
+    if (cfg->max_positions < 1 || cfg->max_positions > ((int64_t)1 << 30))
+        return "max_positions must be in [1, 2^30]";
+    if (cfg->k_steps < 1) return "k_steps must be >= 1";
+    if (cfg->pad_id >= cfg->vocab_n) return "pad_id must be < vocab_n (negative = no padding)";
+    if (cfg->u_total_cap < 0) return "u_total_cap must be >= 0";
+    dv->cap_u = cfg->max_positions < cfg->vocab_n ? cfg->max_positions : cfg->vocab_n;
+    int64_t km = (int64_t)cfg->k_steps * cfg->max_positions;
+    dv->cap_total = cfg->u_total_cap ? cfg->u_total_cap : (km < cfg->vocab_n ? km : cfg->vocab_n);
+    if (dv->cap_total >= ((int64_t)1 << 30)) return "persistent buffer rows must be < 2^30";
+    dv->n_sort_max = cfg->max_positions > dv->cap_total ? cfg->max_positions : dv->cap_total;
+    dv->tiles_scan = (cfg->max_positions + kScanTile - 1) / kScanTile + 1;
+    dv->tiles_seg = (cfg->max_positions + kSegRows - 1) / kSegRows;
+    dv->splits = wgrad_splits_for(*cfg);
+    return nullptr;
+}
+
+// Carves the single device allocation; with base == nullptr only measures.
+int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
+{
+    int64_t off = 0;
+    auto take = [&](int64_t bytes) -> char* {
+        char* p = base ? base + off : nullptr;
+        off += align_up(bytes > 0 ? bytes : 1, 256);
+        return p;
+    };
+    const int64_t d = cfg.d, d_in = cfg.d_in;
+    int* scal = (int*)take(64 * sizeof(int));
+    int* keys0 = (int*)take(dv.n_sort_max * 4);
+    int* keys1 = (int*)take(dv.n_sort_max * 4);
+    int* vals0 = (int*)take(dv.n_sort_max * 4);
+    int* vals1 = (int*)take(dv.n_sort_max * 4);
+    int* table = (int*)take(table_elems_for(dv.n_sort_max) * 4);
+    int* gtot = (int*)take((1 << kMaxDigitBits) * 4);
+    int* tile_sums = (int*)take(dv.tiles_scan * 4);
+    int* offsets = (int*)take((dv.cap_u + 2) * 4);
+    int* seg_of_row = (int*)take(cfg.max_positions * 4);
+    int* uniq_ws = (int*)take(dv.cap_u * 4);
+    int* seg_slot = (int*)take(dv.cap_u * 4);
+    int* long_list = (int*)take(dv.tiles_seg * 4);
+    int* slot_of = (int*)take((int64_t)cfg.vocab_n * 4);
+    int* id_of_slot = (int*)take(dv.cap_total * 4);
+    int* cnt_of_slot = (int*)take(dv.cap_total * 4);
+    float* G = (float*)take(dv.cap_total * d * 4);
+    float* E_ws = (float*)take(dv.cap_u * d * 4);
+    float* seg_first = (float*)take(dv.tiles_seg * d * 4);
+    float* seg_last = (float*)take(dv.tiles_seg * d * 4);
+    void* Wt = take(cfg.xw_dtype == GRAM_BF16 ? d * d_in * 2 : 1);
+    float* wg_partial = (float*)take((int64_t)dv.splits * d_in * d * 4);
+    if (c && base) {
+        c->scal = scal; c->keys[0] = keys0; c->keys[1] = keys1; c->vals[0] = vals0; c->vals[1] = vals1;
+        c->table = table; c->gtot = gtot; c->tile_sums = tile_sums; c->offsets = offsets;
+        c->seg_of_row = seg_of_row; c->uniq_ws = uniq_ws; c->seg_slot = seg_slot;
+        c->long_list = long_list; c->slot_of = slot_of; c->id_of_slot = id_of_slot;
+        c->cnt_of_slot = cnt_of_slot; c->G = G; c->E_ws = E_ws; c->seg_first = seg_first;
+        c->seg_last = seg_last; c->Wt = Wt; c->wg_partial = wg_partial;
+    }
+    return off;
+}
+
+int launch_status(Ctx* c, const char* what)
+{
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? GRAM_OK : hip_fail(c, e, what);
+}
+
+// Copy the device scalars to the host, wait, and turn latched error bits into a status.
+int sync_scalars(Ctx* c, hipStream_t s, const char* what)
+{
+    hipError_t e = hipMemcpyAsync(c->h_pinned, c->scal, kSCount * sizeof(int), hipMemcpyDeviceToHost, s);
+    if (e != hipSuccess) return hip_fail(c, e, what);
+    e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_fail(c, e, what);
+    const int bits = c->h_pinned[kSErr];
+    if (bits) {
+        fill_i32(c->scal + kSErr, 1, 0, s);
+        (void)hipStreamSynchronize(s);
+        if (bits & kErrBitRange)
+            return fail(c, GRAM_ERR_RANGE, "%s: an item ID outside [0, %d) was seen", what, c->cfg.vocab_n);
+        return fail(c, GRAM_ERR_CAPACITY, "%s: the window touched more than %lld unique items", what,
+                    (long long)c->cap_total);
+    }
+    return GRAM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t gram_workspace_bytes(const gram_config* cfg)
+{
+    Derived dv;
+    if (validate(cfg, &dv)) return 0;
+    return layout(nullptr, *cfg, dv, nullptr);
+}
+
+int gram_create(gram_ctx** out, const gram_config* cfg)
+{
+    if (!out) return fail(nullptr, GRAM_ERR_ARG, "gram_create: out is NULL");
+    *out = nullptr;
+    Derived dv;
+    if (const char* why = validate(cfg, &dv)) return fail(nullptr, GRAM_ERR_ARG, "gram_create: %s", why);
+    Ctx* c = new (std::nothrow) Ctx();
+    if (!c) return fail(nullptr, GRAM_ERR_ARG, "gram_create: out of host memory");
+    c->cfg = *cfg;
+    c->cap_u = dv.cap_u;
+    c->cap_total = dv.cap_total;
+    c->key_bits = bits_for(cfg->vocab_n);
+    c->wg_splits = dv.splits;
+    c->ws_bytes = layout(nullptr, *cfg, dv, nullptr);
+    hipError_t e = hipMalloc((void**)&c->ws_base, (size_t)c->ws_bytes);
+    if (e != hipSuccess) {
+        int rc = fail(nullptr, GRAM_ERR_HIP, "gram_create: hipMalloc(%lld bytes): %s",
+                      (long long)c->ws_bytes, hipGetErrorString(e));
+        delete c;
+        return rc;
+    }
+    layout(c, *cfg, dv, c->ws_base);
+    e = hipHostMalloc((void**)&c->h_pinned, 64 * sizeof(int), hipHostMallocDefault);
+    if (e != hipSuccess) {
+        int rc = fail(nullptr, GRAM_ERR_HIP, "gram_create: hipHostMalloc: %s", hipGetErrorString(e));
+        (void)hipFree(c->ws_base);
+        delete c;
+        return rc;
+    }
+    fill_i32(c->scal, 64, 0, nullptr);
+    fill_i32(c->slot_of, cfg->vocab_n, -1, nullptr);
+    e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) {
+        int rc = fail(nullptr, GRAM_ERR_HIP, "gram_create: init: %s", hipGetErrorString(e));
+        (void)hipHostFree(c->h_pinned);
+        (void)hipFree(c->ws_base);
+        delete c;
+        return rc;
+    }
+    *out = reinterpret_cast<gram_ctx*>(c);
+    return GRAM_OK;
+}
+
+int gram_destroy(gram_ctx* ctx)
+{
+    if (!ctx) return GRAM_OK;
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    (void)hipDeviceSynchronize();
+    if (c->h_pinned) (void)hipHostFree(c->h_pinned);
+    if (c->ws_base) (void)hipFree(c->ws_base);
+    delete c;
+    return GRAM_OK;
+}
+
+int gram_unique(gram_ctx* ctx, const int32_t* ids, int64_t m, int32_t* uniq, int32_t* inverse,
+                int32_t* counts, int32_t* u_dev, int32_t* u_host, void* stream)
+{
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (!c) return GRAM_ERR_ARG;
+    if (m < 0) return fail(c, GRAM_ERR_ARG, "gram_unique: m < 0");
+    if (m > c->cfg.max_positions)
+        return fail(c, GRAM_ERR_CAPACITY, "gram_unique: m = %lld exceeds max_positions = %lld",
+                    (long long)m, (long long)c->cfg.max_positions);
+    if (m > 0 && (!ids || !uniq || !inverse || !counts))
+        return fail(c, GRAM_ERR_ARG, "gram_unique: NULL pointer");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    c->have_unique = false;
+    if (m > 0) {
+        const int fix = c->cfg.pad_id >= 0 ? c->cfg.pad_id : 0;
+        const int r = radix_sort_pairs(c, ids, nullptr, (int)m, nullptr, m, true, fix, s);
+        c->sorted_keys = c->keys[r];
+        c->perm = c->vals[r];
+    }
+    unique_from_sorted(c, (int)m, uniq, inverse, counts, u_dev, s);
+    if (int rc = launch_status(c, "gram_unique")) return rc;
+    c->have_unique = true;
+    c->unique_consumed = false;
+    c->cur_m = m;
+    if (u_host) {
+        if (int rc = sync_scalars(c, s, "gram_unique")) return rc;
+        *u_host = c->h_pinned[kSU];
+    }
+    return GRAM_OK;
+}
+
+int gram_encode_gather(gram_ctx* ctx, const void* X, const void* W, const int32_t* uniq,
+                       const int32_t* inverse, const int32_t* u_dev, int64_t m, float* E, float* H,
+                       void* stream)
+{
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (!c) return GRAM_ERR_ARG;
+    if (!c->have_unique)
+        return fail(c, GRAM_ERR_SEQUENCE, "gram_encode_gather: no preceding gram_unique");
+    if (m != c->cur_m)
+        return fail(c, GRAM_ERR_ARG, "gram_encode_gather: m = %lld differs from the last gram_unique (%lld)",
+                    (long long)m, (long long)c->cur_m);
+    if (m > 0 && (!X || !W || !uniq || !inverse || !H))
+        return fail(c, GRAM_ERR_ARG, "gram_encode_gather: NULL pointer");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (m == 0) return GRAM_OK;
+    float* Ep = E ? E : c->E_ws;
+    const int* up = u_dev ? u_dev : c->scal + kSU;
+    encode_forward(c, X, W, uniq, up, m < c->cap_u ? m : c->cap_u, Ep, s);
+    gather_rows(c, Ep, inverse, m, H, s);
+    return launch_status(c, "gram_encode_gather");
+}
+
+int gram_grad_accumulate(gram_ctx* ctx, const float* dH, int64_t m, int32_t step_k, void* stream)
+{
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (!c) return GRAM_ERR_ARG;
+    if (!c->have_unique || c->unique_consumed)
+        return fail(c, GRAM_ERR_SEQUENCE, "gram_grad_accumulate: needs a fresh gram_unique for this batch");
+    if (m != c->cur_m)
+        return fail(c, GRAM_ERR_ARG, "gram_grad_accumulate: m = %lld differs from the last gram_unique (%lld)",
+                    (long long)m, (long long)c->cur_m);
+    if (step_k != c->steps_done || step_k >= c->cfg.k_steps)
+        return fail(c, GRAM_ERR_SEQUENCE, "gram_grad_accumulate: step_k = %d, expected %d (k_steps = %d)",
+                    step_k, c->steps_done, c->cfg.k_steps);
+    if (m > 0 && !dH) return fail(c, GRAM_ERR_ARG, "gram_grad_accumulate: dH is NULL");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    assign_slots(c, s);
+    segment_reduce(c, dH, m, s);
+    if (int rc = launch_status(c, "gram_grad_accumulate")) return rc;
+    c->unique_consumed = true;
+    c->steps_done += 1;
+    return GRAM_OK;
+}
+
+int gram_encoder_wgrad(gram_ctx* ctx, const void* X, float* dW, void* stream)
+{
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (!c) return GRAM_ERR_ARG;
+    if (c->steps_done < 1)
+        return fail(c, GRAM_ERR_SEQUENCE, "gram_encoder_wgrad: no step accumulated in this window");
+    if (!X || !dW) return fail(c, GRAM_ERR_ARG, "gram_encoder_wgrad: NULL pointer");
+    encoder_wgrad(c, X, dW, static_cast<hipStream_t>(stream));
+    return launch_status(c, "gram_encoder_wgrad");
+}
+
+int gram_flush(gram_ctx* ctx, int32_t* uniq_total, int32_t* counts_total, float* G_total,
+               int32_t* u_total_dev, int32_t* u_total_host, void* stream)
+{
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (!c) return GRAM_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    flush_export(c, uniq_total, counts_total, G_total, u_total_dev, s);
+    c->have_unique = false;     // the sort buffers were reused
+    c->steps_done = 0;
+    if (int rc = launch_status(c, "gram_flush")) return rc;
+    if (u_total_host) {
+        if (int rc = sync_scalars(c, s, "gram_flush")) return rc;
+        *u_total_host = c->h_pinned[kSFlushN];
+    }
+    return GRAM_OK;
+}
+
+int gram_check(gram_ctx* ctx, void* stream)
+{
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (!c) return GRAM_ERR_ARG;
+    return sync_scalars(c, static_cast<hipStream_t>(stream), "gram_check");
+}
+
+const char* gram_last_error(const gram_ctx* ctx)
+{
+    const Ctx* c = reinterpret_cast<const Ctx*>(ctx);
+    return c ? c->last_error.c_str() : g_create_error.c_str();
+}
+
+}  // extern "C"

@@ -1,0 +1,108 @@
+// Internal declarations shared by the translation units of libgram (HIP, gfx950).
+// Not part of the public ABI; see include/gram.h for that.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+
+#include "gram.h"
+
+namespace gram {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;             // threads of the integer / streaming kernels
+constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kMaxDigitBits = 10;       // radix digit width limit (1024 LDS bins per wave)
+constexpr int kScanTile = 1024;         // rows per block in the flag-scan kernels
+constexpr int kSegRows = 32;            // sorted rows per tile of the segment reduction
+constexpr int kSegLong = 128;           // segments with at least this many rows are reduced tile by tile
+constexpr int kSlotNew = 1 << 30;       // flag in seg_slot: the buffer row is created by this step
+constexpr int kFixCols4 = 16;           // float4 columns per block of the long-segment combine
+constexpr int kFixLanes = kBlock / kFixCols4;
+
+// Device scalars (ctx->scal[...]).
+enum Scalar { kSU = 0, kSUTotal, kSErr, kSUBase, kSLongCount, kSFlushN, kSCount };
+
+// Device-latched error bits (scal[kSErr]).
+constexpr int kErrBitRange = 1;
+constexpr int kErrBitCapacity = 2;
+
+struct SortPlan {
+    int passes;
+    int digit_bits[4];
+    int items;   // 64-key rounds per wave
+    int nw;      // waves (chunks) over the host upper bound of n
+    int blocks;
+};
+
+struct Ctx {
+    gram_config cfg;
+    int64_t cap_u;        // min(max_positions, vocab_n): upper bound of U per step
+    int64_t cap_total;    // rows of the persistent buffer
+    int key_bits;         // bits needed for an ID
+
+    // --- workspace (device) ---
+    char* ws_base = nullptr;
+    int64_t ws_bytes = 0;
+    int *keys[2] = {nullptr, nullptr}, *vals[2] = {nullptr, nullptr};  // radix ping-pong, [max(M_max, cap_total)]
+    int* table = nullptr;       // [bins * nw] per-wave digit counts / prefixes
+    int* gtot = nullptr;        // [1024] per-digit totals
+    int* tile_sums = nullptr;   // [tiles] flag counts per scan tile
+    int* offsets = nullptr;     // [cap_u + 1] start row of each segment in sorted order
+    int* seg_of_row = nullptr;  // [M_max] segment index of each sorted row
+    int* uniq_ws = nullptr;     // [cap_u] copy of uniq of the current batch
+    int* seg_slot = nullptr;    // [cap_u] buffer row of each segment; kSlotNew set = row is new, -1 = dropped
+    int* scal = nullptr;        // [kSCount] device scalars, see enum Scalar
+    int* long_list = nullptr;   // [tiles_seg] head tiles of the long segments of the current batch
+    int* slot_of = nullptr;     // [N] buffer row of an ID, -1 = absent
+    int* id_of_slot = nullptr;  // [cap_total]
+    int* cnt_of_slot = nullptr; // [cap_total]
+    float* G = nullptr;         // [cap_total, d] persistent per-item gradient
+    float* E_ws = nullptr;      // [cap_u, d] representations when the caller passes E = NULL
+    float* seg_first = nullptr; // [tiles_seg, d] partial sums of segments entering a tile
+    float* seg_last = nullptr;  // [tiles_seg, d] partial sums of segments leaving a tile
+    void* Wt = nullptr;         // [d, d_in] transposed weight (bf16 path)
+    float* wg_partial = nullptr;// [splits, d_in, d] split-K partials of the weight gradient
+    int wg_splits = 1;
+
+    // sorted order of the current batch (point into keys[]/vals[])
+    int* sorted_keys = nullptr;
+    int* perm = nullptr;
+
+    // --- host state ---
+    bool have_unique = false;
+    bool unique_consumed = false;  // the current batch was already accumulated
+    int64_t cur_m = 0;
+    int32_t steps_done = 0;
+    int* h_pinned = nullptr;    // [4] pinned host scratch for small read-backs
+    std::string last_error;
+};
+
+// ---- gram_sort.hip -------------------------------------------------------
+SortPlan make_sort_plan(int key_bits, int64_t n_max);
+int64_t sort_table_elems(const SortPlan& p);
+// Stable LSD radix sort of (key, value) pairs on the low `key_bits` bits.
+// keys_in: n keys (n = *n_dev if n_dev else n_host; n <= n_max).  vals_in may
+// be NULL (value = index).  With check_range, keys outside [0, vocab_n) are
+// replaced by `fix_key` and kErrBitRange is latched.  Results land in
+// ctx->keys[r] / ctx->vals[r]; r is returned.
+int radix_sort_pairs(Ctx* c, const int* keys_in, const int* vals_in, int n_host, const int* n_dev,
+                     int64_t n_max, bool check_range, int fix_key, hipStream_t s);
+void unique_from_sorted(Ctx* c, int n, int* uniq, int* inverse, int* counts, int* u_out, hipStream_t s);
+
+// ---- gram_stream.hip -----------------------------------------------------
+void gather_rows(Ctx* c, const float* E, const int* inverse, int64_t m, float* H, hipStream_t s);
+void assign_slots(Ctx* c, hipStream_t s);
+void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s);
+void flush_export(Ctx* c, int* uniq_total, int* counts_total, float* G_total, int* u_total_dev,
+                  hipStream_t s);
+void fill_i32(int* p, int64_t n, int v, hipStream_t s);
+
+// ---- gram_gemm.hip -------------------------------------------------------
+void encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const int* u_dev,
+                    int64_t rows_max, float* E, hipStream_t s);
+void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s);
+int wgrad_splits_for(const gram_config& cfg);
+
+}  // namespace gram

@@ -1,0 +1,350 @@
+// Dedup of a batch of item IDs: the set B_I of unique items (Table 1 of the
+// paper; Algorithm 1 ranges over it), its inverse index and multiplicities.
+//
+// Method: stable LSD radix sort of (id, position) pairs over only the
+// ceil(log2 N) significant key bits, in digits of up to 10 bits (at most two
+// passes for a vocabulary of a million items), followed by head-flag scan and
+// compaction.  Each 64-lane wave owns a contiguous chunk of keys; ranks inside
+// a wave come from ballot-based digit matching, ranks across waves from a
+// per-wave digit table that one wave per digit prefix-sums.  All counters are
+// integer (LDS atomics are order independent), so the result is exact.
+#include "gram_internal.h"
+
+namespace gram {
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+__device__ __forceinline__ int wave_incl_scan(int v)
+{
+    const int lane = lane_id();
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        int t = __shfl_up(v, o);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+
+// Exclusive scan of one value per thread over a 256-thread block; *total gets the block sum.
+__device__ __forceinline__ int block_excl_scan(int v, int* total, int* sm /*[kWavesPerBlock]*/)
+{
+    const int incl = wave_incl_scan(v);
+    if (lane_id() == kWave - 1) sm[wave_id()] = incl;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) {
+        const int t = sm[w];
+        if (w < wave_id()) base += t;
+        tot += t;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + incl - v;
+}
+
+__device__ __forceinline__ int block_sum(int v, int* sm)
+{
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_down(v, o);
+    if (lane_id() == 0) sm[wave_id()] = v;
+    __syncthreads();
+    int tot = 0;
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) tot += sm[w];
+    __syncthreads();
+    return tot;
+}
+
+SortPlan make_sort_plan(int key_bits, int64_t n_max)
+{
+    SortPlan p{};
+    if (key_bits < 1) key_bits = 1;
+    p.passes = (key_bits + kMaxDigitBits - 1) / kMaxDigitBits;
+    int left = key_bits;
+    for (int i = 0; i < p.passes; ++i) {
+        int b = (left + (p.passes - i) - 1) / (p.passes - i);
+        p.digit_bits[i] = b;
+        left -= b;
+    }
+    int64_t items = (n_max + (int64_t)kWave * 256 - 1) / ((int64_t)kWave * 256);
+    if (items < 4) items = 4;
+    if (items > 64) items = 64;
+    p.items = (int)items;
+    int64_t kpw = (int64_t)kWave * p.items;
+    int64_t nw = (n_max + kpw - 1) / kpw;
+    if (nw < 1) nw = 1;
+    p.nw = (int)nw;
+    p.blocks = (int)((nw + kWavesPerBlock - 1) / kWavesPerBlock);
+    return p;
+}
+
+int64_t sort_table_elems(const SortPlan& p)
+{
+    int mb = 0;
+    for (int i = 0; i < p.passes; ++i) mb = p.digit_bits[i] > mb ? p.digit_bits[i] : mb;
+    return ((int64_t)1 << mb) * p.nw;
+}
+
+// Per-wave digit histogram of one pass.  table[digit * nw + wave] = count.
+template <bool CHECK>
+__global__ __launch_bounds__(kBlock) void k_radix_hist(const int* __restrict__ keys, int n_host,
+                                                       const int* __restrict__ n_dev, int shift,
+                                                       int dbits, int items, int nw,
+                                                       int* __restrict__ table, int vocab_n,
+                                                       int fix_key, int* __restrict__ err)
+{
+    __shared__ int cnt[kWavesPerBlock][1 << kMaxDigitBits];
+    const int n = n_dev ? *n_dev : n_host;
+    const int wave = wave_id(), lane = lane_id();
+    const int gw = blockIdx.x * kWavesPerBlock + wave;
+    const int bins = 1 << dbits;
+    for (int b = lane; b < bins; b += kWave) cnt[wave][b] = 0;
+    __syncthreads();
+    if (gw < nw) {
+        const int64_t base = (int64_t)gw * items * kWave;
+        bool bad = false;
+        for (int it = 0; it < items; ++it) {
+            const int64_t idx = base + (int64_t)it * kWave + lane;
+            if (idx < n) {
+                int k = keys[idx];
+                if (CHECK && (k < 0 || k >= vocab_n)) { bad = true; k = fix_key; }
+                atomicAdd(&cnt[wave][(k >> shift) & (bins - 1)], 1);
+            }
+        }
+        if (CHECK && bad) atomicOr(err, kErrBitRange);
+    }
+    __syncthreads();
+    if (gw < nw)
+        for (int b = lane; b < bins; b += kWave) table[(int64_t)b * nw + gw] = cnt[wave][b];
+}
+
+// One wave per digit: exclusive prefix over the waves' counts (in place), digit total to gtot.
+__global__ __launch_bounds__(kBlock) void k_radix_scan(int* __restrict__ table, int nw, int bins,
+                                                       int* __restrict__ gtot)
+{
+    const int b = blockIdx.x * kWavesPerBlock + wave_id();
+    if (b >= bins) return;
+    const int lane = lane_id();
+    int* row = table + (int64_t)b * nw;
+    int carry = 0;
+    for (int base = 0; base < nw; base += kWave) {
+        const int i = base + lane;
+        const int v = i < nw ? row[i] : 0;
+        const int incl = wave_incl_scan(v);
+        if (i < nw) row[i] = carry + incl - v;
+        carry += __shfl(incl, kWave - 1);
+    }
+    if (lane == 0) gtot[b] = carry;
+}
+
+// Stable scatter of one pass.  A wave walks its chunk in rounds of 64 keys;
+// inside a round, lanes holding the same digit find each other with one
+// ballot per digit bit and take consecutive slots in lane order.
+template <bool CHECK>
+__global__ __launch_bounds__(kBlock) void k_radix_scatter(
+    const int* __restrict__ keys_in, const int* __restrict__ vals_in, int n_host,
+    const int* __restrict__ n_dev, int shift, int dbits, int items, int nw,
+    const int* __restrict__ table, const int* __restrict__ gtot, int* __restrict__ keys_out,
+    int* __restrict__ vals_out, int vocab_n, int fix_key)
+{
+    __shared__ int digit_base[1 << kMaxDigitBits];
+    __shared__ int cnt_s[kWavesPerBlock][1 << kMaxDigitBits];
+    __shared__ int sm[kWavesPerBlock];
+    const int n = n_dev ? *n_dev : n_host;
+    const int wave = wave_id(), lane = lane_id();
+    const int gw = blockIdx.x * kWavesPerBlock + wave;
+    const int bins = 1 << dbits;
+
+    {   // exclusive scan of the digit totals, 4 digits per thread
+        int v[4], s = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int b = threadIdx.x * 4 + i;
+            v[i] = b < bins ? gtot[b] : 0;
+            s += v[i];
+        }
+        int total;
+        int run = block_excl_scan(s, &total, sm);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int b = threadIdx.x * 4 + i;
+            if (b < bins) digit_base[b] = run;
+            run += v[i];
+        }
+    }
+    __syncthreads();
+    volatile int* cnt = cnt_s[wave];
+    if (gw < nw)
+        for (int b = lane; b < bins; b += kWave) cnt[b] = digit_base[b] + table[(int64_t)b * nw + gw];
+    __syncthreads();
+    if (gw >= nw) return;
+
+    const int64_t base = (int64_t)gw * items * kWave;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    for (int it = 0; it < items; ++it) {
+        const int64_t idx = base + (int64_t)it * kWave + lane;
+        const bool valid = idx < n;
+        int k = 0, v = 0;
+        if (valid) {
+            k = keys_in[idx];
+            if (CHECK && (k < 0 || k >= vocab_n)) k = fix_key;
+            v = vals_in ? vals_in[idx] : (int)idx;
+        }
+        const int dg = (k >> shift) & (bins - 1);
+        unsigned long long peers = __ballot(valid);
+        for (int bit = 0; bit < dbits; ++bit) {
+            const bool one = (dg >> bit) & 1;
+            const unsigned long long m = __ballot(one);
+            peers &= one ? m : ~m;
+        }
+        const int below = __popcll(peers & lt_mask);
+        int pos = 0;
+        if (valid) pos = cnt[dg] + below;
+        __builtin_amdgcn_wave_barrier();
+        if (valid && below == 0) cnt[dg] = pos + __popcll(peers);
+        __builtin_amdgcn_wave_barrier();
+        if (valid) {
+            keys_out[pos] = k;
+            vals_out[pos] = v;
+        }
+    }
+}
+
+int radix_sort_pairs(Ctx* c, const int* keys_in, const int* vals_in, int n_host, const int* n_dev,
+                     int64_t n_max, bool check_range, int fix_key, hipStream_t s)
+{
+    const SortPlan p = make_sort_plan(c->key_bits, n_max);
+    const int* kin = keys_in;
+    const int* vin = vals_in;
+    int shift = 0, dst = 0;
+    for (int pass = 0; pass < p.passes; ++pass) {
+        const int db = p.digit_bits[pass];
+        const int bins = 1 << db;
+        const bool chk = check_range && pass == 0;
+        if (chk)
+            hipLaunchKernelGGL(k_radix_hist<true>, dim3(p.blocks), dim3(kBlock), 0, s, kin, n_host,
+                               n_dev, shift, db, p.items, p.nw, c->table, c->cfg.vocab_n, fix_key,
+                               c->scal + kSErr);
+        else
+            hipLaunchKernelGGL(k_radix_hist<false>, dim3(p.blocks), dim3(kBlock), 0, s, kin, n_host,
+                               n_dev, shift, db, p.items, p.nw, c->table, 0, 0, c->scal + kSErr);
+        hipLaunchKernelGGL(k_radix_scan, dim3((bins + kWavesPerBlock - 1) / kWavesPerBlock),
+                           dim3(kBlock), 0, s, c->table, p.nw, bins, c->gtot);
+        if (chk)
+            hipLaunchKernelGGL(k_radix_scatter<true>, dim3(p.blocks), dim3(kBlock), 0, s, kin, vin,
+                               n_host, n_dev, shift, db, p.items, p.nw, c->table, c->gtot,
+                               c->keys[dst], c->vals[dst], c->cfg.vocab_n, fix_key);
+        else
+            hipLaunchKernelGGL(k_radix_scatter<false>, dim3(p.blocks), dim3(kBlock), 0, s, kin, vin,
+                               n_host, n_dev, shift, db, p.items, p.nw, c->table, c->gtot,
+                               c->keys[dst], c->vals[dst], 0, 0);
+        kin = c->keys[dst];
+        vin = c->vals[dst];
+        shift += db;
+        dst ^= 1;
+    }
+    return dst ^ 1;
+}
+
+// ---- head flags -> uniq / inverse / offsets / counts ----------------------
+
+__device__ __forceinline__ bool is_head(const int* __restrict__ sk, int r)
+{
+    return r == 0 || sk[r] != sk[r - 1];
+}
+
+__global__ __launch_bounds__(kBlock) void k_heads_count(const int* __restrict__ sk, int n,
+                                                        int* __restrict__ tile_sums)
+{
+    __shared__ int sm[kWavesPerBlock];
+    const int r0 = blockIdx.x * kScanTile + threadIdx.x * 4;
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (r0 + i < n) s += is_head(sk, r0 + i) ? 1 : 0;
+    const int tot = block_sum(s, sm);
+    if (threadIdx.x == 0) tile_sums[blockIdx.x] = tot;
+}
+
+__global__ __launch_bounds__(kBlock) void k_heads_emit(
+    const int* __restrict__ sk, const int* __restrict__ sv, int n, const int* __restrict__ tile_sums,
+    int* __restrict__ uniq, int* __restrict__ inverse, int* __restrict__ offsets,
+    int* __restrict__ seg_of_row, int* __restrict__ uniq_ws, int* __restrict__ u_ws,
+    int* __restrict__ u_out)
+{
+    __shared__ int sm[kWavesPerBlock];
+    int pre = 0;
+    for (int t = threadIdx.x; t < (int)blockIdx.x; t += kBlock) pre += tile_sums[t];
+    pre = block_sum(pre, sm);
+
+    const int r0 = blockIdx.x * kScanTile + threadIdx.x * 4;
+    bool f[4];
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[i] = (r0 + i < n) && is_head(sk, r0 + i);
+        s += f[i] ? 1 : 0;
+    }
+    int total;
+    int run = pre + block_excl_scan(s, &total, sm);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = r0 + i;
+        if (r < n) {
+            run += f[i] ? 1 : 0;
+            const int seg = run - 1;
+            seg_of_row[r] = seg;
+            inverse[sv[r]] = seg;
+            if (f[i]) {
+                const int key = sk[r];
+                uniq[seg] = key;
+                uniq_ws[seg] = key;
+                offsets[seg] = r;
+            }
+        }
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        const int u = pre + total;
+        *u_ws = u;
+        if (u_out) *u_out = u;
+        offsets[u] = n;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_counts(const int* __restrict__ offsets,
+                                                   const int* __restrict__ u_ws,
+                                                   int* __restrict__ counts)
+{
+    const int j = blockIdx.x * kBlock + threadIdx.x;
+    if (j < *u_ws) counts[j] = offsets[j + 1] - offsets[j];
+}
+
+__global__ void k_unique_empty(int* u_ws, int* u_out, int* offsets)
+{
+    if (threadIdx.x == 0) {
+        *u_ws = 0;
+        if (u_out) *u_out = 0;
+        offsets[0] = 0;
+    }
+}
+
+void unique_from_sorted(Ctx* c, int n, int* uniq, int* inverse, int* counts, int* u_out,
+                        hipStream_t s)
+{
+    if (n == 0) {
+        hipLaunchKernelGGL(k_unique_empty, dim3(1), dim3(kWave), 0, s, c->scal + kSU, u_out, c->offsets);
+        return;
+    }
+    const int tiles = (n + kScanTile - 1) / kScanTile;
+    hipLaunchKernelGGL(k_heads_count, dim3(tiles), dim3(kBlock), 0, s, c->sorted_keys, n, c->tile_sums);
+    hipLaunchKernelGGL(k_heads_emit, dim3(tiles), dim3(kBlock), 0, s, c->sorted_keys, c->perm, n,
+                       c->tile_sums, uniq, inverse, c->offsets, c->seg_of_row, c->uniq_ws, c->scal + kSU,
+                       u_out);
+    const int64_t cap = n < c->cap_u ? n : c->cap_u;
+    hipLaunchKernelGGL(k_counts, dim3((unsigned)((cap + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+                       c->offsets, c->scal + kSU, counts);
+}
+
+}  // namespace gram

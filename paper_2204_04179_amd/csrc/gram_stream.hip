@@ -1,0 +1,448 @@
+// HBM-bound kernels of the GRAM step: row gather of representations to
+// interaction positions (Algorithm 1 step 1, second half), the deterministic
+// per-item reduction of dL/dH (step 3, Eq. 6) into the buffer that persists
+// over a Multi-step window (Section 4.2), and the export of that buffer at the
+// end of the window.
+//
+// No float atomics anywhere: each buffer row has exactly one writer and a
+// fixed order of additions, so results are bit-identical from run to run.
+#include "gram_internal.h"
+
+namespace gram {
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+__device__ __forceinline__ int wave_incl_scan(int v)
+{
+    const int lane = lane_id();
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        int t = __shfl_up(v, o);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+
+__device__ __forceinline__ int block_excl_scan(int v, int* total, int* sm)
+{
+    const int incl = wave_incl_scan(v);
+    if (lane_id() == kWave - 1) sm[wave_id()] = incl;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) {
+        const int t = sm[w];
+        if (w < wave_id()) base += t;
+        tot += t;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + incl - v;
+}
+
+__device__ __forceinline__ int block_sum(int v, int* sm)
+{
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_down(v, o);
+    if (lane_id() == 0) sm[wave_id()] = v;
+    __syncthreads();
+    int tot = 0;
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) tot += sm[w];
+    __syncthreads();
+    return tot;
+}
+
+__device__ __forceinline__ float4 f4_add(float4 a, float4 b)
+{
+    return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w);
+}
+
+// ---- fill ------------------------------------------------------------------
+
+__global__ __launch_bounds__(kBlock) void k_fill_i32(int* __restrict__ p, int64_t n, int v)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (int64_t)gridDim.x * kBlock)
+        p[i] = v;
+}
+
+void fill_i32(int* p, int64_t n, int v, hipStream_t s)
+{
+    if (n <= 0) return;
+    int64_t blocks = (n + kBlock - 1) / kBlock;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)blocks), dim3(kBlock), 0, s, p, n, v);
+}
+
+// ---- gather: H[p,:] = E[inverse[p],:] ---------------------------------------
+
+// One float4 per thread and step; a block walks `rows_per_block` consecutive
+// positions so that its writes to H form one contiguous stream.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(kBlock) void k_gather_rows(const f32x4* __restrict__ E,
+                                                        const int* __restrict__ inverse, int64_t m,
+                                                        int cols4, f32x4* __restrict__ H,
+                                                        int rows_per_block)
+{
+    const int64_t p0 = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t p1 = p0 + rows_per_block < m ? p0 + rows_per_block : m;
+    const int total = (int)(p1 - p0) * cols4;
+    for (int i = threadIdx.x; i < total; i += kBlock) {
+        const int64_t p = p0 + i / cols4;
+        const int c = i % cols4;
+        const f32x4 v = E[(int64_t)inverse[p] * cols4 + c];
+        __builtin_nontemporal_store(v, &H[p * cols4 + c]);   // H is written once and not re-read here
+    }
+}
+
+void gather_rows(Ctx* c, const float* E, const int* inverse, int64_t m, float* H, hipStream_t s)
+{
+    if (m == 0) return;
+    const int cols4 = c->cfg.d / 4;
+    int rows_per_block = (8 * kBlock + cols4 - 1) / cols4;   // ~8 float4 per thread
+    if (rows_per_block < 1) rows_per_block = 1;
+    const int64_t blocks = (m + rows_per_block - 1) / rows_per_block;
+    hipLaunchKernelGGL(k_gather_rows, dim3((unsigned)blocks), dim3(kBlock), 0, s,
+                       reinterpret_cast<const f32x4*>(E), inverse, m, cols4,
+                       reinterpret_cast<f32x4*>(H), rows_per_block);
+}
+
+// ---- buffer rows for the items of this batch --------------------------------
+//
+// An item seen for the first time in the window gets the next free row of the
+// persistent buffer; new items of one batch take consecutive rows in ascending
+// ID order (a scan over "is new" flags), so the row layout, and with it the
+// summation order of the weight gradient, is a function of the data alone.
+
+__global__ __launch_bounds__(kBlock) void k_slot_count(const int* __restrict__ uniq_ws,
+                                                       const int* __restrict__ slot_of,
+                                                       int* __restrict__ scal,
+                                                       int* __restrict__ tile_sums)
+{
+    __shared__ int sm[kWavesPerBlock];
+    const int u = scal[kSU];
+    const int j0 = blockIdx.x * kScanTile + threadIdx.x * 4;
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (j0 + i < u) s += slot_of[uniq_ws[j0 + i]] < 0 ? 1 : 0;
+    const int tot = block_sum(s, sm);
+    if (threadIdx.x == 0) {
+        tile_sums[blockIdx.x] = tot;
+        if (blockIdx.x == 0) {
+            scal[kSUBase] = scal[kSUTotal];
+            scal[kSLongCount] = 0;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_slot_emit(
+    const int* __restrict__ uniq_ws, const int* __restrict__ offsets, int* __restrict__ slot_of,
+    int* __restrict__ id_of_slot, int* __restrict__ cnt_of_slot, int* __restrict__ seg_slot,
+    int* __restrict__ scal, const int* __restrict__ tile_sums, int cap_total)
+{
+    __shared__ int sm[kWavesPerBlock];
+    const int u = scal[kSU];
+    const int u_base = scal[kSUBase];
+    int pre = 0;
+    for (int t = threadIdx.x; t < (int)blockIdx.x; t += kBlock) pre += tile_sums[t];
+    pre = block_sum(pre, sm);
+
+    const int j0 = blockIdx.x * kScanTile + threadIdx.x * 4;
+    int id[4], old[4], s = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        id[i] = 0;
+        old[i] = 0;
+        if (j0 + i < u) {
+            id[i] = uniq_ws[j0 + i];
+            old[i] = slot_of[id[i]];
+            s += old[i] < 0 ? 1 : 0;
+        }
+    }
+    int total;
+    int run = u_base + pre + block_excl_scan(s, &total, sm);
+    bool overflow = false;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int j = j0 + i;
+        if (j < u) {
+            const int cnt = offsets[j + 1] - offsets[j];
+            if (old[i] < 0) {
+                const int slot = run++;
+                if (slot < cap_total) {
+                    slot_of[id[i]] = slot;
+                    id_of_slot[slot] = id[i];
+                    cnt_of_slot[slot] = cnt;
+                    seg_slot[j] = slot | kSlotNew;
+                } else {
+                    seg_slot[j] = -1;      // dropped: the buffer is full
+                    overflow = true;
+                }
+            } else {
+                cnt_of_slot[old[i]] += cnt;
+                seg_slot[j] = old[i];
+            }
+        }
+    }
+    if (overflow) atomicOr(&scal[kSErr], kErrBitCapacity);
+    // tiles past U add nothing, so the last block of the grid sees the full count
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        const int nt = u_base + pre + total;
+        scal[kSUTotal] = nt < cap_total ? nt : cap_total;
+    }
+}
+
+void assign_slots(Ctx* c, hipStream_t s)
+{
+    int64_t bound = c->cur_m < c->cap_u ? c->cur_m : c->cap_u;
+    if (bound < 1) bound = 1;
+    const int tiles = (int)((bound + kScanTile - 1) / kScanTile);
+    hipLaunchKernelGGL(k_slot_count, dim3(tiles), dim3(kBlock), 0, s, c->uniq_ws, c->slot_of, c->scal,
+                       c->tile_sums);
+    hipLaunchKernelGGL(k_slot_emit, dim3(tiles), dim3(kBlock), 0, s, c->uniq_ws, c->offsets,
+                       c->slot_of, c->id_of_slot, c->cnt_of_slot, c->seg_slot, c->scal, c->tile_sums,
+                       (int)c->cap_total);
+}
+
+// ---- sorted-segment reduction -----------------------------------------------
+//
+// Rows of dH are visited in the sorted order of the batch (perm), where the
+// occurrences of one item are adjacent and in ascending position.  The sorted
+// rows are cut into tiles of kSegRows.
+//  * A short segment (< kSegLong rows) is summed, whole and in order, by the
+//    tile that holds its first row, even where it runs past the tile's end; it
+//    needs no partial result.
+//  * A long segment is summed tile by tile into partial rows (seg_last for the
+//    tile where it starts, seg_first for every later tile), and k_seg_combine
+//    adds the partials in ascending tile order.
+// Destination codes kept per row in LDS:
+constexpr int kDstNone = -1;    // nothing to write (dropped item)
+constexpr int kDstFirst = -2;   // partial row seg_first[tile]
+constexpr int kDstLast = -3;    // partial row seg_last[tile]
+constexpr int kSegMaxRows = kSegRows + kSegLong;
+constexpr int kSegUnroll = 8;
+
+__device__ __forceinline__ void write_final(float4* __restrict__ G, int cols4, int col, int code,
+                                            bool is_pad, float4 acc)
+{
+    if (code == kDstNone) return;
+    float4* dst = G + (int64_t)(code & (kSlotNew - 1)) * cols4 + col;
+    if (code & kSlotNew) {
+        *dst = is_pad ? make_float4(0.f, 0.f, 0.f, 0.f) : acc;
+    } else if (!is_pad) {
+        *dst = f4_add(*dst, acc);
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_seg_reduce(
+    const float4* __restrict__ dH, const int* __restrict__ perm, const int* __restrict__ seg_of_row,
+    const int* __restrict__ offsets, const int* __restrict__ uniq_ws,
+    const int* __restrict__ seg_slot, int n, int cols4, int pad_id, float4* __restrict__ G,
+    float4* __restrict__ seg_first, float4* __restrict__ seg_last, int* __restrict__ scal,
+    int* __restrict__ long_list)
+{
+    __shared__ int s_src[kSegMaxRows];    // dH row of each sorted row, -1 = padding (not read)
+    __shared__ int s_dst[kSegMaxRows];    // 0 = keep adding; else destination code + 4 (see below)
+    __shared__ int s_pad[kSegMaxRows];
+
+    const int t = blockIdx.x;
+    const int r0 = t * kSegRows;
+    const int r1 = r0 + kSegRows < n ? r0 + kSegRows : n;
+
+    // first and one-past-last sorted row this tile sums
+    int a, b;
+    {
+        const int sg = seg_of_row[r0];
+        const int o0 = offsets[sg], o1 = offsets[sg + 1];
+        a = (o0 < r0 && o1 - o0 < kSegLong) ? o1 : r0;
+        const int sl = seg_of_row[r1 - 1];
+        const int p0 = offsets[sl], p1 = offsets[sl + 1];
+        b = (p1 - p0 < kSegLong) ? p1 : r1;
+    }
+    if (a >= r1) return;      // the tile lies inside a short segment owned by an earlier tile
+    const int rows = b - a;
+
+    for (int i = threadIdx.x; i < rows; i += blockDim.x) {
+        const int r = a + i;
+        const int sg = seg_of_row[r];
+        const int o0 = offsets[sg], o1 = offsets[sg + 1];
+        const bool is_long = o1 - o0 >= kSegLong;
+        const bool is_pad = uniq_ws[sg] == pad_id;
+        const bool seg_end = r + 1 == o1;
+        int code = 0;
+        if (is_long) {
+            if (seg_end || r + 1 == r1) code = (o0 < r0 ? kDstFirst : kDstLast) + 4;
+        } else if (seg_end) {
+            code = seg_slot[sg] + 4;
+        }
+        s_src[i] = is_pad ? -1 : perm[r];
+        s_dst[i] = code;
+        s_pad[i] = is_pad ? 1 : 0;
+    }
+    __syncthreads();
+
+    const int col = blockIdx.y * blockDim.x + threadIdx.x;
+    if (col >= cols4) return;
+
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i0 = 0; i0 < rows; i0 += kSegUnroll) {
+        float4 v[kSegUnroll];
+#pragma unroll
+        for (int k = 0; k < kSegUnroll; ++k) {
+            const int i = i0 + k;
+            const int src = i < rows ? s_src[i] : -1;
+            v[k] = src >= 0 ? dH[(int64_t)src * cols4 + col] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int k = 0; k < kSegUnroll; ++k) {
+            const int i = i0 + k;
+            if (i < rows) {
+                acc = f4_add(acc, v[k]);
+                const int code = s_dst[i];
+                if (code != 0) {
+                    const int dst = code - 4;
+                    if (dst == kDstFirst) {
+                        seg_first[(int64_t)t * cols4 + col] = acc;
+                    } else if (dst == kDstLast) {
+                        seg_last[(int64_t)t * cols4 + col] = acc;
+                        if (col == 0) long_list[atomicAdd(&scal[kSLongCount], 1)] = t;
+                    } else {
+                        write_final(G, cols4, col, dst, s_pad[i] != 0, acc);
+                    }
+                    acc = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            }
+        }
+    }
+}
+
+// Sum of a long segment's partial rows in ascending tile order.  A block owns
+// kFixCols4 float4 columns; its kFixLanes row lanes each add every
+// kFixLanes-th partial, then lane sums are added in lane order.
+__global__ __launch_bounds__(kBlock) void k_seg_combine(
+    const int* __restrict__ seg_of_row, const int* __restrict__ offsets,
+    const int* __restrict__ uniq_ws, const int* __restrict__ seg_slot, int n, int cols4, int pad_id,
+    float4* __restrict__ G, const float4* __restrict__ seg_first,
+    const float4* __restrict__ seg_last, const int* __restrict__ scal,
+    const int* __restrict__ long_list)
+{
+    __shared__ float4 sm[kFixLanes][kFixCols4];
+    const int cl = threadIdx.x % kFixCols4;
+    const int rl = threadIdx.x / kFixCols4;
+    const int col = blockIdx.y * kFixCols4 + cl;
+    const int count = scal[kSLongCount];
+    for (int w = blockIdx.x; w < count; w += gridDim.x) {
+        const int t = long_list[w];
+        int last_row = (t + 1) * kSegRows - 1;
+        if (last_row > n - 1) last_row = n - 1;
+        const int sg = seg_of_row[last_row];
+        const int seg_end = offsets[sg + 1];
+        const bool is_pad = uniq_ws[sg] == pad_id;
+        // partial i: i = 0 -> seg_last[t]; i >= 1 -> seg_first[t + i]
+        const int parts = 1 + (seg_end - 1) / kSegRows - t;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (!is_pad && col < cols4) {
+            for (int i = rl; i < parts; i += kFixLanes) {
+                const float4* src = i == 0 ? seg_last + (int64_t)t * cols4
+                                           : seg_first + (int64_t)(t + i) * cols4;
+                acc = f4_add(acc, src[col]);
+            }
+        }
+        sm[rl][cl] = acc;
+        __syncthreads();
+        if (rl == 0 && col < cols4) {
+            float4 tot = sm[0][cl];
+#pragma unroll
+            for (int k = 1; k < kFixLanes; ++k) tot = f4_add(tot, sm[k][cl]);
+            write_final(G, cols4, col, seg_slot[sg], is_pad, tot);
+        }
+        __syncthreads();
+    }
+}
+
+void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s)
+{
+    if (m == 0) return;
+    const int n = (int)m;
+    const int cols4 = c->cfg.d / 4;
+    int threads = ((cols4 + kWave - 1) / kWave) * kWave;
+    if (threads > kBlock) threads = kBlock;
+    const int slabs = (cols4 + threads - 1) / threads;
+    const int tiles = (n + kSegRows - 1) / kSegRows;
+    hipLaunchKernelGGL(k_seg_reduce, dim3(tiles, slabs), dim3(threads), 0, s,
+                       reinterpret_cast<const float4*>(dH), c->perm, c->seg_of_row, c->offsets,
+                       c->uniq_ws, c->seg_slot, n, cols4, c->cfg.pad_id,
+                       reinterpret_cast<float4*>(c->G), reinterpret_cast<float4*>(c->seg_first),
+                       reinterpret_cast<float4*>(c->seg_last), c->scal, c->long_list);
+    int fix_blocks = tiles / (kSegLong / kSegRows) + 1;   // upper bound of long segments
+    if (fix_blocks > 256) fix_blocks = 256;
+    hipLaunchKernelGGL(k_seg_combine, dim3(fix_blocks, (cols4 + kFixCols4 - 1) / kFixCols4),
+                       dim3(kBlock), 0, s, c->seg_of_row, c->offsets, c->uniq_ws, c->seg_slot, n,
+                       cols4, c->cfg.pad_id, reinterpret_cast<float4*>(c->G),
+                       reinterpret_cast<const float4*>(c->seg_first),
+                       reinterpret_cast<const float4*>(c->seg_last), c->scal, c->long_list);
+}
+
+// ---- end of the window: export in ascending ID order, then empty ------------
+
+__global__ __launch_bounds__(kBlock) void k_flush_meta(
+    const int* __restrict__ sorted_ids, const int* __restrict__ sorted_slots,
+    const int* __restrict__ cnt_of_slot, int* __restrict__ slot_of, int* __restrict__ uniq_total,
+    int* __restrict__ counts_total, const int* __restrict__ scal)
+{
+    const int n = scal[kSUTotal];
+    for (int r = blockIdx.x * kBlock + threadIdx.x; r < n; r += gridDim.x * kBlock) {
+        const int id = sorted_ids[r];
+        if (uniq_total) uniq_total[r] = id;
+        if (counts_total) counts_total[r] = cnt_of_slot[sorted_slots[r]];
+        slot_of[id] = -1;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_flush_rows(const int* __restrict__ sorted_slots,
+                                                       const float4* __restrict__ G, int cols4,
+                                                       float4* __restrict__ G_total,
+                                                       const int* __restrict__ scal)
+{
+    const int n = scal[kSUTotal];
+    const int64_t total = (int64_t)n * cols4;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * kBlock) {
+        const int64_t r = i / cols4;
+        const int cc = (int)(i % cols4);
+        G_total[i] = G[(int64_t)sorted_slots[r] * cols4 + cc];
+    }
+}
+
+__global__ void k_flush_finish(int* __restrict__ scal, int* __restrict__ u_total_dev)
+{
+    if (threadIdx.x == 0) {
+        const int n = scal[kSUTotal];
+        if (u_total_dev) *u_total_dev = n;
+        scal[kSFlushN] = n;
+        scal[kSUTotal] = 0;
+    }
+}
+
+void flush_export(Ctx* c, int* uniq_total, int* counts_total, float* G_total, int* u_total_dev,
+                  hipStream_t s)
+{
+    const int r = radix_sort_pairs(c, c->id_of_slot, nullptr, 0, c->scal + kSUTotal, c->cap_total,
+                                   false, 0, s);
+    const int* sorted_ids = c->keys[r];
+    const int* sorted_slots = c->vals[r];
+    int64_t blocks = (c->cap_total + kBlock - 1) / kBlock;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(k_flush_meta, dim3((unsigned)blocks), dim3(kBlock), 0, s, sorted_ids,
+                       sorted_slots, c->cnt_of_slot, c->slot_of, uniq_total, counts_total, c->scal);
+    if (G_total)
+        hipLaunchKernelGGL(k_flush_rows, dim3(2048), dim3(kBlock), 0, s, sorted_slots,
+                           reinterpret_cast<const float4*>(c->G), c->cfg.d / 4,
+                           reinterpret_cast<float4*>(G_total), c->scal);
+    hipLaunchKernelGGL(k_flush_finish, dim3(1), dim3(kWave), 0, s, c->scal, u_total_dev);
+}
+
+}  // namespace gram

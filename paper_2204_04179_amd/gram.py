@@ -1,0 +1,155 @@
+"""Thin ctypes binding of libgram (include/gram.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+the library.  PyTorch supplies device memory and the current stream.  There is
+no fallback: if the shared library is missing or fails to load, `load()`
+raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libgram.so")
+
+F32, BF16 = 0, 1
+OK, ERR_ARG, ERR_CAPACITY, ERR_SEQUENCE, ERR_RANGE, ERR_HIP, ERR_UNIMPLEMENTED = 0, -1, -2, -3, -4, -5, -6
+STATUS_NAMES = {OK: "GRAM_OK", ERR_ARG: "GRAM_ERR_ARG", ERR_CAPACITY: "GRAM_ERR_CAPACITY",
+                ERR_SEQUENCE: "GRAM_ERR_SEQUENCE", ERR_RANGE: "GRAM_ERR_RANGE", ERR_HIP: "GRAM_ERR_HIP",
+                ERR_UNIMPLEMENTED: "GRAM_ERR_UNIMPLEMENTED"}
+
+EXPORTS = ("gram_workspace_bytes", "gram_create", "gram_destroy", "gram_unique", "gram_encode_gather",
+           "gram_grad_accumulate", "gram_encoder_wgrad", "gram_flush", "gram_check", "gram_last_error")
+
+
+class GramConfig(C.Structure):
+    _fields_ = [("vocab_n", C.c_int32), ("d_in", C.c_int32), ("d", C.c_int32),
+                ("max_positions", C.c_int64), ("k_steps", C.c_int32), ("pad_id", C.c_int32),
+                ("u_total_cap", C.c_int64), ("xw_dtype", C.c_int32)]
+
+
+class GramError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def load():
+    """Open libgram.so (built by `python -m paper_2204_04179_amd.build`)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2204_04179_amd.build`")
+    L = C.CDLL(LIB_PATH)
+    vp, i32p = C.c_void_p, C.POINTER(C.c_int32)
+    L.gram_workspace_bytes.restype = C.c_int64
+    L.gram_workspace_bytes.argtypes = [C.POINTER(GramConfig)]
+    L.gram_create.restype = C.c_int
+    L.gram_create.argtypes = [C.POINTER(vp), C.POINTER(GramConfig)]
+    L.gram_destroy.restype = C.c_int
+    L.gram_destroy.argtypes = [vp]
+    L.gram_unique.restype = C.c_int
+    L.gram_unique.argtypes = [vp, vp, C.c_int64, vp, vp, vp, vp, i32p, vp]
+    L.gram_encode_gather.restype = C.c_int
+    L.gram_encode_gather.argtypes = [vp, vp, vp, vp, vp, vp, C.c_int64, vp, vp, vp]
+    L.gram_grad_accumulate.restype = C.c_int
+    L.gram_grad_accumulate.argtypes = [vp, vp, C.c_int64, C.c_int32, vp]
+    L.gram_encoder_wgrad.restype = C.c_int
+    L.gram_encoder_wgrad.argtypes = [vp, vp, vp, vp]
+    L.gram_flush.restype = C.c_int
+    L.gram_flush.argtypes = [vp, vp, vp, vp, vp, i32p, vp]
+    L.gram_check.restype = C.c_int
+    L.gram_check.argtypes = [vp, vp]
+    L.gram_last_error.restype = C.c_char_p
+    L.gram_last_error.argtypes = [vp]
+    _lib = L
+    return L
+
+
+def make_config(vocab_n, d_in, d, max_positions, k_steps=1, pad_id=0, u_total_cap=0, xw_dtype=BF16):
+    return GramConfig(int(vocab_n), int(d_in), int(d), int(max_positions), int(k_steps), int(pad_id),
+                      int(u_total_cap), int(xw_dtype))
+
+
+def workspace_bytes(cfg: GramConfig) -> int:
+    return load().gram_workspace_bytes(C.byref(cfg))
+
+
+def _ptr(t):
+    """Device (or NULL) pointer of a torch tensor / raw int."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+class Gram:
+    """A context of the library.  Tensor arguments are CUDA(HIP) torch tensors,
+    contiguous, of the dtypes include/gram.h states; they are passed by pointer."""
+
+    def __init__(self, cfg: GramConfig):
+        self._lib = load()
+        self.cfg = cfg
+        self._h = C.c_void_p()
+        rc = self._lib.gram_create(C.byref(self._h), C.byref(cfg))
+        if rc != OK:
+            raise GramError(rc, (self._lib.gram_last_error(None) or b"").decode())
+
+    def _ck(self, rc):
+        if rc != OK:
+            raise GramError(rc, (self._lib.gram_last_error(self._h) or b"").decode())
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h:
+            self._lib.gram_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def unique(self, ids, uniq, inverse, counts, u_dev=None, want_host_u=False, stream=None):
+        m = ids.numel() if not isinstance(ids, int) else None
+        u_host = C.c_int32(-1)
+        self._ck(self._lib.gram_unique(self._h, _ptr(ids), m, _ptr(uniq), _ptr(inverse), _ptr(counts),
+                                       _ptr(u_dev), C.byref(u_host) if want_host_u else None,
+                                       _stream(stream)))
+        return u_host.value if want_host_u else None
+
+    def encode_gather(self, X, W, uniq, inverse, u_dev, m, E, H, stream=None):
+        self._ck(self._lib.gram_encode_gather(self._h, _ptr(X), _ptr(W), _ptr(uniq), _ptr(inverse),
+                                              _ptr(u_dev), int(m), _ptr(E), _ptr(H), _stream(stream)))
+
+    def grad_accumulate(self, dH, m, step_k, stream=None):
+        self._ck(self._lib.gram_grad_accumulate(self._h, _ptr(dH), int(m), int(step_k), _stream(stream)))
+
+    def encoder_wgrad(self, X, dW, stream=None):
+        self._ck(self._lib.gram_encoder_wgrad(self._h, _ptr(X), _ptr(dW), _stream(stream)))
+
+    def flush(self, uniq_total=None, counts_total=None, G_total=None, u_total_dev=None,
+              want_host_u=False, stream=None):
+        u_host = C.c_int32(-1)
+        self._ck(self._lib.gram_flush(self._h, _ptr(uniq_total), _ptr(counts_total), _ptr(G_total),
+                                      _ptr(u_total_dev), C.byref(u_host) if want_host_u else None,
+                                      _stream(stream)))
+        return u_host.value if want_host_u else None
+
+    def check(self, stream=None):
+        self._ck(self._lib.gram_check(self._h, _stream(stream)))
