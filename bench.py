@@ -1,0 +1,295 @@
+#!/usr/bin/env python3
+"""Benchmark of the GRAM hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic mini-batch:
+gram_unique -> gram_encode_gather -> gram_grad_accumulate, and at the end of
+every window of K steps gram_encoder_wgrad + gram_flush (so their cost is
+amortised over K, as in Multi-step GRAM).  Inputs are resident in HBM before
+the timed region; nothing in the timed region synchronises with the host.
+
+Prints ONE JSON line: throughput in valid item occurrences per second, the
+roofline position of the dominant kernel (its duration measured with HIP
+events by the library itself, on the stream it runs on), and the CPU oracle
+timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Runner:
+    """Device buffers of one workload plus the step loop."""
+
+    def __init__(self, w, export_G=True):
+        import torch
+        from paper_2204_04179_amd import gram, workloads as wl
+        self.torch, self.w, self.K = torch, w, w.K
+        self.M, self.d, self.d_in = w.M, w.d, w.d_in
+        t0 = time.time()
+        X, W = wl.features(w), wl.weights(w)
+        self.ids_np = [wl.ids(w, k).reshape(-1) for k in range(w.K)]
+        dH_np = [wl.upstream_grad(w, k) for k in range(w.K)]
+        log(f"[bench] {w.name}: inputs drawn in {time.time() - t0:.1f}s")
+
+        def dev(a):
+            if a.dtype == np.uint16:
+                return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+            return torch.from_numpy(a).cuda()
+
+        self.X_np, self.W_np, self.dH_np = X, W, dH_np
+        self.X, self.Wt = dev(X), dev(W)
+        self.ids = [dev(a) for a in self.ids_np]
+        self.dH = [dev(a) for a in dH_np]
+        xw = gram.F32 if w.xw_dtype == wl.F32 else gram.BF16
+        cfg = gram.make_config(w.N, w.d_in, w.d, w.M, w.K, 0, 0, xw)
+        self.ws_bytes = gram.workspace_bytes(cfg)
+        self.g = gram.Gram(cfg)
+        cap_u = min(w.M, w.N)
+        cap_t = min(w.K * w.M, w.N)
+        i32 = dict(dtype=torch.int32, device="cuda")
+        self.uniq, self.counts = torch.empty(cap_u, **i32), torch.empty(cap_u, **i32)
+        self.inverse, self.u_dev = torch.empty(w.M, **i32), torch.zeros(1, **i32)
+        self.H = torch.empty(w.M, w.d, device="cuda")
+        self.dW = torch.empty(w.d_in, w.d, device="cuda")
+        self.uniq_t, self.counts_t = torch.empty(cap_t, **i32), torch.empty(cap_t, **i32)
+        self.G_t = torch.empty(cap_t, w.d, device="cuda") if export_G else None
+        self.u_t = torch.zeros(1, **i32)
+        self.pos = 0     # step index inside the current window
+        # host-side statistics for the algorithmic byte counts
+        seen = np.zeros(w.N, bool)
+        self.stats = []
+        for a in self.ids_np:
+            u = np.unique(a)
+            self.stats.append(dict(U=int(u.size), U_old=int(seen[u].sum()), M_valid=int((a != 0).sum())))
+            seen[u] = True
+        self.U_total = int(seen.sum())
+        self.M_valid_per_step = float(np.mean([s["M_valid"] for s in self.stats]))
+
+    def step(self):
+        g, k = self.g, self.pos
+        g.unique(self.ids[k], self.uniq, self.inverse, self.counts, self.u_dev)
+        g.encode_gather(self.X, self.Wt, self.uniq, self.inverse, self.u_dev, self.M, None, self.H)
+        g.grad_accumulate(self.dH[k], self.M, k)
+        self.pos += 1
+        if self.pos == self.K:
+            g.encoder_wgrad(self.X, self.dW)
+            g.flush(self.uniq_t, self.counts_t, self.G_t, self.u_t)
+            self.pos = 0
+
+    def finish_window(self):
+        while self.pos != 0:
+            self.step()
+
+    # algorithmic bytes / flops per launch, averaged over the steps of a window
+    def algorithmic(self):
+        M, d, d_in = self.M, self.d, self.d_in
+        sx = 4 if self.w.xw_dtype == "f32" else 2
+        n = len(self.stats)
+        avg = lambda f: sum(f(s) for s in self.stats) / n
+        return {
+            "seg_reduce": dict(bound="hbm", bytes=avg(lambda s: 4 * s["M_valid"] * d + 4 * M + 4 * s["U"] * d + 4 * s["U_old"] * d)),
+            "gather_rows": dict(bound="hbm", bytes=avg(lambda s: 4 * M + 4 * s["U"] * d + 4 * M * d)),
+            "encode_bf16": dict(bound="mfma", flops=avg(lambda s: 2 * s["U"] * d_in * d),
+                                bytes=avg(lambda s: s["U"] * d_in * sx + d_in * d * sx + 4 * s["U"] * d)),
+            "encode_f32": dict(bound="alu", flops=avg(lambda s: 2 * s["U"] * d_in * d),
+                               bytes=avg(lambda s: s["U"] * d_in * sx + d_in * d * sx + 4 * s["U"] * d)),
+            "wgrad_bf16": dict(bound="mfma", flops=2 * self.U_total * d_in * d,
+                               bytes=self.U_total * d_in * sx + 4 * self.U_total * d + 4 * d_in * d),
+            "wgrad_f32": dict(bound="alu", flops=2 * self.U_total * d_in * d,
+                              bytes=self.U_total * d_in * sx + 4 * self.U_total * d + 4 * d_in * d),
+            "flush_rows": dict(bound="hbm", bytes=8 * self.U_total * d),
+        }
+
+
+def time_steps(r, steps, warmup, profile_kernel=None):
+    torch = r.torch
+    for _ in range(warmup):
+        r.step()
+    r.finish_window()
+    torch.cuda.synchronize()
+    r.g.profile_enable([profile_kernel] if profile_kernel else [], max_launches=max(64, 2 * steps))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        r.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = r.g.profile_read() if profile_kernel else {}
+    r.finish_window()
+    torch.cuda.synchronize()
+    r.g.profile_enable([])
+    return dt, prof
+
+
+def kernel_breakdown(r, windows=3):
+    """Per-kernel average duration over a few untimed, fully instrumented windows."""
+    r.finish_window()
+    r.g.profile_enable(None, max_launches=64 * r.K * windows)
+    for _ in range(r.K * windows):
+        r.step()
+    prof = r.g.profile_read()
+    r.g.profile_enable([])
+    return {k: dict(launches=n, avg_us=1e3 * ms / n, total_us_per_step=1e3 * ms / (r.K * windows))
+            for k, (n, ms) in prof.items()}
+
+
+def roofline_for(kernel, avg_us, alg):
+    a = alg[kernel]
+    if a["bound"] == "hbm":
+        ach = a["bytes"] / (avg_us * 1e-6) / 1e9
+        return dict(kernel=kernel, bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=ach / HBM_PEAK_GBS, algorithmic_bytes=a["bytes"], avg_us=avg_us)
+    ach = a["flops"] / (avg_us * 1e-6) / 1e12
+    peak = MFMA_BF16_PEAK_TFLOPS
+    return dict(kernel=kernel, bound="mfma", achieved=ach, peak=peak, unit="TFLOP/s", frac=ach / peak,
+                algorithmic_flops=a["flops"], avg_us=avg_us)
+
+
+def read_traffic(workload, kernel):
+    """HBM bytes per launch from committed rocprofv3 counter runs, if present."""
+    path = os.path.join(ROOT, "profiles", "pmc_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 3 and not line.startswith("#") and f[0] == workload and f[1] == kernel:
+            return float(f[2])
+    return None
+
+
+def cpu_baseline(r, target_s=12.0):
+    """The CPU oracle (oracle/) on the first rows of every step of one window."""
+    from oracle import gram_oracle as orc
+    w = r.w
+    L = w.L
+
+    def run(rows):
+        mm = orc.GramMulti(r.X_np, r.W_np, pad_id=0)
+        t0 = time.perf_counter()
+        occ = 0
+        for k in range(w.K):
+            ids = r.ids_np[k][: rows * L]
+            mm.step(ids, r.dH_np[k][: rows * L])
+            occ += int((ids != 0).sum())
+        mm.finish()
+        return time.perf_counter() - t0, occ
+
+    rows = max(1, min(w.B, 8))
+    t, occ = run(rows)
+    if rows < w.B and t < target_s / 2:
+        rows = int(min(w.B, max(rows, rows * target_s / max(t, 1e-3) * 0.8)))
+        t, occ = run(rows)
+    return dict(value=occ / t, unit="occurrences/s", cores=orc.num_threads(), kind="oracle",
+                sample=f"first {rows} of {w.B} histories of each of the K={w.K} steps of one window "
+                       f"(encode, gather, accumulate, wgrad), {occ} valid occurrences in {t:.2f}s",
+                seconds=t)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=80)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="stress")
+    ap.add_argument("--also", default="kt", help="second workload reported under 'also' ('' = none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-export-G", action="store_true", help="gram_flush without the G_total copy")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 1 GiB device copy (calibration kernel for counter runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2204_04179_amd import workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    w = wl.get(args.workload)
+    r = Runner(w, export_G=not args.no_export_G)
+    if args.copy_probe:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+    for _ in range(w.K):
+        r.step()
+    torch.cuda.synchronize()
+    kernels = kernel_breakdown(r)
+    dominant = max(kernels, key=lambda k: kernels[k]["total_us_per_step"])
+    alg = r.algorithmic()
+    dt, prof = time_steps(r, args.steps, args.warmup, profile_kernel=dominant)
+    n, ms = prof[dominant]
+    roof = roofline_for(dominant, 1e3 * ms / n, alg)
+    roof["traffic"] = read_traffic(w.name, dominant)
+    roof["timed_launches"] = n
+    ms_per_step = 1e3 * dt / args.steps
+    value = r.M_valid_per_step * args.steps / dt
+
+    for k, v in kernels.items():
+        if k in alg:
+            v.update({kk: vv for kk, vv in roofline_for(k, v["avg_us"], alg).items()
+                      if kk in ("bound", "achieved", "peak", "unit", "frac")})
+    mem_us = sum(kernels[k]["total_us_per_step"] for k in ("gather_rows", "seg_reduce") if k in kernels)
+    mem_bytes = sum(alg[k]["bytes"] for k in ("gather_rows", "seg_reduce"))
+
+    out = {
+        "metric": "item_occurrences_per_sec", "value": value, "unit": "occurrences/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if w.xw_dtype == "f32" else "bf16_in_f32_acc", "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B} L={w.L} N={w.N} Zipf(s={w.s}) d_in={w.d_in} d={w.d} "
+                               f"K={w.K} {w.xw_dtype}",
+                   "positions_per_step": w.M, "valid_per_step": r.M_valid_per_step,
+                   "unique_per_step": float(np.mean([s["U"] for s in r.stats])),
+                   "unique_per_window": r.U_total,
+                   "boost_ratio": r.M_valid_per_step / float(np.mean([s["U"] - (1 if w.padding else 0) for s in r.stats])),
+                   "flush_exports_G": not args.no_export_G, "workspace_bytes": r.ws_bytes},
+        "roofline": roof,
+        "hbm_kernels": {"gather_plus_accumulate_GBs": mem_bytes / (mem_us * 1e-6) / 1e9 if mem_us else None,
+                        "frac_of_8TBs": mem_bytes / (mem_us * 1e-6) / 1e9 / HBM_PEAK_GBS if mem_us else None},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(r)
+        out["gpu_over_cpu"] = value / out["cpu_baseline"]["value"]
+    out["paper_context"] = "paper: Single-step ~4x, Multi-step up to 146x faster than E2E, whole training runs on A100"
+    del r
+    torch.cuda.empty_cache()
+
+    if args.also:
+        w2 = wl.get(args.also)
+        r2 = Runner(w2, export_G=not args.no_export_G)
+        for _ in range(w2.K):
+            r2.step()
+        torch.cuda.synchronize()
+        steps2 = 400
+        dt2, _ = time_steps(r2, steps2, 20)
+        out["also"] = {"workload": w2.name, "value": r2.M_valid_per_step * steps2 / dt2,
+                       "unit": "occurrences/s", "us_per_step": 1e6 * dt2 / steps2, "steps": steps2,
+                       "note": "launch-latency bound: a few microseconds of HBM traffic per step"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

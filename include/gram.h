@@ -149,6 +149,24 @@ int gram_flush(gram_ctx* ctx, int32_t* uniq_total, int32_t* counts_total, float*
 /* Synchronise `stream` and return (and clear) any latched device error. */
 int gram_check(gram_ctx* ctx, void* stream);
 
+/* ---- Measurement aid (not a step of the paper's method) -------------------
+ * The library can bracket its own kernel launches with HIP events on the
+ * caller's stream, so a benchmark can report per-kernel durations without an
+ * external profiler.  Kernel indices run over [0, gram_kernel_count()).
+ *   gram_profile_enable  mask bit k set = time kernel k; 0 switches timing off.
+ *                        The first call creates a fixed pool of events
+ *                        (`max_launches` pairs, not in the hot path); launches
+ *                        beyond the pool are not timed.  Discards earlier
+ *                        readings.
+ *   gram_profile_read    synchronises the device, then returns, for kernel k,
+ *                        the number of timed launches and their summed duration
+ *                        in milliseconds (HOST out-pointers).  Does not reset.
+ */
+int gram_kernel_count(void);
+const char* gram_kernel_name(int k);
+int gram_profile_enable(gram_ctx* ctx, uint32_t mask, int32_t max_launches);
+int gram_profile_read(gram_ctx* ctx, int k, int64_t* launches, double* total_ms);
+
 /* Message of the last failing call on ctx (or of the last failing gram_create
  * when ctx is NULL).  The string is owned by the library. */
 const char* gram_last_error(const gram_ctx* ctx);

@@ -202,6 +202,10 @@ int gram_destroy(gram_ctx* ctx)
     if (!ctx) return GRAM_OK;
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     (void)hipDeviceSynchronize();
+    for (ProfSlot& p : c->prof_pool) {
+        (void)hipEventDestroy(p.start);
+        (void)hipEventDestroy(p.stop);
+    }
     if (c->h_pinned) (void)hipHostFree(c->h_pinned);
     if (c->ws_base) (void)hipFree(c->ws_base);
     delete c;
@@ -308,6 +312,56 @@ int gram_flush(gram_ctx* ctx, int32_t* uniq_total, int32_t* counts_total, float*
         if (int rc = sync_scalars(c, s, "gram_flush")) return rc;
         *u_total_host = c->h_pinned[kSFlushN];
     }
+    return GRAM_OK;
+}
+
+static const char* const kKernelNames[KID_COUNT] = {
+    "radix_hist", "radix_scan", "radix_scatter", "heads_count", "heads_emit", "counts", "unique_empty",
+    "transpose_w", "encode_bf16", "encode_f32", "gather_rows", "slot_count", "slot_emit", "seg_reduce",
+    "seg_combine", "wgrad_bf16", "wgrad_f32", "wgrad_reduce", "flush_meta", "flush_rows", "flush_finish"};
+
+int gram_kernel_count(void) { return KID_COUNT; }
+
+const char* gram_kernel_name(int k) { return (k >= 0 && k < KID_COUNT) ? kKernelNames[k] : ""; }
+
+int gram_profile_enable(gram_ctx* ctx, uint32_t mask, int32_t max_launches)
+{
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (!c) return GRAM_ERR_ARG;
+    if (max_launches < 0 || max_launches > (1 << 20))
+        return fail(c, GRAM_ERR_ARG, "gram_profile_enable: max_launches out of range");
+    (void)hipDeviceSynchronize();
+    while (c->prof_pool.size() < (size_t)max_launches) {
+        ProfSlot p{};
+        hipError_t e = hipEventCreate(&p.start);
+        if (e == hipSuccess) e = hipEventCreate(&p.stop);
+        if (e != hipSuccess) return hip_fail(c, e, "gram_profile_enable");
+        c->prof_pool.push_back(p);
+    }
+    c->prof_used = 0;
+    c->prof_mask = mask;
+    return GRAM_OK;
+}
+
+int gram_profile_read(gram_ctx* ctx, int k, int64_t* launches, double* total_ms)
+{
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (!c || !launches || !total_ms || k < 0 || k >= KID_COUNT) return GRAM_ERR_ARG;
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) return hip_fail(c, e, "gram_profile_read");
+    int64_t n = 0;
+    double ms = 0.0;
+    for (size_t i = 0; i < c->prof_used; ++i) {
+        const ProfSlot& p = c->prof_pool[i];
+        if (p.kid != k) continue;
+        float t = 0.f;
+        e = hipEventElapsedTime(&t, p.start, p.stop);
+        if (e != hipSuccess) return hip_fail(c, e, "gram_profile_read");
+        ms += t;
+        ++n;
+    }
+    *launches = n;
+    *total_ms = ms;
     return GRAM_OK;
 }
 

@@ -168,14 +168,14 @@ void encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
     if (rows_max <= 0) return;
     const int d_in = c->cfg.d_in, d = c->cfg.d;
     if (c->cfg.xw_dtype == GRAM_BF16) {
-        hipLaunchKernelGGL(k_transpose_u16, dim3((d + 31) / 32, (d_in + 31) / 32), dim3(kBlock), 0, s,
+        launch(c, KID_TRANSPOSE_U16, k_transpose_u16, dim3((d + 31) / 32, (d_in + 31) / 32), dim3(kBlock), s,
                            static_cast<const uint16_t*>(W), d_in, d, static_cast<uint16_t*>(c->Wt));
-        hipLaunchKernelGGL(k_encode_bf16, dim3((d + BN - 1) / BN, (unsigned)((rows_max + BM - 1) / BM)),
-                           dim3(kBlock), 0, s, static_cast<const uint16_t*>(X),
+        launch(c, KID_ENCODE_BF16, k_encode_bf16, dim3((d + BN - 1) / BN, (unsigned)((rows_max + BM - 1) / BM)),
+                           dim3(kBlock), s, static_cast<const uint16_t*>(X),
                            static_cast<const uint16_t*>(c->Wt), uniq, u_dev, d_in, d, c->cfg.pad_id, E);
     } else {
-        hipLaunchKernelGGL(k_encode_f32, dim3((d + 63) / 64, (unsigned)((rows_max + 3) / 4)),
-                           dim3(kBlock), 0, s, static_cast<const float*>(X),
+        launch(c, KID_ENCODE_F32, k_encode_f32, dim3((d + 63) / 64, (unsigned)((rows_max + 3) / 4)),
+                           dim3(kBlock), s, static_cast<const float*>(X),
                            static_cast<const float*>(W), uniq, u_dev, d_in, d, c->cfg.pad_id, E);
     }
 }
@@ -308,15 +308,15 @@ void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s)
 {
     const int d_in = c->cfg.d_in, d = c->cfg.d, S = c->wg_splits;
     if (c->cfg.xw_dtype == GRAM_BF16)
-        hipLaunchKernelGGL(k_wgrad_bf16, dim3((d + BN - 1) / BN, (d_in + BM - 1) / BM, S), dim3(kBlock),
-                           0, s, static_cast<const uint16_t*>(X), c->id_of_slot, c->G, c->scal, d_in, d,
+        launch(c, KID_WGRAD_BF16, k_wgrad_bf16, dim3((d + BN - 1) / BN, (d_in + BM - 1) / BM, S), dim3(kBlock),
+                           s, static_cast<const uint16_t*>(X), c->id_of_slot, c->G, c->scal, d_in, d,
                            c->cfg.pad_id, S, c->wg_partial);
     else
-        hipLaunchKernelGGL(k_wgrad_f32, dim3((d + 63) / 64, (d_in + 3) / 4, S), dim3(kBlock), 0, s,
+        launch(c, KID_WGRAD_F32, k_wgrad_f32, dim3((d + 63) / 64, (d_in + 3) / 4, S), dim3(kBlock), s,
                            static_cast<const float*>(X), c->id_of_slot, c->G, c->scal, d_in, d,
                            c->cfg.pad_id, S, c->wg_partial);
     const int64_t n4 = (int64_t)d_in * d / 4;
-    hipLaunchKernelGGL(k_wgrad_reduce, dim3((unsigned)((n4 + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+    launch(c, KID_WGRAD_REDUCE, k_wgrad_reduce, dim3((unsigned)((n4 + kBlock - 1) / kBlock)), dim3(kBlock), s,
                        reinterpret_cast<const float4*>(c->wg_partial), n4, S,
                        reinterpret_cast<float4*>(dW));
 }

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string>
+#include <utility>
+#include <vector>
 
 #include "gram.h"
 
@@ -27,6 +29,19 @@ enum Scalar { kSU = 0, kSUTotal, kSErr, kSUBase, kSLongCount, kSFlushN, kSCount 
 // Device-latched error bits (scal[kSErr]).
 constexpr int kErrBitRange = 1;
 constexpr int kErrBitCapacity = 2;
+
+// Kernel identifiers for the built-in event timer (gram_profile_*).
+enum KernelId {
+    KID_RADIX_HIST = 0, KID_RADIX_SCAN, KID_RADIX_SCATTER, KID_HEADS_COUNT, KID_HEADS_EMIT, KID_COUNTS,
+    KID_UNIQUE_EMPTY, KID_TRANSPOSE_U16, KID_ENCODE_BF16, KID_ENCODE_F32, KID_GATHER_ROWS,
+    KID_SLOT_COUNT, KID_SLOT_EMIT, KID_SEG_REDUCE, KID_SEG_COMBINE, KID_WGRAD_BF16, KID_WGRAD_F32,
+    KID_WGRAD_REDUCE, KID_FLUSH_META, KID_FLUSH_ROWS, KID_FLUSH_FINISH, KID_COUNT
+};
+
+struct ProfSlot {
+    hipEvent_t start, stop;
+    int kid;
+};
 
 struct SortPlan {
     int passes;
@@ -70,6 +85,11 @@ struct Ctx {
     int* sorted_keys = nullptr;
     int* perm = nullptr;
 
+    // --- optional per-kernel event timing ---
+    uint32_t prof_mask = 0;            // bit k set: time launches of kernel k
+    std::vector<ProfSlot> prof_pool;   // events created once by gram_profile_enable
+    size_t prof_used = 0;
+
     // --- host state ---
     bool have_unique = false;
     bool unique_consumed = false;  // the current batch was already accumulated
@@ -78,6 +98,24 @@ struct Ctx {
     int* h_pinned = nullptr;    // [4] pinned host scratch for small read-backs
     std::string last_error;
 };
+
+// Launch a kernel; with profiling enabled for `kid`, bracket it with two events
+// on the same stream.
+template <typename... KArgs, typename... Args>
+inline void launch(Ctx* c, int kid, void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t s,
+                   Args&&... args)
+{
+    ProfSlot* p = nullptr;
+    if ((c->prof_mask >> kid) & 1u) {
+        if (c->prof_used < c->prof_pool.size()) {
+            p = &c->prof_pool[c->prof_used++];
+            p->kid = kid;
+            (void)hipEventRecord(p->start, s);
+        }
+    }
+    hipLaunchKernelGGL(kernel, grid, block, 0, s, std::forward<Args>(args)...);
+    if (p) (void)hipEventRecord(p->stop, s);
+}
 
 // ---- gram_sort.hip -------------------------------------------------------
 SortPlan make_sort_plan(int key_bits, int64_t n_max);

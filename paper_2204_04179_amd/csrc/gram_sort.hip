@@ -224,20 +224,20 @@ int radix_sort_pairs(Ctx* c, const int* keys_in, const int* vals_in, int n_host,
         const int bins = 1 << db;
         const bool chk = check_range && pass == 0;
         if (chk)
-            hipLaunchKernelGGL(k_radix_hist<true>, dim3(p.blocks), dim3(kBlock), 0, s, kin, n_host,
+            launch(c, KID_RADIX_HIST, k_radix_hist<true>, dim3(p.blocks), dim3(kBlock), s, kin, n_host,
                                n_dev, shift, db, p.items, p.nw, c->table, c->cfg.vocab_n, fix_key,
                                c->scal + kSErr);
         else
-            hipLaunchKernelGGL(k_radix_hist<false>, dim3(p.blocks), dim3(kBlock), 0, s, kin, n_host,
+            launch(c, KID_RADIX_HIST, k_radix_hist<false>, dim3(p.blocks), dim3(kBlock), s, kin, n_host,
                                n_dev, shift, db, p.items, p.nw, c->table, 0, 0, c->scal + kSErr);
-        hipLaunchKernelGGL(k_radix_scan, dim3((bins + kWavesPerBlock - 1) / kWavesPerBlock),
-                           dim3(kBlock), 0, s, c->table, p.nw, bins, c->gtot);
+        launch(c, KID_RADIX_SCAN, k_radix_scan, dim3((bins + kWavesPerBlock - 1) / kWavesPerBlock),
+                           dim3(kBlock), s, c->table, p.nw, bins, c->gtot);
         if (chk)
-            hipLaunchKernelGGL(k_radix_scatter<true>, dim3(p.blocks), dim3(kBlock), 0, s, kin, vin,
+            launch(c, KID_RADIX_SCATTER, k_radix_scatter<true>, dim3(p.blocks), dim3(kBlock), s, kin, vin,
                                n_host, n_dev, shift, db, p.items, p.nw, c->table, c->gtot,
                                c->keys[dst], c->vals[dst], c->cfg.vocab_n, fix_key);
         else
-            hipLaunchKernelGGL(k_radix_scatter<false>, dim3(p.blocks), dim3(kBlock), 0, s, kin, vin,
+            launch(c, KID_RADIX_SCATTER, k_radix_scatter<false>, dim3(p.blocks), dim3(kBlock), s, kin, vin,
                                n_host, n_dev, shift, db, p.items, p.nw, c->table, c->gtot,
                                c->keys[dst], c->vals[dst], 0, 0);
         kin = c->keys[dst];
@@ -334,16 +334,16 @@ void unique_from_sorted(Ctx* c, int n, int* uniq, int* inverse, int* counts, int
                         hipStream_t s)
 {
     if (n == 0) {
-        hipLaunchKernelGGL(k_unique_empty, dim3(1), dim3(kWave), 0, s, c->scal + kSU, u_out, c->offsets);
+        launch(c, KID_UNIQUE_EMPTY, k_unique_empty, dim3(1), dim3(kWave), s, c->scal + kSU, u_out, c->offsets);
         return;
     }
     const int tiles = (n + kScanTile - 1) / kScanTile;
-    hipLaunchKernelGGL(k_heads_count, dim3(tiles), dim3(kBlock), 0, s, c->sorted_keys, n, c->tile_sums);
-    hipLaunchKernelGGL(k_heads_emit, dim3(tiles), dim3(kBlock), 0, s, c->sorted_keys, c->perm, n,
+    launch(c, KID_HEADS_COUNT, k_heads_count, dim3(tiles), dim3(kBlock), s, c->sorted_keys, n, c->tile_sums);
+    launch(c, KID_HEADS_EMIT, k_heads_emit, dim3(tiles), dim3(kBlock), s, c->sorted_keys, c->perm, n,
                        c->tile_sums, uniq, inverse, c->offsets, c->seg_of_row, c->uniq_ws, c->scal + kSU,
                        u_out);
     const int64_t cap = n < c->cap_u ? n : c->cap_u;
-    hipLaunchKernelGGL(k_counts, dim3((unsigned)((cap + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+    launch(c, KID_COUNTS, k_counts, dim3((unsigned)((cap + kBlock - 1) / kBlock)), dim3(kBlock), s,
                        c->offsets, c->scal + kSU, counts);
 }
 

@@ -104,7 +104,7 @@ void gather_rows(Ctx* c, const float* E, const int* inverse, int64_t m, float* H
     int rows_per_block = (8 * kBlock + cols4 - 1) / cols4;   // ~8 float4 per thread
     if (rows_per_block < 1) rows_per_block = 1;
     const int64_t blocks = (m + rows_per_block - 1) / rows_per_block;
-    hipLaunchKernelGGL(k_gather_rows, dim3((unsigned)blocks), dim3(kBlock), 0, s,
+    launch(c, KID_GATHER_ROWS, k_gather_rows, dim3((unsigned)blocks), dim3(kBlock), s,
                        reinterpret_cast<const f32x4*>(E), inverse, m, cols4,
                        reinterpret_cast<f32x4*>(H), rows_per_block);
 }
@@ -200,9 +200,9 @@ void assign_slots(Ctx* c, hipStream_t s)
     int64_t bound = c->cur_m < c->cap_u ? c->cur_m : c->cap_u;
     if (bound < 1) bound = 1;
     const int tiles = (int)((bound + kScanTile - 1) / kScanTile);
-    hipLaunchKernelGGL(k_slot_count, dim3(tiles), dim3(kBlock), 0, s, c->uniq_ws, c->slot_of, c->scal,
+    launch(c, KID_SLOT_COUNT, k_slot_count, dim3(tiles), dim3(kBlock), s, c->uniq_ws, c->slot_of, c->scal,
                        c->tile_sums);
-    hipLaunchKernelGGL(k_slot_emit, dim3(tiles), dim3(kBlock), 0, s, c->uniq_ws, c->offsets,
+    launch(c, KID_SLOT_EMIT, k_slot_emit, dim3(tiles), dim3(kBlock), s, c->uniq_ws, c->offsets,
                        c->slot_of, c->id_of_slot, c->cnt_of_slot, c->seg_slot, c->scal, c->tile_sums,
                        (int)c->cap_total);
 }
@@ -372,15 +372,15 @@ void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s)
     if (threads > kBlock) threads = kBlock;
     const int slabs = (cols4 + threads - 1) / threads;
     const int tiles = (n + kSegRows - 1) / kSegRows;
-    hipLaunchKernelGGL(k_seg_reduce, dim3(tiles, slabs), dim3(threads), 0, s,
+    launch(c, KID_SEG_REDUCE, k_seg_reduce, dim3(tiles, slabs), dim3(threads), s,
                        reinterpret_cast<const float4*>(dH), c->perm, c->seg_of_row, c->offsets,
                        c->uniq_ws, c->seg_slot, n, cols4, c->cfg.pad_id,
                        reinterpret_cast<float4*>(c->G), reinterpret_cast<float4*>(c->seg_first),
                        reinterpret_cast<float4*>(c->seg_last), c->scal, c->long_list);
     int fix_blocks = tiles / (kSegLong / kSegRows) + 1;   // upper bound of long segments
     if (fix_blocks > 256) fix_blocks = 256;
-    hipLaunchKernelGGL(k_seg_combine, dim3(fix_blocks, (cols4 + kFixCols4 - 1) / kFixCols4),
-                       dim3(kBlock), 0, s, c->seg_of_row, c->offsets, c->uniq_ws, c->seg_slot, n,
+    launch(c, KID_SEG_COMBINE, k_seg_combine, dim3(fix_blocks, (cols4 + kFixCols4 - 1) / kFixCols4),
+                       dim3(kBlock), s, c->seg_of_row, c->offsets, c->uniq_ws, c->seg_slot, n,
                        cols4, c->cfg.pad_id, reinterpret_cast<float4*>(c->G),
                        reinterpret_cast<const float4*>(c->seg_first),
                        reinterpret_cast<const float4*>(c->seg_last), c->scal, c->long_list);
@@ -436,13 +436,13 @@ void flush_export(Ctx* c, int* uniq_total, int* counts_total, float* G_total, in
     const int* sorted_slots = c->vals[r];
     int64_t blocks = (c->cap_total + kBlock - 1) / kBlock;
     if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL(k_flush_meta, dim3((unsigned)blocks), dim3(kBlock), 0, s, sorted_ids,
+    launch(c, KID_FLUSH_META, k_flush_meta, dim3((unsigned)blocks), dim3(kBlock), s, sorted_ids,
                        sorted_slots, c->cnt_of_slot, c->slot_of, uniq_total, counts_total, c->scal);
     if (G_total)
-        hipLaunchKernelGGL(k_flush_rows, dim3(2048), dim3(kBlock), 0, s, sorted_slots,
+        launch(c, KID_FLUSH_ROWS, k_flush_rows, dim3(2048), dim3(kBlock), s, sorted_slots,
                            reinterpret_cast<const float4*>(c->G), c->cfg.d / 4,
                            reinterpret_cast<float4*>(G_total), c->scal);
-    hipLaunchKernelGGL(k_flush_finish, dim3(1), dim3(kWave), 0, s, c->scal, u_total_dev);
+    launch(c, KID_FLUSH_FINISH, k_flush_finish, dim3(1), dim3(kWave), s, c->scal, u_total_dev);
 }
 
 }  // namespace gram

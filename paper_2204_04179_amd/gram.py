@@ -20,7 +20,8 @@ STATUS_NAMES = {OK: "GRAM_OK", ERR_ARG: "GRAM_ERR_ARG", ERR_CAPACITY: "GRAM_ERR_
                 ERR_UNIMPLEMENTED: "GRAM_ERR_UNIMPLEMENTED"}
 
 EXPORTS = ("gram_workspace_bytes", "gram_create", "gram_destroy", "gram_unique", "gram_encode_gather",
-           "gram_grad_accumulate", "gram_encoder_wgrad", "gram_flush", "gram_check", "gram_last_error")
+           "gram_grad_accumulate", "gram_encoder_wgrad", "gram_flush", "gram_check", "gram_last_error",
+           "gram_kernel_count", "gram_kernel_name", "gram_profile_enable", "gram_profile_read")
 
 
 class GramConfig(C.Structure):
@@ -67,6 +68,14 @@ def load():
     L.gram_check.argtypes = [vp, vp]
     L.gram_last_error.restype = C.c_char_p
     L.gram_last_error.argtypes = [vp]
+    L.gram_kernel_count.restype = C.c_int
+    L.gram_kernel_count.argtypes = []
+    L.gram_kernel_name.restype = C.c_char_p
+    L.gram_kernel_name.argtypes = [C.c_int]
+    L.gram_profile_enable.restype = C.c_int
+    L.gram_profile_enable.argtypes = [vp, C.c_uint32, C.c_int32]
+    L.gram_profile_read.restype = C.c_int
+    L.gram_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_double)]
     _lib = L
     return L
 
@@ -150,6 +159,28 @@ class Gram:
                                       _ptr(u_total_dev), C.byref(u_host) if want_host_u else None,
                                       _stream(stream)))
         return u_host.value if want_host_u else None
+
+    def kernel_names(self):
+        return [self._lib.gram_kernel_name(k).decode() for k in range(self._lib.gram_kernel_count())]
+
+    def profile_enable(self, kernels=None, max_launches=8192):
+        """Time the named kernels (all if None, none if empty) with HIP events."""
+        names = self.kernel_names()
+        mask = 0
+        for k, nm in enumerate(names):
+            if kernels is None or nm in kernels:
+                mask |= 1 << k
+        self._ck(self._lib.gram_profile_enable(self._h, mask, max_launches if mask else 0))
+
+    def profile_read(self):
+        """{kernel: (launches, total_ms)} of the timed launches so far."""
+        out = {}
+        for k, nm in enumerate(self.kernel_names()):
+            n, ms = C.c_int64(0), C.c_double(0.0)
+            self._ck(self._lib.gram_profile_read(self._h, k, C.byref(n), C.byref(ms)))
+            if n.value:
+                out[nm] = (n.value, ms.value)
+        return out
 
     def check(self, stream=None):
         self._ck(self._lib.gram_check(self._h, _stream(stream)))

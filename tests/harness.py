@@ -38,7 +38,7 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
         counts = torch.full((cap_u,), -7, dtype=torch.int32, device="cuda")
         inverse = torch.full((max(1, m),), -7, dtype=torch.int32, device="cuda")
         u_dev = torch.zeros(1, dtype=torch.int32, device="cuda")
-        E = torch.full((cap_u, d), float("nan"), device="cuda") if keep_E else None
+        E = torch.full((cap_u, d), float("nan"), device="cuda")
         H = torch.full((max(1, m), d), float("nan"), device="cuda")
         U = g.unique(ids_d, uniq, inverse, counts, u_dev, want_host_u=True)
         assert int(u_dev.item()) == U
