@@ -106,6 +106,10 @@ int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
     float* seg_last = (float*)take(dv.tiles_seg * d * 4);
     void* Wt = take(cfg.xw_dtype == GRAM_BF16 ? d * d_in * 2 : 1);
     float* wg_partial = (float*)take((int64_t)dv.splits * d_in * d * 4);
+    const bool bf = cfg.xw_dtype == GRAM_BF16;
+    const int64_t ldt = wgrad_pitch_for(dv.cap_total);
+    uint16_t* XT = (uint16_t*)take(bf ? d_in * ldt * 2 : 1);
+    uint16_t* GT = (uint16_t*)take(bf ? d * ldt * 2 : 1);
     if (c && base) {
         c->scal = scal; c->keys[0] = keys0; c->keys[1] = keys1; c->vals[0] = vals0; c->vals[1] = vals1;
         c->table = table; c->gtot = gtot; c->tile_sums = tile_sums; c->offsets = offsets;
@@ -113,6 +117,7 @@ int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
         c->long_list = long_list; c->slot_of = slot_of; c->id_of_slot = id_of_slot;
         c->cnt_of_slot = cnt_of_slot; c->G = G; c->E_ws = E_ws; c->seg_first = seg_first;
         c->seg_last = seg_last; c->Wt = Wt; c->wg_partial = wg_partial;
+        c->XT = XT; c->GT = GT; c->ldt = ldt;
     }
     return off;
 }
@@ -318,7 +323,8 @@ int gram_flush(gram_ctx* ctx, int32_t* uniq_total, int32_t* counts_total, float*
 static const char* const kKernelNames[KID_COUNT] = {
     "radix_hist", "radix_scan", "radix_scatter", "heads_count", "heads_emit", "counts", "unique_empty",
     "transpose_w", "encode_bf16", "encode_f32", "gather_rows", "slot_count", "slot_emit", "seg_reduce",
-    "seg_combine", "wgrad_bf16", "wgrad_f32", "wgrad_reduce", "flush_meta", "flush_rows", "flush_finish"};
+    "seg_combine", "wgrad_bf16", "wgrad_f32", "wgrad_reduce", "transpose_x", "transpose_g", "flush_meta",
+    "flush_rows", "flush_finish"};
 
 int gram_kernel_count(void) { return KID_COUNT; }
 

@@ -3,18 +3,22 @@
 //   forward  (Algorithm 1 step 1, Eq. 4):  E[j,:]  = X[uniq[j],:] . W
 //   wgrad    (Algorithm 1 step 4, Eq. 7/9): dW[i,c] = sum_s X[item_s, i] * G[s, c]
 // bf16 inputs run on the matrix cores (v_mfma_f32_32x32x16_bf16, fp32
-// accumulate); the float32 variant is plain FMA code for small problems.
-// Rows of X are gathered through the ID list inside the tile loads, so the
-// unique items' features are never copied.
+// accumulate) through ONE tuned kernel, k_gemm_nt_bf16: C = A . B^T with both
+// operands stored with the contraction index contiguous.
+//   forward: A = rows of X gathered through the unique-ID list inside the tile
+//            loads (the unique items' features are never copied), B = W^T.
+//   wgrad:   A = XT[i][s] (features of the buffer's items, transposed),
+//            B = GT[c][s] (the gradient buffer rounded to bf16, transposed);
+//            the contraction over buffer rows is split over blocks (split-K)
+//            and the float32 partials are added in split order.
+// The float32 variants are plain FMA code for small problems.
 #include "gram_internal.h"
 
 namespace gram {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-constexpr int BM = 128, BN = 128, BK = 32;
-constexpr int LDS_STRIDE = BK + 8;   // bf16 elements per LDS row (80 bytes: 16-byte aligned, staggers banks)
+typedef __attribute__((address_space(3))) void lds_void;
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
 {
@@ -23,6 +27,12 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
 }
+
+// ---- small forward kernel: 128x128 tile, register-staged LDS ------------------
+// Used when the batch is small (few row tiles) or d_in is not a multiple of 32.
+
+constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int LDS_STRIDE = BK + 8;   // bf16 elements per LDS row (80 bytes: 16-byte aligned, staggers banks)
 
 // One BK slab of a 128x128 block tile: each of the 4 waves owns a 64x64
 // quadrant as 2x2 MFMA tiles.  sA/sB hold [row][k] with k contiguous.
@@ -46,25 +56,7 @@ __device__ __forceinline__ void mma_slab(const uint16_t* sA, const uint16_t* sB,
     }
 }
 
-// Accumulator element r of lane `lane` in a 32x32 MFMA tile sits at
-// (row, col) = ((r / 4) * 8 + (lane / 32) * 4 + r % 4, lane % 32).
-template <typename F>
-__device__ __forceinline__ void for_each_acc(const f32x16 (&acc)[2][2], int wm, int wn, int lane, F f)
-{
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = wm * 64 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                const int col = wn * 64 + j * 32 + (lane & 31);
-                f(row, col, acc[i][j][r]);
-            }
-}
-
-// ---- W[d_in,d] -> Wt[d,d_in] (bf16) ----------------------------------------
-
+// W[d_in,d] -> Wt[d,d_in] (bf16)
 __global__ __launch_bounds__(kBlock) void k_transpose_u16(const uint16_t* __restrict__ W, int rows,
                                                           int cols, uint16_t* __restrict__ Wt)
 {
@@ -77,8 +69,6 @@ __global__ __launch_bounds__(kBlock) void k_transpose_u16(const uint16_t* __rest
     for (int y = ty; y < 32; y += 8)
         if (c0 + y < cols && r0 + tx < rows) Wt[(int64_t)(c0 + y) * rows + r0 + tx] = tile[tx][y];
 }
-
-// ---- forward, bf16 -----------------------------------------------------------
 
 __global__ __launch_bounds__(kBlock) void k_encode_bf16(
     const uint16_t* __restrict__ X, const uint16_t* __restrict__ Wt, const int* __restrict__ uniq,
@@ -137,10 +127,330 @@ __global__ __launch_bounds__(kBlock) void k_encode_bf16(
         __syncthreads();
     }
 
-    for_each_acc(acc, wm, wn, lane, [&](int row, int col, float v) {
-        const int j = m0 + row, c = n0 + col;
-        if (j < U && c < d) E[(int64_t)j * d + c] = uniq[j] == pad_id ? 0.f : v;
-    });
+    // accumulator element r of a lane sits at (row, col) = ((r / 4) * 8 + (lane / 32) * 4 + r % 4, lane % 32)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int j = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                const int cc = n0 + wn * 64 + jt * 32 + (lane & 31);
+                if (j < U && cc < d) E[(int64_t)j * d + cc] = uniq[j] == pad_id ? 0.f : acc[i][jt][r];
+            }
+}
+
+// ---- the tuned kernel: C[M,N] = A[M,K] . B[N,K]^T, bf16 in, fp32 out ---------------
+//
+// 256x256 block tile, 4 waves each owning a 128x128 quadrant (4x4 MFMA tiles,
+// 256 accumulator registers per lane).  K advances in slabs of 32 through a
+// ring of 4 LDS stages filled by direct global->LDS loads
+// (global_load_lds_dwordx4: lane l of a wave writes LDS bytes [16 l, 16 l + 16)
+// of a 1 KiB window, so a wave moves 16 rows x 64 bytes per instruction), ahead
+// of the multiply: gathered rows come from HBM with a latency longer than one
+// slab of MFMA work.
+// LDS rows are 64 bytes (4 chunks of 16); chunk c of row r sits at position
+// c ^ ((r >> 2) & 3), which spreads the 16-byte fragment reads of 16
+// consecutive rows over all banks.  The swizzle is applied by choosing which
+// global chunk each lane fetches.
+// Per slab: the fragment reads of k-step 1 overlap the MFMAs of k-step 0; then
+// one barrier publishes slab s+1 (and retires slab s-1, whose stage is refilled
+// with slab s+3), and the reads of slab s+1's first fragments overlap the MFMAs
+// of k-step 1.
+// Block indices are decoded so that the column tiles of one row tile run on the
+// same XCD (consecutive block indices are dealt round-robin to the 8 XCDs) and
+// share the strip of A through that XCD's L2.
+// GATHER: row j of A is A[row_ids[j]]; a row whose ID equals pad_id yields zeros.
+// Split-K: the K slabs are cut into `splits` contiguous ranges (1, or a multiple
+// of 8) and split z writes C + z * split_stride (an empty range writes zeros);
+// with M given on the host.
+constexpr int TM = 256, TN = 256, TK = 32, TSTAGES = 4;
+constexpr int TROWB = TK * 2;                          // bytes per LDS row
+constexpr int TSTAGEB = (TM + TN) * TROWB;             // bytes per stage
+constexpr size_t TSMEM = (size_t)TSTAGES * TSTAGEB;
+
+// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane.
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(gptr), "s"(lds_base) : "memory");
+}
+// s_waitcnt vmcnt(n) only; the other counters are left unconstrained
+#define GRAM_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+
+template <bool GATHER>
+__global__ __launch_bounds__(kBlock) void k_gemm_nt_bf16(
+    const uint16_t* __restrict__ A, int64_t lda, const int* __restrict__ row_ids,
+    const int* __restrict__ m_dev, int m_host, const uint16_t* __restrict__ B, int64_t ldb, int n,
+    const int* __restrict__ k_dev, int k_host, int splits, int pad_id, int n_tiles,
+    float* __restrict__ C, int64_t ldc, int64_t split_stride)
+{
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    __shared__ int s_pad_row;
+    const int M = m_dev ? *m_dev : m_host;
+    const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+    int m0, n0, z;
+    if (splits == 1) {
+        // row tiles are dealt to XCDs; the column tiles of a row tile stay together
+        m0 = ((q / n_tiles) * 8 + xcd) * TM;
+        n0 = (q % n_tiles) * TN;
+        z = 0;
+    } else {
+        // all tiles of one K range stay on one XCD (splits is a multiple of 8)
+        const int tiles = ((M + TM - 1) / TM) * n_tiles;
+        z = xcd + 8 * (q / tiles);
+        m0 = ((q % tiles) / n_tiles) * TM;
+        n0 = ((q % tiles) % n_tiles) * TN;
+    }
+    if (m0 >= M || z >= splits) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    if (tid == 0) s_pad_row = -1;
+    __syncthreads();
+
+    // K range of this split, in slabs
+    const int ktot = k_dev ? *k_dev : k_host;
+    const int slabs_all = (ktot + TK - 1) / TK;
+    const int per = (slabs_all + splits - 1) / splits;
+    const int sl_begin = z * per;
+    int nslab = slabs_all - sl_begin;
+    if (nslab > per) nslab = per;
+    C += (int64_t)z * split_stride;
+
+    // loader: wave w fills row groups g = 4 w + t (16 rows each) of A and of B; lane l moves the
+    // chunk that belongs at position l & 3 of row 16 g + (l >> 2).  Rows past M / past n are
+    // clamped to a valid row: their products are never stored.
+    const int lrow = lane >> 2;
+    const int lchunk = (lane & 3) ^ ((lane >> 4) & 3);
+    const uint16_t* pa[4];
+    const uint16_t* pb[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int r = (wave * 4 + t) * 16 + lrow;
+        const int j = m0 + r < M ? m0 + r : M - 1;
+        if (GATHER) {
+            const int id = row_ids[j];
+            if (m0 + r < M && id == pad_id) s_pad_row = r;   // at most one row is the padding item
+            pa[t] = A + (int64_t)id * lda;
+        } else {
+            pa[t] = A + (int64_t)j * lda;
+        }
+        pa[t] += (int64_t)sl_begin * TK + lchunk * 8;
+        const int nn = n0 + r;
+        pb[t] = B + (int64_t)(nn < n ? nn : n - 1) * ldb + (int64_t)sl_begin * TK + lchunk * 8;
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void*)smem;
+    // this wave's first row group in A (wave-uniform, kept in a scalar register for M0)
+    const uint32_t wave_dst = __builtin_amdgcn_readfirstlane(lds0 + wave * 4 * 1024);
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // fragment addresses: row = quadrant base + 32 i + (lane & 31); k-step ks reads logical chunk
+    // 2 ks + (lane >> 5), stored at that value ^ ((lane >> 2) & 3)
+    const int ph0 = (lane >> 5) ^ ((lane >> 2) & 3);
+    const int offA = (wm * 128 + (lane & 31)) * TROWB;
+    const int offB = (TM + wn * 128 + (lane & 31)) * TROWB;
+    const int c0 = ph0 * 16, c1 = (ph0 ^ 2) * 16;
+    bf16x8 fa[2][4], fb[2][4];
+#define GRAM_FRAGS(FS, STAGE, COFF)                                                                 \
+    {                                                                                               \
+        const unsigned char* sb_ = smem + (STAGE) * TSTAGEB;                                        \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                             \
+            fa[FS][i] = *reinterpret_cast<const bf16x8*>(sb_ + offA + i * 32 * TROWB + (COFF));     \
+            fb[FS][i] = *reinterpret_cast<const bf16x8*>(sb_ + offB + i * 32 * TROWB + (COFF));     \
+        }                                                                                           \
+    }
+#define GRAM_MMA(FS)                                                                                \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                   \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j)                                               \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[FS][i], fb[FS][j], acc[i][j], 0, 0, 0);
+#define GRAM_INTERLEAVE                                                                             \
+    _Pragma("unroll") for (int g = 0; g < 8; ++g) {                                                 \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                          \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                          \
+    }
+    // Slabs past the end are clamped to the last one: such loads land in a stage that is not read
+    // again, and they keep the count of loads in flight the same in every iteration.
+#define GRAM_ISSUE_CLAMPED(SLAB, STAGE_OF)                                                          \
+    {                                                                                               \
+        const uint32_t st_ = wave_dst + ((STAGE_OF) & (TSTAGES - 1)) * TSTAGEB;                     \
+        const int k_ = ((SLAB) < last ? (SLAB) : last) * TK;                                        \
+        _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                             \
+            dma16(pa[t] + k_, st_ + t * 1024);                                                      \
+            dma16(pb[t] + k_, st_ + TM * TROWB + t * 1024);                                         \
+        }                                                                                           \
+    }
+
+    if (nslab > 0) {
+        const int last = nslab - 1;
+        GRAM_ISSUE_CLAMPED(0, 0)
+        GRAM_ISSUE_CLAMPED(1, 1)
+        GRAM_ISSUE_CLAMPED(2, 2)
+        GRAM_WAIT_VM(16);     // 24 issued, the oldest 8 (slab 0) needed
+        __syncthreads();
+        GRAM_FRAGS(0, 0, c0)
+        for (int sl = 0; sl < last; ++sl) {
+            GRAM_FRAGS(1, sl & (TSTAGES - 1), c1)
+            GRAM_MMA(0)
+            GRAM_INTERLEAVE
+            GRAM_WAIT_VM(8);      // slab sl+1 has landed (this wave's part) ...
+            __syncthreads();      // ... and everybody's part; slab sl-1 is retired
+            GRAM_ISSUE_CLAMPED(sl + 3, sl + 3)
+            GRAM_FRAGS(0, (sl + 1) & (TSTAGES - 1), c0)
+            GRAM_MMA(1)
+            GRAM_INTERLEAVE
+        }
+        GRAM_FRAGS(1, last & (TSTAGES - 1), c1)
+        GRAM_MMA(0)
+        GRAM_INTERLEAVE
+        GRAM_MMA(1)
+        GRAM_WAIT_VM(0);
+    }
+
+    // accumulator element r of a lane sits at (row, col) = ((r / 4) * 8 + (lane / 32) * 4 + r % 4, lane % 32)
+    const int pad_row = GATHER ? s_pad_row : -1;
+    if (m0 + TM <= M && n0 + TN <= n) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int lr = wm * 128 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                float* row = C + (int64_t)(m0 + lr) * ldc + n0 + wn * 128 + (lane & 31);
+                const bool zero = lr == pad_row;
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) row[jj * 32] = zero ? 0.f : acc[i][jj][r];
+            }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int lr = wm * 128 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                if (m0 + lr < M) {
+                    float* row = C + (int64_t)(m0 + lr) * ldc + n0 + wn * 128 + (lane & 31);
+                    const bool zero = lr == pad_row;
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj)
+                        if (n0 + wn * 128 + jj * 32 + (lane & 31) < n) row[jj * 32] = zero ? 0.f : acc[i][jj][r];
+                }
+            }
+    }
+}
+#undef GRAM_ISSUE_CLAMPED
+#undef GRAM_FRAGS
+#undef GRAM_MMA
+#undef GRAM_INTERLEAVE
+
+template <bool GATHER>
+static void launch_gemm_nt(Ctx* c, int kid, const uint16_t* A, int64_t lda, const int* row_ids,
+                           const int* m_dev, int m_host, int64_t m_bound, const uint16_t* B,
+                           int64_t ldb, int n, const int* k_dev, int k_host, int splits, float* C,
+                           int64_t ldc, int64_t split_stride, hipStream_t s)
+{
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16<GATHER>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)TSMEM);
+        attr_set = true;
+    }
+    const int n_tiles = (n + TN - 1) / TN;
+    int64_t blocks;
+    if (splits == 1)
+        blocks = (((m_bound + TM - 1) / TM + 7) / 8 * 8) * n_tiles;
+    else
+        blocks = ((m_bound + TM - 1) / TM) * n_tiles * splits;
+    launch_smem(c, kid, k_gemm_nt_bf16<GATHER>, dim3((unsigned)blocks), dim3(kBlock), TSMEM, s, A, lda, row_ids, m_dev, m_host, B, ldb, n, k_dev, k_host, splits,
+                c->cfg.pad_id, n_tiles, C, ldc, split_stride);
+}
+
+// ---- 64x64 bf16 transposes through LDS (16-byte global accesses both ways) ---------
+
+constexpr int TT = 64;   // transpose tile edge
+
+// id_of_slot == NULL: plain transpose of the first `rows_host` rows (used for W -> W^T).
+__global__ __launch_bounds__(kBlock) void k_transpose_x(
+    const uint16_t* __restrict__ X, const int* __restrict__ id_of_slot, const int* __restrict__ scal,
+    int rows_host, int d_in, int pad_id, uint16_t* __restrict__ XT, int64_t ldt)
+{
+    __shared__ uint16_t tile[TT][TT + 2];     // [buffer row][feature]
+    const int U = id_of_slot ? scal[kSUTotal] : rows_host;
+    const int s_tiles = (U + TT - 1) / TT, i_tiles = (d_in + TT - 1) / TT;
+    for (int t = blockIdx.x; t < s_tiles * i_tiles; t += gridDim.x) {
+        const int s0 = (t / i_tiles) * TT, i0 = (t % i_tiles) * TT;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int cid = threadIdx.x + h * kBlock;
+            const int row = cid >> 3, ch = (cid & 7) * 8;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (s0 + row < U && i0 + ch < d_in) {
+                const int id = id_of_slot ? id_of_slot[s0 + row] : s0 + row;
+                if (!id_of_slot || id != pad_id)
+                    v = *reinterpret_cast<const uint4*>(X + (int64_t)id * d_in + i0 + ch);
+            }
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) tile[row][ch + e] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+        }
+        __syncthreads();
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int cid = threadIdx.x + h * kBlock;
+            const int r = cid >> 3, ch = (cid & 7) * 8;
+            // a plain transpose (no zero padding of the row tail) stops at the last real row
+            if (i0 + r < d_in && (id_of_slot || s0 + ch < U)) {
+                uint32_t w[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    w[e] = (uint32_t)tile[ch + 2 * e][r] | ((uint32_t)tile[ch + 2 * e + 1][r] << 16);
+                *reinterpret_cast<uint4*>(XT + (int64_t)(i0 + r) * ldt + s0 + ch) = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_transpose_g(const float* __restrict__ G,
+                                                        const int* __restrict__ scal, int d,
+                                                        uint16_t* __restrict__ GT, int64_t ldt)
+{
+    __shared__ uint16_t tile[TT][TT + 2];     // [buffer row][column]
+    const int U = scal[kSUTotal];
+    const int s_tiles = (U + TT - 1) / TT, c_tiles = (d + TT - 1) / TT;
+    for (int t = blockIdx.x; t < s_tiles * c_tiles; t += gridDim.x) {
+        const int s0 = (t / c_tiles) * TT, cc0 = (t % c_tiles) * TT;
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            const int cid = threadIdx.x + h * kBlock;
+            const int row = cid >> 4, ch = (cid & 15) * 4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (s0 + row < U && cc0 + ch < d)
+                v = *reinterpret_cast<const float4*>(G + (int64_t)(s0 + row) * d + cc0 + ch);
+            tile[row][ch + 0] = f32_to_bf16_rne(v.x);
+            tile[row][ch + 1] = f32_to_bf16_rne(v.y);
+            tile[row][ch + 2] = f32_to_bf16_rne(v.z);
+            tile[row][ch + 3] = f32_to_bf16_rne(v.w);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int cid = threadIdx.x + h * kBlock;
+            const int r = cid >> 3, ch = (cid & 7) * 8;
+            if (cc0 + r < d) {
+                uint32_t w[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    w[e] = (uint32_t)tile[ch + 2 * e][r] | ((uint32_t)tile[ch + 2 * e + 1][r] << 16);
+                *reinterpret_cast<uint4*>(GT + (int64_t)(cc0 + r) * ldt + s0 + ch) = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        }
+        __syncthreads();
+    }
 }
 
 // ---- forward, float32 --------------------------------------------------------
@@ -168,97 +478,54 @@ void encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
     if (rows_max <= 0) return;
     const int d_in = c->cfg.d_in, d = c->cfg.d;
     if (c->cfg.xw_dtype == GRAM_BF16) {
-        launch(c, KID_TRANSPOSE_U16, k_transpose_u16, dim3((d + 31) / 32, (d_in + 31) / 32), dim3(kBlock), s,
-                           static_cast<const uint16_t*>(W), d_in, d, static_cast<uint16_t*>(c->Wt));
-        launch(c, KID_ENCODE_BF16, k_encode_bf16, dim3((d + BN - 1) / BN, (unsigned)((rows_max + BM - 1) / BM)),
-                           dim3(kBlock), s, static_cast<const uint16_t*>(X),
-                           static_cast<const uint16_t*>(c->Wt), uniq, u_dev, d_in, d, c->cfg.pad_id, E);
+        // W^T; d_in is a multiple of 8, so 16-byte row chunks of W^T never straddle its end
+        if (d % 8 == 0) {
+            const int tiles = ((d_in + TT - 1) / TT) * ((d + TT - 1) / TT);
+            launch(c, KID_TRANSPOSE_U16, k_transpose_x, dim3(tiles < 1024 ? tiles : 1024), dim3(kBlock), s,
+                   static_cast<const uint16_t*>(W), (const int*)nullptr, c->scal, d_in, d, -1,
+                   static_cast<uint16_t*>(c->Wt), (int64_t)d_in);
+        } else {
+            launch(c, KID_TRANSPOSE_U16, k_transpose_u16, dim3((d + 31) / 32, (d_in + 31) / 32), dim3(kBlock), s,
+                   static_cast<const uint16_t*>(W), d_in, d, static_cast<uint16_t*>(c->Wt));
+        }
+        if (rows_max >= 4096 && d_in % TK == 0) {
+            launch_gemm_nt<true>(c, KID_ENCODE_BF16, static_cast<const uint16_t*>(X), d_in, uniq, u_dev, 0,
+                                 rows_max, static_cast<const uint16_t*>(c->Wt), d_in, d, nullptr, d_in, 1,
+                                 E, d, 0, s);
+        } else {
+            launch(c, KID_ENCODE_BF16, k_encode_bf16, dim3((d + BN - 1) / BN, (unsigned)((rows_max + BM - 1) / BM)),
+                   dim3(kBlock), s, static_cast<const uint16_t*>(X),
+                   static_cast<const uint16_t*>(c->Wt), uniq, u_dev, d_in, d, c->cfg.pad_id, E);
+        }
     } else {
         launch(c, KID_ENCODE_F32, k_encode_f32, dim3((d + 63) / 64, (unsigned)((rows_max + 3) / 4)),
-                           dim3(kBlock), s, static_cast<const float*>(X),
-                           static_cast<const float*>(W), uniq, u_dev, d_in, d, c->cfg.pad_id, E);
+               dim3(kBlock), s, static_cast<const float*>(X), static_cast<const float*>(W), uniq, u_dev,
+               d_in, d, c->cfg.pad_id, E);
     }
 }
 
 // ---- weight gradient -----------------------------------------------------------
 //
-// The output is small (d_in x d) and the contraction runs over all buffer rows,
-// so the rows are split into `splits` contiguous ranges (split-K); each range
-// writes a float32 partial and k_wgrad_reduce adds the partials in range
-// order.  The ranges depend only on the number of rows in the buffer.
+// The output is small (d_in x d) and the contraction runs over all rows of the
+// persistent buffer, so the rows are cut into `splits` contiguous ranges
+// (split-K); each range writes a float32 partial and k_wgrad_reduce adds the
+// partials in range order.  The ranges depend only on the number of rows in
+// the buffer, so the result is reproducible.
+//
+// bf16: both operands have the contraction index (buffer row) as their slow
+// dimension in memory, so they are first transposed into workspace:
+//   XT[i][s] = X[item_s][i]            (gather + transpose, zero for padding)
+//   GT[c][s] = bf16(G[s][c])           (round to nearest even + transpose)
+// with rows padded by zeros up to a multiple of 64 buffer rows.
 
-__device__ __forceinline__ void split_range(int u_total, int splits, int z, int align, int* kb, int* ke)
+__device__ __forceinline__ void split_range(int u_total, int splits, int z, int* kb, int* ke)
 {
-    int chunk = (u_total + splits - 1) / splits;
-    chunk = (chunk + align - 1) / align * align;
+    const int chunk = (u_total + splits - 1) / splits;
     const int b = z * chunk;
     int e = b + chunk;
     if (e > u_total) e = u_total;
     *kb = b < u_total ? b : u_total;
     *ke = e < *kb ? *kb : e;
-}
-
-__global__ __launch_bounds__(kBlock) void k_wgrad_bf16(
-    const uint16_t* __restrict__ X, const int* __restrict__ id_of_slot, const float* __restrict__ G,
-    const int* __restrict__ scal, int d_in, int d, int pad_id, int splits,
-    float* __restrict__ partial)
-{
-    __shared__ __attribute__((aligned(16))) uint16_t sA[BM * LDS_STRIDE];   // [i][slot]
-    __shared__ __attribute__((aligned(16))) uint16_t sB[BN * LDS_STRIDE];   // [c][slot]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int i0 = blockIdx.y * BM, n0 = blockIdx.x * BN, z = blockIdx.z;
-    int kb, ke;
-    split_range(scal[kSUTotal], splits, z, BK, &kb, &ke);
-
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
-    for (int k0 = kb; k0 < ke; k0 += BK) {
-        // A: 32 buffer rows x 128 features, 16 bytes (8 features) per chunk, stored transposed
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int cid = tid + h * kBlock;
-            const int kk = cid >> 4, ic = (cid & 15) * 8;
-            uint4 v = zero4;
-            if (k0 + kk < ke && i0 + ic < d_in) {
-                const int id = id_of_slot[k0 + kk];
-                if (id != pad_id) v = *reinterpret_cast<const uint4*>(X + (int64_t)id * d_in + i0 + ic);
-            }
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                sA[(ic + e) * LDS_STRIDE + kk] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
-        }
-        // B: 32 buffer rows x 128 columns of G (float32), rounded to bf16, stored transposed
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            const int cid = tid + h * kBlock;
-            const int kk = cid >> 5, cc = (cid & 31) * 4;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (k0 + kk < ke && n0 + cc < d)
-                v = *reinterpret_cast<const float4*>(G + (int64_t)(k0 + kk) * d + n0 + cc);
-            sB[(cc + 0) * LDS_STRIDE + kk] = f32_to_bf16_rne(v.x);
-            sB[(cc + 1) * LDS_STRIDE + kk] = f32_to_bf16_rne(v.y);
-            sB[(cc + 2) * LDS_STRIDE + kk] = f32_to_bf16_rne(v.z);
-            sB[(cc + 3) * LDS_STRIDE + kk] = f32_to_bf16_rne(v.w);
-        }
-        __syncthreads();
-        mma_slab(sA, sB, wm, wn, lane, acc);
-        __syncthreads();
-    }
-
-    float* out = partial + (int64_t)z * d_in * d;
-    for_each_acc(acc, wm, wn, lane, [&](int row, int col, float v) {
-        const int i = i0 + row, c = n0 + col;
-        if (i < d_in && c < d) out[(int64_t)i * d + c] = v;
-    });
 }
 
 __global__ __launch_bounds__(kBlock) void k_wgrad_f32(
@@ -271,7 +538,7 @@ __global__ __launch_bounds__(kBlock) void k_wgrad_f32(
     const int z = blockIdx.z;
     if (i >= d_in || c >= d) return;
     int kb, ke;
-    split_range(scal[kSUTotal], splits, z, 1, &kb, &ke);
+    split_range(scal[kSUTotal], splits, z, &kb, &ke);
     float acc = 0.f;
     for (int sidx = kb; sidx < ke; ++sidx) {
         const int id = id_of_slot[sidx];
@@ -297,28 +564,33 @@ __global__ __launch_bounds__(kBlock) void k_wgrad_reduce(const float4* __restric
 int wgrad_splits_for(const gram_config& cfg)
 {
     if (cfg.xw_dtype != GRAM_BF16) return 4;
-    const int tiles = ((cfg.d_in + BM - 1) / BM) * ((cfg.d + BN - 1) / BN);
-    int s = 512 / tiles;
-    if (s < 1) s = 1;
+    const int tiles = ((cfg.d_in + TM - 1) / TM) * ((cfg.d + TN - 1) / TN);
+    int s = 256 / tiles / 8 * 8;      // one block per CU; a multiple of 8 (one K range per XCD)
+    if (s < 8) s = 8;
     if (s > 64) s = 64;
     return s;
 }
 
+int64_t wgrad_pitch_for(int64_t cap_total) { return (cap_total + TT - 1) / TT * TT + TT; }
+
 void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s)
 {
     const int d_in = c->cfg.d_in, d = c->cfg.d, S = c->wg_splits;
-    if (c->cfg.xw_dtype == GRAM_BF16)
-        launch(c, KID_WGRAD_BF16, k_wgrad_bf16, dim3((d + BN - 1) / BN, (d_in + BM - 1) / BM, S), dim3(kBlock),
-                           s, static_cast<const uint16_t*>(X), c->id_of_slot, c->G, c->scal, d_in, d,
-                           c->cfg.pad_id, S, c->wg_partial);
-    else
+    if (c->cfg.xw_dtype == GRAM_BF16) {
+        launch(c, KID_TRANSPOSE_X, k_transpose_x, dim3(1024), dim3(kBlock), s,
+               static_cast<const uint16_t*>(X), c->id_of_slot, c->scal, 0, d_in, c->cfg.pad_id, c->XT, c->ldt);
+        launch(c, KID_TRANSPOSE_G, k_transpose_g, dim3(1024), dim3(kBlock), s, c->G, c->scal, d, c->GT,
+               c->ldt);
+        launch_gemm_nt<false>(c, KID_WGRAD_BF16, c->XT, c->ldt, nullptr, nullptr, d_in, d_in, c->GT, c->ldt, d,
+                              c->scal + kSUTotal, 0, S, c->wg_partial, d, (int64_t)d_in * d, s);
+    } else {
         launch(c, KID_WGRAD_F32, k_wgrad_f32, dim3((d + 63) / 64, (d_in + 3) / 4, S), dim3(kBlock), s,
-                           static_cast<const float*>(X), c->id_of_slot, c->G, c->scal, d_in, d,
-                           c->cfg.pad_id, S, c->wg_partial);
+               static_cast<const float*>(X), c->id_of_slot, c->G, c->scal, d_in, d, c->cfg.pad_id, S,
+               c->wg_partial);
+    }
     const int64_t n4 = (int64_t)d_in * d / 4;
     launch(c, KID_WGRAD_REDUCE, k_wgrad_reduce, dim3((unsigned)((n4 + kBlock - 1) / kBlock)), dim3(kBlock), s,
-                       reinterpret_cast<const float4*>(c->wg_partial), n4, S,
-                       reinterpret_cast<float4*>(dW));
+           reinterpret_cast<const float4*>(c->wg_partial), n4, S, reinterpret_cast<float4*>(dW));
 }
 
 }  // namespace gram

@@ -35,7 +35,7 @@ enum KernelId {
     KID_RADIX_HIST = 0, KID_RADIX_SCAN, KID_RADIX_SCATTER, KID_HEADS_COUNT, KID_HEADS_EMIT, KID_COUNTS,
     KID_UNIQUE_EMPTY, KID_TRANSPOSE_U16, KID_ENCODE_BF16, KID_ENCODE_F32, KID_GATHER_ROWS,
     KID_SLOT_COUNT, KID_SLOT_EMIT, KID_SEG_REDUCE, KID_SEG_COMBINE, KID_WGRAD_BF16, KID_WGRAD_F32,
-    KID_WGRAD_REDUCE, KID_FLUSH_META, KID_FLUSH_ROWS, KID_FLUSH_FINISH, KID_COUNT
+    KID_WGRAD_REDUCE, KID_TRANSPOSE_X, KID_TRANSPOSE_G, KID_FLUSH_META, KID_FLUSH_ROWS, KID_FLUSH_FINISH, KID_COUNT
 };
 
 struct ProfSlot {
@@ -79,6 +79,9 @@ struct Ctx {
     float* seg_last = nullptr;  // [tiles_seg, d] partial sums of segments leaving a tile
     void* Wt = nullptr;         // [d, d_in] transposed weight (bf16 path)
     float* wg_partial = nullptr;// [splits, d_in, d] split-K partials of the weight gradient
+    uint16_t* XT = nullptr;     // [d_in, ldt] bf16 features of the buffer's items, transposed (bf16 path)
+    uint16_t* GT = nullptr;     // [d, ldt] bf16 copy of G, transposed (bf16 path)
+    int64_t ldt = 0;            // row pitch of XT / GT in elements
     int wg_splits = 1;
 
     // sorted order of the current batch (point into keys[]/vals[])
@@ -102,8 +105,8 @@ struct Ctx {
 // Launch a kernel; with profiling enabled for `kid`, bracket it with two events
 // on the same stream.
 template <typename... KArgs, typename... Args>
-inline void launch(Ctx* c, int kid, void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t s,
-                   Args&&... args)
+inline void launch_smem(Ctx* c, int kid, void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t smem,
+                        hipStream_t s, Args&&... args)
 {
     ProfSlot* p = nullptr;
     if ((c->prof_mask >> kid) & 1u) {
@@ -113,8 +116,15 @@ inline void launch(Ctx* c, int kid, void (*kernel)(KArgs...), dim3 grid, dim3 bl
             (void)hipEventRecord(p->start, s);
         }
     }
-    hipLaunchKernelGGL(kernel, grid, block, 0, s, std::forward<Args>(args)...);
+    hipLaunchKernelGGL(kernel, grid, block, smem, s, std::forward<Args>(args)...);
     if (p) (void)hipEventRecord(p->stop, s);
+}
+
+template <typename... KArgs, typename... Args>
+inline void launch(Ctx* c, int kid, void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t s,
+                   Args&&... args)
+{
+    launch_smem(c, kid, kernel, grid, block, 0, s, std::forward<Args>(args)...);
 }
 
 // ---- gram_sort.hip -------------------------------------------------------
@@ -142,5 +152,6 @@ void encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
                     int64_t rows_max, float* E, hipStream_t s);
 void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s);
 int wgrad_splits_for(const gram_config& cfg);
+int64_t wgrad_pitch_for(int64_t cap_total);
 
 }  // namespace gram
