@@ -236,8 +236,8 @@ def main():
         r.step()
     torch.cuda.synchronize()
     kernels = kernel_breakdown(r)
-    dominant = max(kernels, key=lambda k: kernels[k]["total_us_per_step"])
     alg = r.algorithmic()
+    dominant = max((k for k in kernels if k in alg), key=lambda k: kernels[k]["total_us_per_step"])
     dt, prof = time_steps(r, args.steps, args.warmup, profile_kernel=dominant)
     n, ms = prof[dominant]
     roof = roofline_for(dominant, 1e3 * ms / n, alg)

@@ -57,6 +57,8 @@ __device__ __forceinline__ int block_sum(int v, int* sm)
     return tot;
 }
 
+constexpr int kSortBatch = 16;   // rounds whose keys are loaded ahead
+
 SortPlan make_sort_plan(int key_bits, int64_t n_max)
 {
     SortPlan p{};
@@ -105,12 +107,23 @@ __global__ __launch_bounds__(kBlock) void k_radix_hist(const int* __restrict__ k
     if (gw < nw) {
         const int64_t base = (int64_t)gw * items * kWave;
         bool bad = false;
-        for (int it = 0; it < items; ++it) {
-            const int64_t idx = base + (int64_t)it * kWave + lane;
-            if (idx < n) {
-                int k = keys[idx];
-                if (CHECK && (k < 0 || k >= vocab_n)) { bad = true; k = fix_key; }
-                atomicAdd(&cnt[wave][(k >> shift) & (bins - 1)], 1);
+        // keys of kSortBatch rounds are fetched together: the rounds are short and otherwise
+        // each would wait for its own global load
+        for (int it0 = 0; it0 < items; it0 += kSortBatch) {
+            int k[kSortBatch];
+#pragma unroll
+            for (int u = 0; u < kSortBatch; ++u) {
+                const int64_t idx = base + (int64_t)(it0 + u) * kWave + lane;
+                k[u] = (it0 + u < items && idx < n) ? keys[idx] : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < kSortBatch; ++u) {
+                const int64_t idx = base + (int64_t)(it0 + u) * kWave + lane;
+                if (it0 + u < items && idx < n) {
+                    int kk = k[u];
+                    if (CHECK && (kk < 0 || kk >= vocab_n)) { bad = true; kk = fix_key; }
+                    atomicAdd(&cnt[wave][(kk >> shift) & (bins - 1)], 1);
+                }
             }
         }
         if (CHECK && bad) atomicOr(err, kErrBitRange);
@@ -183,31 +196,40 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(
 
     const int64_t base = (int64_t)gw * items * kWave;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
-    for (int it = 0; it < items; ++it) {
-        const int64_t idx = base + (int64_t)it * kWave + lane;
-        const bool valid = idx < n;
-        int k = 0, v = 0;
-        if (valid) {
-            k = keys_in[idx];
-            if (CHECK && (k < 0 || k >= vocab_n)) k = fix_key;
-            v = vals_in ? vals_in[idx] : (int)idx;
+    for (int it0 = 0; it0 < items; it0 += kSortBatch) {
+        int kb[kSortBatch], vb[kSortBatch];
+#pragma unroll
+        for (int u = 0; u < kSortBatch; ++u) {
+            const int64_t idx = base + (int64_t)(it0 + u) * kWave + lane;
+            const bool ok = it0 + u < items && idx < n;
+            kb[u] = ok ? keys_in[idx] : 0;
+            vb[u] = ok ? (vals_in ? vals_in[idx] : (int)idx) : 0;
         }
-        const int dg = (k >> shift) & (bins - 1);
-        unsigned long long peers = __ballot(valid);
-        for (int bit = 0; bit < dbits; ++bit) {
-            const bool one = (dg >> bit) & 1;
-            const unsigned long long m = __ballot(one);
-            peers &= one ? m : ~m;
-        }
-        const int below = __popcll(peers & lt_mask);
-        int pos = 0;
-        if (valid) pos = cnt[dg] + below;
-        __builtin_amdgcn_wave_barrier();
-        if (valid && below == 0) cnt[dg] = pos + __popcll(peers);
-        __builtin_amdgcn_wave_barrier();
-        if (valid) {
-            keys_out[pos] = k;
-            vals_out[pos] = v;
+#pragma unroll
+        for (int u = 0; u < kSortBatch; ++u) {
+            if (it0 + u >= items) break;          // wave-uniform
+            const int64_t idx = base + (int64_t)(it0 + u) * kWave + lane;
+            const bool valid = idx < n;
+            int k = kb[u];
+            const int v = vb[u];
+            if (CHECK && valid && (k < 0 || k >= vocab_n)) k = fix_key;
+            const int dg = (k >> shift) & (bins - 1);
+            unsigned long long peers = __ballot(valid);
+            for (int bit = 0; bit < dbits; ++bit) {
+                const bool one = (dg >> bit) & 1;
+                const unsigned long long m = __ballot(one);
+                peers &= one ? m : ~m;
+            }
+            const int below = __popcll(peers & lt_mask);
+            int pos = 0;
+            if (valid) pos = cnt[dg] + below;
+            __builtin_amdgcn_wave_barrier();
+            if (valid && below == 0) cnt[dg] = pos + __popcll(peers);
+            __builtin_amdgcn_wave_barrier();
+            if (valid) {
+                keys_out[pos] = k;
+                vals_out[pos] = v;
+            }
         }
     }
 }

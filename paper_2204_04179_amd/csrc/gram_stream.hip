@@ -77,9 +77,13 @@ void fill_i32(int* p, int64_t n, int v, hipStream_t s)
 
 // ---- gather: H[p,:] = E[inverse[p],:] ---------------------------------------
 
-// One float4 per thread and step; a block walks `rows_per_block` consecutive
-// positions so that its writes to H form one contiguous stream.
+// A block copies `rows_per_block` consecutive positions (about 32 KiB), so its
+// writes to H form one contiguous stream; each thread keeps kGatherUnroll
+// independent 16-byte loads in flight.  H is written once and not re-read here,
+// so its stores bypass the caches; rows of E are re-read (once per occurrence)
+// and keep ordinary cached loads, which measured faster than streaming ones.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kGatherUnroll = 8;
 
 __global__ __launch_bounds__(kBlock) void k_gather_rows(const f32x4* __restrict__ E,
                                                         const int* __restrict__ inverse, int64_t m,
@@ -87,13 +91,24 @@ __global__ __launch_bounds__(kBlock) void k_gather_rows(const f32x4* __restrict_
                                                         int rows_per_block)
 {
     const int64_t p0 = (int64_t)blockIdx.x * rows_per_block;
-    const int64_t p1 = p0 + rows_per_block < m ? p0 + rows_per_block : m;
-    const int total = (int)(p1 - p0) * cols4;
-    for (int i = threadIdx.x; i < total; i += kBlock) {
-        const int64_t p = p0 + i / cols4;
-        const int c = i % cols4;
-        const f32x4 v = E[(int64_t)inverse[p] * cols4 + c];
-        __builtin_nontemporal_store(v, &H[p * cols4 + c]);   // H is written once and not re-read here
+    const int rows = (int)(p0 + rows_per_block < m ? rows_per_block : m - p0);
+    const int total = rows * cols4;
+    f32x4* out = H + p0 * cols4;
+    for (int e0 = 0; e0 < total; e0 += kBlock * kGatherUnroll) {
+        int64_t src[kGatherUnroll];
+#pragma unroll
+        for (int u = 0; u < kGatherUnroll; ++u) {
+            const int e = e0 + u * kBlock + threadIdx.x;
+            const int row = e / cols4;
+            src[u] = e < total ? (int64_t)inverse[p0 + row] * cols4 + (e - row * cols4) : -1;
+        }
+        f32x4 v[kGatherUnroll];
+#pragma unroll
+        for (int u = 0; u < kGatherUnroll; ++u)
+            if (src[u] >= 0) v[u] = E[src[u]];
+#pragma unroll
+        for (int u = 0; u < kGatherUnroll; ++u)
+            if (src[u] >= 0) __builtin_nontemporal_store(v[u], &out[e0 + u * kBlock + threadIdx.x]);
     }
 }
 
@@ -101,12 +116,12 @@ void gather_rows(Ctx* c, const float* E, const int* inverse, int64_t m, float* H
 {
     if (m == 0) return;
     const int cols4 = c->cfg.d / 4;
-    int rows_per_block = (8 * kBlock + cols4 - 1) / cols4;   // ~8 float4 per thread
+    int rows_per_block = (kGatherUnroll * kBlock + cols4 - 1) / cols4;
     if (rows_per_block < 1) rows_per_block = 1;
     const int64_t blocks = (m + rows_per_block - 1) / rows_per_block;
     launch(c, KID_GATHER_ROWS, k_gather_rows, dim3((unsigned)blocks), dim3(kBlock), s,
-                       reinterpret_cast<const f32x4*>(E), inverse, m, cols4,
-                       reinterpret_cast<f32x4*>(H), rows_per_block);
+           reinterpret_cast<const f32x4*>(E), inverse, m, cols4, reinterpret_cast<f32x4*>(H),
+           rows_per_block);
 }
 
 // ---- buffer rows for the items of this batch --------------------------------
@@ -294,7 +309,13 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(
         for (int k = 0; k < kSegUnroll; ++k) {
             const int i = i0 + k;
             const int src = i < rows ? s_src[i] : -1;
-            v[k] = src >= 0 ? dH[(int64_t)src * cols4 + col] : make_float4(0.f, 0.f, 0.f, 0.f);
+            // every row of dH is read exactly once: stream it past the caches
+            v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (src >= 0) {
+                const f32x4 t = __builtin_nontemporal_load(
+                    reinterpret_cast<const f32x4*>(dH) + (int64_t)src * cols4 + col);
+                v[k] = make_float4(t.x, t.y, t.z, t.w);
+            }
         }
 #pragma unroll
         for (int k = 0; k < kSegUnroll; ++k) {
@@ -413,7 +434,9 @@ __global__ __launch_bounds__(kBlock) void k_flush_rows(const int* __restrict__ s
          i += (int64_t)gridDim.x * kBlock) {
         const int64_t r = i / cols4;
         const int cc = (int)(i % cols4);
-        G_total[i] = G[(int64_t)sorted_slots[r] * cols4 + cc];
+        const f32x4 t = __builtin_nontemporal_load(
+            reinterpret_cast<const f32x4*>(G) + (int64_t)sorted_slots[r] * cols4 + cc);
+        __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(G_total) + i);
     }
 }
 
