@@ -40,9 +40,13 @@ int bits_for(int32_t vocab_n)
 
 int64_t table_elems_for(int64_t n_sort_max)
 {
-    int64_t nw = (n_sort_max + 4095) / 4096;
-    if (nw < 256) nw = 256;
-    return ((int64_t)1 << kMaxDigitBits) * nw;
+    // blocks of the radix plan: at least 1024 keys each, at most 256 * 64 keys each
+    int64_t nb = (n_sort_max + 1023) / 1024;
+    if (nb > 256) {
+        nb = (n_sort_max + 16383) / 16384;
+        if (nb < 256) nb = 256;
+    }
+    return ((int64_t)1 << kMaxDigitBits) * (nb + 1);
 }
 
 struct Derived {

@@ -59,6 +59,8 @@ __device__ __forceinline__ int block_sum(int v, int* sm)
 
 constexpr int kSortBatch = 16;   // rounds whose keys are loaded ahead
 
+// A block of 4 waves owns items * 256 consecutive keys; wave w of the block owns
+// the w-th quarter of them.
 SortPlan make_sort_plan(int key_bits, int64_t n_max)
 {
     SortPlan p{};
@@ -70,15 +72,17 @@ SortPlan make_sort_plan(int key_bits, int64_t n_max)
         p.digit_bits[i] = b;
         left -= b;
     }
-    int64_t items = (n_max + (int64_t)kWave * 256 - 1) / ((int64_t)kWave * 256);
+    // about 256 blocks (one per CU): the scatter pass issues two 4-byte stores per key to
+    // unrelated addresses, and the rate of such stores per CU is what bounds it
+    int64_t items = (n_max + (int64_t)kBlock * 256 - 1) / ((int64_t)kBlock * 256);
     if (items < 4) items = 4;
     if (items > 64) items = 64;
     p.items = (int)items;
-    int64_t kpw = (int64_t)kWave * p.items;
-    int64_t nw = (n_max + kpw - 1) / kpw;
-    if (nw < 1) nw = 1;
-    p.nw = (int)nw;
-    p.blocks = (int)((nw + kWavesPerBlock - 1) / kWavesPerBlock);
+    const int64_t kpb = (int64_t)kBlock * p.items;
+    int64_t nb = (n_max + kpb - 1) / kpb;
+    if (nb < 1) nb = 1;
+    p.blocks = (int)nb;
+    p.nw = p.blocks * kWavesPerBlock;
     return p;
 }
 
@@ -86,79 +90,81 @@ int64_t sort_table_elems(const SortPlan& p)
 {
     int mb = 0;
     for (int i = 0; i < p.passes; ++i) mb = p.digit_bits[i] > mb ? p.digit_bits[i] : mb;
-    return ((int64_t)1 << mb) * p.nw;
+    return ((int64_t)1 << mb) * p.blocks;
 }
 
-// Per-wave digit histogram of one pass.  table[digit * nw + wave] = count.
+// Applies `f(key, index, u)` to the keys of one wave's chunk, kSortBatch rounds of 64 keys at a
+// time; the keys of a batch are fetched together, because the rounds are short and otherwise each
+// would wait for its own global load.
+#define GRAM_FOR_WAVE_KEYS(BODY)                                                                    \
+    for (int it0 = 0; it0 < items; it0 += kSortBatch) {                                             \
+        int kb_[kSortBatch];                                                                        \
+        _Pragma("unroll") for (int u = 0; u < kSortBatch; ++u) {                                    \
+            const int64_t idx_ = base + (int64_t)(it0 + u) * kWave + lane;                          \
+            kb_[u] = (it0 + u < items && idx_ < n) ? keys_in[idx_] : 0;                             \
+        }                                                                                           \
+        _Pragma("unroll") for (int u = 0; u < kSortBatch; ++u) {                                    \
+            if (it0 + u >= items) break; /* wave-uniform */                                         \
+            const int64_t idx = base + (int64_t)(it0 + u) * kWave + lane;                           \
+            const bool valid = idx < n;                                                             \
+            int k = kb_[u];                                                                         \
+            BODY                                                                                    \
+        }                                                                                           \
+    }
+
+// Digit histogram of one pass per block.  table[digit * nb + block] = count.
 template <bool CHECK>
-__global__ __launch_bounds__(kBlock) void k_radix_hist(const int* __restrict__ keys, int n_host,
+__global__ __launch_bounds__(kBlock) void k_radix_hist(const int* __restrict__ keys_in, int n_host,
                                                        const int* __restrict__ n_dev, int shift,
-                                                       int dbits, int items, int nw,
+                                                       int dbits, int items,
                                                        int* __restrict__ table, int vocab_n,
                                                        int fix_key, int* __restrict__ err)
 {
-    __shared__ int cnt[kWavesPerBlock][1 << kMaxDigitBits];
+    __shared__ int cnt[1 << kMaxDigitBits];
     const int n = n_dev ? *n_dev : n_host;
     const int wave = wave_id(), lane = lane_id();
-    const int gw = blockIdx.x * kWavesPerBlock + wave;
     const int bins = 1 << dbits;
-    for (int b = lane; b < bins; b += kWave) cnt[wave][b] = 0;
+    for (int b = threadIdx.x; b < bins; b += kBlock) cnt[b] = 0;
     __syncthreads();
-    if (gw < nw) {
-        const int64_t base = (int64_t)gw * items * kWave;
-        bool bad = false;
-        // keys of kSortBatch rounds are fetched together: the rounds are short and otherwise
-        // each would wait for its own global load
-        for (int it0 = 0; it0 < items; it0 += kSortBatch) {
-            int k[kSortBatch];
-#pragma unroll
-            for (int u = 0; u < kSortBatch; ++u) {
-                const int64_t idx = base + (int64_t)(it0 + u) * kWave + lane;
-                k[u] = (it0 + u < items && idx < n) ? keys[idx] : -1;
-            }
-#pragma unroll
-            for (int u = 0; u < kSortBatch; ++u) {
-                const int64_t idx = base + (int64_t)(it0 + u) * kWave + lane;
-                if (it0 + u < items && idx < n) {
-                    int kk = k[u];
-                    if (CHECK && (kk < 0 || kk >= vocab_n)) { bad = true; kk = fix_key; }
-                    atomicAdd(&cnt[wave][(kk >> shift) & (bins - 1)], 1);
-                }
-            }
-        }
-        if (CHECK && bad) atomicOr(err, kErrBitRange);
-    }
+    const int64_t base = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * items * kWave;
+    bool bad = false;
+    GRAM_FOR_WAVE_KEYS(
+        if (valid) {
+            if (CHECK && (k < 0 || k >= vocab_n)) { bad = true; k = fix_key; }
+            atomicAdd(&cnt[(k >> shift) & (bins - 1)], 1);
+        })
+    if (CHECK && bad) atomicOr(err, kErrBitRange);
     __syncthreads();
-    if (gw < nw)
-        for (int b = lane; b < bins; b += kWave) table[(int64_t)b * nw + gw] = cnt[wave][b];
+    for (int b = threadIdx.x; b < bins; b += kBlock) table[(int64_t)b * gridDim.x + blockIdx.x] = cnt[b];
 }
 
-// One wave per digit: exclusive prefix over the waves' counts (in place), digit total to gtot.
-__global__ __launch_bounds__(kBlock) void k_radix_scan(int* __restrict__ table, int nw, int bins,
+// One wave per digit: exclusive prefix over the blocks' counts (in place), digit total to gtot.
+__global__ __launch_bounds__(kBlock) void k_radix_scan(int* __restrict__ table, int nb, int bins,
                                                        int* __restrict__ gtot)
 {
     const int b = blockIdx.x * kWavesPerBlock + wave_id();
     if (b >= bins) return;
     const int lane = lane_id();
-    int* row = table + (int64_t)b * nw;
+    int* row = table + (int64_t)b * nb;
     int carry = 0;
-    for (int base = 0; base < nw; base += kWave) {
+    for (int base = 0; base < nb; base += kWave) {
         const int i = base + lane;
-        const int v = i < nw ? row[i] : 0;
+        const int v = i < nb ? row[i] : 0;
         const int incl = wave_incl_scan(v);
-        if (i < nw) row[i] = carry + incl - v;
+        if (i < nb) row[i] = carry + incl - v;
         carry += __shfl(incl, kWave - 1);
     }
     if (lane == 0) gtot[b] = carry;
 }
 
-// Stable scatter of one pass.  A wave walks its chunk in rounds of 64 keys;
-// inside a round, lanes holding the same digit find each other with one
-// ballot per digit bit and take consecutive slots in lane order.
+// Stable scatter of one pass.  The block recounts its keys per wave, turns the counts into the
+// first output slot of every (wave, digit), then each wave walks its chunk in rounds of 64 keys:
+// lanes holding the same digit find each other with one ballot per digit bit and take consecutive
+// slots in lane order.
 template <bool CHECK>
 __global__ __launch_bounds__(kBlock) void k_radix_scatter(
     const int* __restrict__ keys_in, const int* __restrict__ vals_in, int n_host,
-    const int* __restrict__ n_dev, int shift, int dbits, int items, int nw,
+    const int* __restrict__ n_dev, int shift, int dbits, int items,
     const int* __restrict__ table, const int* __restrict__ gtot, int* __restrict__ keys_out,
     int* __restrict__ vals_out, int vocab_n, int fix_key)
 {
@@ -167,9 +173,12 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(
     __shared__ int sm[kWavesPerBlock];
     const int n = n_dev ? *n_dev : n_host;
     const int wave = wave_id(), lane = lane_id();
-    const int gw = blockIdx.x * kWavesPerBlock + wave;
     const int bins = 1 << dbits;
+    const int64_t base = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * items * kWave;
 
+    for (int b = threadIdx.x; b < bins; b += kBlock)
+#pragma unroll
+        for (int w = 0; w < kWavesPerBlock; ++w) cnt_s[w][b] = 0;
     {   // exclusive scan of the digit totals, 4 digits per thread
         int v[4], s = 0;
 #pragma unroll
@@ -179,7 +188,7 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(
             s += v[i];
         }
         int total;
-        int run = block_excl_scan(s, &total, sm);
+        int run = block_excl_scan(s, &total, sm);      // contains barriers: cnt_s is zero after it
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int b = threadIdx.x * 4 + i;
@@ -187,52 +196,47 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(
             run += v[i];
         }
     }
+    GRAM_FOR_WAVE_KEYS(
+        if (valid) {
+            if (CHECK && (k < 0 || k >= vocab_n)) k = fix_key;
+            atomicAdd(&cnt_s[wave][(k >> shift) & (bins - 1)], 1);
+        })
     __syncthreads();
-    volatile int* cnt = cnt_s[wave];
-    if (gw < nw)
-        for (int b = lane; b < bins; b += kWave) cnt[b] = digit_base[b] + table[(int64_t)b * nw + gw];
-    __syncthreads();
-    if (gw >= nw) return;
-
-    const int64_t base = (int64_t)gw * items * kWave;
-    const unsigned long long lt_mask = (1ull << lane) - 1ull;
-    for (int it0 = 0; it0 < items; it0 += kSortBatch) {
-        int kb[kSortBatch], vb[kSortBatch];
+    for (int b = threadIdx.x; b < bins; b += kBlock) {
+        int o = digit_base[b] + table[(int64_t)b * gridDim.x + blockIdx.x];
 #pragma unroll
-        for (int u = 0; u < kSortBatch; ++u) {
-            const int64_t idx = base + (int64_t)(it0 + u) * kWave + lane;
-            const bool ok = it0 + u < items && idx < n;
-            kb[u] = ok ? keys_in[idx] : 0;
-            vb[u] = ok ? (vals_in ? vals_in[idx] : (int)idx) : 0;
-        }
-#pragma unroll
-        for (int u = 0; u < kSortBatch; ++u) {
-            if (it0 + u >= items) break;          // wave-uniform
-            const int64_t idx = base + (int64_t)(it0 + u) * kWave + lane;
-            const bool valid = idx < n;
-            int k = kb[u];
-            const int v = vb[u];
-            if (CHECK && valid && (k < 0 || k >= vocab_n)) k = fix_key;
-            const int dg = (k >> shift) & (bins - 1);
-            unsigned long long peers = __ballot(valid);
-            for (int bit = 0; bit < dbits; ++bit) {
-                const bool one = (dg >> bit) & 1;
-                const unsigned long long m = __ballot(one);
-                peers &= one ? m : ~m;
-            }
-            const int below = __popcll(peers & lt_mask);
-            int pos = 0;
-            if (valid) pos = cnt[dg] + below;
-            __builtin_amdgcn_wave_barrier();
-            if (valid && below == 0) cnt[dg] = pos + __popcll(peers);
-            __builtin_amdgcn_wave_barrier();
-            if (valid) {
-                keys_out[pos] = k;
-                vals_out[pos] = v;
-            }
+        for (int w = 0; w < kWavesPerBlock; ++w) {
+            const int cw = cnt_s[w][b];
+            cnt_s[w][b] = o;
+            o += cw;
         }
     }
+    __syncthreads();
+
+    volatile int* cnt = cnt_s[wave];
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    GRAM_FOR_WAVE_KEYS(
+        if (CHECK && valid && (k < 0 || k >= vocab_n)) k = fix_key;
+        const int v = valid ? (vals_in ? vals_in[idx] : (int)idx) : 0;
+        const int dg = (k >> shift) & (bins - 1);
+        unsigned long long peers = __ballot(valid);
+        for (int bit = 0; bit < dbits; ++bit) {
+            const bool one = (dg >> bit) & 1;
+            const unsigned long long mm = __ballot(one);
+            peers &= one ? mm : ~mm;
+        }
+        const int below = __popcll(peers & lt_mask);
+        int pos = 0;
+        if (valid) pos = cnt[dg] + below;
+        __builtin_amdgcn_wave_barrier();
+        if (valid && below == 0) cnt[dg] = pos + __popcll(peers);
+        __builtin_amdgcn_wave_barrier();
+        if (valid && (unsigned)pos < (unsigned)n) {     // pos < n always holds; the test keeps a
+            keys_out[pos] = k;                           // logic error from becoming a stray store
+            vals_out[pos] = v;
+        })
 }
+#undef GRAM_FOR_WAVE_KEYS
 
 int radix_sort_pairs(Ctx* c, const int* keys_in, const int* vals_in, int n_host, const int* n_dev,
                      int64_t n_max, bool check_range, int fix_key, hipStream_t s)
@@ -247,20 +251,20 @@ int radix_sort_pairs(Ctx* c, const int* keys_in, const int* vals_in, int n_host,
         const bool chk = check_range && pass == 0;
         if (chk)
             launch(c, KID_RADIX_HIST, k_radix_hist<true>, dim3(p.blocks), dim3(kBlock), s, kin, n_host,
-                               n_dev, shift, db, p.items, p.nw, c->table, c->cfg.vocab_n, fix_key,
+                               n_dev, shift, db, p.items, c->table, c->cfg.vocab_n, fix_key,
                                c->scal + kSErr);
         else
             launch(c, KID_RADIX_HIST, k_radix_hist<false>, dim3(p.blocks), dim3(kBlock), s, kin, n_host,
-                               n_dev, shift, db, p.items, p.nw, c->table, 0, 0, c->scal + kSErr);
+                               n_dev, shift, db, p.items, c->table, 0, 0, c->scal + kSErr);
         launch(c, KID_RADIX_SCAN, k_radix_scan, dim3((bins + kWavesPerBlock - 1) / kWavesPerBlock),
-                           dim3(kBlock), s, c->table, p.nw, bins, c->gtot);
+               dim3(kBlock), s, c->table, p.blocks, bins, c->gtot);
         if (chk)
             launch(c, KID_RADIX_SCATTER, k_radix_scatter<true>, dim3(p.blocks), dim3(kBlock), s, kin, vin,
-                               n_host, n_dev, shift, db, p.items, p.nw, c->table, c->gtot,
+                               n_host, n_dev, shift, db, p.items, c->table, c->gtot,
                                c->keys[dst], c->vals[dst], c->cfg.vocab_n, fix_key);
         else
             launch(c, KID_RADIX_SCATTER, k_radix_scatter<false>, dim3(p.blocks), dim3(kBlock), s, kin, vin,
-                               n_host, n_dev, shift, db, p.items, p.nw, c->table, c->gtot,
+                               n_host, n_dev, shift, db, p.items, c->table, c->gtot,
                                c->keys[dst], c->vals[dst], 0, 0);
         kin = c->keys[dst];
         vin = c->vals[dst];
