@@ -179,7 +179,7 @@ __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base)
 #define GRAM_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
 template <bool GATHER>
-__global__ __launch_bounds__(kBlock) void k_gemm_nt_bf16(
+__global__ __launch_bounds__(kBlock) void k_gemm_nt_bf16_dma(
     const uint16_t* __restrict__ A, int64_t lda, const int* __restrict__ row_ids,
     const int* __restrict__ m_dev, int m_host, const uint16_t* __restrict__ B, int64_t ldb, int n,
     const int* __restrict__ k_dev, int k_host, int splits, int pad_id, int n_tiles,
@@ -347,15 +347,234 @@ __global__ __launch_bounds__(kBlock) void k_gemm_nt_bf16(
 #undef GRAM_MMA
 #undef GRAM_INTERLEAVE
 
+// ---- the same contraction with register-staged buffer loads ----------------------
+//
+// Measured on MI355X: a wave that issues direct-to-LDS loads stalls at issue for
+// as long as the memory pipe needs to take them (about 130 cycles per 1 KiB
+// instruction at 4 waves per CU), and with one wave per SIMD nothing else can
+// issue MFMAs meanwhile, so load time and MFMA time add up.  buffer_load_dwordx4
+// into registers issues in about 20 cycles and completes in the background at
+// the same 29 bytes per clock and CU.  This variant therefore loads slab s+3
+// into one of two register sets, parks slab s+1 in LDS (2 stages, same swizzled
+// layout) just before the barrier that publishes it, and interleaves the load,
+// LDS-write and fragment-read instructions with the MFMAs of the current slab.
+// Operands are addressed through buffer descriptors (base + 32-bit byte offset;
+// reads past the end return zero), which limits each operand to 4 GiB; larger
+// ones take k_gemm_nt_bf16_dma.
+typedef int v4i32 __attribute__((ext_vector_type(4)));
+constexpr int RSTAGES = 2;
+constexpr size_t RSMEM = (size_t)RSTAGES * TSTAGEB;
+constexpr uint32_t kBufferFlags = 0x00027000;   // raw buffer: 32-bit elements, no swizzle
+
 template <bool GATHER>
-static void launch_gemm_nt(Ctx* c, int kid, const uint16_t* A, int64_t lda, const int* row_ids,
-                           const int* m_dev, int m_host, int64_t m_bound, const uint16_t* B,
-                           int64_t ldb, int n, const int* k_dev, int k_host, int splits, float* C,
-                           int64_t ldc, int64_t split_stride, hipStream_t s)
+__global__ __launch_bounds__(kBlock) void k_gemm_nt_bf16(
+    const uint16_t* __restrict__ A, int64_t lda, uint32_t a_bytes, const int* __restrict__ row_ids,
+    const int* __restrict__ m_dev, int m_host, const uint16_t* __restrict__ B, int64_t ldb,
+    uint32_t b_bytes, int n, const int* __restrict__ k_dev, int k_host, int splits, int pad_id,
+    int n_tiles, float* __restrict__ C, int64_t ldc, int64_t split_stride)
+{
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    __shared__ int s_pad_row;
+    const int M = m_dev ? *m_dev : m_host;
+    const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+    int m0, n0, z;
+    if (splits == 1) {
+        m0 = ((q / n_tiles) * 8 + xcd) * TM;
+        n0 = (q % n_tiles) * TN;
+        z = 0;
+    } else {
+        const int tiles = ((M + TM - 1) / TM) * n_tiles;
+        z = xcd + 8 * (q / tiles);
+        m0 = ((q % tiles) / n_tiles) * TM;
+        n0 = ((q % tiles) % n_tiles) * TN;
+    }
+    if (m0 >= M || z >= splits) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    if (tid == 0) s_pad_row = -1;
+    __syncthreads();
+
+    const int ktot = k_dev ? *k_dev : k_host;
+    const int slabs_all = (ktot + TK - 1) / TK;
+    const int per = (slabs_all + splits - 1) / splits;
+    const int sl_begin = z * per;
+    int nslab = slabs_all - sl_begin;
+    if (nslab > per) nslab = per;
+    C += (int64_t)z * split_stride;
+
+    // loader: wave w moves row groups g = 4 w + t (16 rows each) of A and of B; lane l moves the
+    // chunk that belongs at position l & 3 of row 16 g + (l >> 2).  Rows past M / past n are
+    // clamped to a valid row: their products are never stored.
+    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(A), 0, a_bytes, kBufferFlags);
+    const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(B), 0, b_bytes, kBufferFlags);
+    const int lrow = lane >> 2;
+    const int lchunk = (lane & 3) ^ ((lane >> 4) & 3);
+    uint32_t oa[4], ob[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int r = (wave * 4 + t) * 16 + lrow;
+        const int j = m0 + r < M ? m0 + r : M - 1;
+        int64_t rowA = j;
+        if (GATHER) {
+            const int id = row_ids[j];
+            if (m0 + r < M && id == pad_id) s_pad_row = r;   // at most one row is the padding item
+            rowA = id;
+        }
+        oa[t] = (uint32_t)((rowA * lda + (int64_t)sl_begin * TK + lchunk * 8) * 2);
+        const int nn = n0 + r;
+        ob[t] = (uint32_t)(((int64_t)(nn < n ? nn : n - 1) * ldb + (int64_t)sl_begin * TK + lchunk * 8) * 2);
+    }
+    unsigned char* park = smem + (wave * 4) * 1024 + lane * 16;
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int ph0 = (lane >> 5) ^ ((lane >> 2) & 3);
+    const int offA = (wm * 128 + (lane & 31)) * TROWB;
+    const int offB = (TM + wn * 128 + (lane & 31)) * TROWB;
+    const int c0 = ph0 * 16, c1 = (ph0 ^ 2) * 16;
+    bf16x8 fa[2][4], fb[2][4];
+    v4i32 ra[2][4], rb[2][4];
+#define GRAM_FRAGS(FS, STAGE, COFF)                                                                 \
+    {                                                                                               \
+        const unsigned char* sb_ = smem + (STAGE) * TSTAGEB;                                        \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                             \
+            fa[FS][i] = *reinterpret_cast<const bf16x8*>(sb_ + offA + i * 32 * TROWB + (COFF));     \
+            fb[FS][i] = *reinterpret_cast<const bf16x8*>(sb_ + offB + i * 32 * TROWB + (COFF));     \
+        }                                                                                           \
+    }
+#define GRAM_MMA(FS)                                                                                \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                   \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j)                                               \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[FS][i], fb[FS][j], acc[i][j], 0, 0, 0);
+    // Slabs past the end are clamped to the last one (their data is never multiplied).
+#define GRAM_LOAD(SET, SLAB)                                                                        \
+    {                                                                                               \
+        const uint32_t k_ = (uint32_t)(((SLAB) < last ? (SLAB) : last) * (TK * 2));                 \
+        _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                             \
+            ra[SET][t] = __builtin_amdgcn_raw_buffer_load_b128(rsA, oa[t] + k_, 0, 0);              \
+            rb[SET][t] = __builtin_amdgcn_raw_buffer_load_b128(rsB, ob[t] + k_, 0, 0);              \
+        }                                                                                           \
+    }
+#define GRAM_PARK(SET, STAGE)                                                                       \
+    {                                                                                               \
+        unsigned char* p_ = park + (STAGE) * TSTAGEB;                                               \
+        _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                             \
+            *reinterpret_cast<v4i32*>(p_ + t * 1024) = ra[SET][t];                                  \
+            *reinterpret_cast<v4i32*>(p_ + TM * TROWB + t * 1024) = rb[SET][t];                     \
+        }                                                                                           \
+    }
+    // first half of a slab: k-step 0 MFMAs with the k-step 1 fragment reads, then the LDS writes
+    // of the next slab, one or two LDS instructions between MFMAs (a burst of LDS instructions
+    // blocks the wave at issue while the other waves' bursts drain, and the MFMA pipe idles);
+    // second half: k-step 1 MFMAs with the global loads of slab +3 and the fragment reads of the
+    // next slab's k-step 0
+#define GRAM_SCHED_FIRST                                                                            \
+    _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                                 \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                          \
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                          \
+    }                                                                                               \
+    _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                                 \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                          \
+        __builtin_amdgcn_sched_group_barrier(0x200, 2, 0);                                          \
+    }
+    // (for the gathered forward the compiler's own order measured 2 % faster, for the streamed
+    // weight gradient the fixed pattern 25 % faster)
+#define GRAM_SCHED_SECOND                                                                           \
+    if (!GATHER) {                                                                                  \
+        _Pragma("unroll") for (int g = 0; g < 8; ++g) {                                             \
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                      \
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                      \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                      \
+        }                                                                                           \
+    }
+#define GRAM_ITER(SL, P)                                                                            \
+    {                                                                                               \
+        GRAM_FRAGS(1, (SL) & 1, c1)                                                                 \
+        GRAM_MMA(0)                                                                                 \
+        GRAM_PARK(P, ((SL) + 1) & 1)                                                                \
+        GRAM_SCHED_FIRST                                                                            \
+        __syncthreads();                                                                            \
+        GRAM_LOAD(P, (SL) + 3)                                                                      \
+        GRAM_FRAGS(0, ((SL) + 1) & 1, c0)                                                           \
+        GRAM_MMA(1)                                                                                 \
+        GRAM_SCHED_SECOND                                                                           \
+    }
+
+    if (nslab > 0) {
+        const int last = nslab - 1;
+        GRAM_LOAD(0, 0)
+        GRAM_LOAD(1, 1)
+        GRAM_PARK(0, 0)
+        GRAM_LOAD(0, 2)
+        __syncthreads();
+        GRAM_FRAGS(0, 0, c0)
+        int sl = 0;
+        for (; sl + 1 < last; sl += 2) {
+            GRAM_ITER(sl, 1)          // set 1 holds slab sl+1, set 0 holds slab sl+2
+            GRAM_ITER(sl + 1, 0)      // set 0 holds slab sl+2, set 1 holds slab sl+3
+        }
+        if (sl < last) GRAM_ITER(sl, 1)
+        GRAM_FRAGS(1, last & 1, c1)
+        GRAM_MMA(0)
+        GRAM_MMA(1)
+    }
+
+    // accumulator element r of a lane sits at (row, col) = ((r / 4) * 8 + (lane / 32) * 4 + r % 4, lane % 32)
+    const int pad_row = GATHER ? s_pad_row : -1;
+    if (m0 + TM <= M && n0 + TN <= n) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int lr = wm * 128 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                float* row = C + (int64_t)(m0 + lr) * ldc + n0 + wn * 128 + (lane & 31);
+                const bool zero = lr == pad_row;
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) row[jj * 32] = zero ? 0.f : acc[i][jj][r];
+            }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int lr = wm * 128 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                if (m0 + lr < M) {
+                    float* row = C + (int64_t)(m0 + lr) * ldc + n0 + wn * 128 + (lane & 31);
+                    const bool zero = lr == pad_row;
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj)
+                        if (n0 + wn * 128 + jj * 32 + (lane & 31) < n) row[jj * 32] = zero ? 0.f : acc[i][jj][r];
+                }
+            }
+    }
+}
+#undef GRAM_FRAGS
+#undef GRAM_MMA
+#undef GRAM_LOAD
+#undef GRAM_PARK
+#undef GRAM_SCHED_FIRST
+#undef GRAM_SCHED_SECOND
+#undef GRAM_ITER
+
+// a_rows / b_rows: rows of the matrices A and B as allocated (A: all rows that row_ids may name).
+template <bool GATHER>
+static void launch_gemm_nt(Ctx* c, int kid, const uint16_t* A, int64_t lda, int64_t a_rows,
+                           const int* row_ids, const int* m_dev, int m_host, int64_t m_bound,
+                           const uint16_t* B, int64_t ldb, int64_t b_rows, int n, const int* k_dev,
+                           int k_host, int splits, float* C, int64_t ldc, int64_t split_stride,
+                           hipStream_t s)
 {
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16<GATHER>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)RSMEM);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16_dma<GATHER>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)TSMEM);
         attr_set = true;
     }
@@ -365,8 +584,16 @@ static void launch_gemm_nt(Ctx* c, int kid, const uint16_t* A, int64_t lda, cons
         blocks = (((m_bound + TM - 1) / TM + 7) / 8 * 8) * n_tiles;
     else
         blocks = ((m_bound + TM - 1) / TM) * n_tiles * splits;
-    launch_smem(c, kid, k_gemm_nt_bf16<GATHER>, dim3((unsigned)blocks), dim3(kBlock), TSMEM, s, A, lda, row_ids, m_dev, m_host, B, ldb, n, k_dev, k_host, splits,
-                c->cfg.pad_id, n_tiles, C, ldc, split_stride);
+    const int64_t a_bytes = a_rows * lda * 2, b_bytes = b_rows * ldb * 2;
+    const int64_t window = (int64_t)1 << 32;
+    if (a_bytes < window && b_bytes < window)
+        launch_smem(c, kid, k_gemm_nt_bf16<GATHER>, dim3((unsigned)blocks), dim3(kBlock), RSMEM, s, A, lda,
+                    (uint32_t)a_bytes, row_ids, m_dev, m_host, B, ldb, (uint32_t)b_bytes, n, k_dev, k_host,
+                    splits, c->cfg.pad_id, n_tiles, C, ldc, split_stride);
+    else
+        launch_smem(c, kid, k_gemm_nt_bf16_dma<GATHER>, dim3((unsigned)blocks), dim3(kBlock), TSMEM, s, A,
+                    lda, row_ids, m_dev, m_host, B, ldb, n, k_dev, k_host, splits, c->cfg.pad_id, n_tiles,
+                    C, ldc, split_stride);
 }
 
 // ---- 64x64 bf16 transposes through LDS (16-byte global accesses both ways) ---------
@@ -489,9 +716,9 @@ void encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
                    static_cast<const uint16_t*>(W), d_in, d, static_cast<uint16_t*>(c->Wt));
         }
         if (rows_max >= 4096 && d_in % TK == 0) {
-            launch_gemm_nt<true>(c, KID_ENCODE_BF16, static_cast<const uint16_t*>(X), d_in, uniq, u_dev, 0,
-                                 rows_max, static_cast<const uint16_t*>(c->Wt), d_in, d, nullptr, d_in, 1,
-                                 E, d, 0, s);
+            launch_gemm_nt<true>(c, KID_ENCODE_BF16, static_cast<const uint16_t*>(X), d_in, c->cfg.vocab_n,
+                                 uniq, u_dev, 0, rows_max, static_cast<const uint16_t*>(c->Wt), d_in, d, d,
+                                 nullptr, d_in, 1, E, d, 0, s);
         } else {
             launch(c, KID_ENCODE_BF16, k_encode_bf16, dim3((d + BN - 1) / BN, (unsigned)((rows_max + BM - 1) / BM)),
                    dim3(kBlock), s, static_cast<const uint16_t*>(X),
@@ -581,8 +808,8 @@ void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s)
                static_cast<const uint16_t*>(X), c->id_of_slot, c->scal, 0, d_in, c->cfg.pad_id, c->XT, c->ldt);
         launch(c, KID_TRANSPOSE_G, k_transpose_g, dim3(1024), dim3(kBlock), s, c->G, c->scal, d, c->GT,
                c->ldt);
-        launch_gemm_nt<false>(c, KID_WGRAD_BF16, c->XT, c->ldt, nullptr, nullptr, d_in, d_in, c->GT, c->ldt, d,
-                              c->scal + kSUTotal, 0, S, c->wg_partial, d, (int64_t)d_in * d, s);
+        launch_gemm_nt<false>(c, KID_WGRAD_BF16, c->XT, c->ldt, d_in, nullptr, nullptr, d_in, d_in, c->GT,
+                              c->ldt, d, d, c->scal + kSUTotal, 0, S, c->wg_partial, d, (int64_t)d_in * d, s);
     } else {
         launch(c, KID_WGRAD_F32, k_wgrad_f32, dim3((d + 63) / 64, (d_in + 3) / 4, S), dim3(kBlock), s,
                static_cast<const float*>(X), c->id_of_slot, c->G, c->scal, d_in, d, c->cfg.pad_id, S,
