@@ -236,11 +236,15 @@ int gram_unique(gram_ctx* ctx, const int32_t* ids, int64_t m, int32_t* uniq, int
     c->have_unique = false;
     if (m > 0) {
         const int fix = c->cfg.pad_id >= 0 ? c->cfg.pad_id : 0;
-        const int r = radix_sort_pairs(c, ids, nullptr, (int)m, nullptr, m, true, fix, s);
-        c->sorted_keys = c->keys[r];
-        c->perm = c->vals[r];
+        if (!unique_small(c, ids, (int)m, fix, uniq, inverse, counts, u_dev, s)) {
+            const int r = radix_sort_pairs(c, ids, nullptr, (int)m, nullptr, m, true, fix, s);
+            c->sorted_keys = c->keys[r];
+            c->perm = c->vals[r];
+            unique_from_sorted(c, (int)m, uniq, inverse, counts, u_dev, s);
+        }
+    } else {
+        unique_from_sorted(c, 0, uniq, inverse, counts, u_dev, s);
     }
-    unique_from_sorted(c, (int)m, uniq, inverse, counts, u_dev, s);
     if (int rc = launch_status(c, "gram_unique")) return rc;
     c->have_unique = true;
     c->unique_consumed = false;
@@ -293,6 +297,7 @@ int gram_grad_accumulate(gram_ctx* ctx, const float* dH, int64_t m, int32_t step
     if (int rc = launch_status(c, "gram_grad_accumulate")) return rc;
     c->unique_consumed = true;
     c->steps_done += 1;
+    c->window_positions += m;
     return GRAM_OK;
 }
 
@@ -316,6 +321,7 @@ int gram_flush(gram_ctx* ctx, int32_t* uniq_total, int32_t* counts_total, float*
     flush_export(c, uniq_total, counts_total, G_total, u_total_dev, s);
     c->have_unique = false;     // the sort buffers were reused
     c->steps_done = 0;
+    c->window_positions = 0;
     if (int rc = launch_status(c, "gram_flush")) return rc;
     if (u_total_host) {
         if (int rc = sync_scalars(c, s, "gram_flush")) return rc;
@@ -328,7 +334,7 @@ static const char* const kKernelNames[KID_COUNT] = {
     "radix_hist", "radix_scan", "radix_scatter", "heads_count", "heads_emit", "counts", "unique_empty",
     "transpose_w", "encode_bf16", "encode_f32", "gather_rows", "slot_count", "slot_emit", "seg_reduce",
     "seg_combine", "wgrad_bf16", "wgrad_f32", "wgrad_reduce", "transpose_x", "transpose_g", "flush_meta",
-    "flush_rows", "flush_finish"};
+    "flush_rows", "flush_finish", "unique_small"};
 
 int gram_kernel_count(void) { return KID_COUNT; }
 

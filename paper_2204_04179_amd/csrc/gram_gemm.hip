@@ -715,7 +715,7 @@ void encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
             launch(c, KID_TRANSPOSE_U16, k_transpose_u16, dim3((d + 31) / 32, (d_in + 31) / 32), dim3(kBlock), s,
                    static_cast<const uint16_t*>(W), d_in, d, static_cast<uint16_t*>(c->Wt));
         }
-        if (rows_max >= 4096 && d_in % TK == 0) {
+        if (rows_max >= 512 && d_in % TK == 0) {
             launch_gemm_nt<true>(c, KID_ENCODE_BF16, static_cast<const uint16_t*>(X), d_in, c->cfg.vocab_n,
                                  uniq, u_dev, 0, rows_max, static_cast<const uint16_t*>(c->Wt), d_in, d, d,
                                  nullptr, d_in, 1, E, d, 0, s);
@@ -781,6 +781,7 @@ __global__ __launch_bounds__(kBlock) void k_wgrad_reduce(const float4* __restric
     const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (e >= n4) return;
     float4 acc = partial[e];
+#pragma unroll 8
     for (int z = 1; z < splits; ++z) {
         const float4 v = partial[(int64_t)z * n4 + e];
         acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
@@ -802,8 +803,15 @@ int64_t wgrad_pitch_for(int64_t cap_total) { return (cap_total + TT - 1) / TT * 
 
 void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s)
 {
-    const int d_in = c->cfg.d_in, d = c->cfg.d, S = c->wg_splits;
+    const int d_in = c->cfg.d_in, d = c->cfg.d;
+    int S = c->wg_splits;
     if (c->cfg.xw_dtype == GRAM_BF16) {
+        // a short window does not need all the ranges: at least 8 slabs of 32 buffer rows each
+        // (from the host's bound on the rows in the buffer), still a multiple of 8
+        const int64_t slabs_bound = (c->window_positions < c->cap_total ? c->window_positions : c->cap_total) / TK + 1;
+        int64_t want = slabs_bound / 8 / 8 * 8;
+        if (want < 8) want = 8;
+        if (want < S) S = (int)want;
         launch(c, KID_TRANSPOSE_X, k_transpose_x, dim3(1024), dim3(kBlock), s,
                static_cast<const uint16_t*>(X), c->id_of_slot, c->scal, 0, d_in, c->cfg.pad_id, c->XT, c->ldt);
         launch(c, KID_TRANSPOSE_G, k_transpose_g, dim3(1024), dim3(kBlock), s, c->G, c->scal, d, c->GT,

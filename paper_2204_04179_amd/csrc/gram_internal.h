@@ -35,7 +35,7 @@ enum KernelId {
     KID_RADIX_HIST = 0, KID_RADIX_SCAN, KID_RADIX_SCATTER, KID_HEADS_COUNT, KID_HEADS_EMIT, KID_COUNTS,
     KID_UNIQUE_EMPTY, KID_TRANSPOSE_U16, KID_ENCODE_BF16, KID_ENCODE_F32, KID_GATHER_ROWS,
     KID_SLOT_COUNT, KID_SLOT_EMIT, KID_SEG_REDUCE, KID_SEG_COMBINE, KID_WGRAD_BF16, KID_WGRAD_F32,
-    KID_WGRAD_REDUCE, KID_TRANSPOSE_X, KID_TRANSPOSE_G, KID_FLUSH_META, KID_FLUSH_ROWS, KID_FLUSH_FINISH, KID_COUNT
+    KID_WGRAD_REDUCE, KID_TRANSPOSE_X, KID_TRANSPOSE_G, KID_FLUSH_META, KID_FLUSH_ROWS, KID_FLUSH_FINISH, KID_UNIQUE_SMALL, KID_COUNT
 };
 
 struct ProfSlot {
@@ -98,6 +98,7 @@ struct Ctx {
     bool unique_consumed = false;  // the current batch was already accumulated
     int64_t cur_m = 0;
     int32_t steps_done = 0;
+    int64_t window_positions = 0;  // positions accumulated in this window: bounds the buffer rows
     int* h_pinned = nullptr;    // [4] pinned host scratch for small read-backs
     std::string last_error;
 };
@@ -138,6 +139,9 @@ int64_t sort_table_elems(const SortPlan& p);
 int radix_sort_pairs(Ctx* c, const int* keys_in, const int* vals_in, int n_host, const int* n_dev,
                      int64_t n_max, bool check_range, int fix_key, hipStream_t s);
 void unique_from_sorted(Ctx* c, int n, int* uniq, int* inverse, int* counts, int* u_out, hipStream_t s);
+// One-launch dedup for small batches; returns false if n is too large for it.
+bool unique_small(Ctx* c, const int* ids, int n, int fix_key, int* uniq, int* inverse, int* counts,
+                  int* u_out, hipStream_t s);
 
 // ---- gram_stream.hip -----------------------------------------------------
 void gather_rows(Ctx* c, const float* E, const int* inverse, int64_t m, float* H, hipStream_t s);

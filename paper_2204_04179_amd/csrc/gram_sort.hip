@@ -356,6 +356,174 @@ __global__ void k_unique_empty(int* u_ws, int* u_out, int* offsets)
     }
 }
 
+// ---- small batches: the whole dedup in one block ------------------------------------
+//
+// Up to kSmallMaxN positions: keys and positions live in LDS, the radix passes
+// (8-bit digits, 16 waves, same ballot ranking as above), the head-flag scan and
+// the compaction all run in one launch of 1024 threads.  A step of the
+// paper-shaped KT and news batches moves a few microseconds of HBM traffic, so
+// its cost is the number of launches.
+constexpr int kSmallThreads = 1024;
+constexpr int kSmallWaves = kSmallThreads / kWave;
+constexpr int kSmallMaxN = 8192;
+constexpr int kSmallBits = 8;
+constexpr int kSmallBins = 1 << kSmallBits;
+constexpr size_t kSmallLds = (size_t)(4 * kSmallMaxN + kSmallWaves * kSmallBins + 2 * kSmallWaves) * sizeof(int);
+
+// Exclusive scan of one value per thread over the 1024-thread block.
+__device__ __forceinline__ int block1024_excl_scan(int v, int* total, int* wsum /*[2*kSmallWaves]*/)
+{
+    const int incl = wave_incl_scan(v);
+    if (lane_id() == kWave - 1) wsum[wave_id()] = incl;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kSmallWaves; ++w) {
+        const int t = wsum[w];
+        if (w < wave_id()) base += t;
+        tot += t;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + incl - v;
+}
+
+__global__ __launch_bounds__(kSmallThreads) void k_unique_small(
+    const int* __restrict__ ids, int n, int key_bits, int vocab_n, int fix_key, int* __restrict__ err,
+    int* __restrict__ sorted_keys, int* __restrict__ perm, int* __restrict__ uniq,
+    int* __restrict__ inverse, int* __restrict__ counts, int* __restrict__ offsets,
+    int* __restrict__ seg_of_row, int* __restrict__ uniq_ws, int* __restrict__ u_ws,
+    int* __restrict__ u_out)
+{
+    extern __shared__ int lds[];
+    // keys of order `o` at lds + o * kSmallMaxN, positions at lds + (2 + o) * kSmallMaxN
+#define KBUF(o) (lds + (o) * kSmallMaxN)
+#define VBUF(o) (lds + (2 + (o)) * kSmallMaxN)
+    int* cnt_all = lds + 4 * kSmallMaxN;                 // [kSmallWaves][kSmallBins]
+    int* wsum = cnt_all + kSmallWaves * kSmallBins;
+    const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+
+    bool bad = false;
+    for (int i = tid; i < n; i += kSmallThreads) {
+        int k = ids[i];
+        if (k < 0 || k >= vocab_n) { bad = true; k = fix_key; }
+        KBUF(0)[i] = k;
+        VBUF(0)[i] = i;
+    }
+    if (bad) atomicOr(err, kErrBitRange);
+    __syncthreads();
+
+    // wave w owns the contiguous chunk [w * cw, (w + 1) * cw) of the current order
+    const int cw = ((n + kSmallWaves - 1) / kSmallWaves + kWave - 1) / kWave * kWave;
+    const int cbeg = wave * cw;
+    const int cend = cbeg + cw < n ? cbeg + cw : n;
+    volatile int* cnt = cnt_all + wave * kSmallBins;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    int cur = 0;
+    for (int shift = 0; shift < key_bits; shift += kSmallBits) {
+        for (int b = lane; b < kSmallBins; b += kWave) cnt[b] = 0;
+        __syncthreads();
+        for (int i = cbeg + lane; i < cend; i += kWave)
+            atomicAdd(&cnt_all[wave * kSmallBins + ((KBUF(cur)[i] >> shift) & (kSmallBins - 1))], 1);
+        __syncthreads();
+        {   // exclusive scan in (digit, wave) order; thread t owns digit t / 4, waves 4 (t % 4) .. + 3
+            const int dg = tid >> 2, w0 = (tid & 3) * 4;
+            int v[4], sum = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                v[i] = cnt_all[(w0 + i) * kSmallBins + dg];
+                sum += v[i];
+            }
+            int total;
+            int run = block1024_excl_scan(sum, &total, wsum);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                cnt_all[(w0 + i) * kSmallBins + dg] = run;
+                run += v[i];
+            }
+        }
+        __syncthreads();
+        for (int i0 = cbeg; i0 < cend; i0 += kWave) {        // wave-uniform trip count
+            const int i = i0 + lane;
+            const bool valid = i < cend;
+            const int k = valid ? KBUF(cur)[i] : 0;
+            const int v = valid ? VBUF(cur)[i] : 0;
+            const int dg = (k >> shift) & (kSmallBins - 1);
+            unsigned long long peers = __ballot(valid);
+#pragma unroll
+            for (int bit = 0; bit < kSmallBits; ++bit) {
+                const bool one = (dg >> bit) & 1;
+                const unsigned long long mm = __ballot(one);
+                peers &= one ? mm : ~mm;
+            }
+            const int below = __popcll(peers & lt_mask);
+            int pos = 0;
+            if (valid) pos = cnt[dg] + below;
+            __builtin_amdgcn_wave_barrier();
+            if (valid && below == 0) cnt[dg] = pos + __popcll(peers);
+            __builtin_amdgcn_wave_barrier();
+            if (valid && (unsigned)pos < (unsigned)n) {
+                KBUF(cur ^ 1)[pos] = k;
+                VBUF(cur ^ 1)[pos] = v;
+            }
+        }
+        __syncthreads();
+        cur ^= 1;
+    }
+
+    // head flags and their scan: thread t owns the 8 sorted rows 8 t .. 8 t + 7 and leaves each
+    // row's segment index in LDS; the outputs are then written with consecutive threads on
+    // consecutive rows, so that the stores of a wave coalesce
+    const int* sk = KBUF(cur);
+    const int* sv = VBUF(cur);
+    int* lseg = KBUF(cur ^ 1);     // free after the last pass: segment index of every sorted row
+    int* loff = VBUF(cur ^ 1);     //                           first sorted row of every segment
+    const int r0 = tid * 8;
+    bool f[8];
+    int sum = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = r0 + i;
+        f[i] = r < n && (r == 0 || sk[r] != sk[r - 1]);
+        sum += f[i] ? 1 : 0;
+    }
+    int total;
+    int run = block1024_excl_scan(sum, &total, wsum);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = r0 + i;
+        if (r < n) {
+            run += f[i] ? 1 : 0;
+            lseg[r] = run - 1;
+            if (f[i]) loff[run - 1] = r;
+        }
+    }
+    if (tid == 0) {
+        *u_ws = total;
+        if (u_out) *u_out = total;
+        offsets[total] = n;
+    }
+    __syncthreads();
+    for (int r = tid; r < n; r += kSmallThreads) {
+        const int seg = lseg[r];
+        const int p = sv[r];
+        sorted_keys[r] = sk[r];
+        perm[r] = p;
+        seg_of_row[r] = seg;
+        inverse[p] = seg;
+    }
+    for (int j = tid; j < total; j += kSmallThreads) {
+        const int r = loff[j];
+        const int key = sk[r];
+        uniq[j] = key;
+        uniq_ws[j] = key;
+        offsets[j] = r;
+        counts[j] = (j + 1 < total ? loff[j + 1] : n) - r;
+    }
+#undef KBUF
+#undef VBUF
+}
+
 void unique_from_sorted(Ctx* c, int n, int* uniq, int* inverse, int* counts, int* u_out,
                         hipStream_t s)
 {
@@ -371,6 +539,24 @@ void unique_from_sorted(Ctx* c, int n, int* uniq, int* inverse, int* counts, int
     const int64_t cap = n < c->cap_u ? n : c->cap_u;
     launch(c, KID_COUNTS, k_counts, dim3((unsigned)((cap + kBlock - 1) / kBlock)), dim3(kBlock), s,
                        c->offsets, c->scal + kSU, counts);
+}
+
+bool unique_small(Ctx* c, const int* ids, int n, int fix_key, int* uniq, int* inverse, int* counts,
+                  int* u_out, hipStream_t s)
+{
+    if (n <= 0 || n > kSmallMaxN) return false;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_unique_small),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmallLds);
+        attr_set = true;
+    }
+    c->sorted_keys = c->keys[0];
+    c->perm = c->vals[0];
+    launch_smem(c, KID_UNIQUE_SMALL, k_unique_small, dim3(1), dim3(kSmallThreads), kSmallLds, s, ids, n,
+                c->key_bits, c->cfg.vocab_n, fix_key, c->scal + kSErr, c->sorted_keys, c->perm, uniq, inverse,
+                counts, c->offsets, c->seg_of_row, c->uniq_ws, c->scal + kSU, u_out);
+    return true;
 }
 
 }  // namespace gram

@@ -210,10 +210,73 @@ __global__ __launch_bounds__(kBlock) void k_slot_emit(
     }
 }
 
+// Small batches: the same result from one block that walks the tiles in order (one launch).
+__global__ __launch_bounds__(kBlock) void k_slot_small(
+    const int* __restrict__ uniq_ws, const int* __restrict__ offsets, int* __restrict__ slot_of,
+    int* __restrict__ id_of_slot, int* __restrict__ cnt_of_slot, int* __restrict__ seg_slot,
+    int* __restrict__ scal, int cap_total)
+{
+    __shared__ int sm[kWavesPerBlock];
+    const int u = scal[kSU];
+    int run_base = scal[kSUTotal];
+    bool overflow = false;
+    for (int j0 = threadIdx.x * 4; j0 - threadIdx.x * 4 < u; j0 += kScanTile) {   // uniform trip count
+        int id[4], old[4], sflag = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            id[i] = 0;
+            old[i] = 0;
+            if (j0 + i < u) {
+                id[i] = uniq_ws[j0 + i];
+                old[i] = slot_of[id[i]];
+                sflag += old[i] < 0 ? 1 : 0;
+            }
+        }
+        int total;
+        int run = run_base + block_excl_scan(sflag, &total, sm);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int j = j0 + i;
+            if (j < u) {
+                const int cnt = offsets[j + 1] - offsets[j];
+                if (old[i] < 0) {
+                    const int slot = run++;
+                    if (slot < cap_total) {
+                        slot_of[id[i]] = slot;
+                        id_of_slot[slot] = id[i];
+                        cnt_of_slot[slot] = cnt;
+                        seg_slot[j] = slot | kSlotNew;
+                    } else {
+                        seg_slot[j] = -1;
+                        overflow = true;
+                    }
+                } else {
+                    cnt_of_slot[old[i]] += cnt;
+                    seg_slot[j] = old[i];
+                }
+            }
+        }
+        run_base += total;
+    }
+    if (overflow) atomicOr(&scal[kSErr], kErrBitCapacity);
+    __syncthreads();      // every thread has read scal[kSUTotal] before it changes
+    if (threadIdx.x == 0) {
+        scal[kSUTotal] = run_base < cap_total ? run_base : cap_total;
+        scal[kSLongCount] = 0;
+    }
+}
+
+constexpr int64_t kSmallBatch = 8 * kScanTile;   // positions up to which one-block variants are used
+
 void assign_slots(Ctx* c, hipStream_t s)
 {
     int64_t bound = c->cur_m < c->cap_u ? c->cur_m : c->cap_u;
     if (bound < 1) bound = 1;
+    if (bound <= kSmallBatch) {
+        launch(c, KID_SLOT_EMIT, k_slot_small, dim3(1), dim3(kBlock), s, c->uniq_ws, c->offsets, c->slot_of,
+               c->id_of_slot, c->cnt_of_slot, c->seg_slot, c->scal, (int)c->cap_total);
+        return;
+    }
     const int tiles = (int)((bound + kScanTile - 1) / kScanTile);
     launch(c, KID_SLOT_COUNT, k_slot_count, dim3(tiles), dim3(kBlock), s, c->uniq_ws, c->slot_of, c->scal,
                        c->tile_sums);
@@ -418,7 +481,7 @@ __global__ __launch_bounds__(kBlock) void k_flush_meta(
     for (int r = blockIdx.x * kBlock + threadIdx.x; r < n; r += gridDim.x * kBlock) {
         const int id = sorted_ids[r];
         if (uniq_total) uniq_total[r] = id;
-        if (counts_total) counts_total[r] = cnt_of_slot[sorted_slots[r]];
+        if (counts_total) counts_total[r] = cnt_of_slot[sorted_slots ? sorted_slots[r] : r];
         slot_of[id] = -1;
     }
 }
@@ -435,7 +498,7 @@ __global__ __launch_bounds__(kBlock) void k_flush_rows(const int* __restrict__ s
         const int64_t r = i / cols4;
         const int cc = (int)(i % cols4);
         const f32x4 t = __builtin_nontemporal_load(
-            reinterpret_cast<const f32x4*>(G) + (int64_t)sorted_slots[r] * cols4 + cc);
+            reinterpret_cast<const f32x4*>(G) + (int64_t)(sorted_slots ? sorted_slots[r] : (int)r) * cols4 + cc);
         __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(G_total) + i);
     }
 }
@@ -453,10 +516,16 @@ __global__ void k_flush_finish(int* __restrict__ scal, int* __restrict__ u_total
 void flush_export(Ctx* c, int* uniq_total, int* counts_total, float* G_total, int* u_total_dev,
                   hipStream_t s)
 {
-    const int r = radix_sort_pairs(c, c->id_of_slot, nullptr, 0, c->scal + kSUTotal, c->cap_total,
-                                   false, 0, s);
-    const int* sorted_ids = c->keys[r];
-    const int* sorted_slots = c->vals[r];
+    // After one step the buffer rows are already in ascending ID order (rows are handed out in
+    // that order within a step); only later steps append out of order.
+    const int* sorted_ids = c->id_of_slot;
+    const int* sorted_slots = nullptr;
+    if (c->steps_done > 1) {
+        const int r = radix_sort_pairs(c, c->id_of_slot, nullptr, 0, c->scal + kSUTotal, c->cap_total,
+                                       false, 0, s);
+        sorted_ids = c->keys[r];
+        sorted_slots = c->vals[r];
+    }
     int64_t blocks = (c->cap_total + kBlock - 1) / kBlock;
     if (blocks > 1024) blocks = 1024;
     launch(c, KID_FLUSH_META, k_flush_meta, dim3((unsigned)blocks), dim3(kBlock), s, sorted_ids,

@@ -147,7 +147,8 @@ def check_single(ids, X, W, dH, n, tol, tol_sum, **kw):
     return out, ref
 
 
-@pytest.mark.parametrize("m", [1, 2, 63, 64, 65, 255, 1023, 1025, 4097])
+# batches of up to 8192 positions take the one-launch dedup kernel, larger ones the multi-kernel sort
+@pytest.mark.parametrize("m", [1, 2, 63, 64, 65, 255, 1023, 1025, 4097, 8191, 8192, 8193, 20001])
 @pytest.mark.parametrize("bf16", [False, True])
 def test_ragged_sizes(m, bf16):
     say(f"ragged m={m} bf16={bf16}")
@@ -159,26 +160,28 @@ def test_degenerate_batches():
     n = 300
     for label, ids in (("all distinct", np.random.default_rng(0).permutation(n - 1).astype(np.int32)[:200] + 1),
                        ("all equal", np.full(777, 5, np.int32)),
+                       ("all equal, multi-kernel path", np.full(9000, 5, np.int32)),
                        ("all padding", np.zeros(300, np.int32)),
+                       ("all padding, multi-kernel path", np.zeros(10000, np.int32)),
                        ("empty", np.zeros(0, np.int32))):
         say("degenerate:", label)
         ids, X, W, dH = small_problem(1, ids.size, n, ids=ids)
-        out, ref = check_single(ids, X, W, dH, n, 1e-5, 1e-5, max_positions=1024)
+        out, ref = check_single(ids, X, W, dH, n, 1e-5, 1e-5, max_positions=max(1024, ids.size))
         if label == "all distinct":
             # G is a row permutation of dH: bit-exact
             np.testing.assert_array_equal(out["G_total"][ref["inverse"]], dH)
-        if label == "all padding":
+        if label.startswith("all padding"):
             assert out["U_total"] == 1 and np.all(out["G_total"] == 0) and np.all(out["dW"] == 0)
         if label == "empty":
             assert out["U_total"] == 0
 
 
-@pytest.mark.parametrize("vocab_bits", [1, 10, 11, 20, 21])
-def test_vocabulary_sizes_change_the_radix_plan(vocab_bits):
+@pytest.mark.parametrize("m", [5000, 20000])
+@pytest.mark.parametrize("vocab_bits", [1, 8, 9, 10, 11, 16, 17, 20, 21, 24])
+def test_vocabulary_sizes_change_the_radix_plan(vocab_bits, m):
     n = (1 << vocab_bits) + (1 if vocab_bits in (10, 20) else 0)   # 2^b + 1 needs b+1 bits
-    say(f"vocab n={n}")
+    say(f"vocab n={n} m={m}")
     rng = np.random.default_rng(vocab_bits)
-    m = 5000
     ids = rng.integers(0, n, size=m).astype(np.int32)
     ids[::7] = n - 1
     ids[::11] = 0
@@ -192,7 +195,8 @@ def test_vocabulary_sizes_change_the_radix_plan(vocab_bits):
 def test_segment_lengths_around_tile_and_long_thresholds():
     """Runs of 1..400 equal IDs laid out so that segments start and end at every
     offset relative to the 32-row tiles and cross the 128-row 'long' threshold."""
-    lengths = [1, 2, 31, 32, 33, 1, 127, 128, 129, 1, 1, 160, 64, 400, 3, 96, 255, 256, 257, 5, 1000, 1]
+    lengths = [1, 2, 31, 32, 33, 1, 127, 128, 129, 1, 1, 160, 64, 400, 3, 96, 255, 256, 257, 5, 1000, 1,
+               4000, 7, 2500]      # 10,490 rows: beyond the one-launch dedup as well
     ids = np.concatenate([np.full(L, i + 1, np.int32) for i, L in enumerate(lengths)])
     rng = np.random.default_rng(3)
     ids = ids[rng.permutation(ids.size)]
