@@ -20,6 +20,16 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void lds_void;
 
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
 {
     uint32_t u = __float_as_uint(f);
@@ -745,6 +755,209 @@ void encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
 //   GT[c][s] = bf16(G[s][c])           (round to nearest even + transpose)
 // with rows padded by zeros up to a multiple of 64 buffer rows.
 
+// ---- weight gradient without transposed copies ---------------------------------------
+//
+// dW[i,c] = sum_s X[item_s, i] * bf16(G[s, c]): both operands have the contraction
+// index s (buffer row) as their slow dimension in memory.  Instead of first
+// writing transposed copies, this kernel loads 32 buffer rows x 256 features of
+// X (gathered through id_of_slot) and 32 x 256 columns of G per slab, rounds G
+// to bf16 in registers, parks both in LDS as [s][256] rows and builds the MFMA
+// fragments with the transposing LDS read of gfx950 (ds_read_b64_tr_b16): the
+// 16 lanes of a group supply the addresses of a 4 (s) x 16 (m) block as 8-byte
+// pieces (lane j: row j / 4, columns 4 (j % 4) .. + 3) and lane i of the group
+// receives column i of the 4 rows, i.e. 4 consecutive values of the contraction
+// index for one output row, which is the operand layout of
+// v_mfma_f32_32x32x16_bf16 (two such reads per 8-value fragment).
+// LDS rows are 512 bytes; 16-byte chunk p of row s sits at p ^ ((s & 3) << 1), so
+// the four rows of a group fall into four different 32-byte bank groups.
+// Loads go through buffer descriptors; a row past the end of the buffer, a
+// padding item or a column past the matrix edge is turned into an out-of-range
+// offset, for which the hardware returns zeros.
+// Same pipeline as k_gemm_nt_bf16: two register sets, two LDS stages, one
+// barrier per slab of 32 buffer rows; split-K with one K range per XCD.
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef short v8i16 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
+constexpr int WK = 32;                       // buffer rows per slab
+constexpr int WROWB = 512;                   // bytes per LDS row (256 bf16)
+constexpr int WOPB = WK * WROWB;             // bytes per operand and stage
+constexpr int WSTAGEB = 2 * WOPB;
+constexpr size_t WSMEM = 2 * (size_t)WSTAGEB;
+constexpr uint32_t kOutOfRange = 0xFFFFFFF0u;
+
+__global__ __launch_bounds__(kBlock) void k_wgrad_tn_bf16(
+    const uint16_t* __restrict__ X, uint32_t x_bytes, const int* __restrict__ id_of_slot,
+    const float* __restrict__ G, uint32_t g_bytes, const int* __restrict__ scal, int d_in, int d,
+    int pad_id, int splits, float* __restrict__ partial)
+{
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    const int tiles_c = (d + 255) / 256, tiles = ((d_in + 255) / 256) * tiles_c;
+    const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+    const int z = xcd + 8 * (q / tiles);
+    const int i0 = ((q % tiles) / tiles_c) * 256, c0 = ((q % tiles) % tiles_c) * 256;
+    if (z >= splits) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    const int U = scal[kSUTotal];
+    const int slabs_all = (U + WK - 1) / WK;
+    const int per = (slabs_all + splits - 1) / splits;
+    const int sl_begin = z * per;
+    int nslab = slabs_all - sl_begin;
+    if (nslab > per) nslab = per;
+    partial += (int64_t)z * d_in * d;
+
+    const __amdgpu_buffer_rsrc_t rsX = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(X), 0, x_bytes, kBufferFlags);
+    const __amdgpu_buffer_rsrc_t rsG = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(G), 0, g_bytes, kBufferFlags);
+
+    // X loader: instruction t of wave w moves buffer rows 8 w + 2 t and + 1 (lane / 32 picks the
+    // row), lane % 32 = position of the 16-byte chunk in the LDS row
+    const int a_row = wave * 8 + (lane >> 5);                        // + 2 t
+    const int a_pos = lane & 31;
+    // G loader: instruction t of wave w moves buffer row 8 w + t; lane l holds columns 4 l .. 4 l + 3
+    const int g_col = c0 + 4 * lane;
+    const bool g_col_ok = g_col < d;
+    unsigned char* parkA = smem + (wave * 8) * WROWB + lane * 16;    // + t * 1024 (two rows per t)
+    unsigned char* parkG = smem + WOPB + (wave * 8) * WROWB + (lane & 1) * 8;
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // fragment addresses (see the header comment): group g = lane / 16, j = lane % 16
+    const int j16 = lane & 15, grp = lane >> 4;
+    const int f_row = (grp >> 1) * 8 + (j16 >> 2);                   // + 16 ks + 4 h
+    const int f_x = ((j16 >> 2) & 3) << 1;
+    int f_off[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        f_off[i] = f_row * WROWB + (((i * 4 + (grp & 1) * 2 + ((j16 & 3) >> 1)) ^ f_x) * 16) + (j16 & 1) * 8;
+    const int baseA = wm * 256, baseB = WOPB + wn * 256;             // byte offset of the wave's quadrant
+
+    bf16x8 fa[2][4], fb[2][4];
+    v4i32 ra[2][4], rg[2][8];
+    int ids_next[4];
+
+#define GRAM_TR(PTR) __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(PTR))
+#define GRAM_FRAGS(FS, STAGE, KS)                                                                   \
+    {                                                                                               \
+        const unsigned char* sb_ = smem + (STAGE) * WSTAGEB + (KS) * 16 * WROWB;                    \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                             \
+            const v4i16 a0 = GRAM_TR(sb_ + baseA + f_off[i]);                                       \
+            const v4i16 a1 = GRAM_TR(sb_ + baseA + f_off[i] + 4 * WROWB);                           \
+            const v4i16 b0 = GRAM_TR(sb_ + baseB + f_off[i]);                                       \
+            const v4i16 b1 = GRAM_TR(sb_ + baseB + f_off[i] + 4 * WROWB);                           \
+            fa[FS][i] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7)); \
+            fb[FS][i] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7)); \
+        }                                                                                           \
+    }
+#define GRAM_MMA(FS)                                                                                \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                   \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j)                                               \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[FS][i], fb[FS][j], acc[i][j], 0, 0, 0);
+    // item IDs of the X rows this lane will fetch for slab SLAB (clamped: a slab past the end is
+    // loaded but never multiplied)
+#define GRAM_IDS(SLAB)                                                                              \
+    {                                                                                               \
+        const int sb_ = (sl_begin + ((SLAB) < last ? (SLAB) : last)) * WK;                          \
+        _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                             \
+            const int slot = sb_ + a_row + 2 * t;                                                   \
+            ids_next[t] = slot < U ? id_of_slot[slot] : pad_id;                                     \
+        }                                                                                           \
+    }
+#define GRAM_LOAD(SET, SLAB)                                                                        \
+    {                                                                                               \
+        const int sb_ = (sl_begin + ((SLAB) < last ? (SLAB) : last)) * WK;                          \
+        _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                             \
+            const int kk = a_row + 2 * t;                                                           \
+            const int feat = i0 + ((a_pos ^ ((kk & 3) << 1)) * 8);                                  \
+            const int id = ids_next[t];                                                             \
+            const bool ok = id != pad_id && feat < d_in && sb_ + kk < U;                            \
+            const uint32_t off = ok ? (uint32_t)(((int64_t)id * d_in + feat) * 2) : kOutOfRange;    \
+            ra[SET][t] = __builtin_amdgcn_raw_buffer_load_b128(rsX, off, 0, 0);                     \
+        }                                                                                           \
+        _Pragma("unroll") for (int t = 0; t < 8; ++t) {                                             \
+            const int slot = sb_ + wave * 8 + t;                                                    \
+            const uint32_t off = (g_col_ok && slot < U) ? (uint32_t)(((int64_t)slot * d + g_col) * 4) : kOutOfRange; \
+            rg[SET][t] = __builtin_amdgcn_raw_buffer_load_b128(rsG, off, 0, 0);                     \
+        }                                                                                           \
+    }
+#define GRAM_PARK(SET, STAGE)                                                                       \
+    {                                                                                               \
+        unsigned char* pa_ = parkA + (STAGE) * WSTAGEB;                                             \
+        unsigned char* pg_ = parkG + (STAGE) * WSTAGEB;                                             \
+        _Pragma("unroll") for (int t = 0; t < 4; ++t)                                               \
+            *reinterpret_cast<v4i32*>(pa_ + t * 1024) = ra[SET][t];                                 \
+        _Pragma("unroll") for (int t = 0; t < 8; ++t) {                                             \
+            const v4i32 v = rg[SET][t];                                                             \
+            const uint32_t lo = pack_bf16x2(__int_as_float(v.x), __int_as_float(v.y));              \
+            const uint32_t hi = pack_bf16x2(__int_as_float(v.z), __int_as_float(v.w));              \
+            const int pos = (lane >> 1) ^ ((t & 3) << 1);        /* row 8 w + t: (row & 3) == (t & 3) */ \
+            *reinterpret_cast<uint2*>(pg_ + t * WROWB + pos * 16) = make_uint2(lo, hi);             \
+        }                                                                                           \
+    }
+    // (fixed interleaving patterns measured slower here than the compiler's own order)
+#define GRAM_ITER(SL, P)                                                                            \
+    {                                                                                               \
+        GRAM_FRAGS(1, (SL) & 1, 1)                                                                  \
+        GRAM_MMA(0)                                                                                 \
+        GRAM_PARK(P, ((SL) + 1) & 1)                                                                \
+        __syncthreads();                                                                            \
+        GRAM_LOAD(P, (SL) + 3)                                                                      \
+        GRAM_IDS((SL) + 4)                                                                          \
+        GRAM_FRAGS(0, ((SL) + 1) & 1, 0)                                                            \
+        GRAM_MMA(1)                                                                                 \
+    }
+
+    if (nslab > 0) {
+        const int last = nslab - 1;
+        GRAM_IDS(0)
+        GRAM_LOAD(0, 0)
+        GRAM_IDS(1)
+        GRAM_LOAD(1, 1)
+        GRAM_IDS(2)
+        GRAM_PARK(0, 0)
+        GRAM_LOAD(0, 2)
+        GRAM_IDS(3)
+        __syncthreads();
+        GRAM_FRAGS(0, 0, 0)
+        int sl = 0;
+        for (; sl + 1 < last; sl += 2) {
+            GRAM_ITER(sl, 1)          // set 1 holds slab sl+1, set 0 holds slab sl+2
+            GRAM_ITER(sl + 1, 0)
+        }
+        if (sl < last) GRAM_ITER(sl, 1)
+        GRAM_FRAGS(1, last & 1, 1)
+        GRAM_MMA(0)
+        GRAM_MMA(1)
+    }
+
+    // accumulator element r of a lane sits at (row, col) = ((r / 4) * 8 + (lane / 32) * 4 + r % 4, lane % 32)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int fi = i0 + wm * 128 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+            if (fi < d_in) {
+                float* row = partial + (int64_t)fi * d + c0 + wn * 128 + (lane & 31);
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+                    if (c0 + wn * 128 + jj * 32 + (lane & 31) < d) row[jj * 32] = acc[i][jj][r];
+            }
+        }
+}
+#undef GRAM_TR
+#undef GRAM_FRAGS
+#undef GRAM_MMA
+#undef GRAM_IDS
+#undef GRAM_LOAD
+#undef GRAM_PARK
+#undef GRAM_ITER
+
 __device__ __forceinline__ void split_range(int u_total, int splits, int z, int* kb, int* ke)
 {
     const int chunk = (u_total + splits - 1) / splits;
@@ -812,12 +1025,28 @@ void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s)
         int64_t want = slabs_bound / 8 / 8 * 8;
         if (want < 8) want = 8;
         if (want < S) S = (int)want;
-        launch(c, KID_TRANSPOSE_X, k_transpose_x, dim3(1024), dim3(kBlock), s,
-               static_cast<const uint16_t*>(X), c->id_of_slot, c->scal, 0, d_in, c->cfg.pad_id, c->XT, c->ldt);
-        launch(c, KID_TRANSPOSE_G, k_transpose_g, dim3(1024), dim3(kBlock), s, c->G, c->scal, d, c->GT,
-               c->ldt);
-        launch_gemm_nt<false>(c, KID_WGRAD_BF16, c->XT, c->ldt, d_in, nullptr, nullptr, d_in, d_in, c->GT,
-                              c->ldt, d, d, c->scal + kSUTotal, 0, S, c->wg_partial, d, (int64_t)d_in * d, s);
+        const int64_t x_bytes = (int64_t)c->cfg.vocab_n * d_in * 2, g_bytes = c->cap_total * d * 4;
+        const int64_t window = ((int64_t)1 << 32) - 16;
+        if (x_bytes < window && g_bytes < window) {
+            static bool attr_set = false;
+            if (!attr_set) {
+                (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_wgrad_tn_bf16),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)WSMEM);
+                attr_set = true;
+            }
+            const int tiles = ((d_in + 255) / 256) * ((d + 255) / 256);
+            launch_smem(c, KID_WGRAD_BF16, k_wgrad_tn_bf16, dim3((unsigned)(tiles * S)), dim3(kBlock), WSMEM, s,
+                        static_cast<const uint16_t*>(X), (uint32_t)x_bytes, c->id_of_slot, c->G, (uint32_t)g_bytes,
+                        c->scal, d_in, d, c->cfg.pad_id, S, c->wg_partial);
+        } else {
+            // operands beyond the 4 GiB buffer window: transposed bf16 copies + the NT kernel
+            launch(c, KID_TRANSPOSE_X, k_transpose_x, dim3(1024), dim3(kBlock), s,
+                   static_cast<const uint16_t*>(X), c->id_of_slot, c->scal, 0, d_in, c->cfg.pad_id, c->XT, c->ldt);
+            launch(c, KID_TRANSPOSE_G, k_transpose_g, dim3(1024), dim3(kBlock), s, c->G, c->scal, d, c->GT,
+                   c->ldt);
+            launch_gemm_nt<false>(c, KID_WGRAD_BF16, c->XT, c->ldt, d_in, nullptr, nullptr, d_in, d_in, c->GT,
+                                  c->ldt, d, d, c->scal + kSUTotal, 0, S, c->wg_partial, d, (int64_t)d_in * d, s);
+        }
     } else {
         launch(c, KID_WGRAD_F32, k_wgrad_f32, dim3((d + 63) / 64, (d_in + 3) / 4, S), dim3(kBlock), s,
                static_cast<const float*>(X), c->id_of_slot, c->G, c->scal, d_in, d, c->cfg.pad_id, S,
