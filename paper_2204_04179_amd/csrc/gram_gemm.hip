@@ -376,8 +376,9 @@ constexpr int RSTAGES = 2;
 constexpr size_t RSMEM = (size_t)RSTAGES * TSTAGEB;
 constexpr uint32_t kBufferFlags = 0x00027000;   // raw buffer: 32-bit elements, no swizzle
 
-template <bool GATHER>
-__global__ __launch_bounds__(kBlock) void k_gemm_nt_bf16(
+// NW = waves per block: 4 (each 128x128, one wave per SIMD) or 8 (each 128x64, two per SIMD).
+template <bool GATHER, int NW>
+__global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
     const uint16_t* __restrict__ A, int64_t lda, uint32_t a_bytes, const int* __restrict__ row_ids,
     const int* __restrict__ m_dev, int m_host, const uint16_t* __restrict__ B, int64_t ldb,
     uint32_t b_bytes, int n, const int* __restrict__ k_dev, int k_host, int splits, int pad_id,
@@ -400,7 +401,9 @@ __global__ __launch_bounds__(kBlock) void k_gemm_nt_bf16(
     }
     if (m0 >= M || z >= splits) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    constexpr int NT = NW == 4 ? 4 : 2;          // 32-column MFMA tiles per wave
+    constexpr int GA = 16 / NW;                  // 16-row groups of A (and of B) a wave loads per slab
+    const int wm = NW == 4 ? wave >> 1 : wave >> 2, wn = NW == 4 ? wave & 1 : wave & 3;
     if (tid == 0) s_pad_row = -1;
     __syncthreads();
 
@@ -412,17 +415,17 @@ __global__ __launch_bounds__(kBlock) void k_gemm_nt_bf16(
     if (nslab > per) nslab = per;
     C += (int64_t)z * split_stride;
 
-    // loader: wave w moves row groups g = 4 w + t (16 rows each) of A and of B; lane l moves the
+    // loader: wave w moves row groups g = GA w + t (16 rows each) of A and of B; lane l moves the
     // chunk that belongs at position l & 3 of row 16 g + (l >> 2).  Rows past M / past n are
     // clamped to a valid row: their products are never stored.
     const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(A), 0, a_bytes, kBufferFlags);
     const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(B), 0, b_bytes, kBufferFlags);
     const int lrow = lane >> 2;
     const int lchunk = (lane & 3) ^ ((lane >> 4) & 3);
-    uint32_t oa[4], ob[4];
+    uint32_t oa[GA], ob[GA];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int r = (wave * 4 + t) * 16 + lrow;
+    for (int t = 0; t < GA; ++t) {
+        const int r = (wave * GA + t) * 16 + lrow;
         const int j = m0 + r < M ? m0 + r : M - 1;
         int64_t rowA = j;
         if (GATHER) {
@@ -434,39 +437,39 @@ __global__ __launch_bounds__(kBlock) void k_gemm_nt_bf16(
         const int nn = n0 + r;
         ob[t] = (uint32_t)(((int64_t)(nn < n ? nn : n - 1) * ldb + (int64_t)sl_begin * TK + lchunk * 8) * 2);
     }
-    unsigned char* park = smem + (wave * 4) * 1024 + lane * 16;
+    unsigned char* park = smem + (wave * GA) * 1024 + lane * 16;
 
-    f32x16 acc[4][4];
+    f32x16 acc[4][NT];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NT; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     const int ph0 = (lane >> 5) ^ ((lane >> 2) & 3);
     const int offA = (wm * 128 + (lane & 31)) * TROWB;
-    const int offB = (TM + wn * 128 + (lane & 31)) * TROWB;
+    const int offB = (TM + wn * (NT * 32) + (lane & 31)) * TROWB;
     const int c0 = ph0 * 16, c1 = (ph0 ^ 2) * 16;
-    bf16x8 fa[2][4], fb[2][4];
-    v4i32 ra[2][4], rb[2][4];
+    bf16x8 fa[2][4], fb[2][NT];
+    v4i32 ra[2][GA], rb[2][GA];
 #define GRAM_FRAGS(FS, STAGE, COFF)                                                                 \
     {                                                                                               \
         const unsigned char* sb_ = smem + (STAGE) * TSTAGEB;                                        \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                             \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                               \
             fa[FS][i] = *reinterpret_cast<const bf16x8*>(sb_ + offA + i * 32 * TROWB + (COFF));     \
+        _Pragma("unroll") for (int i = 0; i < NT; ++i)                                              \
             fb[FS][i] = *reinterpret_cast<const bf16x8*>(sb_ + offB + i * 32 * TROWB + (COFF));     \
-        }                                                                                           \
     }
 #define GRAM_MMA(FS)                                                                                \
     _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                   \
-        _Pragma("unroll") for (int j = 0; j < 4; ++j)                                               \
+        _Pragma("unroll") for (int j = 0; j < NT; ++j)                                              \
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[FS][i], fb[FS][j], acc[i][j], 0, 0, 0);
     // Slabs past the end are clamped to the last one (their data is never multiplied).
 #define GRAM_LOAD(SET, SLAB)                                                                        \
     {                                                                                               \
         const uint32_t k_ = (uint32_t)(((SLAB) < last ? (SLAB) : last) * (TK * 2));                 \
-        _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                             \
+        _Pragma("unroll") for (int t = 0; t < GA; ++t) {                                            \
             ra[SET][t] = __builtin_amdgcn_raw_buffer_load_b128(rsA, oa[t] + k_, 0, 0);              \
             rb[SET][t] = __builtin_amdgcn_raw_buffer_load_b128(rsB, ob[t] + k_, 0, 0);              \
         }                                                                                           \
@@ -474,7 +477,7 @@ __global__ __launch_bounds__(kBlock) void k_gemm_nt_bf16(
 #define GRAM_PARK(SET, STAGE)                                                                       \
     {                                                                                               \
         unsigned char* p_ = park + (STAGE) * TSTAGEB;                                               \
-        _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                             \
+        _Pragma("unroll") for (int t = 0; t < GA; ++t) {                                            \
             *reinterpret_cast<v4i32*>(p_ + t * 1024) = ra[SET][t];                                  \
             *reinterpret_cast<v4i32*>(p_ + TM * TROWB + t * 1024) = rb[SET][t];                     \
         }                                                                                           \
@@ -485,18 +488,18 @@ __global__ __launch_bounds__(kBlock) void k_gemm_nt_bf16(
     // second half: k-step 1 MFMAs with the global loads of slab +3 and the fragment reads of the
     // next slab's k-step 0
 #define GRAM_SCHED_FIRST                                                                            \
-    _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                                 \
+    if (NW == 4) _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                                 \
         __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                          \
         __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                          \
     }                                                                                               \
-    _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                                 \
+    if (NW == 4) _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                    \
         __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                          \
         __builtin_amdgcn_sched_group_barrier(0x200, 2, 0);                                          \
     }
     // (for the gathered forward the compiler's own order measured 2 % faster, for the streamed
     // weight gradient the fixed pattern 25 % faster)
 #define GRAM_SCHED_SECOND                                                                           \
-    if (!GATHER) {                                                                                  \
+    if (!GATHER && NW == 4) {                                                                       \
         _Pragma("unroll") for (int g = 0; g < 8; ++g) {                                             \
             __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                      \
             __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                      \
@@ -543,10 +546,10 @@ __global__ __launch_bounds__(kBlock) void k_gemm_nt_bf16(
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int lr = wm * 128 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                float* row = C + (int64_t)(m0 + lr) * ldc + n0 + wn * 128 + (lane & 31);
+                float* row = C + (int64_t)(m0 + lr) * ldc + n0 + wn * (NT * 32) + (lane & 31);
                 const bool zero = lr == pad_row;
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) row[jj * 32] = zero ? 0.f : acc[i][jj][r];
+                for (int jj = 0; jj < NT; ++jj) row[jj * 32] = zero ? 0.f : acc[i][jj][r];
             }
     } else {
 #pragma unroll
@@ -555,11 +558,11 @@ __global__ __launch_bounds__(kBlock) void k_gemm_nt_bf16(
             for (int r = 0; r < 16; ++r) {
                 const int lr = wm * 128 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
                 if (m0 + lr < M) {
-                    float* row = C + (int64_t)(m0 + lr) * ldc + n0 + wn * 128 + (lane & 31);
+                    float* row = C + (int64_t)(m0 + lr) * ldc + n0 + wn * (NT * 32) + (lane & 31);
                     const bool zero = lr == pad_row;
 #pragma unroll
-                    for (int jj = 0; jj < 4; ++jj)
-                        if (n0 + wn * 128 + jj * 32 + (lane & 31) < n) row[jj * 32] = zero ? 0.f : acc[i][jj][r];
+                    for (int jj = 0; jj < NT; ++jj)
+                        if (n0 + wn * (NT * 32) + jj * 32 + (lane & 31) < n) row[jj * 32] = zero ? 0.f : acc[i][jj][r];
                 }
             }
     }
@@ -572,6 +575,8 @@ __global__ __launch_bounds__(kBlock) void k_gemm_nt_bf16(
 #undef GRAM_SCHED_SECOND
 #undef GRAM_ITER
 
+constexpr int kGemmWaves = 8;
+
 // a_rows / b_rows: rows of the matrices A and B as allocated (A: all rows that row_ids may name).
 template <bool GATHER>
 static void launch_gemm_nt(Ctx* c, int kid, const uint16_t* A, int64_t lda, int64_t a_rows,
@@ -582,7 +587,7 @@ static void launch_gemm_nt(Ctx* c, int kid, const uint16_t* A, int64_t lda, int6
 {
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16<GATHER>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16<GATHER, kGemmWaves>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)RSMEM);
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16_dma<GATHER>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)TSMEM);
@@ -597,7 +602,7 @@ static void launch_gemm_nt(Ctx* c, int kid, const uint16_t* A, int64_t lda, int6
     const int64_t a_bytes = a_rows * lda * 2, b_bytes = b_rows * ldb * 2;
     const int64_t window = (int64_t)1 << 32;
     if (a_bytes < window && b_bytes < window)
-        launch_smem(c, kid, k_gemm_nt_bf16<GATHER>, dim3((unsigned)blocks), dim3(kBlock), RSMEM, s, A, lda,
+        launch_smem(c, kid, k_gemm_nt_bf16<GATHER, kGemmWaves>, dim3((unsigned)blocks), dim3(kGemmWaves * 64), RSMEM, s, A, lda,
                     (uint32_t)a_bytes, row_ids, m_dev, m_host, B, ldb, (uint32_t)b_bytes, n, k_dev, k_host,
                     splits, c->cfg.pad_id, n_tiles, C, ldc, split_stride);
     else
