@@ -76,8 +76,10 @@ class Runner:
         seen = np.zeros(w.N, bool)
         self.stats = []
         for a in self.ids_np:
-            u = np.unique(a)
-            self.stats.append(dict(U=int(u.size), U_old=int(seen[u].sum()), M_valid=int((a != 0).sum())))
+            u, cnt = np.unique(a, return_counts=True)
+            heavy = cnt > self.g.light_max()
+            self.stats.append(dict(U=int(u.size), U_old=int(seen[u].sum()), M_valid=int((a != 0).sum()),
+                                   U_heavy=int(heavy.sum()), P_heavy=int(cnt[heavy].sum())))
             seen[u] = True
         self.U_total = int(seen.sum())
         self.M_valid_per_step = float(np.mean([s["M_valid"] for s in self.stats]))
@@ -98,16 +100,31 @@ class Runner:
             self.step()
 
     # algorithmic bytes / flops per launch, averaged over the steps of a window
-    def algorithmic(self):
+    def algorithmic(self, fused=False):
+        """Bytes / flops the method itself has to move per launch.  `fused`: the forward ran as the
+        contraction with the gather in its epilogue (items of at most light_max positions) plus the
+        copy kernel for the heavy items, instead of encode-to-E followed by gather."""
         M, d, d_in = self.M, self.d, self.d_in
         sx = 4 if self.w.xw_dtype == "f32" else 2
         n = len(self.stats)
         avg = lambda f: sum(f(s) for s in self.stats) / n
-        return {
-            "seg_reduce": dict(bound="hbm", bytes=avg(lambda s: 4 * s["M_valid"] * d + 4 * M + 4 * s["U"] * d + 4 * s["U_old"] * d)),
+        fwd = {
             "gather_rows": dict(bound="hbm", bytes=avg(lambda s: 4 * M + 4 * s["U"] * d + 4 * M * d)),
             "encode_bf16": dict(bound="mfma", flops=avg(lambda s: 2 * s["U"] * d_in * d),
                                 bytes=avg(lambda s: s["U"] * d_in * sx + d_in * d * sx + 4 * s["U"] * d)),
+        }
+        if fused:
+            fwd = {
+                # X rows, W, perm + offsets, H rows of the light items, E rows of the heavy ones
+                "encode_bf16": dict(bound="mfma", flops=avg(lambda s: 2 * s["U"] * d_in * d),
+                                    bytes=avg(lambda s: s["U"] * d_in * sx + d_in * d * sx + 4 * M + 8 * s["U"]
+                                              + 4 * d * (M - s["P_heavy"] + s["U_heavy"]))),
+                # seg_of_row + perm + offsets, E rows of the heavy items, their H rows
+                "gather_heavy": dict(bound="hbm", bytes=avg(lambda s: 12 * M + 4 * d * (s["U_heavy"] + s["P_heavy"]))),
+            }
+        return {
+            **fwd,
+            "seg_reduce": dict(bound="hbm", bytes=avg(lambda s: 4 * s["M_valid"] * d + 4 * M + 4 * s["U"] * d + 4 * s["U_old"] * d)),
             "encode_f32": dict(bound="alu", flops=avg(lambda s: 2 * s["U"] * d_in * d),
                                bytes=avg(lambda s: s["U"] * d_in * sx + d_in * d * sx + 4 * s["U"] * d)),
             "wgrad_bf16": dict(bound="mfma", flops=2 * self.U_total * d_in * d,
@@ -263,7 +280,8 @@ def main():
         r.step()
     torch.cuda.synchronize()
     kernels = kernel_breakdown(r)
-    alg = r.algorithmic()
+    fused = "gather_heavy" in kernels
+    alg = r.algorithmic(fused)
     dominant = max((k for k in kernels if k in alg), key=lambda k: kernels[k]["total_us_per_step"])
     dt, prof = time_steps(r, args.steps, args.warmup, profile_kernel=dominant)
     n, ms = prof[dominant]
@@ -277,8 +295,10 @@ def main():
         if k in alg:
             v.update({kk: vv for kk, vv in roofline_for(k, v["avg_us"], alg).items()
                       if kk in ("bound", "achieved", "peak", "unit", "frac")})
-    mem_us = sum(kernels[k]["total_us_per_step"] for k in ("gather_rows", "seg_reduce") if k in kernels)
-    mem_bytes = sum(alg[k]["bytes"] for k in ("gather_rows", "seg_reduce"))
+    # the HBM-bound part of a step: forward (encode + gather, H is its dominant traffic) and accumulate
+    mem_kernels = [k for k in ("encode_bf16", "encode_f32", "gather_rows", "gather_heavy", "seg_reduce") if k in kernels]
+    mem_us = sum(kernels[k]["total_us_per_step"] for k in mem_kernels)
+    mem_bytes = sum(alg[k]["bytes"] for k in mem_kernels)
 
     out = {
         "metric": "item_occurrences_per_sec", "value": value, "unit": "occurrences/s",
@@ -293,7 +313,8 @@ def main():
                    "boost_ratio": r.M_valid_per_step / float(np.mean([s["U"] - (1 if w.padding else 0) for s in r.stats])),
                    "flush_exports_G": not args.no_export_G, "workspace_bytes": r.ws_bytes},
         "roofline": roof,
-        "hbm_kernels": {"gather_plus_accumulate_GBs": mem_bytes / (mem_us * 1e-6) / 1e9 if mem_us else None,
+        "hbm_kernels": {"kernels": mem_kernels, "algorithmic_bytes": mem_bytes, "us": mem_us,
+                        "encode_gather_accumulate_GBs": mem_bytes / (mem_us * 1e-6) / 1e9 if mem_us else None,
                         "frac_of_8TBs": mem_bytes / (mem_us * 1e-6) / 1e9 / HBM_PEAK_GBS if mem_us else None},
         "kernels": kernels,
     }

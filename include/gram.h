@@ -109,8 +109,16 @@ int gram_unique(gram_ctx* ctx, const int32_t* ids, int64_t m, int32_t* uniq, int
  *   m        the m of that gram_unique
  *   E        DEVICE [>= min(m,N), d], nullable   out: E[j,:] = X[uniq[j],:].W,
  *            zero row for the padding ID; NULL keeps E in the workspace
- *   H        DEVICE [m,d]      out: H[p,:] = E[inverse[p],:] (zero at padding)
- * Requires a preceding gram_unique on this context (GRAM_ERR_SEQUENCE). */
+ *   H        DEVICE [m,d]      out: H[p,:] = E[inverse[p],:] (zero at padding);
+ *            16-byte aligned
+ * Requires a preceding gram_unique on this context (GRAM_ERR_SEQUENCE).
+ * When uniq and inverse are the very buffers that gram_unique wrote, large bf16
+ * batches take a fused path: the contraction stores each representation
+ * straight to the positions of its item (using the sort order kept in the
+ * context) and E is written only if the caller passes a buffer for it; an
+ * item with more than gram_light_max() positions is copied to them by a second
+ * kernel.  Any other uniq / inverse pair takes the two-kernel path (encode to
+ * E, then gather).  The results are identical. */
 int gram_encode_gather(gram_ctx* ctx, const void* X, const void* W, const int32_t* uniq,
                        const int32_t* inverse, const int32_t* u_dev, int64_t m, float* E, float* H,
                        void* stream);
@@ -164,6 +172,10 @@ int gram_check(gram_ctx* ctx, void* stream);
  */
 int gram_kernel_count(void);
 const char* gram_kernel_name(int k);
+/* Largest number of positions of an item that the fused forward still stores
+ * from the contraction's epilogue (a benchmark needs it to count the bytes
+ * each of the two forward kernels moves). */
+int gram_light_max(void);
 int gram_profile_enable(gram_ctx* ctx, uint32_t mask, int32_t max_launches);
 int gram_profile_read(gram_ctx* ctx, int k, int64_t* launches, double* total_ms);
 

@@ -176,6 +176,12 @@ int gram_create(gram_ctx** out, const gram_config* cfg)
     c->key_bits = bits_for(cfg->vocab_n);
     c->wg_splits = dv.splits;
     c->ws_bytes = layout(nullptr, *cfg, dv, nullptr);
+    {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+            c->num_cus = cus;
+    }
     hipError_t e = hipMalloc((void**)&c->ws_base, (size_t)c->ws_bytes);
     if (e != hipSuccess) {
         int rc = fail(nullptr, GRAM_ERR_HIP, "gram_create: hipMalloc(%lld bytes): %s",
@@ -247,6 +253,8 @@ int gram_unique(gram_ctx* ctx, const int32_t* ids, int64_t m, int32_t* uniq, int
     }
     if (int rc = launch_status(c, "gram_unique")) return rc;
     c->have_unique = true;
+    c->last_uniq = uniq;
+    c->last_inverse = inverse;
     c->unique_consumed = false;
     c->cur_m = m;
     if (u_host) {
@@ -273,8 +281,13 @@ int gram_encode_gather(gram_ctx* ctx, const void* X, const void* W, const int32_
     if (m == 0) return GRAM_OK;
     float* Ep = E ? E : c->E_ws;
     const int* up = u_dev ? u_dev : c->scal + kSU;
-    encode_forward(c, X, W, uniq, up, m < c->cap_u ? m : c->cap_u, Ep, s);
-    gather_rows(c, Ep, inverse, m, H, s);
+    // The fused epilogue walks the sorted order of the last dedup, so it applies only when the
+    // caller hands back that call's own outputs.
+    const bool own = uniq == c->last_uniq && inverse == c->last_inverse;
+    if (encode_forward(c, X, W, uniq, up, m < c->cap_u ? m : c->cap_u, Ep, s, own ? H : nullptr, E != nullptr))
+        gather_heavy(c, Ep, m, H, s);
+    else
+        gather_rows(c, Ep, inverse, m, H, s);
     return launch_status(c, "gram_encode_gather");
 }
 
@@ -334,9 +347,11 @@ static const char* const kKernelNames[KID_COUNT] = {
     "radix_hist", "radix_scan", "radix_scatter", "heads_count", "heads_emit", "counts", "unique_empty",
     "transpose_w", "encode_bf16", "encode_f32", "gather_rows", "slot_count", "slot_emit", "seg_reduce",
     "seg_combine", "wgrad_bf16", "wgrad_f32", "wgrad_reduce", "transpose_x", "transpose_g", "flush_meta",
-    "flush_rows", "flush_finish", "unique_small"};
+    "flush_rows", "flush_finish", "unique_small", "gather_heavy"};
 
 int gram_kernel_count(void) { return KID_COUNT; }
+
+int gram_light_max(void) { return kLightMax; }
 
 const char* gram_kernel_name(int k) { return (k >= 0 && k < KID_COUNT) ? kKernelNames[k] : ""; }
 

@@ -374,15 +374,36 @@ __global__ __launch_bounds__(kBlock) void k_gemm_nt_bf16_dma(
 typedef int v4i32 __attribute__((ext_vector_type(4)));
 constexpr int RSTAGES = 2;
 constexpr size_t RSMEM = (size_t)RSTAGES * TSTAGEB;
+// fused-gather epilogue: 64 staged rows of TN floats (+16 bytes against bank conflicts)
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kScatterRowB = TN * 4 + 16;
+constexpr int kScatterTileB = 64 * kScatterRowB;
+constexpr size_t RSMEM_SC = kScatterTileB > (int)RSMEM ? (size_t)kScatterTileB : RSMEM;
 constexpr uint32_t kBufferFlags = 0x00027000;   // raw buffer: 32-bit elements, no swizzle
 
 // NW = waves per block: 4 (each 128x128, one wave per SIMD) or 8 (each 128x64, two per SIMD).
-template <bool GATHER, int NW>
+//
+// SCATTER (forward only): the epilogue is the gather of Section 3.1 as well.  Row j of the
+// product is the representation of unique item j; instead of only storing it to C it is stored
+// to H[p,:] for every position p of that item (the positions of item j are perm[seg_off[j] ..
+// seg_off[j+1]) in the sorted order of the dedup step), so the representations never make a
+// round trip through memory.  Items with more than kLightMax positions are written to C once
+// and copied to their positions by k_gather_heavy: a few hundred very popular items own half
+// of the positions, and unrolling their copies here would stall a whole tile on one row.
+struct ScatterArgs {
+    const int* seg_off;   // [U + 1]
+    const int* perm;      // [m] positions in sorted order
+    float* H;             // [m, ldh]
+    int64_t ldh;
+    int write_all;        // also store every row to C (the caller asked for E)
+};
+
+template <bool GATHER, int NW, bool SCATTER>
 __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
     const uint16_t* __restrict__ A, int64_t lda, uint32_t a_bytes, const int* __restrict__ row_ids,
     const int* __restrict__ m_dev, int m_host, const uint16_t* __restrict__ B, int64_t ldb,
     uint32_t b_bytes, int n, const int* __restrict__ k_dev, int k_host, int splits, int pad_id,
-    int n_tiles, float* __restrict__ C, int64_t ldc, int64_t split_stride)
+    int n_tiles, float* __restrict__ C, int64_t ldc, int64_t split_stride, ScatterArgs sc)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     __shared__ int s_pad_row;
@@ -438,6 +459,28 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
         ob[t] = (uint32_t)(((int64_t)(nn < n ? nn : n - 1) * ldb + (int64_t)sl_begin * TK + lchunk * 8) * 2);
     }
     unsigned char* park = smem + (wave * GA) * 1024 + lane * 16;
+
+    // (fused gather) position ranges and position lists of the rows this wave will store in the
+    // epilogue; fetched here so that their latency hides behind the contraction
+    constexpr int RPW = 64 / NW;             // rows per wave and epilogue round
+    int seg_o = 0, seg_n = 0;
+    int pv[SCATTER ? 4 * RPW : 1];
+    if (SCATTER) {
+        {
+            const int k = lane & (4 * RPW - 1);
+            const int lr = (wave / (NW / 2)) * 128 + (k / RPW) * 32 + (wave % (NW / 2)) * RPW + k % RPW;
+            if (m0 + lr < M) {
+                seg_o = sc.seg_off[m0 + lr];
+                seg_n = sc.seg_off[m0 + lr + 1] - seg_o;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 4 * RPW; ++k) {
+            const int cnt = __builtin_amdgcn_readlane(seg_n, k);
+            const int o = __builtin_amdgcn_readlane(seg_o, k);
+            pv[k] = (cnt <= kLightMax && lane < cnt) ? sc.perm[o + lane] : 0;
+        }
+    }
 
     f32x16 acc[4][NT];
 #pragma unroll
@@ -540,7 +583,53 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
 
     // accumulator element r of a lane sits at (row, col) = ((r / 4) * 8 + (lane / 32) * 4 + r % 4, lane % 32)
     const int pad_row = GATHER ? s_pad_row : -1;
-    if (m0 + TM <= M && n0 + TN <= n) {
+    if (SCATTER) {
+        // The stages are dead.  The tile goes through LDS 64 rows at a time (the 32 rows of MFMA
+        // row block i of both wave rows), so that a wave can then store whole 1 KiB row pieces,
+        // 16 bytes per lane: once to C for a heavy item, once per position for a light one.
+        // Wave w stores rows (w / 4) * 128 + i * 32 + (w % 4) * 8 + u of the tile (u < 8) in round
+        // i; lane l < 32 fetches the position range of row i = l / 8, u = l % 8, and the position
+        // lists themselves (lane t: position t of the row) are fetched for all 32 rows at once,
+        // so their latency is paid once.
+        const bool col_ok = n0 + lane * 4 < n;
+        // The position lists arrived long ago.  Reading them here once makes the compiler wait for
+        // them here once; otherwise every row's store loop would begin with a wait for all vector
+        // memory operations, i.e. for the stores of the rows before it.
+#pragma unroll
+        for (int k = 0; k < 4 * RPW; ++k) asm volatile("" : "+v"(pv[k]));
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int rr = (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                const bool zero = wm * 128 + i * 32 + rr == pad_row;
+                float* dst = reinterpret_cast<float*>(smem + (wm * 32 + rr) * kScatterRowB) +
+                             wn * (NT * 32) + (lane & 31);
+#pragma unroll
+                for (int jj = 0; jj < NT; ++jj) dst[jj * 32] = zero ? 0.f : acc[i][jj][r];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < RPW; ++u) {
+                const int cr = (wave / (NW / 2)) * 32 + (wave % (NW / 2)) * RPW + u;   // staged row
+                const int lr = (cr >> 5) * 128 + i * 32 + (cr & 31);                    // row of the tile
+                const int cnt = __builtin_amdgcn_readlane(seg_n, i * RPW + u);
+                if (cnt == 0) continue;
+                const f32x4 v = *reinterpret_cast<const f32x4*>(smem + cr * kScatterRowB + lane * 16);
+                if (cnt > kLightMax || sc.write_all) {
+                    if (col_ok) *reinterpret_cast<f32x4*>(C + (int64_t)(m0 + lr) * ldc + n0 + lane * 4) = v;
+                    if (cnt > kLightMax) continue;
+                }
+                for (int t = 0; t < cnt; ++t) {
+                    const int pos = __builtin_amdgcn_readlane(pv[i * RPW + u], t);
+                    if (col_ok)
+                        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(sc.H + (int64_t)pos * sc.ldh + n0 + lane * 4));
+                }
+            }
+            __syncthreads();
+        }
+    } else if (m0 + TM <= M && n0 + TN <= n) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -583,12 +672,14 @@ static void launch_gemm_nt(Ctx* c, int kid, const uint16_t* A, int64_t lda, int6
                            const int* row_ids, const int* m_dev, int m_host, int64_t m_bound,
                            const uint16_t* B, int64_t ldb, int64_t b_rows, int n, const int* k_dev,
                            int k_host, int splits, float* C, int64_t ldc, int64_t split_stride,
-                           hipStream_t s)
+                           hipStream_t s, const ScatterArgs* scatter = nullptr)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16<GATHER, kGemmWaves>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16<GATHER, kGemmWaves, false>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)RSMEM);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16<GATHER, kGemmWaves, GATHER>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)(GATHER ? RSMEM_SC : RSMEM));
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16_dma<GATHER>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)TSMEM);
         attr_set = true;
@@ -601,10 +692,17 @@ static void launch_gemm_nt(Ctx* c, int kid, const uint16_t* A, int64_t lda, int6
         blocks = ((m_bound + TM - 1) / TM) * n_tiles * splits;
     const int64_t a_bytes = a_rows * lda * 2, b_bytes = b_rows * ldb * 2;
     const int64_t window = (int64_t)1 << 32;
-    if (a_bytes < window && b_bytes < window)
-        launch_smem(c, kid, k_gemm_nt_bf16<GATHER, kGemmWaves>, dim3((unsigned)blocks), dim3(kGemmWaves * 64), RSMEM, s, A, lda,
-                    (uint32_t)a_bytes, row_ids, m_dev, m_host, B, ldb, (uint32_t)b_bytes, n, k_dev, k_host,
-                    splits, c->cfg.pad_id, n_tiles, C, ldc, split_stride);
+    const ScatterArgs none = {nullptr, nullptr, nullptr, 0, 0};
+    if (scatter)
+        launch_smem(c, kid, k_gemm_nt_bf16<GATHER, kGemmWaves, GATHER>, dim3((unsigned)blocks),
+                    dim3(kGemmWaves * 64), GATHER ? RSMEM_SC : RSMEM, s, A, lda, (uint32_t)a_bytes, row_ids,
+                    m_dev, m_host, B, ldb, (uint32_t)b_bytes, n, k_dev, k_host, splits, c->cfg.pad_id,
+                    n_tiles, C, ldc, split_stride, *scatter);
+    else if (a_bytes < window && b_bytes < window)
+        launch_smem(c, kid, k_gemm_nt_bf16<GATHER, kGemmWaves, false>, dim3((unsigned)blocks),
+                    dim3(kGemmWaves * 64), RSMEM, s, A, lda, (uint32_t)a_bytes, row_ids, m_dev, m_host, B,
+                    ldb, (uint32_t)b_bytes, n, k_dev, k_host, splits, c->cfg.pad_id, n_tiles, C, ldc,
+                    split_stride, none);
     else
         launch_smem(c, kid, k_gemm_nt_bf16_dma<GATHER>, dim3((unsigned)blocks), dim3(kBlock), TSMEM, s, A,
                     lda, row_ids, m_dev, m_host, B, ldb, n, k_dev, k_host, splits, c->cfg.pad_id, n_tiles,
@@ -714,10 +812,10 @@ __global__ __launch_bounds__(kBlock) void k_encode_f32(
     E[(int64_t)j * d + c] = acc;
 }
 
-void encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const int* u_dev,
-                    int64_t rows_max, float* E, hipStream_t s)
+bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const int* u_dev,
+                    int64_t rows_max, float* E, hipStream_t s, float* H_scatter, bool caller_wants_E)
 {
-    if (rows_max <= 0) return;
+    if (rows_max <= 0) return false;
     const int d_in = c->cfg.d_in, d = c->cfg.d;
     if (c->cfg.xw_dtype == GRAM_BF16) {
         // W^T; d_in is a multiple of 8, so 16-byte row chunks of W^T never straddle its end
@@ -731,9 +829,16 @@ void encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
                    static_cast<const uint16_t*>(W), d_in, d, static_cast<uint16_t*>(c->Wt));
         }
         if (rows_max >= 512 && d_in % TK == 0) {
+            const int64_t window = (int64_t)1 << 32;
+            // Fusing the gather pays when there are tiles for every CU: with a handful of tiles the
+            // position stores of a tile run on one CU while a separate gather spreads over all.
+            const int64_t tile_bound = ((rows_max + TM - 1) / TM) * ((d + TN - 1) / TN);
+            const bool fuse = H_scatter && (int64_t)c->cfg.vocab_n * d_in * 2 < window && tile_bound >= c->num_cus;
+            const ScatterArgs sc = {c->offsets, c->perm, H_scatter, (int64_t)d, caller_wants_E ? 1 : 0};
             launch_gemm_nt<true>(c, KID_ENCODE_BF16, static_cast<const uint16_t*>(X), d_in, c->cfg.vocab_n,
                                  uniq, u_dev, 0, rows_max, static_cast<const uint16_t*>(c->Wt), d_in, d, d,
-                                 nullptr, d_in, 1, E, d, 0, s);
+                                 nullptr, d_in, 1, E, d, 0, s, fuse ? &sc : nullptr);
+            return fuse;
         } else {
             launch(c, KID_ENCODE_BF16, k_encode_bf16, dim3((d + BN - 1) / BN, (unsigned)((rows_max + BM - 1) / BM)),
                    dim3(kBlock), s, static_cast<const uint16_t*>(X),
@@ -744,6 +849,7 @@ void encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
                dim3(kBlock), s, static_cast<const float*>(X), static_cast<const float*>(W), uniq, u_dev,
                d_in, d, c->cfg.pad_id, E);
     }
+    return false;
 }
 
 // ---- weight gradient -----------------------------------------------------------
@@ -789,8 +895,11 @@ constexpr int WOPB = WK * WROWB;             // bytes per operand and stage
 constexpr int WSTAGEB = 2 * WOPB;
 constexpr size_t WSMEM = 2 * (size_t)WSTAGEB;
 constexpr uint32_t kOutOfRange = 0xFFFFFFF0u;
+constexpr int kWgradWaves = 8;
 
-__global__ __launch_bounds__(kBlock) void k_wgrad_tn_bf16(
+// NW = waves per block: 4 (128x128 each) or 8 (128x64 each, two per SIMD).
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
     const uint16_t* __restrict__ X, uint32_t x_bytes, const int* __restrict__ id_of_slot,
     const float* __restrict__ G, uint32_t g_bytes, const int* __restrict__ scal, int d_in, int d,
     int pad_id, int splits, float* __restrict__ partial)
@@ -802,7 +911,13 @@ __global__ __launch_bounds__(kBlock) void k_wgrad_tn_bf16(
     const int i0 = ((q % tiles) / tiles_c) * 256, c0 = ((q % tiles) % tiles_c) * 256;
     if (z >= splits) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    constexpr int NT = NW == 4 ? 4 : 2;          // 32-column MFMA tiles per wave
+    constexpr int RW = 32 / NW;                  // buffer rows of a slab this wave loads
+    // register sets for loads in flight: two with one wave per SIMD (a load has two slabs to
+    // land); one with two waves per SIMD, where the other wave covers the wait and the
+    // registers are needed for the second wave to fit
+    constexpr int SETS = NW == 4 ? 2 : 1;
+    const int wm = NW == 4 ? wave >> 1 : wave >> 2, wn = NW == 4 ? wave & 1 : wave & 3;
 
     const int U = scal[kSUTotal];
     const int slabs_all = (U + WK - 1) / WK;
@@ -815,21 +930,21 @@ __global__ __launch_bounds__(kBlock) void k_wgrad_tn_bf16(
     const __amdgpu_buffer_rsrc_t rsX = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(X), 0, x_bytes, kBufferFlags);
     const __amdgpu_buffer_rsrc_t rsG = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(G), 0, g_bytes, kBufferFlags);
 
-    // X loader: instruction t of wave w moves buffer rows 8 w + 2 t and + 1 (lane / 32 picks the
+    // X loader: instruction t of wave w moves buffer rows RW w + 2 t and + 1 (lane / 32 picks the
     // row), lane % 32 = position of the 16-byte chunk in the LDS row
-    const int a_row = wave * 8 + (lane >> 5);                        // + 2 t
+    const int a_row = wave * RW + (lane >> 5);                        // + 2 t
     const int a_pos = lane & 31;
-    // G loader: instruction t of wave w moves buffer row 8 w + t; lane l holds columns 4 l .. 4 l + 3
+    // G loader: instruction t of wave w moves buffer row RW w + t; lane l holds columns 4 l .. 4 l + 3
     const int g_col = c0 + 4 * lane;
     const bool g_col_ok = g_col < d;
-    unsigned char* parkA = smem + (wave * 8) * WROWB + lane * 16;    // + t * 1024 (two rows per t)
-    unsigned char* parkG = smem + WOPB + (wave * 8) * WROWB + (lane & 1) * 8;
+    unsigned char* parkA = smem + (wave * RW) * WROWB + lane * 16;   // + t * 1024 (two rows per t)
+    unsigned char* parkG = smem + WOPB + (wave * RW) * WROWB + (lane & 1) * 8;
 
-    f32x16 acc[4][4];
+    f32x16 acc[4][NT];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NT; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
@@ -841,11 +956,11 @@ __global__ __launch_bounds__(kBlock) void k_wgrad_tn_bf16(
 #pragma unroll
     for (int i = 0; i < 4; ++i)
         f_off[i] = f_row * WROWB + (((i * 4 + (grp & 1) * 2 + ((j16 & 3) >> 1)) ^ f_x) * 16) + (j16 & 1) * 8;
-    const int baseA = wm * 256, baseB = WOPB + wn * 256;             // byte offset of the wave's quadrant
+    const int baseA = wm * 256, baseB = WOPB + wn * (NT * 64);             // byte offset of the wave's quadrant
 
-    bf16x8 fa[2][4], fb[2][4];
-    v4i32 ra[2][4], rg[2][8];
-    int ids_next[4];
+    bf16x8 fa[2][4], fb[2][NT];
+    v4i32 ra[SETS][RW / 2], rg[SETS][RW];
+    int ids_next[RW / 2];
 
 #define GRAM_TR(PTR) __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(PTR))
 #define GRAM_FRAGS(FS, STAGE, KS)                                                                   \
@@ -854,22 +969,24 @@ __global__ __launch_bounds__(kBlock) void k_wgrad_tn_bf16(
         _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                             \
             const v4i16 a0 = GRAM_TR(sb_ + baseA + f_off[i]);                                       \
             const v4i16 a1 = GRAM_TR(sb_ + baseA + f_off[i] + 4 * WROWB);                           \
+            fa[FS][i] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7)); \
+        }                                                                                           \
+        _Pragma("unroll") for (int i = 0; i < NT; ++i) {                                            \
             const v4i16 b0 = GRAM_TR(sb_ + baseB + f_off[i]);                                       \
             const v4i16 b1 = GRAM_TR(sb_ + baseB + f_off[i] + 4 * WROWB);                           \
-            fa[FS][i] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7)); \
             fb[FS][i] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7)); \
         }                                                                                           \
     }
 #define GRAM_MMA(FS)                                                                                \
     _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                   \
-        _Pragma("unroll") for (int j = 0; j < 4; ++j)                                               \
+        _Pragma("unroll") for (int j = 0; j < NT; ++j)                                              \
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[FS][i], fb[FS][j], acc[i][j], 0, 0, 0);
     // item IDs of the X rows this lane will fetch for slab SLAB (clamped: a slab past the end is
     // loaded but never multiplied)
 #define GRAM_IDS(SLAB)                                                                              \
     {                                                                                               \
         const int sb_ = (sl_begin + ((SLAB) < last ? (SLAB) : last)) * WK;                          \
-        _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                             \
+        _Pragma("unroll") for (int t = 0; t < RW / 2; ++t) {                                        \
             const int slot = sb_ + a_row + 2 * t;                                                   \
             ids_next[t] = slot < U ? id_of_slot[slot] : pad_id;                                     \
         }                                                                                           \
@@ -877,31 +994,31 @@ __global__ __launch_bounds__(kBlock) void k_wgrad_tn_bf16(
 #define GRAM_LOAD(SET, SLAB)                                                                        \
     {                                                                                               \
         const int sb_ = (sl_begin + ((SLAB) < last ? (SLAB) : last)) * WK;                          \
-        _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                             \
+        _Pragma("unroll") for (int t = 0; t < RW / 2; ++t) {                                        \
             const int kk = a_row + 2 * t;                                                           \
             const int feat = i0 + ((a_pos ^ ((kk & 3) << 1)) * 8);                                  \
             const int id = ids_next[t];                                                             \
             const bool ok = id != pad_id && feat < d_in && sb_ + kk < U;                            \
             const uint32_t off = ok ? (uint32_t)(((int64_t)id * d_in + feat) * 2) : kOutOfRange;    \
-            ra[SET][t] = __builtin_amdgcn_raw_buffer_load_b128(rsX, off, 0, 0);                     \
+            ra[(SET) % SETS][t] = __builtin_amdgcn_raw_buffer_load_b128(rsX, off, 0, 0);                     \
         }                                                                                           \
-        _Pragma("unroll") for (int t = 0; t < 8; ++t) {                                             \
-            const int slot = sb_ + wave * 8 + t;                                                    \
+        _Pragma("unroll") for (int t = 0; t < RW; ++t) {                                            \
+            const int slot = sb_ + wave * RW + t;                                                    \
             const uint32_t off = (g_col_ok && slot < U) ? (uint32_t)(((int64_t)slot * d + g_col) * 4) : kOutOfRange; \
-            rg[SET][t] = __builtin_amdgcn_raw_buffer_load_b128(rsG, off, 0, 0);                     \
+            rg[(SET) % SETS][t] = __builtin_amdgcn_raw_buffer_load_b128(rsG, off, 0, 0);                     \
         }                                                                                           \
     }
 #define GRAM_PARK(SET, STAGE)                                                                       \
     {                                                                                               \
         unsigned char* pa_ = parkA + (STAGE) * WSTAGEB;                                             \
         unsigned char* pg_ = parkG + (STAGE) * WSTAGEB;                                             \
-        _Pragma("unroll") for (int t = 0; t < 4; ++t)                                               \
-            *reinterpret_cast<v4i32*>(pa_ + t * 1024) = ra[SET][t];                                 \
-        _Pragma("unroll") for (int t = 0; t < 8; ++t) {                                             \
-            const v4i32 v = rg[SET][t];                                                             \
+        _Pragma("unroll") for (int t = 0; t < RW / 2; ++t)                                          \
+            *reinterpret_cast<v4i32*>(pa_ + t * 1024) = ra[(SET) % SETS][t];                                 \
+        _Pragma("unroll") for (int t = 0; t < RW; ++t) {                                            \
+            const v4i32 v = rg[(SET) % SETS][t];                                                             \
             const uint32_t lo = pack_bf16x2(__int_as_float(v.x), __int_as_float(v.y));              \
             const uint32_t hi = pack_bf16x2(__int_as_float(v.z), __int_as_float(v.w));              \
-            const int pos = (lane >> 1) ^ ((t & 3) << 1);        /* row 8 w + t: (row & 3) == (t & 3) */ \
+            const int pos = (lane >> 1) ^ ((t & 3) << 1);        /* row RW w + t: (row & 3) == (t & 3) */ \
             *reinterpret_cast<uint2*>(pg_ + t * WROWB + pos * 16) = make_uint2(lo, hi);             \
         }                                                                                           \
     }
@@ -912,8 +1029,8 @@ __global__ __launch_bounds__(kBlock) void k_wgrad_tn_bf16(
         GRAM_MMA(0)                                                                                 \
         GRAM_PARK(P, ((SL) + 1) & 1)                                                                \
         __syncthreads();                                                                            \
-        GRAM_LOAD(P, (SL) + 3)                                                                      \
-        GRAM_IDS((SL) + 4)                                                                          \
+        GRAM_LOAD(P, (SL) + 1 + SETS)                                                               \
+        GRAM_IDS((SL) + 2 + SETS)                                                                   \
         GRAM_FRAGS(0, ((SL) + 1) & 1, 0)                                                            \
         GRAM_MMA(1)                                                                                 \
     }
@@ -923,16 +1040,18 @@ __global__ __launch_bounds__(kBlock) void k_wgrad_tn_bf16(
         GRAM_IDS(0)
         GRAM_LOAD(0, 0)
         GRAM_IDS(1)
-        GRAM_LOAD(1, 1)
-        GRAM_IDS(2)
+        if (SETS == 2) {
+            GRAM_LOAD(1, 1)
+            GRAM_IDS(2)
+        }
         GRAM_PARK(0, 0)
-        GRAM_LOAD(0, 2)
-        GRAM_IDS(3)
+        GRAM_LOAD(0, SETS)
+        GRAM_IDS(SETS + 1)
         __syncthreads();
         GRAM_FRAGS(0, 0, 0)
         int sl = 0;
         for (; sl + 1 < last; sl += 2) {
-            GRAM_ITER(sl, 1)          // set 1 holds slab sl+1, set 0 holds slab sl+2
+            GRAM_ITER(sl, 1)          // (two sets) set 1 holds slab sl+1, set 0 holds slab sl+2
             GRAM_ITER(sl + 1, 0)
         }
         if (sl < last) GRAM_ITER(sl, 1)
@@ -948,10 +1067,10 @@ __global__ __launch_bounds__(kBlock) void k_wgrad_tn_bf16(
         for (int r = 0; r < 16; ++r) {
             const int fi = i0 + wm * 128 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
             if (fi < d_in) {
-                float* row = partial + (int64_t)fi * d + c0 + wn * 128 + (lane & 31);
+                float* row = partial + (int64_t)fi * d + c0 + wn * (NT * 32) + (lane & 31);
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj)
-                    if (c0 + wn * 128 + jj * 32 + (lane & 31) < d) row[jj * 32] = acc[i][jj][r];
+                for (int jj = 0; jj < NT; ++jj)
+                    if (c0 + wn * (NT * 32) + jj * 32 + (lane & 31) < d) row[jj * 32] = acc[i][jj][r];
             }
         }
 }
@@ -1035,12 +1154,12 @@ void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s)
         if (x_bytes < window && g_bytes < window) {
             static bool attr_set = false;
             if (!attr_set) {
-                (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_wgrad_tn_bf16),
+                (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_wgrad_tn_bf16<kWgradWaves>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)WSMEM);
                 attr_set = true;
             }
             const int tiles = ((d_in + 255) / 256) * ((d + 255) / 256);
-            launch_smem(c, KID_WGRAD_BF16, k_wgrad_tn_bf16, dim3((unsigned)(tiles * S)), dim3(kBlock), WSMEM, s,
+            launch_smem(c, KID_WGRAD_BF16, k_wgrad_tn_bf16<kWgradWaves>, dim3((unsigned)(tiles * S)), dim3(kWgradWaves * 64), WSMEM, s,
                         static_cast<const uint16_t*>(X), (uint32_t)x_bytes, c->id_of_slot, c->G, (uint32_t)g_bytes,
                         c->scal, d_in, d, c->cfg.pad_id, S, c->wg_partial);
         } else {

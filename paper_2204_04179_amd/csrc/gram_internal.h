@@ -19,6 +19,7 @@ constexpr int kMaxDigitBits = 10;       // radix digit width limit (1024 LDS bin
 constexpr int kScanTile = 1024;         // rows per block in the flag-scan kernels
 constexpr int kSegRows = 32;            // sorted rows per tile of the segment reduction
 constexpr int kSegLong = 128;           // segments with at least this many rows are reduced tile by tile
+constexpr int kLightMax = 32;           // items with more positions are gathered by a separate copy kernel
 constexpr int kSlotNew = 1 << 30;       // flag in seg_slot: the buffer row is created by this step
 constexpr int kFixCols4 = 16;           // float4 columns per block of the long-segment combine
 constexpr int kFixLanes = kBlock / kFixCols4;
@@ -35,7 +36,8 @@ enum KernelId {
     KID_RADIX_HIST = 0, KID_RADIX_SCAN, KID_RADIX_SCATTER, KID_HEADS_COUNT, KID_HEADS_EMIT, KID_COUNTS,
     KID_UNIQUE_EMPTY, KID_TRANSPOSE_U16, KID_ENCODE_BF16, KID_ENCODE_F32, KID_GATHER_ROWS,
     KID_SLOT_COUNT, KID_SLOT_EMIT, KID_SEG_REDUCE, KID_SEG_COMBINE, KID_WGRAD_BF16, KID_WGRAD_F32,
-    KID_WGRAD_REDUCE, KID_TRANSPOSE_X, KID_TRANSPOSE_G, KID_FLUSH_META, KID_FLUSH_ROWS, KID_FLUSH_FINISH, KID_UNIQUE_SMALL, KID_COUNT
+    KID_WGRAD_REDUCE, KID_TRANSPOSE_X, KID_TRANSPOSE_G, KID_FLUSH_META, KID_FLUSH_ROWS, KID_FLUSH_FINISH, KID_UNIQUE_SMALL,
+    KID_GATHER_HEAVY, KID_COUNT
 };
 
 struct ProfSlot {
@@ -83,6 +85,7 @@ struct Ctx {
     uint16_t* GT = nullptr;     // [d, ldt] bf16 copy of G, transposed (bf16 path)
     int64_t ldt = 0;            // row pitch of XT / GT in elements
     int wg_splits = 1;
+    int num_cus = 256;          // compute units of the device (one contraction block each)
 
     // sorted order of the current batch (point into keys[]/vals[])
     int* sorted_keys = nullptr;
@@ -95,6 +98,8 @@ struct Ctx {
 
     // --- host state ---
     bool have_unique = false;
+    const int* last_uniq = nullptr;      // outputs of the most recent gram_unique (identity only)
+    const int* last_inverse = nullptr;
     bool unique_consumed = false;  // the current batch was already accumulated
     int64_t cur_m = 0;
     int32_t steps_done = 0;
@@ -145,6 +150,7 @@ bool unique_small(Ctx* c, const int* ids, int n, int fix_key, int* uniq, int* in
 
 // ---- gram_stream.hip -----------------------------------------------------
 void gather_rows(Ctx* c, const float* E, const int* inverse, int64_t m, float* H, hipStream_t s);
+void gather_heavy(Ctx* c, const float* E, int64_t m, float* H, hipStream_t s);
 void assign_slots(Ctx* c, hipStream_t s);
 void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s);
 void flush_export(Ctx* c, int* uniq_total, int* counts_total, float* G_total, int* u_total_dev,
@@ -152,8 +158,11 @@ void flush_export(Ctx* c, int* uniq_total, int* counts_total, float* G_total, in
 void fill_i32(int* p, int64_t n, int v, hipStream_t s);
 
 // ---- gram_gemm.hip -------------------------------------------------------
-void encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const int* u_dev,
-                    int64_t rows_max, float* E, hipStream_t s);
+// Returns true when H_scatter was given and the contraction's epilogue has already written H
+// for every item with at most kLightMax positions (gather_heavy must follow); false when only E
+// was written (gather_rows must follow).
+bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const int* u_dev,
+                    int64_t rows_max, float* E, hipStream_t s, float* H_scatter, bool caller_wants_E);
 void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s);
 int wgrad_splits_for(const gram_config& cfg);
 int64_t wgrad_pitch_for(int64_t cap_total);

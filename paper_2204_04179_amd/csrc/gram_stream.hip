@@ -124,6 +124,56 @@ void gather_rows(Ctx* c, const float* E, const int* inverse, int64_t m, float* H
            rows_per_block);
 }
 
+// Second half of the fused forward: items with more than kLightMax positions were written to
+// E only; their rows are copied to their positions here.  Blocks walk the SORTED order (all
+// positions of an item adjacent), 64 rows each, and leave at once when none of their rows
+// belongs to such an item, so the row of E being copied stays in cache across many blocks.
+__global__ __launch_bounds__(kBlock) void k_gather_heavy(const f32x4* __restrict__ E,
+                                                         const int* __restrict__ seg_of_row,
+                                                         const int* __restrict__ offsets,
+                                                         const int* __restrict__ perm, int64_t m,
+                                                         int cols4, f32x4* __restrict__ H,
+                                                         int rows_per_block)
+{
+    __shared__ int s_src[64], s_dst[64];
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+    const int rows = (int)(r0 + rows_per_block < m ? rows_per_block : m - r0);
+    int heavy = 0;
+    if ((int)threadIdx.x < rows) {
+        const int j = seg_of_row[r0 + threadIdx.x];
+        heavy = offsets[j + 1] - offsets[j] > kLightMax;
+        s_src[threadIdx.x] = heavy ? j : -1;
+        s_dst[threadIdx.x] = perm[r0 + threadIdx.x];
+    }
+    if (!__syncthreads_or(heavy)) return;
+    // consecutive sorted rows mostly belong to one item: its row of E is loaded once and kept in
+    // registers while it is stored to position after position
+    for (int cp = threadIdx.x; cp < cols4; cp += kBlock) {
+        int cur = -1;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        for (int row = 0; row < rows; ++row) {
+            const int j = s_src[row];
+            if (j < 0) continue;
+            if (j != cur) {
+                v = E[(int64_t)j * cols4 + cp];
+                cur = j;
+            }
+            __builtin_nontemporal_store(v, &H[(int64_t)s_dst[row] * cols4 + cp]);
+        }
+    }
+}
+
+void gather_heavy(Ctx* c, const float* E, int64_t m, float* H, hipStream_t s)
+{
+    if (m == 0) return;
+    const int cols4 = c->cfg.d / 4;
+    const int rows_per_block = 64;      // the size of the kernel's row tables
+    const int64_t blocks = (m + rows_per_block - 1) / rows_per_block;
+    launch(c, KID_GATHER_HEAVY, k_gather_heavy, dim3((unsigned)blocks), dim3(kBlock), s,
+           reinterpret_cast<const f32x4*>(E), c->seg_of_row, c->offsets, c->perm, m, cols4,
+           reinterpret_cast<f32x4*>(H), rows_per_block);
+}
+
 // ---- buffer rows for the items of this batch --------------------------------
 //
 // An item seen for the first time in the window gets the next free row of the

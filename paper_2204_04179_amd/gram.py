@@ -21,7 +21,8 @@ STATUS_NAMES = {OK: "GRAM_OK", ERR_ARG: "GRAM_ERR_ARG", ERR_CAPACITY: "GRAM_ERR_
 
 EXPORTS = ("gram_workspace_bytes", "gram_create", "gram_destroy", "gram_unique", "gram_encode_gather",
            "gram_grad_accumulate", "gram_encoder_wgrad", "gram_flush", "gram_check", "gram_last_error",
-           "gram_kernel_count", "gram_kernel_name", "gram_profile_enable", "gram_profile_read")
+           "gram_kernel_count", "gram_kernel_name", "gram_light_max", "gram_profile_enable",
+           "gram_profile_read")
 
 
 class GramConfig(C.Structure):
@@ -70,6 +71,8 @@ def load():
     L.gram_last_error.argtypes = [vp]
     L.gram_kernel_count.restype = C.c_int
     L.gram_kernel_count.argtypes = []
+    L.gram_light_max.restype = C.c_int
+    L.gram_light_max.argtypes = []
     L.gram_kernel_name.restype = C.c_char_p
     L.gram_kernel_name.argtypes = [C.c_int]
     L.gram_profile_enable.restype = C.c_int
@@ -159,6 +162,9 @@ class Gram:
                                       _ptr(u_total_dev), C.byref(u_host) if want_host_u else None,
                                       _stream(stream)))
         return u_host.value if want_host_u else None
+
+    def light_max(self):
+        return int(self._lib.gram_light_max())
 
     def kernel_names(self):
         return [self._lib.gram_kernel_name(k).decode() for k in range(self._lib.gram_kernel_count())]

@@ -14,9 +14,14 @@ def to_dev(a, torch):
 
 
 def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=None, u_total_cap=0,
-               keep_H=True, keep_E=True, want_G=True, gram_obj=None, X_dev=None, W_dev=None):
+               keep_H=True, keep_E=True, want_G=True, gram_obj=None, X_dev=None, W_dev=None,
+               pass_E=True, foreign_buffers=False, profile=None):
     """batches: list of (ids int32 [m], dH float32 [m,d]).  Returns dict with per-step
-    uniq/inverse/counts/E/H and the window's uniq_total/counts_total/G_total/dW."""
+    uniq/inverse/counts/E/H and the window's uniq_total/counts_total/G_total/dW.
+    pass_E=False calls gram_encode_gather with E = NULL (no "E" in the result);
+    foreign_buffers=True hands it copies of uniq / inverse instead of the buffers gram_unique
+    wrote, which selects the two-kernel forward.  profile: kernel names whose launches are counted
+    (result key "profile": name -> (launches, ms))."""
     import torch
     from paper_2204_04179_amd import gram
 
@@ -26,6 +31,8 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
     M_max = max_positions or max(1, max(b[0].size for b in batches))
     cfg = gram.make_config(vocab_n, d_in, d, M_max, K, pad_id, u_total_cap, xw)
     g = gram_obj or gram.Gram(cfg)
+    if profile:
+        g.profile_enable(profile, max_launches=256)
     Xd = X_dev if X_dev is not None else to_dev(X, torch)
     Wd = W_dev if W_dev is not None else to_dev(W, torch)
     cap_u = max(1, min(M_max, vocab_n))
@@ -42,13 +49,14 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
         H = torch.full((max(1, m), d), float("nan"), device="cuda")
         U = g.unique(ids_d, uniq, inverse, counts, u_dev, want_host_u=True)
         assert int(u_dev.item()) == U
-        g.encode_gather(Xd, Wd, uniq, inverse, u_dev, m, E, H)
+        uq, inv = (uniq.clone(), inverse.clone()) if foreign_buffers else (uniq, inverse)
+        g.encode_gather(Xd, Wd, uq, inv, u_dev, m, E if pass_E else None, H)
         g.grad_accumulate(dH_d, m, k)
         torch.cuda.synchronize()
         st = dict(U=U, uniq=uniq[:U].cpu().numpy(), counts=counts[:U].cpu().numpy(),
                   inverse=inverse[:m].cpu().numpy(),
                   uniq_tail_untouched=bool((uniq[U:] == -7).all().item()))
-        if keep_E:
+        if keep_E and pass_E:
             st["E"] = E[:U].cpu().numpy()
         if keep_H:
             st["H"] = H[:m].cpu().numpy()
@@ -66,6 +74,9 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
     out = dict(steps=steps, dW=dW.cpu().numpy(), U_total=n, uniq_total=ut[:n].cpu().numpy(),
                counts_total=ct[:n].cpu().numpy(), gram=g, X_dev=Xd, W_dev=Wd)
     assert int(utd.item()) == n
+    if profile:
+        out["profile"] = g.profile_read()
+        g.profile_enable([])
     if want_G:
         out["G_total"] = Gt[:n].cpu().numpy()
     return out
