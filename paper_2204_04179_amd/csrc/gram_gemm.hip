@@ -378,7 +378,7 @@ constexpr size_t RSMEM = (size_t)RSTAGES * TSTAGEB;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kScatterRowB = TN * 4 + 16;
 constexpr int kScatterTileB = 64 * kScatterRowB;
-constexpr size_t RSMEM_SC = kScatterTileB > (int)RSMEM ? (size_t)kScatterTileB : RSMEM;
+constexpr size_t RSMEM_SC = 2 * (size_t)kScatterTileB;     // two staging buffers (they overlay the dead stages)
 constexpr uint32_t kBufferFlags = 0x00027000;   // raw buffer: 32-bit elements, no swizzle
 
 // NW = waves per block: 4 (each 128x128, one wave per SIMD) or 8 (each 128x64, two per SIMD).
@@ -598,36 +598,42 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
 #pragma unroll
         for (int k = 0; k < 4 * RPW; ++k) asm volatile("" : "+v"(pv[k]));
         __syncthreads();
+        // two staging buffers: a wave that has stored its rows of round i stages round i + 1
+        // while the others still store, and one barrier per round is enough (round i + 2 reuses
+        // the buffer of round i only after the barrier of round i + 1)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
+            unsigned char* stage = smem + (i & 1) * kScatterTileB;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int rr = (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
                 const bool zero = wm * 128 + i * 32 + rr == pad_row;
-                float* dst = reinterpret_cast<float*>(smem + (wm * 32 + rr) * kScatterRowB) +
+                float* dst = reinterpret_cast<float*>(stage + (wm * 32 + rr) * kScatterRowB) +
                              wn * (NT * 32) + (lane & 31);
 #pragma unroll
                 for (int jj = 0; jj < NT; ++jj) dst[jj * 32] = zero ? 0.f : acc[i][jj][r];
             }
             __syncthreads();
+            const int cr0 = (wave / (NW / 2)) * 32 + (wave % (NW / 2)) * RPW;           // first staged row
+            f32x4 v[RPW];
+#pragma unroll
+            for (int u = 0; u < RPW; ++u)
+                v[u] = *reinterpret_cast<const f32x4*>(stage + (cr0 + u) * kScatterRowB + lane * 16);
 #pragma unroll
             for (int u = 0; u < RPW; ++u) {
-                const int cr = (wave / (NW / 2)) * 32 + (wave % (NW / 2)) * RPW + u;   // staged row
-                const int lr = (cr >> 5) * 128 + i * 32 + (cr & 31);                    // row of the tile
+                const int lr = (cr0 >> 5) * 128 + i * 32 + (cr0 & 31) + u;               // row of the tile
                 const int cnt = __builtin_amdgcn_readlane(seg_n, i * RPW + u);
                 if (cnt == 0) continue;
-                const f32x4 v = *reinterpret_cast<const f32x4*>(smem + cr * kScatterRowB + lane * 16);
                 if (cnt > kLightMax || sc.write_all) {
-                    if (col_ok) *reinterpret_cast<f32x4*>(C + (int64_t)(m0 + lr) * ldc + n0 + lane * 4) = v;
+                    if (col_ok) *reinterpret_cast<f32x4*>(C + (int64_t)(m0 + lr) * ldc + n0 + lane * 4) = v[u];
                     if (cnt > kLightMax) continue;
                 }
                 for (int t = 0; t < cnt; ++t) {
                     const int pos = __builtin_amdgcn_readlane(pv[i * RPW + u], t);
                     if (col_ok)
-                        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(sc.H + (int64_t)pos * sc.ldh + n0 + lane * 4));
+                        __builtin_nontemporal_store(v[u], reinterpret_cast<f32x4*>(sc.H + (int64_t)pos * sc.ldh + n0 + lane * 4));
                 }
             }
-            __syncthreads();
         }
     } else if (m0 + TM <= M && n0 + TN <= n) {
 #pragma unroll
