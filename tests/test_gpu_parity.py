@@ -242,6 +242,46 @@ def test_fused_forward_stores_representations_to_positions(d, variant):
     assert launches == ({"gather_rows": 1} if variant.startswith("foreign") else {"gather_heavy": 1})
 
 
+def test_feature_matrix_beyond_4_gib_takes_the_wide_address_kernels():
+    """X of 4.3 GB cannot be addressed through a 32-bit buffer descriptor: the forward runs the
+    contraction fed by direct-to-LDS loads and the weight gradient the transposed copies.  X is
+    drawn on the device; the oracle sees only the rows the batch names, under IDs renumbered in
+    ascending order (which leaves uniq order, inverse, H, G and dW unchanged)."""
+    import torch
+    n, d_in, d, m = 2_100_000, 1024, 256, 6000
+    say(f"wide addresses: X = {n * d_in * 2 / 2**30:.2f} GiB")
+    g = torch.Generator(device="cuda").manual_seed(5)
+    X_dev = torch.empty(n, d_in, dtype=torch.bfloat16, device="cuda")
+    X_dev.normal_(generator=g)
+    rng = np.random.default_rng(21)
+    ids = rng.integers(1, n, size=m).astype(np.int32)
+    ids[: m // 3] = rng.choice(ids[m // 3:], size=m // 3)         # repeats
+    ids[rng.random(m) < 0.1] = 0
+    ids[-1] = n - 1                                                # the last row of X
+    W = wl.f32_to_bf16_bits((rng.standard_normal((d_in, d)) / np.sqrt(d_in)).astype(np.float32))
+    dH = rng.standard_normal((m, d)).astype(np.float32)
+    out = run_window(np.zeros((1, 1), np.uint16), W, [(ids, dH)], vocab_n=n, X_dev=X_dev,
+                     profile=["encode_bf16", "gather_rows", "transpose_x", "transpose_g", "wgrad_bf16"])
+    uniq = np.unique(ids)
+    rows = X_dev[torch.from_numpy(uniq.astype(np.int64)).cuda()].view(torch.int16).cpu().numpy().view(np.uint16)
+    small_ids = np.searchsorted(uniq, ids).astype(np.int32)       # 0 stays 0: the padding ID is the smallest
+    assert uniq[0] == 0
+    ref = orc.gram_single(small_ids, rows, W, dH, pad_id=0)
+    st = out["steps"][0]
+    np.testing.assert_array_equal(st["uniq"], uniq)
+    np.testing.assert_array_equal(st["inverse"], ref["inverse"])
+    np.testing.assert_array_equal(st["counts"], ref["counts"])
+    assert_close(st["E"], ref["E"], TOL_SUM[wl.BF16], "E")
+    assert_close(st["H"], ref["H"], TOL_SUM[wl.BF16], "H")
+    assert_close(out["G_total"], ref["G"], TOL_SUM[wl.BF16], "G")
+    assert_close(out["dW"], ref["dW"], TOL[wl.BF16], "dW")
+    launches = {k: v[0] for k, v in out["profile"].items()}
+    say("   launches:", launches)
+    assert launches.get("transpose_x") == 1 and launches.get("transpose_g") == 1 and launches.get("gather_rows") == 1
+    del X_dev
+    torch.cuda.empty_cache()
+
+
 def test_no_padding_id_and_other_padding_id():
     ids, X, W, dH = small_problem(9, 500, 40, pad_frac=0.3)
     for pad in (-1, 0, 7):
