@@ -16,7 +16,10 @@
  * Parity pins (tests/test_oracle_pins.py): brute force on tiny batches, the
  * worked example of Fig. 1 (12 interactions, 5 items), E2E == Single-step
  * (Section 4.1), the Proposition (Eq. 1-3), N = 1 reduces Multi-step to
- * Single-step (Section 4.3), library unique/matmul/scatter-add cross-checks.
+ * Single-step (Section 4.3), library unique/matmul/scatter-add cross-checks;
+ * pseudo-targets: a hand-worked case, one SGD step of rate 1 on a quadratic
+ * loss lands on its target, the derivative of the pseudo-loss with respect to
+ * W equals the weight gradient, pseudo-loss = half the squared norm of G.
  * No function here is "parity unpinned".
  */
 #include <stdint.h>
@@ -310,5 +313,45 @@ int oracle_buffer_export(const oracle_buffer *b, int32_t *ids, int64_t *counts, 
     if (ids) memcpy(ids, b->ids, (size_t)b->n * sizeof *ids);
     if (counts) memcpy(counts, b->counts, (size_t)b->n * sizeof *counts);
     if (G) memcpy(G, b->G, (size_t)b->n * b->d * sizeof *G);
+    return 0;
+}
+
+/* Rows of the buffer for the given IDs (ascending or not): G_out[j,:] = the
+ * gradient accumulated so far for ids[j], zeros for an ID the buffer does not
+ * hold. */
+int oracle_buffer_rows(const oracle_buffer *b, const int32_t *ids, int64_t u, double *G_out)
+{
+    for (int64_t j = 0; j < u; ++j) {
+        int64_t lo = 0, hi = b->n;                 /* first entry >= ids[j] */
+        while (lo < hi) {
+            int64_t mid = lo + (hi - lo) / 2;
+            if (b->ids[mid] < ids[j]) lo = mid + 1; else hi = mid;
+        }
+        int found = lo < b->n && b->ids[lo] == ids[j];
+        for (int32_t k = 0; k < b->d; ++k) G_out[j * b->d + k] = found ? b->G[lo * b->d + k] : 0.0;
+    }
+    return 0;
+}
+
+/*
+ * Pseudo-targets (Algorithm 1 step 3, Eq. 6): the representation of an item is
+ * treated as a trainable embedding and moved by one plain gradient step of
+ * rate 1, h~_i = h_i - grad L(h_i), where grad L(h_i) is the gradient
+ * accumulated for item i (all its occurrences; all steps of the window so far,
+ * Section 4.2).  The pseudo-loss of Eq. 7 at the current encoder is
+ * 1/2 sum_i |h~_i - h_i|^2.  E, G, Ht are [u, d]; *loss receives the scalar.
+ */
+int oracle_pseudo_target(const double *E, const double *G, int64_t u, int32_t d, double *Ht,
+                         double *loss)
+{
+    double total = 0.0;
+    for (int64_t j = 0; j < u; ++j)
+        for (int32_t k = 0; k < d; ++k) {
+            double target = E[j * d + k] - G[j * d + k];
+            double miss = target - E[j * d + k];
+            Ht[j * d + k] = target;
+            total += 0.5 * miss * miss;
+        }
+    *loss = total;
     return 0;
 }

@@ -75,6 +75,10 @@ def lib():
         L.oracle_buffer_add.argtypes = [vp, i32p, i32p, f64p, C.c_int64]
         L.oracle_buffer_export.restype = C.c_int
         L.oracle_buffer_export.argtypes = [vp, i32p, i64p, f64p]
+        L.oracle_buffer_rows.restype = C.c_int
+        L.oracle_buffer_rows.argtypes = [vp, i32p, C.c_int64, f64p]
+        L.oracle_pseudo_target.restype = C.c_int
+        L.oracle_pseudo_target.argtypes = [f64p, f64p, C.c_int64, C.c_int32, f64p, f64p]
         _lib = L
     return _lib
 
@@ -189,6 +193,20 @@ def wgrad_entries(item, X, G, pad_id, rows, cols):
     return out
 
 
+def pseudo_target(E, G):
+    """Pseudo-targets of Algorithm 1 step 3 (Eq. 6), h~ = h - grad L(h), and the pseudo-loss of
+    Eq. 7 at the current encoder.  E, G: [U, d] float64 (G = the gradient accumulated for each
+    item).  Returns (Ht [U, d] float64, loss)."""
+    E = np.ascontiguousarray(E, dtype=np.float64)
+    G = np.ascontiguousarray(G, dtype=np.float64)
+    assert E.shape == G.shape and E.ndim == 2
+    Ht = np.empty_like(E)
+    loss = C.c_double(0.0)
+    _check(lib().oracle_pseudo_target(_p(E, C.c_double), _p(G, C.c_double), E.shape[0], E.shape[1],
+                                      _p(Ht, C.c_double), C.byref(loss)), "pseudo_target")
+    return Ht, loss.value
+
+
 def e2e(ids, X, W, dH, pad_id=0):
     """End-to-end baseline (Section 3.3): the encoder runs forward and backward
     once per interaction.  Returns float64 (H [M,d], dW [d_in,d])."""
@@ -231,6 +249,14 @@ class GramMulti:
                                        _p(G, C.c_double), uniq.size), "buffer_add")
         self.steps += 1
         return dict(uniq=uniq, inverse=inverse, counts=counts, E=E, H=H, G=G)
+
+    def rows(self, ids):
+        """Gradient accumulated so far in the window for each of `ids` (zeros if absent)."""
+        ids = np.ascontiguousarray(ids, dtype=np.int32).reshape(-1)
+        G = np.empty((ids.size, self.d), np.float64)
+        _check(lib().oracle_buffer_rows(self._buf, _p(ids, C.c_int32), ids.size, _p(G, C.c_double)),
+               "buffer_rows")
+        return G
 
     def export(self):
         n = lib().oracle_buffer_size(self._buf)

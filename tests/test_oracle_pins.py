@@ -241,6 +241,76 @@ def test_proposition_pseudo_target():
     np.testing.assert_allclose(-Xu.T @ (h_tilde - Xu @ Wd), r["dW"], rtol=1e-10, atol=1e-10)
 
 
+def test_pseudo_target_hand_example(golden_dir):
+    ex = json.load(open(os.path.join(golden_dir, "hand_example.json")))
+    Ht, loss = orc.pseudo_target(np.array(ex["E"], float), np.array(ex["G"], float))
+    np.testing.assert_array_equal(Ht, np.array(ex["Ht"], float))
+    assert loss == ex["pseudo_loss"]
+
+
+def test_pseudo_target_is_one_gradient_step_of_rate_one():
+    """Section 4.3: the representation is a trainable embedding moved by plain gradient descent
+    with rate 1.  For L = 1/2 sum_p |H[p] - y_p|^2 the step lands on the target when an item
+    occurs once, and on h (1 - c) + sum of its c targets in general."""
+    ids, X, W, _ = rand_problem(41, m=50, n=30, d_in=4, d=3, pad_frac=0.0)
+    r0 = orc.gram_single(ids, X, W, np.zeros((ids.size, 3), np.float32))
+    rng = np.random.default_rng(5)
+    y = rng.standard_normal((ids.size, 3))
+    dH = (r0["H"] - y).astype(np.float32)            # dL/dH of the quadratic loss
+    r = orc.gram_single(ids, X, W, dH)
+    Ht, loss = orc.pseudo_target(r["E"], r["G"])
+    c = r["counts"][:, None].astype(np.float64)
+    ysum = np.zeros_like(r["E"])
+    np.add.at(ysum, r["inverse"], y)
+    np.testing.assert_allclose(Ht, r["E"] * (1 - c) + ysum, rtol=0, atol=1e-5)
+    once = r["counts"] == 1
+    assert once.any()
+    np.testing.assert_allclose(Ht[once], ysum[once], rtol=0, atol=1e-6)
+    assert abs(loss - 0.5 * np.sum(r["G"] ** 2)) <= 1e-12 * loss
+
+
+def test_pseudo_loss_derivative_is_the_weight_gradient():
+    """Eq. 7-9: with the pseudo-targets held fixed, d/dW' of the oracle's pseudo-loss at W' = W is
+    the weight gradient of Algorithm 1 step 4 (central differences through the oracle itself)."""
+    ids, X, W, dH = rand_problem(42, m=60, n=13, d_in=4, d=3)
+    r = orc.gram_single(ids, X, W, dH)
+    Ht, _ = orc.pseudo_target(r["E"], r["G"])
+
+    def pseudo_loss(Wm):
+        E = orc.encode(r["uniq"], X, Wm.astype(np.float32), 0)
+        return orc.pseudo_target(E, E - Ht)[1]       # targets fixed: G' = E' - Ht
+
+    Wd = widen(W)
+    num = np.zeros_like(Wd)
+    eps = 2.0 ** -6                                   # exactly representable steps of a float32 W
+    for i in range(Wd.shape[0]):
+        for c in range(Wd.shape[1]):
+            Wp, Wm = Wd.copy(), Wd.copy()
+            Wp[i, c] += eps
+            Wm[i, c] -= eps
+            num[i, c] = (pseudo_loss(Wp) - pseudo_loss(Wm)) / (2 * eps)
+    np.testing.assert_allclose(r["dW"], num, rtol=1e-4, atol=1e-4)
+
+
+def test_pseudo_target_over_a_window_uses_the_accumulated_gradient():
+    """Section 4.2: within a window the buffer row of an item is the sum over the steps so far."""
+    X = np.random.default_rng(1).standard_normal((20, 4)).astype(np.float32)
+    W = np.random.default_rng(2).standard_normal((4, 3)).astype(np.float32)
+    mm = orc.GramMulti(X, W)
+    total = {}
+    for k in range(3):
+        ids, _, _, dH = rand_problem(70 + k, m=30, n=20, d_in=4, d=3)
+        st = mm.step(ids, dH)
+        for j, i in enumerate(st["uniq"]):
+            total[int(i)] = total.get(int(i), 0) + st["G"][j]
+        G = mm.rows(st["uniq"])
+        np.testing.assert_allclose(G, np.array([total[int(i)] for i in st["uniq"]]), rtol=0, atol=1e-12)
+        Ht, loss = orc.pseudo_target(st["E"], G)
+        np.testing.assert_allclose(Ht, st["E"] - G, rtol=0, atol=0)
+        assert abs(loss - 0.5 * np.sum(G ** 2)) <= 1e-12 * max(loss, 1.0)
+    np.testing.assert_array_equal(mm.rows(np.array([19, 0, 7], np.int32))[1], np.zeros(3))   # padding row
+
+
 def test_dw_linearity_and_entries():
     ids, X, W, dH1 = rand_problem(33, m=80, bf16=True)
     dH2 = np.random.default_rng(5).standard_normal(dH1.shape).astype(np.float32)
@@ -335,3 +405,6 @@ def test_pins_catch_planted_mistakes():
     assert np.abs(E_bad - r["E"]).max() > 1e-3
     # (3) wrong sign of the accumulated gradient
     assert np.abs(orc.wgrad(uniq, X, -r["G"], 0) - dW).max() > 1e-3 * scale
+    # (4) pseudo-target moved up the gradient instead of down: the hand example tells them apart
+    Ht_bad, _ = orc.pseudo_target(r["E"], -r["G"])
+    assert np.abs(Ht_bad - (r["E"] - r["G"])).max() > 1e-3
