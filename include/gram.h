@@ -14,6 +14,10 @@
  *   gram_grad_accumulate  step 3, Eq. 6: dL/dH summed per unique item into the
  *                         buffer that persists over the N mini-batches of a
  *                         Multi-step window (Section 4.2)
+ *   gram_pseudo_target    step 3 as the paper writes it: the pseudo-target
+ *                         h~ = h - grad L(h) of each item of the batch and the
+ *                         pseudo-loss of Eq. 7 (optional; gram_gather gathers
+ *                         such rows to positions)
  *   gram_encoder_wgrad    step 4, Eq. 7/9: encoder weight gradient once per
  *                         unique item, dW = X[items]^T . G
  *   gram_flush            end of the window ("t mod N"): export and empty the
@@ -133,6 +137,29 @@ int gram_encode_gather(gram_ctx* ctx, const void* X, const void* W, const int32_
  * No float atomics are used: every buffer row has one writer and a fixed
  * summation order. */
 int gram_grad_accumulate(gram_ctx* ctx, const float* dH, int64_t m, int32_t step_k, void* stream);
+
+/* Pseudo-targets of the items of the current batch (Algorithm 1 step 3, Eq. 6:
+ * the representation is moved by one plain gradient step of rate 1, Section 4.3)
+ * and the pseudo-loss of Eq. 7 at the current encoder.
+ *   E        DEVICE [>= U, d]   the representations gram_encode_gather wrote for
+ *                               this batch (pass it a buffer for E)
+ *   Ht       DEVICE [>= U, d], nullable   out: Ht[j,:] = E[j,:] - G(uniq[j]),
+ *            G = the gradient accumulated for the item so far in the window,
+ *            this batch included; zero row for the padding ID
+ *   loss_dev DEVICE [1] double, nullable  out: 1/2 sum_j |Ht[j,:] - E[j,:]|^2
+ *            (summed in double in a fixed order)
+ * Requires the gram_grad_accumulate of this batch (GRAM_ERR_SEQUENCE); rows
+ * >= U are untouched.  16-byte aligned pointers. */
+int gram_pseudo_target(gram_ctx* ctx, const float* E, float* Ht, double* loss_dev, void* stream);
+
+/* The gather step alone: H[p,:] = src[inverse[p],:] for p < m, e.g. to feed the
+ * collaborative-filtering model with pseudo-targets instead of fresh
+ * representations in later steps of a window (Section 4.3: item vectors as
+ * trainable embeddings).
+ *   src      DEVICE [>= U, d]   inverse  DEVICE [m], values < U
+ *   H        DEVICE [m, d]      16-byte aligned pointers */
+int gram_gather(gram_ctx* ctx, const float* src, const int32_t* inverse, int64_t m, float* H,
+                void* stream);
 
 /* Encoder weight gradient over all items accumulated in the window
  * (Algorithm 1 step 4): dW[i,c] = sum_items X[item,i] * G[item,c].

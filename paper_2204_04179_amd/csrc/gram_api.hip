@@ -106,6 +106,7 @@ int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
     int* cnt_of_slot = (int*)take(dv.cap_total * 4);
     float* G = (float*)take(dv.cap_total * d * 4);
     float* E_ws = (float*)take(dv.cap_u * d * 4);
+    double* loss_part = (double*)take((dv.cap_u / kPseudoRows + 1) * 8);
     float* seg_first = (float*)take(dv.tiles_seg * d * 4);
     float* seg_last = (float*)take(dv.tiles_seg * d * 4);
     void* Wt = take(cfg.xw_dtype == GRAM_BF16 ? d * d_in * 2 : 1);
@@ -119,7 +120,7 @@ int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
         c->table = table; c->gtot = gtot; c->tile_sums = tile_sums; c->offsets = offsets;
         c->seg_of_row = seg_of_row; c->uniq_ws = uniq_ws; c->seg_slot = seg_slot;
         c->long_list = long_list; c->slot_of = slot_of; c->id_of_slot = id_of_slot;
-        c->cnt_of_slot = cnt_of_slot; c->G = G; c->E_ws = E_ws; c->seg_first = seg_first;
+        c->cnt_of_slot = cnt_of_slot; c->G = G; c->E_ws = E_ws; c->loss_part = loss_part; c->seg_first = seg_first;
         c->seg_last = seg_last; c->Wt = Wt; c->wg_partial = wg_partial;
         c->XT = XT; c->GT = GT; c->ldt = ldt;
     }
@@ -314,6 +315,29 @@ int gram_grad_accumulate(gram_ctx* ctx, const float* dH, int64_t m, int32_t step
     return GRAM_OK;
 }
 
+int gram_pseudo_target(gram_ctx* ctx, const float* E, float* Ht, double* loss_dev, void* stream)
+{
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (!c) return GRAM_ERR_ARG;
+    if (!c->have_unique || !c->unique_consumed)
+        return fail(c, GRAM_ERR_SEQUENCE, "gram_pseudo_target: needs the gram_grad_accumulate of this batch");
+    if (c->cur_m > 0 && (!E || (!Ht && !loss_dev)))
+        return fail(c, GRAM_ERR_ARG, "gram_pseudo_target: E and at least one output are required");
+    pseudo_target(c, E, Ht, loss_dev, static_cast<hipStream_t>(stream));
+    return launch_status(c, "gram_pseudo_target");
+}
+
+int gram_gather(gram_ctx* ctx, const float* src, const int32_t* inverse, int64_t m, float* H, void* stream)
+{
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (!c) return GRAM_ERR_ARG;
+    if (m < 0 || m > c->cfg.max_positions)
+        return fail(c, GRAM_ERR_ARG, "gram_gather: m = %lld outside [0, max_positions]", (long long)m);
+    if (m > 0 && (!src || !inverse || !H)) return fail(c, GRAM_ERR_ARG, "gram_gather: NULL pointer");
+    gather_rows(c, src, inverse, m, H, static_cast<hipStream_t>(stream));
+    return launch_status(c, "gram_gather");
+}
+
 int gram_encoder_wgrad(gram_ctx* ctx, const void* X, float* dW, void* stream)
 {
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
@@ -347,7 +371,7 @@ static const char* const kKernelNames[KID_COUNT] = {
     "radix_hist", "radix_scan", "radix_scatter", "heads_count", "heads_emit", "counts", "unique_empty",
     "transpose_w", "encode_bf16", "encode_f32", "gather_rows", "slot_count", "slot_emit", "seg_reduce",
     "seg_combine", "wgrad_bf16", "wgrad_f32", "wgrad_reduce", "transpose_x", "transpose_g", "flush_meta",
-    "flush_rows", "flush_finish", "unique_small", "gather_heavy"};
+    "flush_rows", "flush_finish", "unique_small", "gather_heavy", "pseudo_target", "pseudo_loss"};
 
 int gram_kernel_count(void) { return KID_COUNT; }
 

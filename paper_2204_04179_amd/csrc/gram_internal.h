@@ -20,7 +20,8 @@ constexpr int kScanTile = 1024;         // rows per block in the flag-scan kerne
 constexpr int kSegRows = 32;            // sorted rows per tile of the segment reduction
 constexpr int kSegLong = 128;           // segments with at least this many rows are reduced tile by tile
 constexpr int kLightMax = 32;           // items with more positions are gathered by a separate copy kernel
-constexpr int kSlotNew = 1 << 30;       // flag in seg_slot: the buffer row is created by this step
+constexpr int kSlotNew = 1 << 30;
+constexpr int kPseudoRows = 8;          // unique items per block of the pseudo-target kernel       // flag in seg_slot: the buffer row is created by this step
 constexpr int kFixCols4 = 16;           // float4 columns per block of the long-segment combine
 constexpr int kFixLanes = kBlock / kFixCols4;
 
@@ -37,7 +38,7 @@ enum KernelId {
     KID_UNIQUE_EMPTY, KID_TRANSPOSE_U16, KID_ENCODE_BF16, KID_ENCODE_F32, KID_GATHER_ROWS,
     KID_SLOT_COUNT, KID_SLOT_EMIT, KID_SEG_REDUCE, KID_SEG_COMBINE, KID_WGRAD_BF16, KID_WGRAD_F32,
     KID_WGRAD_REDUCE, KID_TRANSPOSE_X, KID_TRANSPOSE_G, KID_FLUSH_META, KID_FLUSH_ROWS, KID_FLUSH_FINISH, KID_UNIQUE_SMALL,
-    KID_GATHER_HEAVY, KID_COUNT
+    KID_GATHER_HEAVY, KID_PSEUDO_TARGET, KID_PSEUDO_LOSS, KID_COUNT
 };
 
 struct ProfSlot {
@@ -77,6 +78,7 @@ struct Ctx {
     int* cnt_of_slot = nullptr; // [cap_total]
     float* G = nullptr;         // [cap_total, d] persistent per-item gradient
     float* E_ws = nullptr;      // [cap_u, d] representations when the caller passes E = NULL
+    double* loss_part = nullptr; // [cap_u / kPseudoRows + 1] per-block sums of the pseudo-loss
     float* seg_first = nullptr; // [tiles_seg, d] partial sums of segments entering a tile
     float* seg_last = nullptr;  // [tiles_seg, d] partial sums of segments leaving a tile
     void* Wt = nullptr;         // [d, d_in] transposed weight (bf16 path)
@@ -151,6 +153,7 @@ bool unique_small(Ctx* c, const int* ids, int n, int fix_key, int* uniq, int* in
 // ---- gram_stream.hip -----------------------------------------------------
 void gather_rows(Ctx* c, const float* E, const int* inverse, int64_t m, float* H, hipStream_t s);
 void gather_heavy(Ctx* c, const float* E, int64_t m, float* H, hipStream_t s);
+void pseudo_target(Ctx* c, const float* E, float* Ht, double* loss_dev, hipStream_t s);
 void assign_slots(Ctx* c, hipStream_t s);
 void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s);
 void flush_export(Ctx* c, int* uniq_total, int* counts_total, float* G_total, int* u_total_dev,

@@ -174,6 +174,78 @@ void gather_heavy(Ctx* c, const float* E, int64_t m, float* H, hipStream_t s)
            reinterpret_cast<f32x4*>(H), rows_per_block);
 }
 
+// ---- pseudo-targets (Algorithm 1 step 3, Eq. 6) and the pseudo-loss (Eq. 7) -------------
+//
+// Ht[j,:] = E[j,:] - G[row of item j,:] for the unique items of the current batch, with G the
+// gradient accumulated so far in the window (this batch included), and
+// loss = 1/2 sum |Ht - E|^2 = 1/2 sum G^2 over those rows.  A block takes kPseudoRows items;
+// its threads add their squares in double, the block adds the thread sums in a fixed tree
+// and writes one partial; k_pseudo_loss adds the partials in index order: no atomics, the
+// same bits on every run.  An item whose row was dropped (buffer full) keeps Ht = E.
+__global__ __launch_bounds__(kBlock) void k_pseudo_target(const f32x4* __restrict__ E,
+                                                          const f32x4* __restrict__ G,
+                                                          const int* __restrict__ seg_slot,
+                                                          const int* __restrict__ u_ws, int cols4,
+                                                          f32x4* __restrict__ Ht,
+                                                          double* __restrict__ partial)
+{
+    __shared__ double s_sum[kBlock];
+    const int U = *u_ws;
+    const int j0 = blockIdx.x * kPseudoRows;
+    double sum = 0.0;
+    if (j0 < U) {
+        const int rows = U - j0 < kPseudoRows ? U - j0 : kPseudoRows;
+        const int total = rows * cols4;
+        for (int e = threadIdx.x; e < total; e += kBlock) {
+            const int r = e / cols4, cq = e - r * cols4;
+            const int code = seg_slot[j0 + r];
+            f32x4 g = {0.f, 0.f, 0.f, 0.f};
+            if (code >= 0) g = G[(int64_t)(code & (kSlotNew - 1)) * cols4 + cq];
+            const f32x4 h = E[(int64_t)(j0 + r) * cols4 + cq];
+            if (Ht) __builtin_nontemporal_store(h - g, &Ht[(int64_t)(j0 + r) * cols4 + cq]);
+            sum += (double)g.x * g.x + (double)g.y * g.y + (double)g.z * g.z + (double)g.w * g.w;
+        }
+    }
+    s_sum[threadIdx.x] = sum;
+    __syncthreads();
+    for (int w = kBlock / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) s_sum[threadIdx.x] += s_sum[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partial[blockIdx.x] = s_sum[0];
+}
+
+__global__ __launch_bounds__(kBlock) void k_pseudo_loss(const double* __restrict__ partial,
+                                                        const int* __restrict__ u_ws,
+                                                        double* __restrict__ loss)
+{
+    __shared__ double s_sum[kBlock];
+    const int n = (*u_ws + kPseudoRows - 1) / kPseudoRows;
+    // thread t adds partials t, t + 256, ... in ascending order, then the fixed tree
+    double sum = 0.0;
+    for (int i = threadIdx.x; i < n; i += kBlock) sum += partial[i];
+    s_sum[threadIdx.x] = sum;
+    __syncthreads();
+    for (int w = kBlock / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) s_sum[threadIdx.x] += s_sum[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *loss = 0.5 * s_sum[0];
+}
+
+void pseudo_target(Ctx* c, const float* E, float* Ht, double* loss_dev, hipStream_t s)
+{
+    const int64_t rows_max = c->cur_m < c->cap_u ? c->cur_m : c->cap_u;
+    const int64_t blocks = (rows_max + kPseudoRows - 1) / kPseudoRows;
+    if (blocks > 0)
+        launch(c, KID_PSEUDO_TARGET, k_pseudo_target, dim3((unsigned)blocks), dim3(kBlock), s,
+               reinterpret_cast<const f32x4*>(E), reinterpret_cast<const f32x4*>(c->G), c->seg_slot,
+               c->scal + kSU, c->cfg.d / 4, reinterpret_cast<f32x4*>(Ht), c->loss_part);
+    if (loss_dev)
+        launch(c, KID_PSEUDO_LOSS, k_pseudo_loss, dim3(1), dim3(kBlock), s, c->loss_part, c->scal + kSU,
+               loss_dev);
+}
+
 // ---- buffer rows for the items of this batch --------------------------------
 //
 // An item seen for the first time in the window gets the next free row of the

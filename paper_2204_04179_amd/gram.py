@@ -20,7 +20,8 @@ STATUS_NAMES = {OK: "GRAM_OK", ERR_ARG: "GRAM_ERR_ARG", ERR_CAPACITY: "GRAM_ERR_
                 ERR_UNIMPLEMENTED: "GRAM_ERR_UNIMPLEMENTED"}
 
 EXPORTS = ("gram_workspace_bytes", "gram_create", "gram_destroy", "gram_unique", "gram_encode_gather",
-           "gram_grad_accumulate", "gram_encoder_wgrad", "gram_flush", "gram_check", "gram_last_error",
+           "gram_grad_accumulate", "gram_pseudo_target", "gram_gather", "gram_encoder_wgrad", "gram_flush",
+           "gram_check", "gram_last_error",
            "gram_kernel_count", "gram_kernel_name", "gram_light_max", "gram_profile_enable",
            "gram_profile_read")
 
@@ -61,6 +62,10 @@ def load():
     L.gram_encode_gather.argtypes = [vp, vp, vp, vp, vp, vp, C.c_int64, vp, vp, vp]
     L.gram_grad_accumulate.restype = C.c_int
     L.gram_grad_accumulate.argtypes = [vp, vp, C.c_int64, C.c_int32, vp]
+    L.gram_pseudo_target.restype = C.c_int
+    L.gram_pseudo_target.argtypes = [vp, vp, vp, vp, vp]
+    L.gram_gather.restype = C.c_int
+    L.gram_gather.argtypes = [vp, vp, vp, C.c_int64, vp, vp]
     L.gram_encoder_wgrad.restype = C.c_int
     L.gram_encoder_wgrad.argtypes = [vp, vp, vp, vp]
     L.gram_flush.restype = C.c_int
@@ -151,6 +156,12 @@ class Gram:
 
     def grad_accumulate(self, dH, m, step_k, stream=None):
         self._ck(self._lib.gram_grad_accumulate(self._h, _ptr(dH), int(m), int(step_k), _stream(stream)))
+
+    def pseudo_target(self, E, Ht=None, loss_dev=None, stream=None):
+        self._ck(self._lib.gram_pseudo_target(self._h, _ptr(E), _ptr(Ht), _ptr(loss_dev), _stream(stream)))
+
+    def gather(self, src, inverse, m, H, stream=None):
+        self._ck(self._lib.gram_gather(self._h, _ptr(src), _ptr(inverse), int(m), _ptr(H), _stream(stream)))
 
     def encoder_wgrad(self, X, dW, stream=None):
         self._ck(self._lib.gram_encoder_wgrad(self._h, _ptr(X), _ptr(dW), _stream(stream)))

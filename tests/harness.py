@@ -15,13 +15,14 @@ def to_dev(a, torch):
 
 def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=None, u_total_cap=0,
                keep_H=True, keep_E=True, want_G=True, gram_obj=None, X_dev=None, W_dev=None,
-               pass_E=True, foreign_buffers=False, profile=None):
+               pass_E=True, foreign_buffers=False, profile=None, pseudo=False):
     """batches: list of (ids int32 [m], dH float32 [m,d]).  Returns dict with per-step
     uniq/inverse/counts/E/H and the window's uniq_total/counts_total/G_total/dW.
     pass_E=False calls gram_encode_gather with E = NULL (no "E" in the result);
     foreign_buffers=True hands it copies of uniq / inverse instead of the buffers gram_unique
     wrote, which selects the two-kernel forward.  profile: kernel names whose launches are counted
-    (result key "profile": name -> (launches, ms))."""
+    (result key "profile": name -> (launches, ms)).  pseudo=True also calls gram_pseudo_target
+    and gram_gather after each accumulate (step keys "Ht", "loss", "H_tilde")."""
     import torch
     from paper_2204_04179_amd import gram
 
@@ -52,6 +53,12 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
         uq, inv = (uniq.clone(), inverse.clone()) if foreign_buffers else (uniq, inverse)
         g.encode_gather(Xd, Wd, uq, inv, u_dev, m, E if pass_E else None, H)
         g.grad_accumulate(dH_d, m, k)
+        if pseudo:
+            Ht = torch.full((cap_u, d), float("nan"), device="cuda")
+            loss = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda")
+            H2 = torch.full((max(1, m), d), float("nan"), device="cuda")
+            g.pseudo_target(E, Ht, loss)
+            g.gather(Ht, inverse, m, H2)
         torch.cuda.synchronize()
         st = dict(U=U, uniq=uniq[:U].cpu().numpy(), counts=counts[:U].cpu().numpy(),
                   inverse=inverse[:m].cpu().numpy(),
@@ -60,6 +67,9 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
             st["E"] = E[:U].cpu().numpy()
         if keep_H:
             st["H"] = H[:m].cpu().numpy()
+        if pseudo:
+            st["Ht"], st["loss"], st["H_tilde"] = Ht[:U].cpu().numpy(), float(loss.item()), H2[:m].cpu().numpy()
+            st["Ht_tail_untouched"] = bool(torch.isnan(Ht[U:]).all().item())
         st["H_dev"], st["E_dev"], st["inverse_dev"] = H, E, inverse
         steps.append(st)
     dW = torch.full((d_in, d), float("nan"), device="cuda")

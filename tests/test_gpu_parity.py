@@ -311,6 +311,56 @@ def test_multi_step_window_and_bitwise_reproducibility():
     assert_close(out3["dW"], ref["dW"], TOL[wl.BF16], "dW K=1")
 
 
+def test_pseudo_targets_and_pseudo_loss_over_a_window():
+    """Algorithm 1 step 3 (Eq. 6) with the gradient accumulated over the window (Section 4.2), the
+    pseudo-loss of Eq. 7, and the gather of pseudo-targets to positions."""
+    K, n = 3, 2500
+    for bf16, d in ((False, 12), (True, 64)):
+        probs = [small_problem(200 + k, 7000 + 500 * k, n, d_in=32, d=d, bf16=bf16) for k in range(K)]
+        X, W = probs[0][1], probs[0][2]
+        batches = [(p[0], p[3]) for p in probs]
+        say(f"pseudo-targets K={K} bf16={bf16}")
+        out = run_window(X, W, batches, vocab_n=n, k_steps=K, max_positions=8000, pseudo=True)
+        mm = orc.GramMulti(X, W)
+        tol = TOL_SUM[wl.BF16 if bf16 else wl.F32]
+        for k, (ids, dH) in enumerate(batches):
+            ref = mm.step(ids, dH)
+            Ht_ref, loss_ref = orc.pseudo_target(ref["E"], mm.rows(ref["uniq"]))
+            st = out["steps"][k]
+            assert_close(st["Ht"], Ht_ref, tol, f"Ht step {k}")
+            assert abs(st["loss"] - loss_ref) <= tol * loss_ref
+            assert st["Ht_tail_untouched"]
+            np.testing.assert_array_equal(st["H_tilde"], st["Ht"][ref["inverse"]])     # a pure row copy
+            pad = ref["uniq"] == 0
+            assert pad.any() and np.all(st["Ht"][pad] == 0.0)
+        # one-step window: the pseudo-target of an item met once is h - dL/dh of that position
+        one = run_window(X, W, batches[:1], vocab_n=n, k_steps=1, pseudo=True)["steps"][0]
+        ref = orc.gram_single(batches[0][0], X, W, batches[0][1])
+        once = np.flatnonzero((ref["counts"] == 1) & (ref["uniq"] != 0))
+        first = np.full(ref["uniq"].size, -1)
+        first[ref["inverse"][::-1]] = np.arange(batches[0][0].size)[::-1]
+        np.testing.assert_array_equal(one["Ht"][once], (one["E"][once] - batches[0][1][first[once]]).astype(np.float32))
+
+
+def test_pseudo_targets_after_the_fused_forward():
+    """Large batch: E comes from the contraction that also stored H to the positions."""
+    n, m = 70000, 70000
+    rng = np.random.default_rng(31)
+    ids = rng.integers(1, 3000, size=m).astype(np.int32)         # every item many times ...
+    ids[: m // 2] = rng.integers(1, n, size=m // 2)              # ... or about once
+    ids[rng.random(m) < 0.05] = 0
+    ids, X, W, dH = small_problem(32, m, n, d_in=64, d=256, bf16=True, ids=ids)
+    say("pseudo-targets after the fused forward")
+    out = run_window(X, W, [(ids, dH)], vocab_n=n, pseudo=True, profile=["gather_heavy", "pseudo_target", "pseudo_loss"])
+    assert {k: v[0] for k, v in out["profile"].items()} == {"gather_heavy": 1, "pseudo_target": 1, "pseudo_loss": 1}
+    ref = orc.gram_single(ids, X, W, dH)
+    Ht_ref, loss_ref = orc.pseudo_target(ref["E"], ref["G"])
+    st = out["steps"][0]
+    assert_close(st["Ht"], Ht_ref, TOL_SUM[wl.BF16], "Ht")
+    assert abs(st["loss"] - loss_ref) <= TOL_SUM[wl.BF16] * loss_ref
+    np.testing.assert_array_equal(st["H_tilde"], st["Ht"][ref["inverse"]])
+
+
 def test_error_paths():
     import torch
     from paper_2204_04179_amd import gram
@@ -332,6 +382,7 @@ def test_error_paths():
 
     say("errors: sequence")
     assert status(lambda: g.grad_accumulate(dH, m, 0)) == gram.ERR_SEQUENCE        # no unique yet
+    assert status(lambda: g.pseudo_target(dH, dH)) == gram.ERR_SEQUENCE            # nothing accumulated yet
     assert status(lambda: g.encoder_wgrad(X, dW)) == gram.ERR_SEQUENCE             # empty window
     g.unique(ids, uniq, inv, cnt)
     assert status(lambda: g.grad_accumulate(dH, m, 1)) == gram.ERR_SEQUENCE        # wrong step index
