@@ -246,6 +246,37 @@ def cpu_baseline(r, target_s=12.0):
                 seconds=t)
 
 
+def pseudo_target_leg(r, reps=20):
+    """Outside the timed steps: the pseudo-target kernel (Algorithm 1 step 3, Eq. 6) on the items of
+    one step, E requested from the forward; algorithmic bytes = E and G rows read, Ht rows written."""
+    torch, g, w = r.torch, r.g, r.w
+    r.finish_window()
+    cap_u = min(w.M, w.N)
+    E = torch.empty(cap_u, w.d, device="cuda")
+    Ht = torch.empty(cap_u, w.d, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    g.unique(r.ids[0], r.uniq, r.inverse, r.counts, r.u_dev)
+    g.encode_gather(r.X, r.Wt, r.uniq, r.inverse, r.u_dev, r.M, E, r.H)
+    g.grad_accumulate(r.dH[0], r.M, 0)
+    r.pos = 1
+    g.pseudo_target(E, Ht, loss)
+    torch.cuda.synchronize()
+    g.profile_enable(["pseudo_target", "pseudo_loss"], max_launches=4 * reps)
+    for _ in range(reps):
+        g.pseudo_target(E, Ht, loss)
+    prof = g.profile_read()
+    g.profile_enable([])
+    r.finish_window()
+    torch.cuda.synchronize()
+    n, ms = prof["pseudo_target"]
+    us = 1e3 * ms / n
+    nbytes = 3 * 4 * r.stats[0]["U"] * w.d
+    return {"avg_us": us, "loss_reduce_us": 1e3 * prof["pseudo_loss"][1] / prof["pseudo_loss"][0],
+            "bound": "hbm", "algorithmic_bytes": nbytes, "achieved": nbytes / (us * 1e-6) / 1e9,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+            "pseudo_loss": float(loss.item())}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -321,6 +352,7 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(r)
         out["gpu_over_cpu"] = value / out["cpu_baseline"]["value"]
+    out["next_rows"] = {"pseudo_target": pseudo_target_leg(r)}
     out["paper_context"] = "paper: Single-step ~4x, Multi-step up to 146x faster than E2E, whole training runs on A100"
     del r
     torch.cuda.empty_cache()
