@@ -283,7 +283,8 @@ def main():
     ap.add_argument("--steps", type=int, default=80)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="stress")
-    ap.add_argument("--also", default="kt", help="second workload reported under 'also' ('' = none)")
+    ap.add_argument("--also", default="kt,news,kt_multi",
+                    help="comma-separated workloads reported under 'also' ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-export-G", action="store_true", help="gram_flush without the G_total copy")
     ap.add_argument("--copy-probe", action="store_true",
@@ -357,8 +358,9 @@ def main():
     del r
     torch.cuda.empty_cache()
 
-    if args.also:
-        w2 = wl.get(args.also)
+    also = []
+    for name in [a for a in args.also.split(",") if a]:
+        w2 = wl.get(name)
         r2 = Runner(w2, export_G=not args.no_export_G)
         for _ in range(w2.K):
             r2.step()
@@ -367,12 +369,16 @@ def main():
         dt2, _ = time_steps(r2, steps2, 20)
         windows2 = steps2 // w2.K
         dt3 = time_windows_graph(r2, windows2)
-        out["also"] = {"workload": w2.name, "value": r2.M_valid_per_step * steps2 / dt2,
-                       "unit": "occurrences/s", "us_per_step": 1e6 * dt2 / steps2, "steps": steps2,
-                       "hip_graph_replay": {"value": r2.M_valid_per_step * windows2 * w2.K / dt3,
-                                            "us_per_step": 1e6 * dt3 / (windows2 * w2.K)},
-                       "kernels_us": {k: round(v["avg_us"], 1) for k, v in kernel_breakdown(r2, 20).items()},
-                       "note": "launch-latency bound: a few microseconds of HBM traffic per step"}
+        also.append({"workload": w2.name, "value": r2.M_valid_per_step * steps2 / dt2,
+                     "unit": "occurrences/s", "us_per_step": 1e6 * dt2 / steps2, "steps": steps2,
+                     "hip_graph_replay": {"value": r2.M_valid_per_step * windows2 * w2.K / dt3,
+                                          "us_per_step": 1e6 * dt3 / (windows2 * w2.K)},
+                     "kernels_us": {k: round(v["avg_us"], 1) for k, v in kernel_breakdown(r2, 20).items()},
+                     "note": "launch-latency bound: a few microseconds of HBM traffic per step"})
+        del r2
+        torch.cuda.empty_cache()
+    if also:
+        out["also"] = also
     print(json.dumps(out))
 
 
