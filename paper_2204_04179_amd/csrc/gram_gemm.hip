@@ -2,15 +2,19 @@
 // for the content encoder:
 //   forward  (Algorithm 1 step 1, Eq. 4):  E[j,:]  = X[uniq[j],:] . W
 //   wgrad    (Algorithm 1 step 4, Eq. 7/9): dW[i,c] = sum_s X[item_s, i] * G[s, c]
-// bf16 inputs run on the matrix cores (v_mfma_f32_32x32x16_bf16, fp32
-// accumulate) through ONE tuned kernel, k_gemm_nt_bf16: C = A . B^T with both
-// operands stored with the contraction index contiguous.
-//   forward: A = rows of X gathered through the unique-ID list inside the tile
-//            loads (the unique items' features are never copied), B = W^T.
-//   wgrad:   A = XT[i][s] (features of the buffer's items, transposed),
-//            B = GT[c][s] (the gradient buffer rounded to bf16, transposed);
-//            the contraction over buffer rows is split over blocks (split-K)
-//            and the float32 partials are added in split order.
+// bf16 inputs run on the matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
+//   forward: k_gemm_nt_bf16, C = A . B^T with both operands stored with the
+//            contraction index contiguous: A = rows of X gathered through the
+//            unique-ID list inside the tile loads (the unique items' features are
+//            never copied), B = W^T.  For large batches its epilogue is the gather
+//            as well: every representation is stored straight to the positions of
+//            its item.  Small batches take k_encode_bf16.
+//   wgrad:   k_wgrad_tn_bf16 contracts over the rows of the gradient buffer, which
+//            is the slow dimension of both operands in memory, with transposing
+//            LDS reads; split-K over blocks, float32 partials added in split order.
+//   Operands beyond 4 GiB cannot be addressed through a buffer descriptor: the
+//   forward then takes k_gemm_nt_bf16_dma, the weight gradient transposed bf16
+//   copies (k_transpose_x / k_transpose_g) followed by k_gemm_nt_bf16.
 // The float32 variants are plain FMA code for small problems.
 #include "gram_internal.h"
 
@@ -150,8 +154,10 @@ __global__ __launch_bounds__(kBlock) void k_encode_bf16(
             }
 }
 
-// ---- the tuned kernel: C[M,N] = A[M,K] . B[N,K]^T, bf16 in, fp32 out ---------------
+// ---- C[M,N] = A[M,K] . B[N,K]^T, bf16 in, fp32 out: direct-to-LDS variant -----------
 //
+// (Used for operands beyond 4 GiB; see k_gemm_nt_bf16 below for the faster
+// register-staged variant.)
 // 256x256 block tile, 4 waves each owning a 128x128 quadrant (4x4 MFMA tiles,
 // 256 accumulator registers per lane).  K advances in slabs of 32 through a
 // ring of 4 LDS stages filled by direct global->LDS loads
@@ -866,11 +872,13 @@ bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
 // partials in range order.  The ranges depend only on the number of rows in
 // the buffer, so the result is reproducible.
 //
-// bf16: both operands have the contraction index (buffer row) as their slow
-// dimension in memory, so they are first transposed into workspace:
+// Wide-address path only (an operand beyond 4 GiB): both operands have the
+// contraction index (buffer row) as their slow dimension in memory, so they are
+// first transposed into workspace by the two transpose kernels above,
 //   XT[i][s] = X[item_s][i]            (gather + transpose, zero for padding)
 //   GT[c][s] = bf16(G[s][c])           (round to nearest even + transpose)
-// with rows padded by zeros up to a multiple of 64 buffer rows.
+// with rows padded by zeros up to a multiple of 64 buffer rows, and contracted by
+// k_gemm_nt_bf16.
 
 // ---- weight gradient without transposed copies ---------------------------------------
 //
@@ -890,7 +898,7 @@ bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
 // Loads go through buffer descriptors; a row past the end of the buffer, a
 // padding item or a column past the matrix edge is turned into an out-of-range
 // offset, for which the hardware returns zeros.
-// Same pipeline as k_gemm_nt_bf16: two register sets, two LDS stages, one
+// Same pipeline as k_gemm_nt_bf16: register-staged loads, two LDS stages, one
 // barrier per slab of 32 buffer rows; split-K with one K range per XCD.
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 typedef short v8i16 __attribute__((ext_vector_type(8)));
