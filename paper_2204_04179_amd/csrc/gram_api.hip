@@ -371,7 +371,7 @@ static const char* const kKernelNames[KID_COUNT] = {
     "radix_hist", "radix_scan", "radix_scatter", "heads_count", "heads_emit", "counts", "unique_empty",
     "transpose_w", "encode_bf16", "encode_f32", "gather_rows", "slot_count", "slot_emit", "seg_reduce",
     "seg_combine", "wgrad_bf16", "wgrad_f32", "wgrad_reduce", "transpose_x", "transpose_g", "flush_meta",
-    "flush_rows", "flush_finish", "unique_small", "gather_heavy", "pseudo_target", "pseudo_loss"};
+    "flush_rows", "unique_small", "gather_heavy", "pseudo_target", "pseudo_loss"};
 
 int gram_kernel_count(void) { return KID_COUNT; }
 

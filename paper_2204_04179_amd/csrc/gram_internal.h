@@ -18,7 +18,9 @@ constexpr int kWavesPerBlock = kBlock / kWave;
 constexpr int kMaxDigitBits = 10;       // radix digit width limit (1024 LDS bins per wave)
 constexpr int kScanTile = 1024;         // rows per block in the flag-scan kernels
 constexpr int kSegRows = 32;            // sorted rows per tile of the segment reduction
-constexpr int kSegLong = 128;           // segments with at least this many rows are reduced tile by tile
+constexpr int kSegLong = 64;            // segments with at least this many rows are reduced tile by tile ...
+constexpr int kSegLongSmall = 32;       // ... or this many when the batch has at most kSegSmallBatch positions
+constexpr int kSegSmallBatch = 65536;
 constexpr int kLightMax = 32;           // items with more positions are gathered by a separate copy kernel
 constexpr int kSlotNew = 1 << 30;
 constexpr int kPseudoRows = 8;          // unique items per block of the pseudo-target kernel       // flag in seg_slot: the buffer row is created by this step
@@ -37,7 +39,7 @@ enum KernelId {
     KID_RADIX_HIST = 0, KID_RADIX_SCAN, KID_RADIX_SCATTER, KID_HEADS_COUNT, KID_HEADS_EMIT, KID_COUNTS,
     KID_UNIQUE_EMPTY, KID_TRANSPOSE_U16, KID_ENCODE_BF16, KID_ENCODE_F32, KID_GATHER_ROWS,
     KID_SLOT_COUNT, KID_SLOT_EMIT, KID_SEG_REDUCE, KID_SEG_COMBINE, KID_WGRAD_BF16, KID_WGRAD_F32,
-    KID_WGRAD_REDUCE, KID_TRANSPOSE_X, KID_TRANSPOSE_G, KID_FLUSH_META, KID_FLUSH_ROWS, KID_FLUSH_FINISH, KID_UNIQUE_SMALL,
+    KID_WGRAD_REDUCE, KID_TRANSPOSE_X, KID_TRANSPOSE_G, KID_FLUSH_META, KID_FLUSH_ROWS, KID_UNIQUE_SMALL,
     KID_GATHER_HEAVY, KID_PSEUDO_TARGET, KID_PSEUDO_LOSS, KID_COUNT
 };
 

@@ -256,7 +256,7 @@ void pseudo_target(Ctx* c, const float* E, float* Ht, double* loss_dev, hipStrea
 __global__ __launch_bounds__(kBlock) void k_slot_count(const int* __restrict__ uniq_ws,
                                                        const int* __restrict__ slot_of,
                                                        int* __restrict__ scal,
-                                                       int* __restrict__ tile_sums)
+                                                       int* __restrict__ tile_sums, int first_step)
 {
     __shared__ int sm[kWavesPerBlock];
     const int u = scal[kSU];
@@ -269,7 +269,7 @@ __global__ __launch_bounds__(kBlock) void k_slot_count(const int* __restrict__ u
     if (threadIdx.x == 0) {
         tile_sums[blockIdx.x] = tot;
         if (blockIdx.x == 0) {
-            scal[kSUBase] = scal[kSUTotal];
+            scal[kSUBase] = first_step ? 0 : scal[kSUTotal];   // a flush leaves the old count behind
             scal[kSLongCount] = 0;
         }
     }
@@ -336,11 +336,11 @@ __global__ __launch_bounds__(kBlock) void k_slot_emit(
 __global__ __launch_bounds__(kBlock) void k_slot_small(
     const int* __restrict__ uniq_ws, const int* __restrict__ offsets, int* __restrict__ slot_of,
     int* __restrict__ id_of_slot, int* __restrict__ cnt_of_slot, int* __restrict__ seg_slot,
-    int* __restrict__ scal, int cap_total)
+    int* __restrict__ scal, int cap_total, int first_step)
 {
     __shared__ int sm[kWavesPerBlock];
     const int u = scal[kSU];
-    int run_base = scal[kSUTotal];
+    int run_base = first_step ? 0 : scal[kSUTotal];             // a flush leaves the old count behind
     bool overflow = false;
     for (int j0 = threadIdx.x * 4; j0 - threadIdx.x * 4 < u; j0 += kScanTile) {   // uniform trip count
         int id[4], old[4], sflag = 0;
@@ -394,14 +394,15 @@ void assign_slots(Ctx* c, hipStream_t s)
 {
     int64_t bound = c->cur_m < c->cap_u ? c->cur_m : c->cap_u;
     if (bound < 1) bound = 1;
+    const int first_step = c->steps_done == 0 ? 1 : 0;
     if (bound <= kSmallBatch) {
         launch(c, KID_SLOT_EMIT, k_slot_small, dim3(1), dim3(kBlock), s, c->uniq_ws, c->offsets, c->slot_of,
-               c->id_of_slot, c->cnt_of_slot, c->seg_slot, c->scal, (int)c->cap_total);
+               c->id_of_slot, c->cnt_of_slot, c->seg_slot, c->scal, (int)c->cap_total, first_step);
         return;
     }
     const int tiles = (int)((bound + kScanTile - 1) / kScanTile);
     launch(c, KID_SLOT_COUNT, k_slot_count, dim3(tiles), dim3(kBlock), s, c->uniq_ws, c->slot_of, c->scal,
-                       c->tile_sums);
+                       c->tile_sums, first_step);
     launch(c, KID_SLOT_EMIT, k_slot_emit, dim3(tiles), dim3(kBlock), s, c->uniq_ws, c->offsets,
                        c->slot_of, c->id_of_slot, c->cnt_of_slot, c->seg_slot, c->scal, c->tile_sums,
                        (int)c->cap_total);
@@ -412,7 +413,7 @@ void assign_slots(Ctx* c, hipStream_t s)
 // Rows of dH are visited in the sorted order of the batch (perm), where the
 // occurrences of one item are adjacent and in ascending position.  The sorted
 // rows are cut into tiles of kSegRows.
-//  * A short segment (< kSegLong rows) is summed, whole and in order, by the
+//  * A short segment (< seg_long rows: kSegLong, or kSegLongSmall for small batches) is summed, whole and in order, by the
 //    tile that holds its first row, even where it runs past the tile's end; it
 //    needs no partial result.
 //  * A long segment is summed tile by tile into partial rows (seg_last for the
@@ -442,7 +443,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(
     const int* __restrict__ offsets, const int* __restrict__ uniq_ws,
     const int* __restrict__ seg_slot, int n, int cols4, int pad_id, float4* __restrict__ G,
     float4* __restrict__ seg_first, float4* __restrict__ seg_last, int* __restrict__ scal,
-    int* __restrict__ long_list)
+    int* __restrict__ long_list, int seg_long)
 {
     __shared__ int s_src[kSegMaxRows];    // dH row of each sorted row, -1 = padding (not read)
     __shared__ int s_dst[kSegMaxRows];    // 0 = keep adding; else destination code + 4 (see below)
@@ -457,10 +458,10 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(
     {
         const int sg = seg_of_row[r0];
         const int o0 = offsets[sg], o1 = offsets[sg + 1];
-        a = (o0 < r0 && o1 - o0 < kSegLong) ? o1 : r0;
+        a = (o0 < r0 && o1 - o0 < seg_long) ? o1 : r0;
         const int sl = seg_of_row[r1 - 1];
         const int p0 = offsets[sl], p1 = offsets[sl + 1];
-        b = (p1 - p0 < kSegLong) ? p1 : r1;
+        b = (p1 - p0 < seg_long) ? p1 : r1;
     }
     if (a >= r1) return;      // the tile lies inside a short segment owned by an earlier tile
     const int rows = b - a;
@@ -469,7 +470,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(
         const int r = a + i;
         const int sg = seg_of_row[r];
         const int o0 = offsets[sg], o1 = offsets[sg + 1];
-        const bool is_long = o1 - o0 >= kSegLong;
+        const bool is_long = o1 - o0 >= seg_long;
         const bool is_pad = uniq_ws[sg] == pad_id;
         const bool seg_end = r + 1 == o1;
         int code = 0;
@@ -577,13 +578,16 @@ void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s)
     int threads = ((cols4 + kWave - 1) / kWave) * kWave;
     if (threads > kBlock) threads = kBlock;
     const int slabs = (cols4 + threads - 1) / threads;
+    // Whole-segment sums are one block's serial chain of row loads: short chains matter most when
+    // the batch has few tiles to hide them behind.
+    const int seg_long = n > kSegSmallBatch ? kSegLong : kSegLongSmall;
     const int tiles = (n + kSegRows - 1) / kSegRows;
     launch(c, KID_SEG_REDUCE, k_seg_reduce, dim3(tiles, slabs), dim3(threads), s,
                        reinterpret_cast<const float4*>(dH), c->perm, c->seg_of_row, c->offsets,
                        c->uniq_ws, c->seg_slot, n, cols4, c->cfg.pad_id,
                        reinterpret_cast<float4*>(c->G), reinterpret_cast<float4*>(c->seg_first),
-                       reinterpret_cast<float4*>(c->seg_last), c->scal, c->long_list);
-    int fix_blocks = tiles / (kSegLong / kSegRows) + 1;   // upper bound of long segments
+                       reinterpret_cast<float4*>(c->seg_last), c->scal, c->long_list, seg_long);
+    int fix_blocks = tiles / (seg_long / kSegRows) + 1;   // upper bound of long segments
     if (fix_blocks > 256) fix_blocks = 256;
     launch(c, KID_SEG_COMBINE, k_seg_combine, dim3(fix_blocks, (cols4 + kFixCols4 - 1) / kFixCols4),
                        dim3(kBlock), s, c->seg_of_row, c->offsets, c->uniq_ws, c->seg_slot, n,
@@ -593,25 +597,41 @@ void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s)
 }
 
 // ---- end of the window: export in ascending ID order, then empty ------------
+//
+// One launch: rows of G are copied out in ascending ID order; the thread that moves the first
+// piece of a row also exports its ID and count and clears the item's entry of the slot map.
+// The count of buffer rows (scal[kSUTotal]) is left as it is: every block reads it here, and
+// the first step of the next window starts from zero by itself.  `n_zero`: the window is empty.
+
+__device__ __forceinline__ void flush_meta_row(int r, const int* sorted_ids, const int* sorted_slots,
+                                               const int* cnt_of_slot, int* slot_of, int* uniq_total,
+                                               int* counts_total)
+{
+    const int id = sorted_ids[r];
+    if (uniq_total) uniq_total[r] = id;
+    if (counts_total) counts_total[r] = cnt_of_slot[sorted_slots ? sorted_slots[r] : r];
+    slot_of[id] = -1;
+}
 
 __global__ __launch_bounds__(kBlock) void k_flush_meta(
     const int* __restrict__ sorted_ids, const int* __restrict__ sorted_slots,
     const int* __restrict__ cnt_of_slot, int* __restrict__ slot_of, int* __restrict__ uniq_total,
-    int* __restrict__ counts_total, const int* __restrict__ scal)
+    int* __restrict__ counts_total, int* __restrict__ scal, int* __restrict__ u_total_dev, int n_zero)
 {
-    const int n = scal[kSUTotal];
-    for (int r = blockIdx.x * kBlock + threadIdx.x; r < n; r += gridDim.x * kBlock) {
-        const int id = sorted_ids[r];
-        if (uniq_total) uniq_total[r] = id;
-        if (counts_total) counts_total[r] = cnt_of_slot[sorted_slots ? sorted_slots[r] : r];
-        slot_of[id] = -1;
+    const int n = n_zero ? 0 : scal[kSUTotal];
+    for (int r = blockIdx.x * kBlock + threadIdx.x; r < n; r += gridDim.x * kBlock)
+        flush_meta_row(r, sorted_ids, sorted_slots, cnt_of_slot, slot_of, uniq_total, counts_total);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        if (u_total_dev) *u_total_dev = n;
+        scal[kSFlushN] = n;
     }
 }
 
-__global__ __launch_bounds__(kBlock) void k_flush_rows(const int* __restrict__ sorted_slots,
-                                                       const float4* __restrict__ G, int cols4,
-                                                       float4* __restrict__ G_total,
-                                                       const int* __restrict__ scal)
+__global__ __launch_bounds__(kBlock) void k_flush_rows(
+    const int* __restrict__ sorted_ids, const int* __restrict__ sorted_slots,
+    const int* __restrict__ cnt_of_slot, int* __restrict__ slot_of, int* __restrict__ uniq_total,
+    int* __restrict__ counts_total, const float4* __restrict__ G, int cols4,
+    float4* __restrict__ G_total, int* __restrict__ scal, int* __restrict__ u_total_dev)
 {
     const int n = scal[kSUTotal];
     const int64_t total = (int64_t)n * cols4;
@@ -622,22 +642,23 @@ __global__ __launch_bounds__(kBlock) void k_flush_rows(const int* __restrict__ s
         const f32x4 t = __builtin_nontemporal_load(
             reinterpret_cast<const f32x4*>(G) + (int64_t)(sorted_slots ? sorted_slots[r] : (int)r) * cols4 + cc);
         __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(G_total) + i);
+        if (cc == 0)
+            flush_meta_row((int)r, sorted_ids, sorted_slots, cnt_of_slot, slot_of, uniq_total, counts_total);
     }
-}
-
-__global__ void k_flush_finish(int* __restrict__ scal, int* __restrict__ u_total_dev)
-{
-    if (threadIdx.x == 0) {
-        const int n = scal[kSUTotal];
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
         if (u_total_dev) *u_total_dev = n;
         scal[kSFlushN] = n;
-        scal[kSUTotal] = 0;
     }
 }
 
 void flush_export(Ctx* c, int* uniq_total, int* counts_total, float* G_total, int* u_total_dev,
                   hipStream_t s)
 {
+    if (c->steps_done == 0) {       // nothing accumulated since the last flush
+        launch(c, KID_FLUSH_META, k_flush_meta, dim3(1), dim3(kBlock), s, c->id_of_slot, (const int*)nullptr,
+               c->cnt_of_slot, c->slot_of, uniq_total, counts_total, c->scal, u_total_dev, 1);
+        return;
+    }
     // After one step the buffer rows are already in ascending ID order (rows are handed out in
     // that order within a step); only later steps append out of order.
     const int* sorted_ids = c->id_of_slot;
@@ -648,15 +669,18 @@ void flush_export(Ctx* c, int* uniq_total, int* counts_total, float* G_total, in
         sorted_ids = c->keys[r];
         sorted_slots = c->vals[r];
     }
-    int64_t blocks = (c->cap_total + kBlock - 1) / kBlock;
-    if (blocks > 1024) blocks = 1024;
-    launch(c, KID_FLUSH_META, k_flush_meta, dim3((unsigned)blocks), dim3(kBlock), s, sorted_ids,
-                       sorted_slots, c->cnt_of_slot, c->slot_of, uniq_total, counts_total, c->scal);
-    if (G_total)
-        launch(c, KID_FLUSH_ROWS, k_flush_rows, dim3(2048), dim3(kBlock), s, sorted_slots,
-                           reinterpret_cast<const float4*>(c->G), c->cfg.d / 4,
-                           reinterpret_cast<float4*>(G_total), c->scal);
-    launch(c, KID_FLUSH_FINISH, k_flush_finish, dim3(1), dim3(kWave), s, c->scal, u_total_dev);
+    if (G_total) {
+        int64_t blocks = (c->cap_total * (c->cfg.d / 4) + kBlock - 1) / kBlock;
+        if (blocks > 2048) blocks = 2048;
+        launch(c, KID_FLUSH_ROWS, k_flush_rows, dim3((unsigned)blocks), dim3(kBlock), s, sorted_ids, sorted_slots,
+               c->cnt_of_slot, c->slot_of, uniq_total, counts_total, reinterpret_cast<const float4*>(c->G),
+               c->cfg.d / 4, reinterpret_cast<float4*>(G_total), c->scal, u_total_dev);
+    } else {
+        int64_t blocks = (c->cap_total + kBlock - 1) / kBlock;
+        if (blocks > 1024) blocks = 1024;
+        launch(c, KID_FLUSH_META, k_flush_meta, dim3((unsigned)blocks), dim3(kBlock), s, sorted_ids,
+               sorted_slots, c->cnt_of_slot, c->slot_of, uniq_total, counts_total, c->scal, u_total_dev, 0);
+    }
 }
 
 }  // namespace gram

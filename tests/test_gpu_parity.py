@@ -195,9 +195,10 @@ def test_vocabulary_sizes_change_the_radix_plan(vocab_bits, m):
 
 def test_segment_lengths_around_tile_and_long_thresholds():
     """Runs of 1..400 equal IDs laid out so that segments start and end at every
-    offset relative to the 32-row tiles and cross the 128-row 'long' threshold."""
-    lengths = [1, 2, 31, 32, 33, 1, 127, 128, 129, 1, 1, 160, 64, 400, 3, 96, 255, 256, 257, 5, 1000, 1,
-               4000, 7, 2500]      # 10,490 rows: beyond the one-launch dedup as well
+    offset relative to the 32-row tiles and cross the 'long segment' threshold (32 rows at this
+    batch size; the 64-row threshold of large batches is crossed in the fused-forward test)."""
+    lengths = [1, 2, 31, 32, 33, 1, 127, 128, 129, 1, 1, 160, 63, 64, 65, 400, 3, 96, 255, 256, 257, 5, 1000, 1,
+               4000, 7, 2500]      # 10,618 rows: beyond the one-launch dedup as well
     ids = np.concatenate([np.full(L, i + 1, np.int32) for i, L in enumerate(lengths)])
     rng = np.random.default_rng(3)
     ids = ids[rng.permutation(ids.size)]
@@ -359,6 +360,35 @@ def test_pseudo_targets_after_the_fused_forward():
     assert_close(st["Ht"], Ht_ref, TOL_SUM[wl.BF16], "Ht")
     assert abs(st["loss"] - loss_ref) <= TOL_SUM[wl.BF16] * loss_ref
     np.testing.assert_array_equal(st["H_tilde"], st["Ht"][ref["inverse"]])
+
+
+def test_flush_variants_and_back_to_back_windows():
+    """gram_flush with and without the G export gives the same IDs and counts; a second flush of an
+    empty window returns nothing; a context runs window after window with one- and multi-step
+    windows mixed (the count of buffer rows restarts with each window)."""
+    import torch
+    n, K = 900, 3
+    probs = [small_problem(300 + k, 3000, n, d_in=16, d=8) for k in range(K)]
+    X, W = probs[0][1], probs[0][2]
+    batches = [(p[0], p[3]) for p in probs]
+    a = run_window(X, W, batches, vocab_n=n, k_steps=K, want_G=True)
+    b = run_window(X, W, batches, vocab_n=n, k_steps=K, want_G=False, gram_obj=a["gram"])
+    np.testing.assert_array_equal(a["uniq_total"], b["uniq_total"])
+    np.testing.assert_array_equal(a["counts_total"], b["counts_total"])
+    assert a["dW"].tobytes() == b["dW"].tobytes()
+    g = a["gram"]
+    u = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    cnt = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    ud = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    assert g.flush(u, cnt, None, ud, want_host_u=True) == 0          # empty window
+    assert int(ud.item()) == 0 and bool((u == -7).all().item())
+    # a one-step window on the same context, then the full window again
+    c = run_window(X, W, batches[:1], vocab_n=n, k_steps=K, gram_obj=g, max_positions=3000)
+    ref = orc.gram_single(batches[0][0], X, W, batches[0][1])
+    np.testing.assert_array_equal(c["uniq_total"], ref["uniq"])
+    assert_close(c["G_total"], ref["G"], 1e-5, "G one-step window")
+    d = run_window(X, W, batches, vocab_n=n, k_steps=K, gram_obj=g)
+    assert d["G_total"].tobytes() == a["G_total"].tobytes() and d["dW"].tobytes() == a["dW"].tobytes()
 
 
 def test_error_paths():
