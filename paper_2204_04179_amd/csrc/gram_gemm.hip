@@ -42,33 +42,16 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     return (uint16_t)(u >> 16);
 }
 
-// ---- small forward kernel: 128x128 tile, register-staged LDS ------------------
-// Used when the batch is small (few row tiles) or d_in is not a multiple of 32.
+// ---- small forward kernel: latency first ------------------------------------------
+//
+// Batches whose unique items give the 256x256 kernel fewer tiles than there are CUs (and any
+// d_in that is not a multiple of 32).  Such a launch is bound by the latency of its loads,
+// not by arithmetic: a 64x64 tile per block (one 32x32 MFMA tile per wave) puts a block on
+// nearly every CU, K advances in slabs of 64, and the loads of three slabs are in flight in
+// registers ahead of the one being multiplied.  Two LDS buffers, one barrier per slab.
 
-constexpr int BM = 128, BN = 128, BK = 32;
-constexpr int LDS_STRIDE = BK + 8;   // bf16 elements per LDS row (80 bytes: 16-byte aligned, staggers banks)
-
-// One BK slab of a 128x128 block tile: each of the 4 waves owns a 64x64
-// quadrant as 2x2 MFMA tiles.  sA/sB hold [row][k] with k contiguous.
-__device__ __forceinline__ void mma_slab(const uint16_t* sA, const uint16_t* sB, int wm, int wn,
-                                         int lane, f32x16 (&acc)[2][2])
-{
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-        const int koff = ks * 16 + (lane >> 5) * 8;
-        bf16x8 a[2], b[2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            a[i] = *reinterpret_cast<const bf16x8*>(&sA[(wm * 64 + i * 32 + (lane & 31)) * LDS_STRIDE + koff]);
-            b[i] = *reinterpret_cast<const bf16x8*>(&sB[(wn * 64 + i * 32 + (lane & 31)) * LDS_STRIDE + koff]);
-        }
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
-}
+constexpr int BM = 64, BN = 64, BK = 64, kSmallDepth = 3;
+constexpr int LDS_STRIDE = BK + 8;   // bf16 elements per LDS row (144 bytes: 16-byte aligned, staggers banks)
 
 // W[d_in,d] -> Wt[d,d_in] (bf16)
 __global__ __launch_bounds__(kBlock) void k_transpose_u16(const uint16_t* __restrict__ W, int rows,
@@ -84,74 +67,102 @@ __global__ __launch_bounds__(kBlock) void k_transpose_u16(const uint16_t* __rest
         if (c0 + y < cols && r0 + tx < rows) Wt[(int64_t)(c0 + y) * rows + r0 + tx] = tile[tx][y];
 }
 
+__device__ __forceinline__ uint4 and4(uint4 v, uint32_t m) { return make_uint4(v.x & m, v.y & m, v.z & m, v.w & m); }
+
 __global__ __launch_bounds__(kBlock) void k_encode_bf16(
     const uint16_t* __restrict__ X, const uint16_t* __restrict__ Wt, const int* __restrict__ uniq,
     const int* __restrict__ u_dev, int d_in, int d, int pad_id, float* __restrict__ E)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t sA[BM * LDS_STRIDE];
-    __shared__ __attribute__((aligned(16))) uint16_t sB[BN * LDS_STRIDE];
+    __shared__ __attribute__((aligned(16))) uint16_t sA[2][BM * LDS_STRIDE];
+    __shared__ __attribute__((aligned(16))) uint16_t sB[2][BN * LDS_STRIDE];
     const int U = *u_dev;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     if (m0 >= U) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
 
-    // each thread moves two 16-byte chunks of A and of B per slab
-    const uint16_t* pa[2];
-    const uint16_t* pb[2];
-    int kc[2], lrow[2];
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int cid = tid + h * kBlock;
-        lrow[h] = cid >> 2;
-        kc[h] = (cid & 3) * 8;
-        const int j = m0 + lrow[h];
-        pa[h] = j < U ? X + (int64_t)uniq[j] * d_in : nullptr;
-        pb[h] = n0 + lrow[h] < d ? Wt + (int64_t)(n0 + lrow[h]) * d_in : nullptr;
+    // each thread moves two 16-byte chunks of A and of B per slab: chunk cid = tid + 256 h is
+    // bytes [16 (cid % 8), +16) of row cid / 8.  Rows past the end are clamped to a valid row
+    // (their products are never stored); chunks past d_in are loaded from the row's start and
+    // replaced by zeros.
+    const uint16_t* pa0;
+    const uint16_t* pa1;
+    const uint16_t* pb0;
+    const uint16_t* pb1;
+    const int kc0 = (tid & 7) * 8, kc1 = kc0;               // 256 is a multiple of 8: same chunk column
+    const int lrow0 = tid >> 3, lrow1 = (tid + kBlock) >> 3;
+    {
+        const int j0 = m0 + lrow0 < U ? m0 + lrow0 : U - 1, j1 = m0 + lrow1 < U ? m0 + lrow1 : U - 1;
+        pa0 = X + (int64_t)uniq[j0] * d_in;
+        pa1 = X + (int64_t)uniq[j1] * d_in;
+        const int c0 = n0 + lrow0 < d ? n0 + lrow0 : d - 1, c1 = n0 + lrow1 < d ? n0 + lrow1 : d - 1;
+        pb0 = Wt + (int64_t)c0 * d_in;
+        pb1 = Wt + (int64_t)c1 * d_in;
     }
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
-    uint4 ra[2], rb[2];
-    auto load_slab = [&](int k0) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const bool kin = k0 + kc[h] < d_in;
-            ra[h] = (pa[h] && kin) ? *reinterpret_cast<const uint4*>(pa[h] + k0 + kc[h]) : zero4;
-            rb[h] = (pb[h] && kin) ? *reinterpret_cast<const uint4*>(pb[h] + k0 + kc[h]) : zero4;
-        }
-    };
-
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    load_slab(0);
-    for (int k0 = 0; k0 < d_in; k0 += BK) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            *reinterpret_cast<uint4*>(&sA[lrow[h] * LDS_STRIDE + kc[h]]) = ra[h];
-            *reinterpret_cast<uint4*>(&sB[lrow[h] * LDS_STRIDE + kc[h]]) = rb[h];
-        }
-        __syncthreads();
-        if (k0 + BK < d_in) load_slab(k0 + BK);
-        mma_slab(sA, sB, wm, wn, lane, acc);
-        __syncthreads();
+    uint4 a00, a01, b00, b01, a10, a11, b10, b11, a20, a21, b20, b21;     // three register sets
+#define GRAM_LOAD_SLAB(S, K0)                                                                       \
+    {                                                                                               \
+        const int k_ = (K0) + kc0;                                                                  \
+        const int ks_ = k_ < d_in ? k_ : 0;                                                         \
+        a##S##0 = *reinterpret_cast<const uint4*>(pa0 + ks_);                                       \
+        a##S##1 = *reinterpret_cast<const uint4*>(pa1 + ks_);                                       \
+        b##S##0 = *reinterpret_cast<const uint4*>(pb0 + ks_);                                       \
+        b##S##1 = *reinterpret_cast<const uint4*>(pb1 + ks_);                                       \
     }
+#define GRAM_PARK_SLAB(S, K0, BUF)                                                                  \
+    {                                                                                               \
+        const uint32_t keep_ = (K0) + kc0 < d_in ? 0xFFFFFFFFu : 0u;                                \
+        *reinterpret_cast<uint4*>(&sA[BUF][lrow0 * LDS_STRIDE + kc0]) = and4(a##S##0, keep_);       \
+        *reinterpret_cast<uint4*>(&sA[BUF][lrow1 * LDS_STRIDE + kc1]) = and4(a##S##1, keep_);       \
+        *reinterpret_cast<uint4*>(&sB[BUF][lrow0 * LDS_STRIDE + kc0]) = and4(b##S##0, keep_);       \
+        *reinterpret_cast<uint4*>(&sB[BUF][lrow1 * LDS_STRIDE + kc1]) = and4(b##S##1, keep_);       \
+    }
+
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+
+    const int nslab = (d_in + BK - 1) / BK;
+    const int arow = (wm * 32 + (lane & 31)) * LDS_STRIDE + (lane >> 5) * 8;
+    const int brow = (wn * 32 + (lane & 31)) * LDS_STRIDE + (lane >> 5) * 8;
+    // slab sl lives in register set sl % 3; in iteration sl the set of slab sl + 1 is parked in
+    // the other LDS buffer and refilled with slab sl + 4.  Nothing is conditional (slabs past the
+    // end park zeros), so the count of loads in flight is known at every wait.
+#define GRAM_SMALL_ITER(SNEXT, SL)                                                                  \
+    {                                                                                               \
+        GRAM_PARK_SLAB(SNEXT, ((SL) + 1) * BK, ((SL) + 1) & 1)                                      \
+        GRAM_LOAD_SLAB(SNEXT, ((SL) + 1 + kSmallDepth) * BK)                                        \
+        const uint16_t* a_ = &sA[(SL) & 1][arow];                                                   \
+        const uint16_t* b_ = &sB[(SL) & 1][brow];                                                   \
+        _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                    \
+            const bf16x8 fa = *reinterpret_cast<const bf16x8*>(a_ + ks * 16);                       \
+            const bf16x8 fb = *reinterpret_cast<const bf16x8*>(b_ + ks * 16);                       \
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc, 0, 0, 0);                    \
+        }                                                                                           \
+        __syncthreads();                                                                            \
+    }
+    GRAM_LOAD_SLAB(0, 0)
+    GRAM_LOAD_SLAB(1, BK)
+    GRAM_LOAD_SLAB(2, 2 * BK)
+    GRAM_PARK_SLAB(0, 0, 0)
+    GRAM_LOAD_SLAB(0, 3 * BK)
+    __syncthreads();
+    for (int s0 = 0; s0 < nslab; s0 += kSmallDepth) {
+        GRAM_SMALL_ITER(1, s0)
+        GRAM_SMALL_ITER(2, s0 + 1)
+        GRAM_SMALL_ITER(0, s0 + 2)
+    }
+#undef GRAM_LOAD_SLAB
+#undef GRAM_PARK_SLAB
+#undef GRAM_SMALL_ITER
 
     // accumulator element r of a lane sits at (row, col) = ((r / 4) * 8 + (lane / 32) * 4 + r % 4, lane % 32)
+    const int cc = n0 + wn * 32 + (lane & 31);
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int jt = 0; jt < 2; ++jt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int j = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                const int cc = n0 + wn * 64 + jt * 32 + (lane & 31);
-                if (j < U && cc < d) E[(int64_t)j * d + cc] = uniq[j] == pad_id ? 0.f : acc[i][jt][r];
-            }
+    for (int r = 0; r < 16; ++r) {
+        const int j = m0 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        if (j < U && cc < d) E[(int64_t)j * d + cc] = uniq[j] == pad_id ? 0.f : acc[r];
+    }
 }
 
 // ---- C[M,N] = A[M,K] . B[N,K]^T, bf16 in, fp32 out: direct-to-LDS variant -----------
@@ -840,12 +851,12 @@ bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
             launch(c, KID_TRANSPOSE_U16, k_transpose_u16, dim3((d + 31) / 32, (d_in + 31) / 32), dim3(kBlock), s,
                    static_cast<const uint16_t*>(W), d_in, d, static_cast<uint16_t*>(c->Wt));
         }
-        if (rows_max >= 512 && d_in % TK == 0) {
-            const int64_t window = (int64_t)1 << 32;
+        const int64_t window = (int64_t)1 << 32;
+        const int64_t tile_bound = ((rows_max + TM - 1) / TM) * ((d + TN - 1) / TN);
+        if (tile_bound >= c->num_cus && d_in % TK == 0) {
             // Fusing the gather pays when there are tiles for every CU: with a handful of tiles the
             // position stores of a tile run on one CU while a separate gather spreads over all.
-            const int64_t tile_bound = ((rows_max + TM - 1) / TM) * ((d + TN - 1) / TN);
-            const bool fuse = H_scatter && (int64_t)c->cfg.vocab_n * d_in * 2 < window && tile_bound >= c->num_cus;
+            const bool fuse = H_scatter && (int64_t)c->cfg.vocab_n * d_in * 2 < window;
             const ScatterArgs sc = {c->offsets, c->perm, H_scatter, (int64_t)d, caller_wants_E ? 1 : 0};
             launch_gemm_nt<true>(c, KID_ENCODE_BF16, static_cast<const uint16_t*>(X), d_in, c->cfg.vocab_n,
                                  uniq, u_dev, 0, rows_max, static_cast<const uint16_t*>(c->Wt), d_in, d, d,
