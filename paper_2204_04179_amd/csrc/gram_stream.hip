@@ -24,14 +24,15 @@ __device__ __forceinline__ int wave_incl_scan(int v)
     return v;
 }
 
-__device__ __forceinline__ int block_excl_scan(int v, int* total, int* sm)
+template <int NWAVES = kWavesPerBlock>
+__device__ __forceinline__ int block_excl_scan(int v, int* total, int* sm /*[NWAVES]*/)
 {
     const int incl = wave_incl_scan(v);
     if (lane_id() == kWave - 1) sm[wave_id()] = incl;
     __syncthreads();
     int base = 0, tot = 0;
 #pragma unroll
-    for (int w = 0; w < kWavesPerBlock; ++w) {
+    for (int w = 0; w < NWAVES; ++w) {
         const int t = sm[w];
         if (w < wave_id()) base += t;
         tot += t;
@@ -332,17 +333,19 @@ __global__ __launch_bounds__(kBlock) void k_slot_emit(
     }
 }
 
-// Small batches: the same result from one block that walks the tiles in order (one launch).
-__global__ __launch_bounds__(kBlock) void k_slot_small(
+// Small batches: the same result from one block of 1024 threads that walks tiles of 4096 items in
+// order (one launch, and for most small batches one pass).
+constexpr int kSlotSmallThreads = 1024;
+__global__ __launch_bounds__(kSlotSmallThreads) void k_slot_small(
     const int* __restrict__ uniq_ws, const int* __restrict__ offsets, int* __restrict__ slot_of,
     int* __restrict__ id_of_slot, int* __restrict__ cnt_of_slot, int* __restrict__ seg_slot,
     int* __restrict__ scal, int cap_total, int first_step)
 {
-    __shared__ int sm[kWavesPerBlock];
+    __shared__ int sm[kSlotSmallThreads / kWave];
     const int u = scal[kSU];
     int run_base = first_step ? 0 : scal[kSUTotal];             // a flush leaves the old count behind
     bool overflow = false;
-    for (int j0 = threadIdx.x * 4; j0 - threadIdx.x * 4 < u; j0 += kScanTile) {   // uniform trip count
+    for (int j0 = threadIdx.x * 4; j0 - threadIdx.x * 4 < u; j0 += kSlotSmallThreads * 4) {   // uniform trip count
         int id[4], old[4], sflag = 0;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -355,7 +358,7 @@ __global__ __launch_bounds__(kBlock) void k_slot_small(
             }
         }
         int total;
-        int run = run_base + block_excl_scan(sflag, &total, sm);
+        int run = run_base + block_excl_scan<kSlotSmallThreads / kWave>(sflag, &total, sm);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int j = j0 + i;
@@ -396,7 +399,7 @@ void assign_slots(Ctx* c, hipStream_t s)
     if (bound < 1) bound = 1;
     const int first_step = c->steps_done == 0 ? 1 : 0;
     if (bound <= kSmallBatch) {
-        launch(c, KID_SLOT_EMIT, k_slot_small, dim3(1), dim3(kBlock), s, c->uniq_ws, c->offsets, c->slot_of,
+        launch(c, KID_SLOT_EMIT, k_slot_small, dim3(1), dim3(kSlotSmallThreads), s, c->uniq_ws, c->offsets, c->slot_of,
                c->id_of_slot, c->cnt_of_slot, c->seg_slot, c->scal, (int)c->cap_total, first_step);
         return;
     }
