@@ -359,16 +359,28 @@ __global__ void k_unique_empty(int* u_ws, int* u_out, int* offsets)
 // ---- small batches: the whole dedup in one block ------------------------------------
 //
 // Up to kSmallMaxN positions: keys and positions live in LDS, the radix passes
-// (8-bit digits, 16 waves, same ballot ranking as above), the head-flag scan and
-// the compaction all run in one launch of 1024 threads.  A step of the
-// paper-shaped KT and news batches moves a few microseconds of HBM traffic, so
-// its cost is the number of launches.
+// (8-bit digits, 16 waves), the head-flag scan and the compaction all run in one launch
+// of 1024 threads.  A step of the paper-shaped KT and news batches moves a few
+// microseconds of HBM traffic, so its cost is the number of launches - and, inside this
+// one block, the number of instructions its 16 waves issue on one CU:
+//  * the lanes of a wave that hold the same digit find each other through a per-wave table
+//    of 64-bit lane masks in LDS (one atomic OR and one read per round; the first lane of a
+//    group clears the entry again) instead of one ballot per digit bit;
+//  * positions are 16-bit, which makes room for that table;
+//  * `inverse` is assembled in LDS and written in position order, because a CU retires
+//    scattered 4-byte stores at about one lane per clock.
 constexpr int kSmallThreads = 1024;
 constexpr int kSmallWaves = kSmallThreads / kWave;
 constexpr int kSmallMaxN = 8192;
 constexpr int kSmallBits = 8;
 constexpr int kSmallBins = 1 << kSmallBits;
-constexpr size_t kSmallLds = (size_t)(4 * kSmallMaxN + kSmallWaves * kSmallBins + 2 * kSmallWaves) * sizeof(int);
+// LDS, in ints: keys x2 | positions x2 (16-bit) | per-wave digit counts | per-wave peer masks (64-bit) | wave sums
+constexpr int kSmallOffV = 2 * kSmallMaxN;
+constexpr int kSmallOffCnt = kSmallOffV + kSmallMaxN;
+constexpr int kSmallOffPeer = kSmallOffCnt + kSmallWaves * kSmallBins;
+constexpr int kSmallOffSum = kSmallOffPeer + 2 * kSmallWaves * kSmallBins;
+constexpr size_t kSmallLds = (size_t)(kSmallOffSum + 2 * kSmallWaves) * sizeof(int);
+static_assert(2 * kSmallWaves * kSmallBins >= kSmallMaxN, "the peer table doubles as the segment-start list");
 
 // Exclusive scan of one value per thread over the 1024-thread block.
 __device__ __forceinline__ int block1024_excl_scan(int v, int* total, int* wsum /*[2*kSmallWaves]*/)
@@ -395,12 +407,13 @@ __global__ __launch_bounds__(kSmallThreads) void k_unique_small(
     int* __restrict__ seg_of_row, int* __restrict__ uniq_ws, int* __restrict__ u_ws,
     int* __restrict__ u_out)
 {
-    extern __shared__ int lds[];
-    // keys of order `o` at lds + o * kSmallMaxN, positions at lds + (2 + o) * kSmallMaxN
+    extern __shared__ __attribute__((aligned(16))) int lds[];
+    // keys of order `o` at KBUF(o), positions at VBUF(o)
 #define KBUF(o) (lds + (o) * kSmallMaxN)
-#define VBUF(o) (lds + (2 + (o)) * kSmallMaxN)
-    int* cnt_all = lds + 4 * kSmallMaxN;                 // [kSmallWaves][kSmallBins]
-    int* wsum = cnt_all + kSmallWaves * kSmallBins;
+#define VBUF(o) (reinterpret_cast<uint16_t*>(lds + kSmallOffV) + (o) * kSmallMaxN)
+    int* cnt_all = lds + kSmallOffCnt;                   // [kSmallWaves][kSmallBins]
+    unsigned long long* peer_all = reinterpret_cast<unsigned long long*>(lds + kSmallOffPeer);
+    int* wsum = lds + kSmallOffSum;
     const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
 
     bool bad = false;
@@ -408,9 +421,10 @@ __global__ __launch_bounds__(kSmallThreads) void k_unique_small(
         int k = ids[i];
         if (k < 0 || k >= vocab_n) { bad = true; k = fix_key; }
         KBUF(0)[i] = k;
-        VBUF(0)[i] = i;
+        VBUF(0)[i] = (uint16_t)i;
     }
     if (bad) atomicOr(err, kErrBitRange);
+    for (int b = tid; b < kSmallWaves * kSmallBins; b += kSmallThreads) peer_all[b] = 0ull;
     __syncthreads();
 
     // wave w owns the contiguous chunk [w * cw, (w + 1) * cw) of the current order
@@ -418,13 +432,23 @@ __global__ __launch_bounds__(kSmallThreads) void k_unique_small(
     const int cbeg = wave * cw;
     const int cend = cbeg + cw < n ? cbeg + cw : n;
     volatile int* cnt = cnt_all + wave * kSmallBins;
+    volatile unsigned long long* peer = peer_all + wave * kSmallBins;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
     int cur = 0;
     for (int shift = 0; shift < key_bits; shift += kSmallBits) {
         for (int b = lane; b < kSmallBins; b += kWave) cnt[b] = 0;
         __syncthreads();
-        for (int i = cbeg + lane; i < cend; i += kWave)
-            atomicAdd(&cnt_all[wave * kSmallBins + ((KBUF(cur)[i] >> shift) & (kSmallBins - 1))], 1);
+        for (int i0 = cbeg; i0 < cend; i0 += kWave) {        // wave-uniform trip count
+            const int i = i0 + lane;
+            const bool valid = i < cend;
+            const int dg = valid ? (KBUF(cur)[i] >> shift) & (kSmallBins - 1) : -1;
+            // the digit of the round's first key is counted once for all lanes that hold it:
+            // padding and very popular items would otherwise pile up on one LDS counter
+            const int d0 = __builtin_amdgcn_readfirstlane(dg);
+            const unsigned long long m0 = __ballot(dg == d0);
+            if (lane == 0) atomicAdd(&cnt_all[wave * kSmallBins + d0], (int)__popcll(m0));
+            else if (valid && dg != d0) atomicAdd(&cnt_all[wave * kSmallBins + dg], 1);
+        }
         __syncthreads();
         {   // exclusive scan in (digit, wave) order; thread t owns digit t / 4, waves 4 (t % 4) .. + 3
             const int dg = tid >> 2, w0 = (tid & 3) * 4;
@@ -449,22 +473,33 @@ __global__ __launch_bounds__(kSmallThreads) void k_unique_small(
             const int k = valid ? KBUF(cur)[i] : 0;
             const int v = valid ? VBUF(cur)[i] : 0;
             const int dg = (k >> shift) & (kSmallBins - 1);
-            unsigned long long peers = __ballot(valid);
-#pragma unroll
-            for (int bit = 0; bit < kSmallBits; ++bit) {
-                const bool one = (dg >> bit) & 1;
-                const unsigned long long mm = __ballot(one);
-                peers &= one ? mm : ~mm;
+            // Lanes holding the digit of the round's first key know their group from one ballot
+            // (padding and very popular items fill most of a round); the others meet through the
+            // mask table.  LDS operations of one wave execute in program order: every lane's OR
+            // lands before the reads below, and every lane has read before a group's first lane
+            // writes.
+            const int d0 = __builtin_amdgcn_readfirstlane(dg);
+            const unsigned long long m0 = __ballot(valid && dg == d0);
+            const bool in0 = valid && dg == d0;
+            if (valid && !in0) atomicOr(const_cast<unsigned long long*>(&peer[dg]), 1ull << lane);
+            __builtin_amdgcn_wave_barrier();
+            unsigned long long peers = 0ull;
+            int pos = 0;
+            if (valid) {
+                peers = in0 ? m0 : peer[dg];
+                pos = cnt[dg];
             }
             const int below = __popcll(peers & lt_mask);
-            int pos = 0;
-            if (valid) pos = cnt[dg] + below;
+            pos += below;
             __builtin_amdgcn_wave_barrier();
-            if (valid && below == 0) cnt[dg] = pos + __popcll(peers);
+            if (valid && below == 0) {
+                cnt[dg] = pos + __popcll(peers);
+                if (!in0) peer[dg] = 0ull;
+            }
             __builtin_amdgcn_wave_barrier();
             if (valid && (unsigned)pos < (unsigned)n) {
                 KBUF(cur ^ 1)[pos] = k;
-                VBUF(cur ^ 1)[pos] = v;
+                VBUF(cur ^ 1)[pos] = (uint16_t)v;
             }
         }
         __syncthreads();
@@ -473,30 +508,51 @@ __global__ __launch_bounds__(kSmallThreads) void k_unique_small(
 
     // head flags and their scan: thread t owns the 8 sorted rows 8 t .. 8 t + 7 and leaves each
     // row's segment index in LDS; the outputs are then written with consecutive threads on
-    // consecutive rows, so that the stores of a wave coalesce
+    // consecutive rows / positions, so that the stores of a wave coalesce
     const int* sk = KBUF(cur);
-    const int* sv = VBUF(cur);
-    int* lseg = KBUF(cur ^ 1);     // free after the last pass: segment index of every sorted row
-    int* loff = VBUF(cur ^ 1);     //                           first sorted row of every segment
+    const uint16_t* sv = VBUF(cur);
+    int* lseg = KBUF(cur ^ 1);                               // free after the last pass: segment of every sorted row
+    int* loff = reinterpret_cast<int*>(peer_all);            // first sorted row of every segment
+    uint16_t* linv = VBUF(cur ^ 1);                          // segment of every position
     const int r0 = tid * 8;
+    // the thread's 8 keys and positions as 16-byte LDS reads (rows 8 t .. 8 t + 7 one by one
+    // would hit the same banks in every lane)
+    int key[8];
+    uint16_t posn[8];
+    {
+        const int4 k0 = *reinterpret_cast<const int4*>(sk + r0);
+        const int4 k1 = *reinterpret_cast<const int4*>(sk + r0 + 4);
+        key[0] = k0.x; key[1] = k0.y; key[2] = k0.z; key[3] = k0.w;
+        key[4] = k1.x; key[5] = k1.y; key[6] = k1.z; key[7] = k1.w;
+        const uint4 p4 = *reinterpret_cast<const uint4*>(sv + r0);
+        posn[0] = (uint16_t)p4.x; posn[1] = (uint16_t)(p4.x >> 16); posn[2] = (uint16_t)p4.y; posn[3] = (uint16_t)(p4.y >> 16);
+        posn[4] = (uint16_t)p4.z; posn[5] = (uint16_t)(p4.z >> 16); posn[6] = (uint16_t)p4.w; posn[7] = (uint16_t)(p4.w >> 16);
+    }
+    const int prev = r0 > 0 && r0 < n ? sk[r0 - 1] : -1;
     bool f[8];
     int sum = 0;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int r = r0 + i;
-        f[i] = r < n && (r == 0 || sk[r] != sk[r - 1]);
+        f[i] = r < n && (r == 0 || key[i] != (i ? key[i - 1] : prev));
         sum += f[i] ? 1 : 0;
     }
     int total;
     int run = block1024_excl_scan(sum, &total, wsum);
+    int seg8[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int r = r0 + i;
+        run += f[i] ? 1 : 0;
+        seg8[i] = run - 1;
         if (r < n) {
-            run += f[i] ? 1 : 0;
-            lseg[r] = run - 1;
+            linv[posn[i]] = (uint16_t)(run - 1);
             if (f[i]) loff[run - 1] = r;
         }
+    }
+    if (r0 < n) {       // rows past n inside the last thread's 8 are never read back
+        *reinterpret_cast<int4*>(lseg + r0) = make_int4(seg8[0], seg8[1], seg8[2], seg8[3]);
+        *reinterpret_cast<int4*>(lseg + r0 + 4) = make_int4(seg8[4], seg8[5], seg8[6], seg8[7]);
     }
     if (tid == 0) {
         *u_ws = total;
@@ -505,12 +561,10 @@ __global__ __launch_bounds__(kSmallThreads) void k_unique_small(
     }
     __syncthreads();
     for (int r = tid; r < n; r += kSmallThreads) {
-        const int seg = lseg[r];
-        const int p = sv[r];
         sorted_keys[r] = sk[r];
-        perm[r] = p;
-        seg_of_row[r] = seg;
-        inverse[p] = seg;
+        perm[r] = sv[r];
+        seg_of_row[r] = lseg[r];
+        inverse[r] = linv[r];
     }
     for (int j = tid; j < total; j += kSmallThreads) {
         const int r = loff[j];
