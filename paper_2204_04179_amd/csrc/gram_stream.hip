@@ -601,8 +601,8 @@ void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s)
 
 // ---- end of the window: export in ascending ID order, then empty ------------
 //
-// One launch: rows of G are copied out in ascending ID order; the thread that moves the first
-// piece of a row also exports its ID and count and clears the item's entry of the slot map.
+// One launch: rows of G are copied out in ascending ID order while a few extra blocks export the
+// IDs and counts and clear the items' entries of the slot map.
 // The count of buffer rows (scal[kSUTotal]) is left as it is: every block reads it here, and
 // the first step of the next window starts from zero by itself.  `n_zero`: the window is empty.
 
@@ -630,27 +630,34 @@ __global__ __launch_bounds__(kBlock) void k_flush_meta(
     }
 }
 
+// Blocks [0, copy_blocks) copy rows; the blocks after them export IDs and counts and clear the
+// slot map (kept out of the copy loop: their scattered accesses would stall the copying waves).
 __global__ __launch_bounds__(kBlock) void k_flush_rows(
     const int* __restrict__ sorted_ids, const int* __restrict__ sorted_slots,
     const int* __restrict__ cnt_of_slot, int* __restrict__ slot_of, int* __restrict__ uniq_total,
     int* __restrict__ counts_total, const float4* __restrict__ G, int cols4,
-    float4* __restrict__ G_total, int* __restrict__ scal, int* __restrict__ u_total_dev)
+    float4* __restrict__ G_total, int* __restrict__ scal, int* __restrict__ u_total_dev,
+    int copy_blocks)
 {
     const int n = scal[kSUTotal];
+    if ((int)blockIdx.x >= copy_blocks) {
+        const int mb = blockIdx.x - copy_blocks, nmb = gridDim.x - copy_blocks;
+        for (int r = mb * kBlock + threadIdx.x; r < n; r += nmb * kBlock)
+            flush_meta_row(r, sorted_ids, sorted_slots, cnt_of_slot, slot_of, uniq_total, counts_total);
+        if (mb == 0 && threadIdx.x == 0) {
+            if (u_total_dev) *u_total_dev = n;
+            scal[kSFlushN] = n;
+        }
+        return;
+    }
     const int64_t total = (int64_t)n * cols4;
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
-         i += (int64_t)gridDim.x * kBlock) {
+         i += (int64_t)copy_blocks * kBlock) {
         const int64_t r = i / cols4;
         const int cc = (int)(i % cols4);
         const f32x4 t = __builtin_nontemporal_load(
             reinterpret_cast<const f32x4*>(G) + (int64_t)(sorted_slots ? sorted_slots[r] : (int)r) * cols4 + cc);
         __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(G_total) + i);
-        if (cc == 0)
-            flush_meta_row((int)r, sorted_ids, sorted_slots, cnt_of_slot, slot_of, uniq_total, counts_total);
-    }
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        if (u_total_dev) *u_total_dev = n;
-        scal[kSFlushN] = n;
     }
 }
 
@@ -675,9 +682,12 @@ void flush_export(Ctx* c, int* uniq_total, int* counts_total, float* G_total, in
     if (G_total) {
         int64_t blocks = (c->cap_total * (c->cfg.d / 4) + kBlock - 1) / kBlock;
         if (blocks > 2048) blocks = 2048;
-        launch(c, KID_FLUSH_ROWS, k_flush_rows, dim3((unsigned)blocks), dim3(kBlock), s, sorted_ids, sorted_slots,
-               c->cnt_of_slot, c->slot_of, uniq_total, counts_total, reinterpret_cast<const float4*>(c->G),
-               c->cfg.d / 4, reinterpret_cast<float4*>(G_total), c->scal, u_total_dev);
+        int64_t meta_blocks = (c->cap_total + kBlock - 1) / kBlock;
+        if (meta_blocks > 64) meta_blocks = 64;
+        launch(c, KID_FLUSH_ROWS, k_flush_rows, dim3((unsigned)(blocks + meta_blocks)), dim3(kBlock), s, sorted_ids,
+               sorted_slots, c->cnt_of_slot, c->slot_of, uniq_total, counts_total,
+               reinterpret_cast<const float4*>(c->G), c->cfg.d / 4, reinterpret_cast<float4*>(G_total), c->scal,
+               u_total_dev, (int)blocks);
     } else {
         int64_t blocks = (c->cap_total + kBlock - 1) / kBlock;
         if (blocks > 1024) blocks = 1024;
