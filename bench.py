@@ -277,6 +277,32 @@ def pseudo_target_leg(r, reps=20):
             "pseudo_loss": float(loss.item())}
 
 
+def chunked_wgrad_leg(r, chunk_rows=32768, reps=3):
+    """Outside the timed steps: the weight gradient of one full window taken in chunks of
+    `chunk_rows` buffer rows (content-encoder batches), accumulated into dW."""
+    torch, g, w = r.torch, r.g, r.w
+    r.finish_window()
+    for k in range(w.K):
+        g.unique(r.ids[k], r.uniq, r.inverse, r.counts, r.u_dev)
+        g.encode_gather(r.X, r.Wt, r.uniq, r.inverse, r.u_dev, r.M, None, r.H)
+        g.grad_accumulate(r.dH[k], r.M, k)
+    n_chunks = (r.U_total + chunk_rows - 1) // chunk_rows
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        for i in range(n_chunks):
+            g.encoder_wgrad_chunk(r.X, r.dW, i * chunk_rows, chunk_rows, i > 0)
+    torch.cuda.synchronize()
+    us = 1e6 * (time.perf_counter() - t0) / reps
+    g.flush(r.uniq_t, r.counts_t, None, r.u_t)
+    r.pos = 0
+    torch.cuda.synchronize()
+    flops = 2 * r.U_total * w.d_in * w.d
+    return {"chunk_rows": chunk_rows, "chunks": n_chunks, "us_per_window": us, "bound": "mfma",
+            "achieved": flops / (us * 1e-6) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": flops / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -354,6 +380,8 @@ def main():
         out["cpu_baseline"] = cpu_baseline(r)
         out["gpu_over_cpu"] = value / out["cpu_baseline"]["value"]
     out["next_rows"] = {"pseudo_target": pseudo_target_leg(r)}
+    if w.xw_dtype != wl.F32:
+        out["next_rows"]["chunked_wgrad"] = chunked_wgrad_leg(r)
     out["paper_context"] = "paper: Single-step ~4x, Multi-step up to 146x faster than E2E, whole training runs on A100"
     del r
     torch.cuda.empty_cache()

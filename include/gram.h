@@ -170,6 +170,22 @@ int gram_gather(gram_ctx* ctx, const float* src, const int32_t* inverse, int64_t
  * enters the matrix cores; products are summed in float32. */
 int gram_encoder_wgrad(gram_ctx* ctx, const void* X, float* dW, void* stream);
 
+/* The same weight gradient over a chunk of the accumulated items, for an encoder
+ * update that walks the items of the window in batches of a fixed size (the
+ * content-encoder batch size of the paper's section on GPU memory consumption
+ * and its table):
+ *   dW (+)= sum over buffer rows s in [first_row, first_row + n_rows) of
+ *           X[item_s,:]^T . G[s,:]
+ *   first_row, n_rows  rows of the buffer in the order the items entered the
+ *                      window (ascending ID within a step, step after step); the
+ *                      range is clipped to the rows held
+ *   accumulate         0: dW is overwritten; otherwise the chunk is added to dW
+ * The chunks of a partition of the held rows add up to gram_encoder_wgrad's dW
+ * (up to the order of the float32 sums).  No workspace grows with the chunk.
+ * GRAM_ERR_UNIMPLEMENTED when X or the buffer exceeds 4 GiB. */
+int gram_encoder_wgrad_chunk(gram_ctx* ctx, const void* X, float* dW, int64_t first_row,
+                             int64_t n_rows, int32_t accumulate, void* stream);
+
 /* End of the accumulation window: export the buffer in ascending ID order,
  * then empty it and reset the step counter.
  *   uniq_total    DEVICE [>= u_total_cap], nullable  out: IDs seen in the window

@@ -345,8 +345,24 @@ int gram_encoder_wgrad(gram_ctx* ctx, const void* X, float* dW, void* stream)
     if (c->steps_done < 1)
         return fail(c, GRAM_ERR_SEQUENCE, "gram_encoder_wgrad: no step accumulated in this window");
     if (!X || !dW) return fail(c, GRAM_ERR_ARG, "gram_encoder_wgrad: NULL pointer");
-    encoder_wgrad(c, X, dW, static_cast<hipStream_t>(stream));
+    encoder_wgrad(c, X, dW, static_cast<hipStream_t>(stream), 0, c->cap_total, false);
     return launch_status(c, "gram_encoder_wgrad");
+}
+
+int gram_encoder_wgrad_chunk(gram_ctx* ctx, const void* X, float* dW, int64_t first_row, int64_t n_rows,
+                             int32_t accumulate, void* stream)
+{
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (!c) return GRAM_ERR_ARG;
+    if (c->steps_done < 1)
+        return fail(c, GRAM_ERR_SEQUENCE, "gram_encoder_wgrad_chunk: no step accumulated in this window");
+    if (!X || !dW) return fail(c, GRAM_ERR_ARG, "gram_encoder_wgrad_chunk: NULL pointer");
+    if (first_row < 0 || n_rows < 0)
+        return fail(c, GRAM_ERR_ARG, "gram_encoder_wgrad_chunk: negative row range");
+    if (!encoder_wgrad(c, X, dW, static_cast<hipStream_t>(stream), first_row, n_rows, accumulate != 0))
+        return fail(c, GRAM_ERR_UNIMPLEMENTED,
+                    "gram_encoder_wgrad_chunk: chunks are not available when X or the buffer exceeds 4 GiB");
+    return launch_status(c, "gram_encoder_wgrad_chunk");
 }
 
 int gram_flush(gram_ctx* ctx, int32_t* uniq_total, int32_t* counts_total, float* G_total,

@@ -927,7 +927,7 @@ template <int NW>
 __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
     const uint16_t* __restrict__ X, uint32_t x_bytes, const int* __restrict__ id_of_slot,
     const float* __restrict__ G, uint32_t g_bytes, const int* __restrict__ scal, int d_in, int d,
-    int pad_id, int splits, float* __restrict__ partial)
+    int pad_id, int splits, float* __restrict__ partial, int row_begin, int row_end)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const int tiles_c = (d + 255) / 256, tiles = ((d_in + 255) / 256) * tiles_c;
@@ -944,11 +944,14 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
     constexpr int SETS = NW == 4 ? 2 : 1;
     const int wm = NW == 4 ? wave >> 1 : wave >> 2, wn = NW == 4 ? wave & 1 : wave & 3;
 
-    const int U = scal[kSUTotal];
-    const int slabs_all = (U + WK - 1) / WK;
+    // buffer rows [row_begin, U) take part (row_end clips U: the chunked call); slabs stay aligned
+    // to multiples of WK rows, rows outside the range are loaded as zeros
+    const int U = scal[kSUTotal] < row_end ? scal[kSUTotal] : row_end;
+    const int sl0 = row_begin / WK;
+    const int slabs_all = U > row_begin ? (U + WK - 1) / WK - sl0 : 0;
     const int per = (slabs_all + splits - 1) / splits;
-    const int sl_begin = z * per;
-    int nslab = slabs_all - sl_begin;
+    const int sl_begin = sl0 + z * per;
+    int nslab = sl0 + slabs_all - sl_begin;
     if (nslab > per) nslab = per;
     partial += (int64_t)z * d_in * d;
 
@@ -1013,7 +1016,7 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
         const int sb_ = (sl_begin + ((SLAB) < last ? (SLAB) : last)) * WK;                          \
         _Pragma("unroll") for (int t = 0; t < RW / 2; ++t) {                                        \
             const int slot = sb_ + a_row + 2 * t;                                                   \
-            ids_next[t] = slot < U ? id_of_slot[slot] : pad_id;                                     \
+            ids_next[t] = (slot < U && slot >= row_begin) ? id_of_slot[slot] : pad_id;              \
         }                                                                                           \
     }
 #define GRAM_LOAD(SET, SLAB)                                                                        \
@@ -1023,13 +1026,13 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
             const int kk = a_row + 2 * t;                                                           \
             const int feat = i0 + ((a_pos ^ ((kk & 3) << 1)) * 8);                                  \
             const int id = ids_next[t];                                                             \
-            const bool ok = id != pad_id && feat < d_in && sb_ + kk < U;                            \
+            const bool ok = id != pad_id && feat < d_in && sb_ + kk < U && sb_ + kk >= row_begin;   \
             const uint32_t off = ok ? (uint32_t)(((int64_t)id * d_in + feat) * 2) : kOutOfRange;    \
             ra[(SET) % SETS][t] = __builtin_amdgcn_raw_buffer_load_b128(rsX, off, 0, 0);                     \
         }                                                                                           \
         _Pragma("unroll") for (int t = 0; t < RW; ++t) {                                            \
             const int slot = sb_ + wave * RW + t;                                                    \
-            const uint32_t off = (g_col_ok && slot < U) ? (uint32_t)(((int64_t)slot * d + g_col) * 4) : kOutOfRange; \
+            const uint32_t off = (g_col_ok && slot < U && slot >= row_begin) ? (uint32_t)(((int64_t)slot * d + g_col) * 4) : kOutOfRange; \
             rg[(SET) % SETS][t] = __builtin_amdgcn_raw_buffer_load_b128(rsG, off, 0, 0);                     \
         }                                                                                           \
     }
@@ -1120,14 +1123,17 @@ __device__ __forceinline__ void split_range(int u_total, int splits, int z, int*
 __global__ __launch_bounds__(kBlock) void k_wgrad_f32(
     const float* __restrict__ X, const int* __restrict__ id_of_slot, const float* __restrict__ G,
     const int* __restrict__ scal, int d_in, int d, int pad_id, int splits,
-    float* __restrict__ partial)
+    float* __restrict__ partial, int row_begin, int row_end)
 {
     const int c = blockIdx.x * 64 + (threadIdx.x & 63);
     const int i = blockIdx.y * 4 + (threadIdx.x >> 6);
     const int z = blockIdx.z;
     if (i >= d_in || c >= d) return;
     int kb, ke;
-    split_range(scal[kSUTotal], splits, z, &kb, &ke);
+    const int u_end = scal[kSUTotal] < row_end ? scal[kSUTotal] : row_end;
+    split_range(u_end > row_begin ? u_end - row_begin : 0, splits, z, &kb, &ke);
+    kb += row_begin;
+    ke += row_begin;
     float acc = 0.f;
     for (int sidx = kb; sidx < ke; ++sidx) {
         const int id = id_of_slot[sidx];
@@ -1138,13 +1144,13 @@ __global__ __launch_bounds__(kBlock) void k_wgrad_f32(
 
 __global__ __launch_bounds__(kBlock) void k_wgrad_reduce(const float4* __restrict__ partial,
                                                          int64_t n4, int splits,
-                                                         float4* __restrict__ dW)
+                                                         float4* __restrict__ dW, int accumulate)
 {
     const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (e >= n4) return;
-    float4 acc = partial[e];
+    float4 acc = accumulate ? dW[e] : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll 8
-    for (int z = 1; z < splits; ++z) {
+    for (int z = 0; z < splits; ++z) {
         const float4 v = partial[(int64_t)z * n4 + e];
         acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
     }
@@ -1163,14 +1169,20 @@ int wgrad_splits_for(const gram_config& cfg)
 
 int64_t wgrad_pitch_for(int64_t cap_total) { return (cap_total + TT - 1) / TT * TT + TT; }
 
-void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s)
+bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t first_row, int64_t n_rows,
+                   bool accumulate)
 {
     const int d_in = c->cfg.d_in, d = c->cfg.d;
     int S = c->wg_splits;
+    const bool chunked = first_row > 0 || n_rows < c->cap_total;
+    const int row_begin = (int)(first_row < c->cap_total ? first_row : c->cap_total);
+    const int row_end = (int)(n_rows < c->cap_total - row_begin ? row_begin + n_rows : c->cap_total);
     if (c->cfg.xw_dtype == GRAM_BF16) {
         // a short window does not need all the ranges: at least 8 slabs of 32 buffer rows each
         // (from the host's bound on the rows in the buffer), still a multiple of 8
-        const int64_t slabs_bound = (c->window_positions < c->cap_total ? c->window_positions : c->cap_total) / TK + 1;
+        int64_t rows_bound = c->window_positions < c->cap_total ? c->window_positions : c->cap_total;
+        if (rows_bound > row_end - row_begin) rows_bound = row_end - row_begin;
+        const int64_t slabs_bound = rows_bound / TK + 1;
         int64_t want = slabs_bound / 8 / 8 * 8;
         if (want < 8) want = 8;
         if (want < S) S = (int)want;
@@ -1186,8 +1198,9 @@ void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s)
             const int tiles = ((d_in + 255) / 256) * ((d + 255) / 256);
             launch_smem(c, KID_WGRAD_BF16, k_wgrad_tn_bf16<kWgradWaves>, dim3((unsigned)(tiles * S)), dim3(kWgradWaves * 64), WSMEM, s,
                         static_cast<const uint16_t*>(X), (uint32_t)x_bytes, c->id_of_slot, c->G, (uint32_t)g_bytes,
-                        c->scal, d_in, d, c->cfg.pad_id, S, c->wg_partial);
+                        c->scal, d_in, d, c->cfg.pad_id, S, c->wg_partial, row_begin, row_end);
         } else {
+            if (chunked) return false;      // the transposed copies cover the whole buffer only
             // operands beyond the 4 GiB buffer window: transposed bf16 copies + the NT kernel
             launch(c, KID_TRANSPOSE_X, k_transpose_x, dim3(1024), dim3(kBlock), s,
                    static_cast<const uint16_t*>(X), c->id_of_slot, c->scal, 0, d_in, c->cfg.pad_id, c->XT, c->ldt);
@@ -1199,11 +1212,12 @@ void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s)
     } else {
         launch(c, KID_WGRAD_F32, k_wgrad_f32, dim3((d + 63) / 64, (d_in + 3) / 4, S), dim3(kBlock), s,
                static_cast<const float*>(X), c->id_of_slot, c->G, c->scal, d_in, d, c->cfg.pad_id, S,
-               c->wg_partial);
+               c->wg_partial, row_begin, row_end);
     }
     const int64_t n4 = (int64_t)d_in * d / 4;
     launch(c, KID_WGRAD_REDUCE, k_wgrad_reduce, dim3((unsigned)((n4 + kBlock - 1) / kBlock)), dim3(kBlock), s,
-           reinterpret_cast<const float4*>(c->wg_partial), n4, S, reinterpret_cast<float4*>(dW));
+           reinterpret_cast<const float4*>(c->wg_partial), n4, S, reinterpret_cast<float4*>(dW), accumulate ? 1 : 0);
+    return true;
 }
 
 }  // namespace gram

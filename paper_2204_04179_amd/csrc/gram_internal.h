@@ -168,7 +168,11 @@ void fill_i32(int* p, int64_t n, int v, hipStream_t s);
 // was written (gather_rows must follow).
 bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const int* u_dev,
                     int64_t rows_max, float* E, hipStream_t s, float* H_scatter, bool caller_wants_E);
-void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s);
+// Weight gradient over the buffer rows [first_row, first_row + n_rows) (clipped to the rows held),
+// written to dW or added to it.  Returns false if the range is a proper chunk and an operand is
+// beyond 4 GiB (nothing is launched).
+bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t first_row, int64_t n_rows,
+                   bool accumulate);
 int wgrad_splits_for(const gram_config& cfg);
 int64_t wgrad_pitch_for(int64_t cap_total);
 

@@ -15,14 +15,16 @@ def to_dev(a, torch):
 
 def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=None, u_total_cap=0,
                keep_H=True, keep_E=True, want_G=True, gram_obj=None, X_dev=None, W_dev=None,
-               pass_E=True, foreign_buffers=False, profile=None, pseudo=False):
+               pass_E=True, foreign_buffers=False, profile=None, pseudo=False, wgrad_chunks=None):
     """batches: list of (ids int32 [m], dH float32 [m,d]).  Returns dict with per-step
     uniq/inverse/counts/E/H and the window's uniq_total/counts_total/G_total/dW.
     pass_E=False calls gram_encode_gather with E = NULL (no "E" in the result);
     foreign_buffers=True hands it copies of uniq / inverse instead of the buffers gram_unique
     wrote, which selects the two-kernel forward.  profile: kernel names whose launches are counted
     (result key "profile": name -> (launches, ms)).  pseudo=True also calls gram_pseudo_target
-    and gram_gather after each accumulate (step keys "Ht", "loss", "H_tilde")."""
+    and gram_gather after each accumulate (step keys "Ht", "loss", "H_tilde").  wgrad_chunks: list of
+    (first_row, n_rows); before the full weight gradient each chunk is taken alone (key "dW_chunks")
+    and all of them accumulated into one matrix (key "dW_chunked")."""
     import torch
     from paper_2204_04179_amd import gram
 
@@ -72,6 +74,17 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
             st["Ht_tail_untouched"] = bool(torch.isnan(Ht[U:]).all().item())
         st["H_dev"], st["E_dev"], st["inverse_dev"] = H, E, inverse
         steps.append(st)
+    chunk_out = {}
+    if wgrad_chunks:
+        acc = torch.full((d_in, d), float("nan"), device="cuda")
+        singles = []
+        for i, (a, nrows) in enumerate(wgrad_chunks):
+            one = torch.full((d_in, d), float("nan"), device="cuda")
+            g.encoder_wgrad_chunk(Xd, one, a, nrows, False)
+            g.encoder_wgrad_chunk(Xd, acc, a, nrows, i > 0)
+            singles.append(one)
+        torch.cuda.synchronize()
+        chunk_out = dict(dW_chunks=[t.cpu().numpy() for t in singles], dW_chunked=acc.cpu().numpy())
     dW = torch.full((d_in, d), float("nan"), device="cuda")
     g.encoder_wgrad(Xd, dW)
     cap_total = u_total_cap or max(1, min(K * M_max, vocab_n))
@@ -81,7 +94,7 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
     utd = torch.zeros(1, dtype=torch.int32, device="cuda")
     n = g.flush(ut, ct, Gt, utd, want_host_u=True)
     torch.cuda.synchronize()
-    out = dict(steps=steps, dW=dW.cpu().numpy(), U_total=n, uniq_total=ut[:n].cpu().numpy(),
+    out = dict(steps=steps, dW=dW.cpu().numpy(), U_total=n, **chunk_out, uniq_total=ut[:n].cpu().numpy(),
                counts_total=ct[:n].cpu().numpy(), gram=g, X_dev=Xd, W_dev=Wd)
     assert int(utd.item()) == n
     if profile:

@@ -362,6 +362,72 @@ def test_pseudo_targets_after_the_fused_forward():
     np.testing.assert_array_equal(st["H_tilde"], st["Ht"][ref["inverse"]])
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_weight_gradient_in_chunks_of_items(bf16):
+    """The encoder update walked in batches of items (content-encoder batch size): each chunk of
+    buffer rows gives the weight gradient of exactly those items, and the chunks add up to the
+    whole.  Buffer order = order of first appearance: ascending ID within a step, step by step."""
+    K, n, d_in, d = 3, 1200, 64, 40
+    probs = [small_problem(400 + k, 2500, n, d_in=d_in, d=d, bf16=bf16) for k in range(K)]
+    X, W = probs[0][1], probs[0][2]
+    batches = [(p[0], p[3]) for p in probs]
+    chunks = [(0, 100), (100, 37), (137, 500), (637, 1), (638, 100000), (5000, 10)]   # ragged, unaligned, past the end, empty
+    say(f"chunked wgrad bf16={bf16}")
+    out = run_window(X, W, batches, vocab_n=n, k_steps=K, wgrad_chunks=chunks)
+    mm = orc.GramMulti(X, W)
+    order, seen = [], set()
+    for ids, dH in batches:
+        st = mm.step(ids, dH)
+        for i in st["uniq"]:
+            if int(i) not in seen:
+                seen.add(int(i))
+                order.append(int(i))
+    order = np.array(order, np.int32)
+    assert order.size == out["U_total"]
+    tol = TOL[wl.BF16 if bf16 else wl.F32]
+    full = mm.finish()["dW"]
+    scale = np.abs(full).max()
+    for (a, nrows), got in zip(chunks, out["dW_chunks"]):
+        items = order[a:a + nrows]
+        ref = orc.wgrad(items, X, mm_rows(batches, X, W, items), 0) if items.size else np.zeros_like(full)
+        assert np.abs(got - ref).max() <= tol * scale, (a, nrows)
+    assert_close(out["dW_chunked"], full, tol, "sum of chunks")
+    assert_close(out["dW"], full, tol, "dW")
+
+
+def mm_rows(batches, X, W, items):
+    """Gradient rows of `items` at the end of the window, from a fresh oracle run."""
+    mm = orc.GramMulti(X, W)
+    for ids, dH in batches:
+        mm.step(ids, dH)
+    return mm.rows(items)
+
+
+def test_long_window_reaches_the_whole_vocabulary():
+    """Epoch-scale accumulation (Section 4.2 with a long period): 40 steps over a vocabulary of 1,500,
+    so the buffer ends up holding every item; counts and rows are sums over all steps."""
+    K, n, m = 40, 1500, 2500
+    rng = np.random.default_rng(77)
+    X = rng.standard_normal((n, 16)).astype(np.float32)
+    W = (rng.standard_normal((16, 12)) / 4).astype(np.float32)
+    batches = []
+    for k in range(K):
+        ids = rng.integers(0, n, size=m).astype(np.int32)
+        batches.append((ids, rng.standard_normal((m, 12)).astype(np.float32)))
+    say(f"long window K={K}")
+    out = run_window(X, W, batches, vocab_n=n, k_steps=K, keep_H=False, keep_E=False)
+    mm = orc.GramMulti(X, W)
+    for ids, dH in batches:
+        mm.step(ids, dH)
+    ref = mm.finish()
+    assert out["U_total"] == n                      # every item (and the padding ID) was met
+    np.testing.assert_array_equal(out["uniq_total"], ref["uniq"])
+    np.testing.assert_array_equal(out["counts_total"], ref["counts"])
+    assert out["counts_total"].sum() == K * m
+    assert_close(out["G_total"], ref["G"], 1e-5, "G_total")
+    assert_close(out["dW"], ref["dW"], 1e-5, "dW")
+
+
 def test_flush_variants_and_back_to_back_windows():
     """gram_flush with and without the G export gives the same IDs and counts; a second flush of an
     empty window returns nothing; a context runs window after window with one- and multi-step
