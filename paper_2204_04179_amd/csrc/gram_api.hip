@@ -40,7 +40,9 @@ int bits_for(int32_t vocab_n)
 
 int64_t table_elems_for(int64_t n_sort_max)
 {
-    // blocks of the radix plan: at least 1024 keys each, at most 256 * 64 keys each
+    // Upper bound, over every n <= n_sort_max, of the digit table make_sort_plan(n) needs: its blocks
+    // hold at least 1024 and at most 256 * 64 keys each, and there are at most 256 of them until the
+    // keys per block reach that maximum.
     int64_t nb = (n_sort_max + 1023) / 1024;
     if (nb > 256) {
         nb = (n_sort_max + 16383) / 16384;

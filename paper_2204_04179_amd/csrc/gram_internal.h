@@ -139,7 +139,6 @@ inline void launch(Ctx* c, int kid, void (*kernel)(KArgs...), dim3 grid, dim3 bl
 
 // ---- gram_sort.hip -------------------------------------------------------
 SortPlan make_sort_plan(int key_bits, int64_t n_max);
-int64_t sort_table_elems(const SortPlan& p);
 // Stable LSD radix sort of (key, value) pairs on the low `key_bits` bits.
 // keys_in: n keys (n = *n_dev if n_dev else n_host; n <= n_max).  vals_in may
 // be NULL (value = index).  With check_range, keys outside [0, vocab_n) are

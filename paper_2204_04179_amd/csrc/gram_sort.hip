@@ -5,9 +5,11 @@
 // ceil(log2 N) significant key bits, in digits of up to 10 bits (at most two
 // passes for a vocabulary of a million items), followed by head-flag scan and
 // compaction.  Each 64-lane wave owns a contiguous chunk of keys; ranks inside
-// a wave come from ballot-based digit matching, ranks across waves from a
-// per-wave digit table that one wave per digit prefix-sums.  All counters are
-// integer (LDS atomics are order independent), so the result is exact.
+// a wave come from ballot-based digit matching, ranks across blocks from a
+// per-block digit table that one wave per digit prefix-sums.  Small batches
+// take a one-launch variant that keeps everything in LDS (k_unique_small).
+// All counters are integer (LDS atomics are order independent), so the result
+// is exact.
 #include "gram_internal.h"
 
 namespace gram {
@@ -84,13 +86,6 @@ SortPlan make_sort_plan(int key_bits, int64_t n_max)
     p.blocks = (int)nb;
     p.nw = p.blocks * kWavesPerBlock;
     return p;
-}
-
-int64_t sort_table_elems(const SortPlan& p)
-{
-    int mb = 0;
-    for (int i = 0; i < p.passes; ++i) mb = p.digit_bits[i] > mb ? p.digit_bits[i] : mb;
-    return ((int64_t)1 << mb) * p.blocks;
 }
 
 // Applies `f(key, index, u)` to the keys of one wave's chunk, kSortBatch rounds of 64 keys at a

@@ -1,8 +1,10 @@
 // HBM-bound kernels of the GRAM step: row gather of representations to
-// interaction positions (Algorithm 1 step 1, second half), the deterministic
-// per-item reduction of dL/dH (step 3, Eq. 6) into the buffer that persists
-// over a Multi-step window (Section 4.2), and the export of that buffer at the
-// end of the window.
+// interaction positions (Algorithm 1 step 1, second half; for large batches the
+// contraction in gram_gemm.hip does most of it and only the copy for very
+// popular items runs here), the pseudo-targets of step 3 (Eq. 6), the
+// deterministic per-item reduction of dL/dH (step 3, Eq. 6) into the buffer
+// that persists over a Multi-step window (Section 4.2), and the export of that
+// buffer at the end of the window.
 //
 // No float atomics anywhere: each buffer row has exactly one writer and a
 // fixed order of additions, so results are bit-identical from run to run.
