@@ -313,6 +313,9 @@ def main():
                     help="comma-separated workloads reported under 'also' ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-export-G", action="store_true", help="gram_flush without the G_total copy")
+    ap.add_argument("--legs", default="pseudo_target,chunked_wgrad",
+                    help="extra measurements outside the timed steps (profiling runs drop chunked_wgrad so that "
+                         "the weight-gradient kernel's statistics cover the timed windows only)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device copy (calibration kernel for counter runs)")
     args = ap.parse_args()
@@ -379,8 +382,11 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(r)
         out["gpu_over_cpu"] = value / out["cpu_baseline"]["value"]
-    out["next_rows"] = {"pseudo_target": pseudo_target_leg(r)}
-    if w.xw_dtype != wl.F32:
+    legs = [x for x in args.legs.split(",") if x]
+    out["next_rows"] = {}
+    if "pseudo_target" in legs:
+        out["next_rows"]["pseudo_target"] = pseudo_target_leg(r)
+    if "chunked_wgrad" in legs and w.xw_dtype != wl.F32:
         out["next_rows"]["chunked_wgrad"] = chunked_wgrad_leg(r)
     out["paper_context"] = "paper: Single-step ~4x, Multi-step up to 146x faster than E2E, whole training runs on A100"
     del r
