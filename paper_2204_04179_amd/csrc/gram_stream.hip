@@ -429,7 +429,7 @@ constexpr int kDstNone = -1;    // nothing to write (dropped item)
 constexpr int kDstFirst = -2;   // partial row seg_first[tile]
 constexpr int kDstLast = -3;    // partial row seg_last[tile]
 constexpr int kSegMaxRows = kSegRows + kSegLong;
-constexpr int kSegUnroll = 8;
+constexpr int kSegUnroll = 16;
 
 __device__ __forceinline__ void write_final(float4* __restrict__ G, int cols4, int col, int code,
                                             bool is_pad, float4 acc)
