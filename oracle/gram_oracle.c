@@ -19,7 +19,12 @@
  * Single-step (Section 4.3), library unique/matmul/scatter-add cross-checks;
  * pseudo-targets: a hand-worked case, one SGD step of rate 1 on a quadratic
  * loss lands on its target, the derivative of the pseudo-loss with respect to
- * W equals the weight gradient, pseudo-loss = half the squared norm of G.
+ * W equals the weight gradient, pseudo-loss = half the squared norm of G;
+ * content-encoder batch: with targets taken at the same weights its gradient
+ * is the end-to-end gradient (Proposition), a central difference of an
+ * independently written pseudo-loss matches it, a Newton step from it solves
+ * a consistent regression exactly, and it vanishes at the regression's
+ * solution.
  * No function here is "parity unpinned".
  */
 #include <stdint.h>
@@ -354,4 +359,34 @@ int oracle_pseudo_target(const double *E, const double *G, int64_t u, int32_t d,
         }
     *loss = total;
     return 0;
+}
+
+/*
+ * One content-encoder batch of the update of Algorithm 1 step 4: the encoder
+ * is regressed towards the stored pseudo-targets of the listed items (Eq. 7;
+ * the content-encoder batch size of the GPU-memory table says that this update
+ * runs over the accumulated items a chunk at a time).  With the encoder's
+ * CURRENT weights W, which may have moved since the targets were taken,
+ *   h_j    = X[item[j],:] . W                         (Eq. 4)
+ *   miss_j = h_j - Ht[j,:]
+ *   loss   = 1/2 sum_j |Ht[j,:] - h_j|^2              (Eq. 7)
+ *   dW     = d loss / d W = sum_j X[item[j],:]^T miss_j
+ * A padding item takes no part: zero miss row, nothing added to loss or dW.
+ * miss is [n, d], dW is [d_in, d]; *loss receives the scalar.
+ */
+int oracle_pseudo_loss_grad(const int32_t *item, int64_t n_items, int32_t vocab_n, int32_t pad_id,
+                            const void *X, const void *W, int xw_dtype, int32_t d_in, int32_t d,
+                            const double *Ht, double *miss, double *loss, double *dW)
+{
+    int rc = oracle_encode(item, n_items, vocab_n, pad_id, X, W, xw_dtype, d_in, d, miss);
+    if (rc < 0) return rc;
+    double total = 0.0;
+    for (int64_t j = 0; j < n_items; ++j)
+        for (int32_t c = 0; c < d; ++c) {
+            double r = item[j] == pad_id ? 0.0 : miss[j * d + c] - Ht[j * d + c];
+            miss[j * d + c] = r;
+            total += 0.5 * r * r;
+        }
+    *loss = total;
+    return oracle_wgrad(item, n_items, vocab_n, pad_id, X, xw_dtype, d_in, d, miss, dW);
 }

@@ -79,6 +79,9 @@ def lib():
         L.oracle_buffer_rows.argtypes = [vp, i32p, C.c_int64, f64p]
         L.oracle_pseudo_target.restype = C.c_int
         L.oracle_pseudo_target.argtypes = [f64p, f64p, C.c_int64, C.c_int32, f64p, f64p]
+        L.oracle_pseudo_loss_grad.restype = C.c_int
+        L.oracle_pseudo_loss_grad.argtypes = [i32p, C.c_int64, C.c_int32, C.c_int32, vp, vp, C.c_int,
+                                              C.c_int32, C.c_int32, f64p, f64p, f64p, f64p]
         _lib = L
     return _lib
 
@@ -205,6 +208,28 @@ def pseudo_target(E, G):
     _check(lib().oracle_pseudo_target(_p(E, C.c_double), _p(G, C.c_double), E.shape[0], E.shape[1],
                                       _p(Ht, C.c_double), C.byref(loss)), "pseudo_target")
     return Ht, loss.value
+
+
+def pseudo_loss_grad(item, X, W, Ht, pad_id=0):
+    """One content-encoder batch of Algorithm 1 step 4: pseudo-loss of Eq. 7 for the listed items
+    at the CURRENT weights W against stored pseudo-targets Ht [n, d], and its gradient.
+    Returns float64 (miss [n, d] = X[item].W - Ht, loss, dW [d_in, d])."""
+    item = np.ascontiguousarray(item, dtype=np.int32).reshape(-1)
+    X = np.ascontiguousarray(X)
+    W = np.ascontiguousarray(W)
+    Ht = np.ascontiguousarray(Ht, dtype=np.float64)
+    dt = _xw_dtype(X)
+    assert _xw_dtype(W) == dt and X.shape[1] == W.shape[0]
+    d_in, d = W.shape
+    assert Ht.shape == (item.size, d)
+    miss = np.empty((item.size, d), np.float64)
+    dW = np.empty((d_in, d), np.float64)
+    loss = C.c_double(0.0)
+    _check(lib().oracle_pseudo_loss_grad(_p(item, C.c_int32), item.size, X.shape[0], pad_id,
+                                         X.ctypes.data, W.ctypes.data, dt, d_in, d, _p(Ht, C.c_double),
+                                         _p(miss, C.c_double), C.byref(loss), _p(dW, C.c_double)),
+           "pseudo_loss_grad")
+    return miss, loss.value, dW
 
 
 def e2e(ids, X, W, dH, pad_id=0):

@@ -387,6 +387,86 @@ def test_boost_ratio_definition_and_monotone_growth():
     assert orc.boost_ratio(ids) > orc.boost_ratio(ids[:2])
 
 
+# ------------------------------ content-encoder batch of the update (step 4) --
+
+def test_encoder_batch_with_fresh_targets_is_the_end_to_end_gradient():
+    """Proposition (Eq. 1-3) for the chunked update: targets taken at the same weights make the
+    gradient of the pseudo-loss the end-to-end gradient, whether the window's items are visited
+    in one batch or in several, and the pseudo-loss is half the squared norm of G."""
+    ids, X, W, dH = rand_problem(70, m=80, n=17, d_in=5, d=4)
+    r = orc.gram_single(ids, X, W, dH)
+    _, dW_e2e = orc.e2e(ids, X, W, dH)
+    Ht, loss0 = orc.pseudo_target(r["E"], r["G"])
+    miss, loss, dW = orc.pseudo_loss_grad(r["uniq"], X, W, Ht)
+    np.testing.assert_allclose(dW, dW_e2e, rtol=0, atol=1e-9 * np.abs(dW_e2e).max())
+    pad = r["uniq"] == 0
+    np.testing.assert_allclose(miss[~pad], r["G"][~pad], rtol=0, atol=1e-12)
+    assert np.all(miss[pad] == 0)
+    assert abs(loss - loss0) <= 1e-12 * loss0
+    parts = [orc.pseudo_loss_grad(r["uniq"][a:b], X, W, Ht[a:b]) for a, b in ((0, 3), (3, 4), (4, r["uniq"].size))]
+    np.testing.assert_allclose(sum(p[2] for p in parts), dW_e2e, rtol=0, atol=1e-9 * np.abs(dW_e2e).max())
+    assert abs(sum(p[1] for p in parts) - loss0) <= 1e-12 * loss0
+
+
+def test_encoder_batch_gradient_is_the_derivative_of_an_independent_pseudo_loss():
+    """Eq. 7 at weights that have moved since the targets were taken: a central difference of
+    the loss written out with numpy matches the oracle's dW, and the oracle's loss matches it."""
+    rng = np.random.default_rng(71)
+    n, d_in, d = 9, 4, 3
+    X = rng.standard_normal((12, d_in)).astype(np.float32)
+    W = (rng.integers(-8, 9, size=(d_in, d)) / 8.0).astype(np.float32)
+    item = np.array([3, 0, 7, 1, 11, 5, 2, 9, 4], np.int32)       # 0 = padding
+    Ht = rng.standard_normal((n, d))
+    live = item != 0
+
+    def loss_np(Wm):
+        return 0.5 * np.sum((Ht[live] - X[item[live]].astype(np.float64) @ Wm) ** 2)
+
+    miss, loss, dW = orc.pseudo_loss_grad(item, X, W, Ht)
+    Wd = W.astype(np.float64)
+    assert abs(loss - loss_np(Wd)) <= 1e-12 * loss
+    eps = 2.0 ** -10
+    for i in range(d_in):
+        for c in range(d):
+            Wp, Wm = Wd.copy(), Wd.copy()
+            Wp[i, c] += eps
+            Wm[i, c] -= eps
+            num = (loss_np(Wp) - loss_np(Wm)) / (2 * eps)     # exact for a quadratic, up to rounding
+            assert abs(num - dW[i, c]) <= 1e-7 * max(1.0, abs(num))
+
+
+def test_encoder_batch_newton_step_solves_a_consistent_regression():
+    """Closed form: if the targets are the outputs of some weights W*, the loss is the quadratic
+    1/2 |X_c (W - W*)|^2, so dW = X_c^T X_c (W - W*) and W - (X_c^T X_c)^-1 dW = W*; at W* itself
+    loss and gradient vanish."""
+    rng = np.random.default_rng(72)
+    n, d_in, d = 11, 4, 3
+    X = rng.integers(-3, 4, size=(16, d_in)).astype(np.float32)
+    item = rng.permutation(np.arange(1, 16))[:n].astype(np.int32)
+    W_star = rng.integers(-4, 5, size=(d_in, d)).astype(np.float32)
+    W = rng.integers(-4, 5, size=(d_in, d)).astype(np.float32)
+    Xc = X[item].astype(np.float64)
+    assert np.linalg.matrix_rank(Xc) == d_in
+    Ht = Xc @ W_star.astype(np.float64)
+    _, loss, dW = orc.pseudo_loss_grad(item, X, W, Ht)
+    np.testing.assert_allclose(W - np.linalg.solve(Xc.T @ Xc, dW), W_star, rtol=0, atol=1e-9)
+    assert loss > 0
+    miss, loss, dW = orc.pseudo_loss_grad(item, X, W_star, Ht)
+    assert loss == 0 and not dW.any() and not miss.any()
+
+
+def test_encoder_batch_handles_bf16_weights_exactly():
+    """bf16 X and W widen exactly: the result equals that of the same values held as float32."""
+    ids, X, W, dH = rand_problem(73, m=40, n=19, d_in=6, d=4, bf16=True)
+    Xf, Wf = wl.bf16_bits_to_f32(X), wl.bf16_bits_to_f32(W)
+    item = np.unique(ids)
+    Ht = np.random.default_rng(3).standard_normal((item.size, 4))
+    a = orc.pseudo_loss_grad(item, X, W, Ht)
+    b = orc.pseudo_loss_grad(item, Xf, Wf, Ht)
+    for u, v in zip(a, b):
+        np.testing.assert_array_equal(u, v)
+
+
 # -------------------------------------------------- planted-mistake checks --
 
 def test_pins_catch_planted_mistakes():
@@ -408,3 +488,8 @@ def test_pins_catch_planted_mistakes():
     # (4) pseudo-target moved up the gradient instead of down: the hand example tells them apart
     Ht_bad, _ = orc.pseudo_target(r["E"], -r["G"])
     assert np.abs(Ht_bad - (r["E"] - r["G"])).max() > 1e-3
+    # (5) regression error taken as target minus output: the gradient of step 4 changes sign
+    Ht, _ = orc.pseudo_target(r["E"], r["G"])
+    miss, _, dW4 = orc.pseudo_loss_grad(uniq, X, W, Ht)
+    assert np.abs(orc.wgrad(uniq, X, -miss, 0) - dW).max() > 1e-3 * scale
+    assert np.abs(dW4 - dW).max() <= 1e-9 * scale
