@@ -303,6 +303,47 @@ def chunked_wgrad_leg(r, chunk_rows=32768, reps=3):
             "frac": flops / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
 
 
+def encoder_batches_leg(r, chunk_rows=32768, reps=3):
+    """Outside the timed steps: Algorithm 1 step 4 as a regression towards stored pseudo-targets
+    (Eq. 7), over the items of one full window in content-encoder batches of `chunk_rows` items:
+    re-encode at the current weights, regression miss and pseudo-loss, weight gradient.  The
+    window's exported gradient rows stand in for the targets (same shape and dtype)."""
+    torch, g, w = r.torch, r.g, r.w
+    r.finish_window()
+    for k in range(w.K):
+        g.unique(r.ids[k], r.uniq, r.inverse, r.counts, r.u_dev)
+        g.encode_gather(r.X, r.Wt, r.uniq, r.inverse, r.u_dev, r.M, None, r.H)
+        g.grad_accumulate(r.dH[k], r.M, k)
+    Ht = r.G_t if r.G_t is not None else torch.zeros(r.uniq_t.numel(), w.d, device="cuda")
+    g.flush(r.uniq_t, r.counts_t, r.G_t, r.u_t)
+    r.pos = 0
+    n_items = int(r.u_t.item())
+    R = torch.empty(min(chunk_rows, n_items), w.d, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    bounds = [(a, min(chunk_rows, n_items - a)) for a in range(0, n_items, chunk_rows)]
+
+    def window():
+        for i, (a, n) in enumerate(bounds):
+            g.pseudo_loss_grad(r.X, r.Wt, r.uniq_t[a:a + n], Ht[a:a + n], n, R, r.dW, i > 0, loss)
+
+    window()
+    torch.cuda.synchronize()
+    names = ["encode_bf16", "encode_f32", "pseudo_miss", "wgrad_bf16", "wgrad_f32", "wgrad_reduce"]
+    g.profile_enable(names, max_launches=16 * reps * len(bounds))
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        window()
+    torch.cuda.synchronize()
+    us = 1e6 * (time.perf_counter() - t0) / reps
+    prof = g.profile_read()
+    g.profile_enable([])
+    flops = 4 * n_items * w.d_in * w.d
+    return {"chunk_rows": chunk_rows, "chunks": len(bounds), "items": n_items, "us_per_window": us,
+            "kernels_us_per_window": {k: round(1e3 * v[1] / reps, 1) for k, v in prof.items() if v[0]},
+            "bound": "mfma", "achieved": flops / (us * 1e-6) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": flops / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -313,7 +354,7 @@ def main():
                     help="comma-separated workloads reported under 'also' ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-export-G", action="store_true", help="gram_flush without the G_total copy")
-    ap.add_argument("--legs", default="pseudo_target,chunked_wgrad",
+    ap.add_argument("--legs", default="pseudo_target,chunked_wgrad,encoder_batches",
                     help="extra measurements outside the timed steps (profiling runs drop chunked_wgrad so that "
                          "the weight-gradient kernel's statistics cover the timed windows only)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -388,6 +429,8 @@ def main():
         out["next_rows"]["pseudo_target"] = pseudo_target_leg(r)
     if "chunked_wgrad" in legs and w.xw_dtype != wl.F32:
         out["next_rows"]["chunked_wgrad"] = chunked_wgrad_leg(r)
+    if "encoder_batches" in legs and w.xw_dtype != wl.F32:
+        out["next_rows"]["encoder_batches"] = encoder_batches_leg(r)
     out["paper_context"] = "paper: Single-step ~4x, Multi-step up to 146x faster than E2E, whole training runs on A100"
     del r
     torch.cuda.empty_cache()

@@ -22,6 +22,9 @@
  *                         unique item, dW = X[items]^T . G
  *   gram_flush            end of the window ("t mod N"): export and empty the
  *                         buffer
+ *   gram_pseudo_loss_grad step 4 as a regression towards stored pseudo-targets,
+ *                         one content-encoder batch at a time, at the encoder's
+ *                         current weights (optional)
  *
  * Memory.  Every pointer marked DEVICE is memory of the current HIP device,
  * owned by the caller (the library never frees, reallocates or keeps it beyond
@@ -185,6 +188,36 @@ int gram_encoder_wgrad(gram_ctx* ctx, const void* X, float* dW, void* stream);
  * GRAM_ERR_UNIMPLEMENTED when X or the buffer exceeds 4 GiB. */
 int gram_encoder_wgrad_chunk(gram_ctx* ctx, const void* X, float* dW, int64_t first_row,
                              int64_t n_rows, int32_t accumulate, void* stream);
+
+/* One content-encoder batch of the update of Algorithm 1 step 4, written as the
+ * paper states it: the encoder is regressed towards the pseudo-targets of the
+ * listed items (pseudo-loss of Eq. 7), at the weights it has NOW, which may have
+ * moved since the targets were taken (an optimiser step per batch; the
+ * content-encoder batch size of the section on GPU memory consumption):
+ *   h_j   = X[ids[j],:] . W
+ *   R[j,:] = h_j - Ht[j,:]             (zero row for the padding ID)
+ *   loss  = 1/2 sum_j |Ht[j,:] - h_j|^2
+ *   dW (+)= sum_j X[ids[j],:]^T . R[j,:]
+ * With targets taken at the same W this is gram_encoder_wgrad's gradient over
+ * those items (Proposition, Eq. 1-3).
+ *   X        DEVICE [N,d_in]    W  DEVICE [d_in,d]   (the context's xw_dtype)
+ *   ids      DEVICE [n] int32   items of the batch, e.g. a range of gram_flush's
+ *                               uniq_total; an ID outside [0,N) latches
+ *                               GRAM_ERR_RANGE (reported by the next call that
+ *                               synchronises) and counts as the padding item
+ *   Ht       DEVICE [n,d]       their pseudo-targets
+ *   n        0 <= n <= max(min(max_positions, N), rows of the buffer)
+ *   R        DEVICE [n,d]       out: the regression miss; also the only workspace
+ *                               the call needs beyond the context's
+ *   dW       DEVICE [d_in,d]    out; accumulate = 0 overwrites, else adds
+ *   loss_dev DEVICE [1] double, nullable  out (summed in double, fixed order)
+ * With bf16 features R is rounded to bf16 (nearest-even) as it enters the matrix
+ * cores, like G in gram_encoder_wgrad.  Independent of the window's state: may
+ * be called at any point.  GRAM_ERR_UNIMPLEMENTED when X or R exceeds 4 GiB.
+ * 16-byte aligned pointers. */
+int gram_pseudo_loss_grad(gram_ctx* ctx, const void* X, const void* W, const int32_t* ids,
+                          const float* Ht, int64_t n, float* R, float* dW, int32_t accumulate,
+                          double* loss_dev, void* stream);
 
 /* End of the accumulation window: export the buffer in ascending ID order,
  * then empty it and reset the step counter.

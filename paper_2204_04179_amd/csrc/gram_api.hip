@@ -52,7 +52,7 @@ int64_t table_elems_for(int64_t n_sort_max)
 }
 
 struct Derived {
-    int64_t cap_u, cap_total, n_sort_max, tiles_scan, tiles_seg;
+    int64_t cap_u, cap_total, cap_chunk, n_sort_max, tiles_scan, tiles_seg;
     int splits;
 };
 
@@ -73,6 +73,7 @@ const char* validate(const gram_config* cfg, Derived* dv)
     int64_t km = (int64_t)cfg->k_steps * cfg->max_positions;
     dv->cap_total = cfg->u_total_cap ? cfg->u_total_cap : (km < cfg->vocab_n ? km : cfg->vocab_n);
     if (dv->cap_total >= ((int64_t)1 << 30)) return "persistent buffer rows must be < 2^30";
+    dv->cap_chunk = dv->cap_u > dv->cap_total ? dv->cap_u : dv->cap_total;
     dv->n_sort_max = cfg->max_positions > dv->cap_total ? cfg->max_positions : dv->cap_total;
     dv->tiles_scan = (cfg->max_positions + kScanTile - 1) / kScanTile + 1;
     dv->tiles_seg = (cfg->max_positions + kSegRows - 1) / kSegRows;
@@ -108,7 +109,8 @@ int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
     int* cnt_of_slot = (int*)take(dv.cap_total * 4);
     float* G = (float*)take(dv.cap_total * d * 4);
     float* E_ws = (float*)take(dv.cap_u * d * 4);
-    double* loss_part = (double*)take((dv.cap_u / kPseudoRows + 1) * 8);
+    double* loss_part = (double*)take((dv.cap_chunk / kPseudoRows + 1) * 8);
+    int* chunk_ids = (int*)take(dv.cap_chunk * 4);
     float* seg_first = (float*)take(dv.tiles_seg * d * 4);
     float* seg_last = (float*)take(dv.tiles_seg * d * 4);
     void* Wt = take(cfg.xw_dtype == GRAM_BF16 ? d * d_in * 2 : 1);
@@ -122,7 +124,7 @@ int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
         c->table = table; c->gtot = gtot; c->tile_sums = tile_sums; c->offsets = offsets;
         c->seg_of_row = seg_of_row; c->uniq_ws = uniq_ws; c->seg_slot = seg_slot;
         c->long_list = long_list; c->slot_of = slot_of; c->id_of_slot = id_of_slot;
-        c->cnt_of_slot = cnt_of_slot; c->G = G; c->E_ws = E_ws; c->loss_part = loss_part; c->seg_first = seg_first;
+        c->cnt_of_slot = cnt_of_slot; c->G = G; c->E_ws = E_ws; c->loss_part = loss_part; c->chunk_ids = chunk_ids; c->seg_first = seg_first;
         c->seg_last = seg_last; c->Wt = Wt; c->wg_partial = wg_partial;
         c->XT = XT; c->GT = GT; c->ldt = ldt;
     }
@@ -176,6 +178,7 @@ int gram_create(gram_ctx** out, const gram_config* cfg)
     c->cfg = *cfg;
     c->cap_u = dv.cap_u;
     c->cap_total = dv.cap_total;
+    c->cap_chunk = dv.cap_chunk;
     c->key_bits = bits_for(cfg->vocab_n);
     c->wg_splits = dv.splits;
     c->ws_bytes = layout(nullptr, *cfg, dv, nullptr);
@@ -367,6 +370,30 @@ int gram_encoder_wgrad_chunk(gram_ctx* ctx, const void* X, float* dW, int64_t fi
     return launch_status(c, "gram_encoder_wgrad_chunk");
 }
 
+int gram_pseudo_loss_grad(gram_ctx* ctx, const void* X, const void* W, const int32_t* ids, const float* Ht,
+                          int64_t n, float* R, float* dW, int32_t accumulate, double* loss_dev, void* stream)
+{
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (!c) return GRAM_ERR_ARG;
+    if (n < 0 || n > c->cap_chunk)
+        return fail(c, GRAM_ERR_ARG, "gram_pseudo_loss_grad: n = %lld outside [0, %lld]", (long long)n,
+                    (long long)c->cap_chunk);
+    if (!X || !W || !dW || (n > 0 && (!ids || !Ht || !R)))
+        return fail(c, GRAM_ERR_ARG, "gram_pseudo_loss_grad: NULL pointer");
+    const int64_t window = ((int64_t)1 << 32) - 16;
+    if (c->cfg.xw_dtype == GRAM_BF16 &&
+        ((int64_t)c->cfg.vocab_n * c->cfg.d_in * 2 >= window || n * c->cfg.d * 4 >= window))
+        return fail(c, GRAM_ERR_UNIMPLEMENTED, "gram_pseudo_loss_grad: not available when X or R exceeds 4 GiB");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    chunk_ids_prepare(c, ids, n, s);
+    encode_forward(c, X, W, c->chunk_ids, c->scal + kSChunkN, n, R, s, nullptr, true);
+    pseudo_miss(c, R, Ht, n, loss_dev, s);
+    const WgradRows rows = {c->chunk_ids, R, c->scal + kSChunkN, n};
+    if (!encoder_wgrad(c, X, dW, s, 0, n, accumulate != 0, &rows))
+        return fail(c, GRAM_ERR_UNIMPLEMENTED, "gram_pseudo_loss_grad: batch too large for the buffer window");
+    return launch_status(c, "gram_pseudo_loss_grad");
+}
+
 int gram_flush(gram_ctx* ctx, int32_t* uniq_total, int32_t* counts_total, float* G_total,
                int32_t* u_total_dev, int32_t* u_total_host, void* stream)
 {
@@ -389,7 +416,8 @@ static const char* const kKernelNames[KID_COUNT] = {
     "radix_hist", "radix_scan", "radix_scatter", "heads_count", "heads_emit", "counts", "unique_empty",
     "transpose_w", "encode_bf16", "encode_f32", "gather_rows", "slot_count", "slot_emit", "seg_reduce",
     "seg_combine", "wgrad_bf16", "wgrad_f32", "wgrad_reduce", "transpose_x", "transpose_g", "flush_meta",
-    "flush_rows", "unique_small", "gather_heavy", "pseudo_target", "pseudo_loss"};
+    "flush_rows", "unique_small", "gather_heavy", "pseudo_target", "pseudo_loss", "chunk_ids",
+    "pseudo_miss"};
 
 int gram_kernel_count(void) { return KID_COUNT; }
 

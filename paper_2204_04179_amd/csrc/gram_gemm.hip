@@ -926,7 +926,7 @@ constexpr int kWgradWaves = 8;
 template <int NW>
 __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
     const uint16_t* __restrict__ X, uint32_t x_bytes, const int* __restrict__ id_of_slot,
-    const float* __restrict__ G, uint32_t g_bytes, const int* __restrict__ scal, int d_in, int d,
+    const float* __restrict__ G, uint32_t g_bytes, const int* __restrict__ rows_dev, int d_in, int d,
     int pad_id, int splits, float* __restrict__ partial, int row_begin, int row_end)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -946,7 +946,8 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
 
     // buffer rows [row_begin, U) take part (row_end clips U: the chunked call); slabs stay aligned
     // to multiples of WK rows, rows outside the range are loaded as zeros
-    const int U = scal[kSUTotal] < row_end ? scal[kSUTotal] : row_end;
+    const int rows_held = *rows_dev;
+    const int U = rows_held < row_end ? rows_held : row_end;
     const int sl0 = row_begin / WK;
     const int slabs_all = U > row_begin ? (U + WK - 1) / WK - sl0 : 0;
     const int per = (slabs_all + splits - 1) / splits;
@@ -1129,7 +1130,7 @@ __device__ __forceinline__ void split_range(int u_total, int splits, int z, int*
 
 __global__ __launch_bounds__(kBlock) void k_wgrad_f32(
     const float* __restrict__ X, const int* __restrict__ id_of_slot, const float* __restrict__ G,
-    const int* __restrict__ scal, int d_in, int d, int pad_id, int splits,
+    const int* __restrict__ rows_dev, int d_in, int d, int pad_id, int splits,
     float* __restrict__ partial, int row_begin, int row_end)
 {
     const int c = blockIdx.x * 64 + (threadIdx.x & 63);
@@ -1137,7 +1138,8 @@ __global__ __launch_bounds__(kBlock) void k_wgrad_f32(
     const int z = blockIdx.z;
     if (i >= d_in || c >= d) return;
     int kb, ke;
-    const int u_end = scal[kSUTotal] < row_end ? scal[kSUTotal] : row_end;
+    const int rows_held = *rows_dev;
+    const int u_end = rows_held < row_end ? rows_held : row_end;
     split_range(u_end > row_begin ? u_end - row_begin : 0, splits, z, &kb, &ke);
     kb += row_begin;
     ke += row_begin;
@@ -1177,23 +1179,28 @@ int wgrad_splits_for(const gram_config& cfg)
 int64_t wgrad_pitch_for(int64_t cap_total) { return (cap_total + TT - 1) / TT * TT + TT; }
 
 bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t first_row, int64_t n_rows,
-                   bool accumulate)
+                   bool accumulate, const WgradRows* other)
 {
     const int d_in = c->cfg.d_in, d = c->cfg.d;
     int S = c->wg_splits;
-    const bool chunked = first_row > 0 || n_rows < c->cap_total;
-    const int row_begin = (int)(first_row < c->cap_total ? first_row : c->cap_total);
-    const int row_end = (int)(n_rows < c->cap_total - row_begin ? row_begin + n_rows : c->cap_total);
+    // the rows contracted over: the persistent buffer, or the caller's (ids, rows) pairs
+    const int64_t cap = other ? other->n_max : c->cap_total;
+    const int* ids = other ? other->ids : c->id_of_slot;
+    const float* rows = other ? other->rows : c->G;
+    const int* rows_dev = other ? other->n_dev : c->scal + kSUTotal;
+    const bool chunked = other || first_row > 0 || n_rows < cap;
+    const int row_begin = (int)(first_row < cap ? first_row : cap);
+    const int row_end = (int)(n_rows < cap - row_begin ? row_begin + n_rows : cap);
     if (c->cfg.xw_dtype == GRAM_BF16) {
         // a short window does not need all the ranges: at least 8 slabs of 32 buffer rows each
         // (from the host's bound on the rows in the buffer), still a multiple of 8
-        int64_t rows_bound = c->window_positions < c->cap_total ? c->window_positions : c->cap_total;
+        int64_t rows_bound = other ? cap : (c->window_positions < cap ? c->window_positions : cap);
         if (rows_bound > row_end - row_begin) rows_bound = row_end - row_begin;
         const int64_t slabs_bound = rows_bound / TK + 1;
         int64_t want = slabs_bound / 8 / 8 * 8;
         if (want < 8) want = 8;
         if (want < S) S = (int)want;
-        const int64_t x_bytes = (int64_t)c->cfg.vocab_n * d_in * 2, g_bytes = c->cap_total * d * 4;
+        const int64_t x_bytes = (int64_t)c->cfg.vocab_n * d_in * 2, g_bytes = cap * d * 4;
         const int64_t window = ((int64_t)1 << 32) - 16;
         if (x_bytes < window && g_bytes < window) {
             static bool attr_set = false;
@@ -1204,8 +1211,8 @@ bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t firs
             }
             const int tiles = ((d_in + 255) / 256) * ((d + 255) / 256);
             launch_smem(c, KID_WGRAD_BF16, k_wgrad_tn_bf16<kWgradWaves>, dim3((unsigned)(tiles * S)), dim3(kWgradWaves * 64), WSMEM, s,
-                        static_cast<const uint16_t*>(X), (uint32_t)x_bytes, c->id_of_slot, c->G, (uint32_t)g_bytes,
-                        c->scal, d_in, d, c->cfg.pad_id, S, c->wg_partial, row_begin, row_end);
+                        static_cast<const uint16_t*>(X), (uint32_t)x_bytes, ids, rows, (uint32_t)g_bytes,
+                        rows_dev, d_in, d, c->cfg.pad_id, S, c->wg_partial, row_begin, row_end);
         } else {
             if (chunked) return false;      // the transposed copies cover the whole buffer only
             // operands beyond the 4 GiB buffer window: transposed bf16 copies + the NT kernel
@@ -1218,7 +1225,7 @@ bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t firs
         }
     } else {
         launch(c, KID_WGRAD_F32, k_wgrad_f32, dim3((d + 63) / 64, (d_in + 3) / 4, S), dim3(kBlock), s,
-               static_cast<const float*>(X), c->id_of_slot, c->G, c->scal, d_in, d, c->cfg.pad_id, S,
+               static_cast<const float*>(X), ids, rows, rows_dev, d_in, d, c->cfg.pad_id, S,
                c->wg_partial, row_begin, row_end);
     }
     const int64_t n4 = (int64_t)d_in * d / 4;

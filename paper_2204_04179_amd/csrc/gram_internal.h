@@ -22,13 +22,13 @@ constexpr int kSegLong = 64;            // segments with at least this many rows
 constexpr int kSegLongSmall = 32;       // ... or this many when the batch has at most kSegSmallBatch positions
 constexpr int kSegSmallBatch = 65536;
 constexpr int kLightMax = 32;           // items with more positions are gathered by a separate copy kernel
-constexpr int kSlotNew = 1 << 30;
-constexpr int kPseudoRows = 8;          // unique items per block of the pseudo-target kernel       // flag in seg_slot: the buffer row is created by this step
+constexpr int kSlotNew = 1 << 30;       // flag in seg_slot: the buffer row is created by this step
+constexpr int kPseudoRows = 8;          // unique items per block of the pseudo-target kernel
 constexpr int kFixCols4 = 16;           // float4 columns per block of the long-segment combine
 constexpr int kFixLanes = kBlock / kFixCols4;
 
 // Device scalars (ctx->scal[...]).
-enum Scalar { kSU = 0, kSUTotal, kSErr, kSUBase, kSLongCount, kSFlushN, kSCount };
+enum Scalar { kSU = 0, kSUTotal, kSErr, kSUBase, kSLongCount, kSFlushN, kSChunkN, kSCount };
 
 // Device-latched error bits (scal[kSErr]).
 constexpr int kErrBitRange = 1;
@@ -40,7 +40,7 @@ enum KernelId {
     KID_UNIQUE_EMPTY, KID_TRANSPOSE_U16, KID_ENCODE_BF16, KID_ENCODE_F32, KID_GATHER_ROWS,
     KID_SLOT_COUNT, KID_SLOT_EMIT, KID_SEG_REDUCE, KID_SEG_COMBINE, KID_WGRAD_BF16, KID_WGRAD_F32,
     KID_WGRAD_REDUCE, KID_TRANSPOSE_X, KID_TRANSPOSE_G, KID_FLUSH_META, KID_FLUSH_ROWS, KID_UNIQUE_SMALL,
-    KID_GATHER_HEAVY, KID_PSEUDO_TARGET, KID_PSEUDO_LOSS, KID_COUNT
+    KID_GATHER_HEAVY, KID_PSEUDO_TARGET, KID_PSEUDO_LOSS, KID_CHUNK_IDS, KID_PSEUDO_MISS, KID_COUNT
 };
 
 struct ProfSlot {
@@ -60,6 +60,7 @@ struct Ctx {
     gram_config cfg;
     int64_t cap_u;        // min(max_positions, vocab_n): upper bound of U per step
     int64_t cap_total;    // rows of the persistent buffer
+    int64_t cap_chunk;    // max(cap_u, cap_total): upper bound of a content-encoder batch
     int key_bits;         // bits needed for an ID
 
     // --- workspace (device) ---
@@ -80,7 +81,8 @@ struct Ctx {
     int* cnt_of_slot = nullptr; // [cap_total]
     float* G = nullptr;         // [cap_total, d] persistent per-item gradient
     float* E_ws = nullptr;      // [cap_u, d] representations when the caller passes E = NULL
-    double* loss_part = nullptr; // [cap_u / kPseudoRows + 1] per-block sums of the pseudo-loss
+    double* loss_part = nullptr; // [cap_chunk / kPseudoRows + 1] per-block sums of the pseudo-loss
+    int* chunk_ids = nullptr;   // [cap_chunk] checked copy of a content-encoder batch's item IDs
     float* seg_first = nullptr; // [tiles_seg, d] partial sums of segments entering a tile
     float* seg_last = nullptr;  // [tiles_seg, d] partial sums of segments leaving a tile
     void* Wt = nullptr;         // [d, d_in] transposed weight (bf16 path)
@@ -155,6 +157,11 @@ bool unique_small(Ctx* c, const int* ids, int n, int fix_key, int* uniq, int* in
 void gather_rows(Ctx* c, const float* E, const int* inverse, int64_t m, float* H, hipStream_t s);
 void gather_heavy(Ctx* c, const float* E, int64_t m, float* H, hipStream_t s);
 void pseudo_target(Ctx* c, const float* E, float* Ht, double* loss_dev, hipStream_t s);
+// Checked copy of a content-encoder batch's IDs into c->chunk_ids and its size into scal[kSChunkN].
+void chunk_ids_prepare(Ctx* c, const int* ids, int64_t n, hipStream_t s);
+// R[j,:] -= Ht[j,:] for the n rows of the batch in c->chunk_ids (zero for the padding item) and,
+// with loss_dev, 1/2 of the sum of the squares of the result.
+void pseudo_miss(Ctx* c, float* R, const float* Ht, int64_t n, double* loss_dev, hipStream_t s);
 void assign_slots(Ctx* c, hipStream_t s);
 void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s);
 void flush_export(Ctx* c, int* uniq_total, int* counts_total, float* G_total, int* u_total_dev,
@@ -167,11 +174,19 @@ void fill_i32(int* p, int64_t n, int v, hipStream_t s);
 // was written (gather_rows must follow).
 bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const int* u_dev,
                     int64_t rows_max, float* E, hipStream_t s, float* H_scatter, bool caller_wants_E);
+// Rows the weight gradient contracts over when they are not the persistent buffer's: row j pairs
+// item ids[j] with rows[j,:] (float32, d columns); *n_dev rows are held, at most n_max.
+struct WgradRows {
+    const int* ids;
+    const float* rows;
+    const int* n_dev;
+    int64_t n_max;
+};
 // Weight gradient over the buffer rows [first_row, first_row + n_rows) (clipped to the rows held),
-// written to dW or added to it.  Returns false if the range is a proper chunk and an operand is
-// beyond 4 GiB (nothing is launched).
+// or over the rows of `other`, written to dW or added to it.  Returns false if the range is a
+// proper chunk, or `other` is given, and an operand is beyond 4 GiB (nothing is launched).
 bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t first_row, int64_t n_rows,
-                   bool accumulate);
+                   bool accumulate, const WgradRows* other = nullptr);
 int wgrad_splits_for(const gram_config& cfg);
 int64_t wgrad_pitch_for(int64_t cap_total);
 

@@ -249,6 +249,76 @@ void pseudo_target(Ctx* c, const float* E, float* Ht, double* loss_dev, hipStrea
                loss_dev);
 }
 
+// ---- one content-encoder batch of the update (Alg. 1 step 4, Eq. 7) ---------
+//
+// The caller lists the items of the batch.  The IDs are copied once, checked: an ID outside
+// [0, N) is replaced by a harmless one (the padding item, else item 0) and latches the range
+// error, so the contraction kernels never form an address from it.
+__global__ __launch_bounds__(kBlock) void k_chunk_ids(const int* __restrict__ ids, int n, int vocab_n,
+                                                      int fix_id, int* __restrict__ out,
+                                                      int* __restrict__ scal)
+{
+    const int j = blockIdx.x * kBlock + threadIdx.x;
+    if (j == 0) scal[kSChunkN] = n;
+    if (j >= n) return;
+    int id = ids[j];
+    if (id < 0 || id >= vocab_n) {
+        id = fix_id;
+        atomicOr(&scal[kSErr], kErrBitRange);
+    }
+    out[j] = id;
+}
+
+void chunk_ids_prepare(Ctx* c, const int* ids, int64_t n, hipStream_t s)
+{
+    const int64_t blocks = n > 0 ? (n + kBlock - 1) / kBlock : 1;
+    launch(c, KID_CHUNK_IDS, k_chunk_ids, dim3((unsigned)blocks), dim3(kBlock), s, ids, (int)n,
+           c->cfg.vocab_n, c->cfg.pad_id >= 0 ? c->cfg.pad_id : 0, c->chunk_ids, c->scal);
+}
+
+// R[j,:] holds the encoder's output for item j of the batch; it becomes the regression miss
+// R[j,:] - Ht[j,:] (zero for the padding item), and the block's share of sum |miss|^2 goes to
+// partial[] exactly as in k_pseudo_target (double per thread, fixed tree, k_pseudo_loss adds
+// the blocks in index order).
+__global__ __launch_bounds__(kBlock) void k_pseudo_miss(f32x4* __restrict__ R,
+                                                        const f32x4* __restrict__ Ht,
+                                                        const int* __restrict__ ids, int n, int pad_id,
+                                                        int cols4, double* __restrict__ partial)
+{
+    __shared__ double s_sum[kBlock];
+    const int j0 = blockIdx.x * kPseudoRows;
+    double sum = 0.0;
+    const int rows = n - j0 < kPseudoRows ? n - j0 : kPseudoRows;
+    const int total = rows * cols4;
+    for (int e = threadIdx.x; e < total; e += kBlock) {
+        const int r = e / cols4, cq = e - r * cols4;
+        const int64_t at = (int64_t)(j0 + r) * cols4 + cq;
+        f32x4 m = {0.f, 0.f, 0.f, 0.f};
+        if (ids[j0 + r] != pad_id) m = R[at] - __builtin_nontemporal_load(&Ht[at]);
+        R[at] = m;
+        sum += (double)m.x * m.x + (double)m.y * m.y + (double)m.z * m.z + (double)m.w * m.w;
+    }
+    s_sum[threadIdx.x] = sum;
+    __syncthreads();
+    for (int w = kBlock / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) s_sum[threadIdx.x] += s_sum[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partial[blockIdx.x] = s_sum[0];
+}
+
+void pseudo_miss(Ctx* c, float* R, const float* Ht, int64_t n, double* loss_dev, hipStream_t s)
+{
+    const int64_t blocks = (n + kPseudoRows - 1) / kPseudoRows;
+    if (blocks > 0)
+        launch(c, KID_PSEUDO_MISS, k_pseudo_miss, dim3((unsigned)blocks), dim3(kBlock), s,
+               reinterpret_cast<f32x4*>(R), reinterpret_cast<const f32x4*>(Ht), c->chunk_ids, (int)n,
+               c->cfg.pad_id, c->cfg.d / 4, c->loss_part);
+    if (loss_dev)
+        launch(c, KID_PSEUDO_LOSS, k_pseudo_loss, dim3(1), dim3(kBlock), s, c->loss_part,
+               c->scal + kSChunkN, loss_dev);
+}
+
 // ---- buffer rows for the items of this batch --------------------------------
 //
 // An item seen for the first time in the window gets the next free row of the

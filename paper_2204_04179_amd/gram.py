@@ -21,7 +21,7 @@ STATUS_NAMES = {OK: "GRAM_OK", ERR_ARG: "GRAM_ERR_ARG", ERR_CAPACITY: "GRAM_ERR_
 
 EXPORTS = ("gram_workspace_bytes", "gram_create", "gram_destroy", "gram_unique", "gram_encode_gather",
            "gram_grad_accumulate", "gram_pseudo_target", "gram_gather", "gram_encoder_wgrad",
-           "gram_encoder_wgrad_chunk", "gram_flush",
+           "gram_encoder_wgrad_chunk", "gram_pseudo_loss_grad", "gram_flush",
            "gram_check", "gram_last_error",
            "gram_kernel_count", "gram_kernel_name", "gram_light_max", "gram_profile_enable",
            "gram_profile_read")
@@ -65,6 +65,8 @@ def load():
     L.gram_grad_accumulate.argtypes = [vp, vp, C.c_int64, C.c_int32, vp]
     L.gram_encoder_wgrad_chunk.restype = C.c_int
     L.gram_encoder_wgrad_chunk.argtypes = [vp, vp, vp, C.c_int64, C.c_int64, C.c_int32, vp]
+    L.gram_pseudo_loss_grad.restype = C.c_int
+    L.gram_pseudo_loss_grad.argtypes = [vp, vp, vp, vp, vp, C.c_int64, vp, vp, C.c_int32, vp, vp]
     L.gram_pseudo_target.restype = C.c_int
     L.gram_pseudo_target.argtypes = [vp, vp, vp, vp, vp]
     L.gram_gather.restype = C.c_int
@@ -172,6 +174,11 @@ class Gram:
     def encoder_wgrad_chunk(self, X, dW, first_row, n_rows, accumulate, stream=None):
         self._ck(self._lib.gram_encoder_wgrad_chunk(self._h, _ptr(X), _ptr(dW), int(first_row), int(n_rows),
                                                     1 if accumulate else 0, _stream(stream)))
+
+    def pseudo_loss_grad(self, X, W, ids, Ht, n, R, dW, accumulate=False, loss_dev=None, stream=None):
+        self._ck(self._lib.gram_pseudo_loss_grad(self._h, _ptr(X), _ptr(W), _ptr(ids), _ptr(Ht), int(n),
+                                                 _ptr(R), _ptr(dW), 1 if accumulate else 0,
+                                                 _ptr(loss_dev), _stream(stream)))
 
     def flush(self, uniq_total=None, counts_total=None, G_total=None, u_total_dev=None,
               want_host_u=False, stream=None):

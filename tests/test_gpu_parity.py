@@ -406,6 +406,127 @@ def mm_rows(batches, X, W, items):
     return mm.rows(items)
 
 
+def encoder_batches(X, W_now, items, Ht, splits, vocab_n, max_positions):
+    """gram_pseudo_loss_grad over consecutive batches of `items` (sizes in `splits`), the gradient
+    accumulated across them.  Returns (R rows, per-batch losses, dW)."""
+    import torch
+    from paper_2204_04179_amd import gram
+    from harness import to_dev
+    d_in, d = W_now.shape
+    xw = gram.F32 if X.dtype == np.float32 else gram.BF16
+    g = gram.Gram(gram.make_config(vocab_n, d_in, d, max_positions, 1, 0, 0, xw))
+    Xd, Wd = to_dev(X, torch), to_dev(W_now, torch)
+    items_d = torch.from_numpy(items).cuda()
+    Ht_d = torch.from_numpy(Ht.astype(np.float32)).cuda()
+    R = torch.full((max(1, items.size) + 1, d), float("nan"), device="cuda")
+    dW = torch.full((d_in, d), float("nan"), device="cuda")
+    losses, a = [], 0
+    for i, n in enumerate(splits):
+        loss = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda")
+        g.pseudo_loss_grad(Xd, Wd, items_d[a:a + n], Ht_d[a:a + n], n, R[a:a + n], dW, accumulate=i > 0,
+                           loss_dev=loss)
+        losses.append(float(loss.item()))
+        a += n
+    g.check()
+    assert bool(torch.isnan(R[a:]).all())                       # rows past the batches are untouched
+    out = R[:a].cpu().numpy(), losses, dW.cpu().numpy()
+    g.close()
+    return out
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_encoder_update_in_batches_against_stored_pseudo_targets(bf16):
+    """Algorithm 1 step 4 one content-encoder batch at a time (Eq. 7): regression miss, pseudo-loss
+    and gradient at weights that differ from those the targets came from; ragged batch sizes, a
+    batch of one, an empty batch, the padding item inside a batch."""
+    n, d_in, d = 3000, 64, 40
+    rng = np.random.default_rng(77)
+    _, X, W_now, _ = small_problem(500, 10, n, d_in=d_in, d=d, bf16=bf16)
+    items = np.sort(rng.choice(np.arange(1, n), size=1500, replace=False)).astype(np.int32)
+    items[700] = 0                                              # the padding item, mid-batch
+    Ht = rng.standard_normal((items.size, d)).astype(np.float32)
+    splits = [100, 37, 1, 0, 1000, 362]
+    say(f"encoder batches bf16={bf16}")
+    R, losses, dW = encoder_batches(X, W_now, items, Ht, splits, n, 4000)
+    miss_ref, loss_ref, dW_ref = orc.pseudo_loss_grad(items, X, W_now, Ht.astype(np.float64))
+    dt = wl.BF16 if bf16 else wl.F32
+    assert_close(R, miss_ref, TOL_SUM[dt], "R")
+    assert np.all(R[700] == 0.0)
+    a = 0
+    for n_b, got in zip(splits, losses):
+        ref = orc.pseudo_loss_grad(items[a:a + n_b], X, W_now, Ht[a:a + n_b].astype(np.float64))[1]
+        assert abs(got - ref) <= TOL_SUM[dt] * max(ref, 1e-300), (a, n_b)
+        a += n_b
+    assert abs(sum(losses) - loss_ref) <= TOL_SUM[dt] * loss_ref
+    assert_close(dW, dW_ref, TOL[dt], "dW")
+
+
+def test_encoder_update_batch_with_tiles_for_every_compute_unit():
+    """A batch large enough for the 256x256 contraction kernels on both sides."""
+    n, d_in, d = 80000, 64, 256
+    rng = np.random.default_rng(78)
+    _, X, W_now, _ = small_problem(501, 10, n, d_in=d_in, d=d, bf16=True)
+    items = np.sort(rng.choice(np.arange(0, n), size=70001, replace=False)).astype(np.int32)
+    Ht = rng.standard_normal((items.size, d)).astype(np.float32)
+    say("encoder batch, large")
+    R, losses, dW = encoder_batches(X, W_now, items, Ht, [items.size], n, 80000)
+    miss_ref, loss_ref, dW_ref = orc.pseudo_loss_grad(items, X, W_now, Ht.astype(np.float64))
+    assert_close(R, miss_ref, TOL_SUM[wl.BF16], "R")
+    assert abs(losses[0] - loss_ref) <= TOL_SUM[wl.BF16] * loss_ref
+    assert_close(dW, dW_ref, TOL[wl.BF16], "dW")
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_encoder_update_with_fresh_targets_gives_the_window_gradient(bf16):
+    """Proposition (Eq. 1-3) through the library: the pseudo-targets gram_pseudo_target wrote,
+    regressed at the same weights, give the weight gradient gram_encoder_wgrad took from the
+    buffer, and the end-to-end gradient of the oracle."""
+    import torch
+    from paper_2204_04179_amd import gram
+    from harness import to_dev
+    n, d_in, d = 2500, 32, 64
+    ids, X, W, dH = small_problem(502, 7000, n, d_in=d_in, d=d, bf16=bf16)
+    say(f"proposition through the library bf16={bf16}")
+    out = run_window(X, W, [(ids, dH)], vocab_n=n, pseudo=True)
+    st = out["steps"][0]
+    R, losses, dW = encoder_batches(X, W, st["uniq"], st["Ht"], [500, st["uniq"].size - 500], n, 8000)
+    dt = wl.BF16 if bf16 else wl.F32
+    _, dW_e2e = orc.e2e(ids, X, W, dH)
+    assert_close(dW, dW_e2e, TOL[dt], "dW vs end-to-end")
+    assert_close(dW, out["dW"], TOL[dt], "dW vs gram_encoder_wgrad")
+    assert abs(sum(losses) - st["loss"]) <= 1e-4 * st["loss"]
+    assert_close(R, out["G_total"], 1e-4, "miss vs accumulated gradient")
+
+
+def test_encoder_update_argument_errors():
+    import torch
+    from paper_2204_04179_amd import gram
+    n, d_in, d = 100, 16, 8
+    g = gram.Gram(gram.make_config(n, d_in, d, 50, 1, 0, 100, gram.F32))     # 100 buffer rows
+    X = torch.zeros(n, d_in, device="cuda")
+    W = torch.zeros(d_in, d, device="cuda")
+    ids = torch.arange(0, 100, dtype=torch.int32, device="cuda")
+    Ht = torch.zeros(100, d, device="cuda")
+    R = torch.zeros(100, d, device="cuda")
+    dW = torch.ones(d_in, d, device="cuda")
+
+    def status(fn):
+        with pytest.raises(gram.GramError) as e:
+            fn()
+        return e.value.status
+
+    assert status(lambda: g.pseudo_loss_grad(X, W, ids, Ht, 101, R, dW)) == gram.ERR_ARG      # beyond max(50, 100) rows
+    assert status(lambda: g.pseudo_loss_grad(X, W, ids, Ht, -1, R, dW)) == gram.ERR_ARG
+    assert status(lambda: g.pseudo_loss_grad(X, W, None, Ht, 5, R, dW)) == gram.ERR_ARG
+    g.pseudo_loss_grad(X, W, None, None, 0, None, dW)            # an empty batch overwrites dW with zeros
+    g.check()
+    assert not bool(dW.any())
+    ids[3] = 100                                                 # outside [0, N): latched, no bad access
+    g.pseudo_loss_grad(X, W, ids, Ht, 100, R, dW)
+    assert status(lambda: g.check()) == gram.ERR_RANGE
+    g.close()
+
+
 def test_long_window_reaches_the_whole_vocabulary():
     """Epoch-scale accumulation (Section 4.2 with a long period): 40 steps over a vocabulary of 1,500,
     so the buffer ends up holding every item; counts and rows are sums over all steps."""
