@@ -281,8 +281,11 @@ void oracle_buffer_free(oracle_buffer *b)
 
 int64_t oracle_buffer_size(const oracle_buffer *b) { return b->n; }
 
-int oracle_buffer_add(oracle_buffer *b, const int32_t *uniq, const int32_t *counts,
-                      const double *G, int64_t u)
+/* Merge (uniq ascending, counts, G rows) into the buffer; counts are 64-bit: a window of
+ * epoch length (Section 4.2; the half-epoch and one-epoch periods of the experiments) can see
+ * one item, the padding item above all, more than 2^31 times. */
+int oracle_buffer_add64(oracle_buffer *b, const int32_t *uniq, const int64_t *counts,
+                        const double *G, int64_t u)
 {
     int32_t d = b->d;
     int64_t cap = b->n + u;
@@ -310,6 +313,17 @@ int oracle_buffer_add(oracle_buffer *b, const int32_t *uniq, const int32_t *coun
     free(b->ids); free(b->counts); free(b->G);
     b->ids = ids; b->counts = cnt; b->G = g; b->n = n;
     return 0;
+}
+
+int oracle_buffer_add(oracle_buffer *b, const int32_t *uniq, const int32_t *counts,
+                      const double *G, int64_t u)
+{
+    int64_t *wide = (int64_t *)malloc((size_t)(u ? u : 1) * sizeof *wide);
+    if (!wide) return -1;
+    for (int64_t j = 0; j < u; ++j) wide[j] = counts[j];
+    int rc = oracle_buffer_add64(b, uniq, wide, G, u);
+    free(wide);
+    return rc;
 }
 
 /* Copy the buffer out (ascending ID).  Any pointer may be NULL. */

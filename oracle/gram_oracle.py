@@ -73,6 +73,8 @@ def lib():
         L.oracle_buffer_size.argtypes = [vp]
         L.oracle_buffer_add.restype = C.c_int
         L.oracle_buffer_add.argtypes = [vp, i32p, i32p, f64p, C.c_int64]
+        L.oracle_buffer_add64.restype = C.c_int
+        L.oracle_buffer_add64.argtypes = [vp, i32p, i64p, f64p, C.c_int64]
         L.oracle_buffer_export.restype = C.c_int
         L.oracle_buffer_export.argtypes = [vp, i32p, i64p, f64p]
         L.oracle_buffer_rows.restype = C.c_int
@@ -274,6 +276,16 @@ class GramMulti:
                                        _p(G, C.c_double), uniq.size), "buffer_add")
         self.steps += 1
         return dict(uniq=uniq, inverse=inverse, counts=counts, E=E, H=H, G=G)
+
+    def resume(self, ids, counts, G):
+        """Merge a saved window state (ids ascending, 64-bit counts, gradient rows) into the
+        buffer: a window interrupted after some steps and resumed gives the uninterrupted result."""
+        ids = np.ascontiguousarray(ids, dtype=np.int32).reshape(-1)
+        counts = np.ascontiguousarray(counts, dtype=np.int64).reshape(-1)
+        G = np.ascontiguousarray(G, dtype=np.float64).reshape(ids.size, self.d)
+        assert counts.size == ids.size and np.all(np.diff(ids) > 0)
+        _check(lib().oracle_buffer_add64(self._buf, _p(ids, C.c_int32), _p(counts, C.c_int64),
+                                         _p(G, C.c_double), ids.size), "buffer_add64")
 
     def rows(self, ids):
         """Gradient accumulated so far in the window for each of `ids` (zeros if absent)."""
