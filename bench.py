@@ -344,6 +344,62 @@ def encoder_batches_leg(r, chunk_rows=32768, reps=3):
             "unit": "TFLOP/s", "frac": flops / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
 
 
+def long_window_leg(K=32, windows=3):
+    """Outside the timed steps: an accumulation window of K mini-batches of the kt_multi shape (the
+    regime of the half-epoch / one-epoch periods: the window reaches most of the vocabulary), once
+    with the slot-table buffer and once with the dense one-row-per-ID buffer.  One upstream-gradient
+    matrix is reused for every step (its values do not change the work)."""
+    import torch
+    from paper_2204_04179_amd import gram, workloads as wl
+    w = wl.get("kt_multi", K=K)
+    X, W = wl.features(w), wl.weights(w)
+    ids_np = [wl.ids(w, k).reshape(-1) for k in range(K)]
+    u_total = int(np.unique(np.concatenate(ids_np)).size)
+
+    def dev(a):
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16) if a.dtype == np.uint16 \
+            else torch.from_numpy(a).cuda()
+
+    Xd, Wd, dH = dev(X), dev(W), dev(wl.upstream_grad(w, 0))
+    ids = [dev(a) for a in ids_np]
+    i32 = dict(dtype=torch.int32, device="cuda")
+    uniq, counts, inverse = torch.empty(w.N, **i32), torch.empty(w.N, **i32), torch.empty(w.M, **i32)
+    u_dev, u_t = torch.zeros(1, **i32), torch.zeros(1, **i32)
+    H, dW = torch.empty(w.M, w.d, device="cuda"), torch.empty(w.d_in, w.d, device="cuda")
+    uniq_t, G_t = torch.empty(w.N, **i32), torch.empty(w.N, w.d, device="cuda")
+    out = {"workload": f"kt_multi with K={K}", "items_of_window": u_total, "vocabulary": w.N}
+    for name, layout in (("slot_table", 0), ("dense", 1)):
+        g = gram.Gram(gram.make_config(w.N, w.d_in, w.d, w.M, K, 0, 0, gram.BF16, layout))
+        counts_t = torch.empty(w.N, dtype=torch.int64 if layout else torch.int32, device="cuda")
+
+        def window(end=True):
+            for k in range(K):
+                g.unique(ids[k], uniq, inverse, counts, u_dev)
+                g.encode_gather(Xd, Wd, uniq, inverse, u_dev, w.M, None, H)
+                g.grad_accumulate(dH, w.M, k)
+            if end:
+                g.encoder_wgrad(Xd, dW)
+                (g.flush64 if layout else g.flush)(uniq_t, counts_t, G_t, u_t)
+
+        window()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(windows):
+            window()
+        torch.cuda.synchronize()
+        t_all = (time.perf_counter() - t0) / windows
+        g.profile_enable(None, max_launches=64 * K)
+        window()
+        prof = g.profile_read()
+        g.profile_enable([])
+        end_us = sum(1e3 * v[1] for k, v in prof.items() if k.startswith(("wgrad", "flush")))
+        slot_us = sum(1e3 * prof[k][1] for k in ("slot_count", "slot_emit") if k in prof) / K
+        out[name] = {"us_per_step": 1e6 * t_all / K, "window_end_us": end_us, "slot_kernels_us_per_step": slot_us,
+                     "workspace_MB": gram.workspace_bytes(gram.make_config(w.N, w.d_in, w.d, w.M, K, 0, 0, gram.BF16, layout)) / 1e6}
+        g.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -354,7 +410,7 @@ def main():
                     help="comma-separated workloads reported under 'also' ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-export-G", action="store_true", help="gram_flush without the G_total copy")
-    ap.add_argument("--legs", default="pseudo_target,chunked_wgrad,encoder_batches",
+    ap.add_argument("--legs", default="pseudo_target,chunked_wgrad,encoder_batches,long_window",
                     help="extra measurements outside the timed steps (profiling runs drop chunked_wgrad so that "
                          "the weight-gradient kernel's statistics cover the timed windows only)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -434,6 +490,8 @@ def main():
     out["paper_context"] = "paper: Single-step ~4x, Multi-step up to 146x faster than E2E, whole training runs on A100"
     del r
     torch.cuda.empty_cache()
+    if "long_window" in legs:
+        out["next_rows"]["long_window"] = long_window_leg()
 
     also = []
     for name in [a for a in args.also.split(",") if a]:

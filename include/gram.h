@@ -72,6 +72,17 @@ typedef enum gram_status {
 
 typedef enum gram_dtype { GRAM_F32 = 0, GRAM_BF16 = 1 } gram_dtype;
 
+/* Layout of the persistent gradient buffer.
+ * GRAM_BUFFER_SLOTS: a compact table; an item gets the next free row when the
+ *   window first meets it.  Sized for min(K*M_max, N) items (or u_total_cap).
+ * GRAM_BUFFER_DENSE: one row per ID, G[N,d], like an embedding matrix; no slot
+ *   map, counts are kept in 64 bits.  Meant for windows of epoch length
+ *   (Section 4.2 and the half-epoch / one-epoch alternation periods of the
+ *   experiments), where the window reaches most of the vocabulary: the weight
+ *   gradient then contracts over all N rows (rows of items the window has not
+ *   met are zero).  Needs X and N*d*4 bytes below 4 GiB each for bf16. */
+typedef enum gram_buffer_layout { GRAM_BUFFER_SLOTS = 0, GRAM_BUFFER_DENSE = 1 } gram_buffer_layout;
+
 typedef struct gram_config {
     int32_t vocab_n;       /* N: IDs are valid in [0,N); row r of X belongs to ID r    */
     int32_t d_in;          /* content-feature width; multiple of 8                     */
@@ -81,6 +92,7 @@ typedef struct gram_config {
     int32_t pad_id;        /* padding ID (0 in the paper-shaped workloads); < 0: none  */
     int64_t u_total_cap;   /* rows of the persistent buffer; 0 => min(K*M_max, N)      */
     int32_t xw_dtype;      /* gram_dtype of X and W                                    */
+    int32_t buffer_layout; /* gram_buffer_layout; DENSE: u_total_cap must be 0 or N    */
 } gram_config;
 
 /* Bytes of device memory gram_create would allocate for cfg (0 if cfg is invalid). */
@@ -185,6 +197,8 @@ int gram_encoder_wgrad(gram_ctx* ctx, const void* X, float* dW, void* stream);
  *   accumulate         0: dW is overwritten; otherwise the chunk is added to dW
  * The chunks of a partition of the held rows add up to gram_encoder_wgrad's dW
  * (up to the order of the float32 sums).  No workspace grows with the chunk.
+ * With the dense buffer the rows are the IDs themselves: the chunk is the ID
+ * range [first_row, first_row + n_rows).
  * GRAM_ERR_UNIMPLEMENTED when X or the buffer exceeds 4 GiB. */
 int gram_encoder_wgrad_chunk(gram_ctx* ctx, const void* X, float* dW, int64_t first_row,
                              int64_t n_rows, int32_t accumulate, void* stream);
@@ -229,6 +243,28 @@ int gram_pseudo_loss_grad(gram_ctx* ctx, const void* X, const void* W, const int
  *                                       returns latched device errors */
 int gram_flush(gram_ctx* ctx, int32_t* uniq_total, int32_t* counts_total, float* G_total,
                int32_t* u_total_dev, int32_t* u_total_host, void* stream);
+
+/* gram_flush for the dense buffer with the counts in 64 bits (an epoch-long
+ * window can meet one item, the padding item above all, more than 2^31 times;
+ * gram_flush itself saturates such a count at INT32_MAX).  Same arguments
+ * otherwise; the output buffers need room for N items.
+ * GRAM_ERR_UNIMPLEMENTED for the slot-table layout. */
+int gram_flush64(gram_ctx* ctx, int32_t* uniq_total, int64_t* counts_total, float* G_total,
+                 int32_t* u_total_dev, int32_t* u_total_host, void* stream);
+
+/* Merge a saved window state into the dense buffer, e.g. what gram_flush64
+ * exported before an interruption: counts[j] is added to the count of ids[j]
+ * and, if given, G_rows[j,:] to its gradient row.  A window saved after some
+ * steps, imported and continued ends like the uninterrupted window (Section
+ * 4.2: the buffer is the whole state of a window).
+ *   ids     DEVICE [n] int32    distinct IDs (any order); an ID outside [0,N)
+ *                               latches GRAM_ERR_RANGE and is skipped
+ *   counts  DEVICE [n] int64    G_rows  DEVICE [n,d], nullable
+ * Does not count as a step (the next gram_grad_accumulate keeps its index) but
+ * makes the window non-empty for gram_encoder_wgrad.
+ * GRAM_ERR_UNIMPLEMENTED for the slot-table layout. */
+int gram_window_import(gram_ctx* ctx, const int32_t* ids, const int64_t* counts, const float* G_rows,
+                       int64_t n, void* stream);
 
 /* Synchronise `stream` and return (and clear) any latched device error. */
 int gram_check(gram_ctx* ctx, void* stream);

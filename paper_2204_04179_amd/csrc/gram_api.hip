@@ -69,9 +69,21 @@ const char* validate(const gram_config* cfg, Derived* dv)
     if (cfg->k_steps < 1) return "k_steps must be >= 1";
     if (cfg->pad_id >= cfg->vocab_n) return "pad_id must be < vocab_n (negative = no padding)";
     if (cfg->u_total_cap < 0) return "u_total_cap must be >= 0";
+    if (cfg->buffer_layout != GRAM_BUFFER_SLOTS && cfg->buffer_layout != GRAM_BUFFER_DENSE)
+        return "buffer_layout must be GRAM_BUFFER_SLOTS or GRAM_BUFFER_DENSE";
+    const bool dense = cfg->buffer_layout == GRAM_BUFFER_DENSE;
+    if (dense && cfg->u_total_cap != 0 && cfg->u_total_cap != cfg->vocab_n)
+        return "the dense buffer has one row per ID: u_total_cap must be 0 or vocab_n";
     dv->cap_u = cfg->max_positions < cfg->vocab_n ? cfg->max_positions : cfg->vocab_n;
     int64_t km = (int64_t)cfg->k_steps * cfg->max_positions;
     dv->cap_total = cfg->u_total_cap ? cfg->u_total_cap : (km < cfg->vocab_n ? km : cfg->vocab_n);
+    if (dense) {
+        dv->cap_total = cfg->vocab_n;
+        const int64_t window = ((int64_t)1 << 32) - 16;
+        if (cfg->xw_dtype == GRAM_BF16 && ((int64_t)cfg->vocab_n * cfg->d * 4 >= window ||
+                                           (int64_t)cfg->vocab_n * cfg->d_in * 2 >= window))
+            return "the dense buffer needs X and the N x d buffer below 4 GiB each";
+    }
     if (dv->cap_total >= ((int64_t)1 << 30)) return "persistent buffer rows must be < 2^30";
     dv->cap_chunk = dv->cap_u > dv->cap_total ? dv->cap_u : dv->cap_total;
     dv->n_sort_max = cfg->max_positions > dv->cap_total ? cfg->max_positions : dv->cap_total;
@@ -104,9 +116,12 @@ int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
     int* uniq_ws = (int*)take(dv.cap_u * 4);
     int* seg_slot = (int*)take(dv.cap_u * 4);
     int* long_list = (int*)take(dv.tiles_seg * 4);
-    int* slot_of = (int*)take((int64_t)cfg.vocab_n * 4);
-    int* id_of_slot = (int*)take(dv.cap_total * 4);
-    int* cnt_of_slot = (int*)take(dv.cap_total * 4);
+    const bool dense = cfg.buffer_layout == GRAM_BUFFER_DENSE;
+    int* slot_of = (int*)take(dense ? 1 : (int64_t)cfg.vocab_n * 4);
+    int* id_of_slot = (int*)take(dense ? 1 : dv.cap_total * 4);
+    int* cnt_of_slot = (int*)take(dense ? 1 : dv.cap_total * 4);
+    long long* cnt64 = (long long*)take(dense ? (int64_t)cfg.vocab_n * 8 : 1);
+    int* dense_sums = (int*)take(dense ? ((int64_t)cfg.vocab_n / kScanTile + 2) * 4 : 1);
     float* G = (float*)take(dv.cap_total * d * 4);
     float* E_ws = (float*)take(dv.cap_u * d * 4);
     double* loss_part = (double*)take((dv.cap_chunk / kPseudoRows + 1) * 8);
@@ -117,14 +132,14 @@ int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
     float* wg_partial = (float*)take((int64_t)dv.splits * d_in * d * 4);
     const bool bf = cfg.xw_dtype == GRAM_BF16;
     const int64_t ldt = wgrad_pitch_for(dv.cap_total);
-    uint16_t* XT = (uint16_t*)take(bf ? d_in * ldt * 2 : 1);
-    uint16_t* GT = (uint16_t*)take(bf ? d * ldt * 2 : 1);
+    uint16_t* XT = (uint16_t*)take(bf && !dense ? d_in * ldt * 2 : 1);   // wide-address path only:
+    uint16_t* GT = (uint16_t*)take(bf && !dense ? d * ldt * 2 : 1);      // never taken by a dense buffer
     if (c && base) {
         c->scal = scal; c->keys[0] = keys0; c->keys[1] = keys1; c->vals[0] = vals0; c->vals[1] = vals1;
         c->table = table; c->gtot = gtot; c->tile_sums = tile_sums; c->offsets = offsets;
         c->seg_of_row = seg_of_row; c->uniq_ws = uniq_ws; c->seg_slot = seg_slot;
-        c->long_list = long_list; c->slot_of = slot_of; c->id_of_slot = id_of_slot;
-        c->cnt_of_slot = cnt_of_slot; c->G = G; c->E_ws = E_ws; c->loss_part = loss_part; c->chunk_ids = chunk_ids; c->seg_first = seg_first;
+        c->long_list = long_list; c->slot_of = slot_of; c->id_of_slot = dense ? nullptr : id_of_slot;
+        c->cnt_of_slot = cnt_of_slot; c->cnt64 = cnt64; c->dense_sums = dense_sums; c->G = G; c->E_ws = E_ws; c->loss_part = loss_part; c->chunk_ids = chunk_ids; c->seg_first = seg_first;
         c->seg_last = seg_last; c->Wt = Wt; c->wg_partial = wg_partial;
         c->XT = XT; c->GT = GT; c->ldt = ldt;
     }
@@ -179,6 +194,7 @@ int gram_create(gram_ctx** out, const gram_config* cfg)
     c->cap_u = dv.cap_u;
     c->cap_total = dv.cap_total;
     c->cap_chunk = dv.cap_chunk;
+    c->dense = cfg->buffer_layout == GRAM_BUFFER_DENSE;
     c->key_bits = bits_for(cfg->vocab_n);
     c->wg_splits = dv.splits;
     c->ws_bytes = layout(nullptr, *cfg, dv, nullptr);
@@ -204,7 +220,13 @@ int gram_create(gram_ctx** out, const gram_config* cfg)
         return rc;
     }
     fill_i32(c->scal, 64, 0, nullptr);
-    fill_i32(c->slot_of, cfg->vocab_n, -1, nullptr);
+    if (c->dense) {
+        // rows and counts are zero outside a window; gram_flush restores that for what it exports
+        fill_i32(reinterpret_cast<int*>(c->G), (int64_t)cfg->vocab_n * cfg->d, 0, nullptr);
+        fill_i32(reinterpret_cast<int*>(c->cnt64), (int64_t)cfg->vocab_n * 2, 0, nullptr);
+    } else {
+        fill_i32(c->slot_of, cfg->vocab_n, -1, nullptr);
+    }
     e = hipDeviceSynchronize();
     if (e == hipSuccess) e = hipGetLastError();
     if (e != hipSuccess) {
@@ -347,7 +369,7 @@ int gram_encoder_wgrad(gram_ctx* ctx, const void* X, float* dW, void* stream)
 {
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     if (!c) return GRAM_ERR_ARG;
-    if (c->steps_done < 1)
+    if (c->steps_done < 1 && !c->window_imported)
         return fail(c, GRAM_ERR_SEQUENCE, "gram_encoder_wgrad: no step accumulated in this window");
     if (!X || !dW) return fail(c, GRAM_ERR_ARG, "gram_encoder_wgrad: NULL pointer");
     encoder_wgrad(c, X, dW, static_cast<hipStream_t>(stream), 0, c->cap_total, false);
@@ -359,7 +381,7 @@ int gram_encoder_wgrad_chunk(gram_ctx* ctx, const void* X, float* dW, int64_t fi
 {
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     if (!c) return GRAM_ERR_ARG;
-    if (c->steps_done < 1)
+    if (c->steps_done < 1 && !c->window_imported)
         return fail(c, GRAM_ERR_SEQUENCE, "gram_encoder_wgrad_chunk: no step accumulated in this window");
     if (!X || !dW) return fail(c, GRAM_ERR_ARG, "gram_encoder_wgrad_chunk: NULL pointer");
     if (first_row < 0 || n_rows < 0)
@@ -394,21 +416,60 @@ int gram_pseudo_loss_grad(gram_ctx* ctx, const void* X, const void* W, const int
     return launch_status(c, "gram_pseudo_loss_grad");
 }
 
+static int flush_any(Ctx* c, int32_t* uniq_total, int32_t* counts_total, int64_t* counts64_total,
+                     float* G_total, int32_t* u_total_dev, int32_t* u_total_host, hipStream_t s,
+                     const char* what)
+{
+    if (c->dense)
+        flush_dense(c, uniq_total, counts_total, reinterpret_cast<long long*>(counts64_total), G_total,
+                    u_total_dev, s);
+    else
+        flush_export(c, uniq_total, counts_total, G_total, u_total_dev, s);
+    c->have_unique = false;     // the sort buffers were reused
+    c->steps_done = 0;
+    c->window_positions = 0;
+    c->window_imported = false;
+    if (int rc = launch_status(c, what)) return rc;
+    if (u_total_host) {
+        if (int rc = sync_scalars(c, s, what)) return rc;
+        *u_total_host = c->h_pinned[kSFlushN];
+    }
+    return GRAM_OK;
+}
+
 int gram_flush(gram_ctx* ctx, int32_t* uniq_total, int32_t* counts_total, float* G_total,
                int32_t* u_total_dev, int32_t* u_total_host, void* stream)
 {
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     if (!c) return GRAM_ERR_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    flush_export(c, uniq_total, counts_total, G_total, u_total_dev, s);
-    c->have_unique = false;     // the sort buffers were reused
-    c->steps_done = 0;
-    c->window_positions = 0;
-    if (int rc = launch_status(c, "gram_flush")) return rc;
-    if (u_total_host) {
-        if (int rc = sync_scalars(c, s, "gram_flush")) return rc;
-        *u_total_host = c->h_pinned[kSFlushN];
-    }
+    return flush_any(c, uniq_total, counts_total, nullptr, G_total, u_total_dev, u_total_host,
+                     static_cast<hipStream_t>(stream), "gram_flush");
+}
+
+int gram_flush64(gram_ctx* ctx, int32_t* uniq_total, int64_t* counts_total, float* G_total,
+                 int32_t* u_total_dev, int32_t* u_total_host, void* stream)
+{
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (!c) return GRAM_ERR_ARG;
+    if (!c->dense)
+        return fail(c, GRAM_ERR_UNIMPLEMENTED, "gram_flush64: 64-bit counts are kept by the dense buffer only");
+    return flush_any(c, uniq_total, nullptr, counts_total, G_total, u_total_dev, u_total_host,
+                     static_cast<hipStream_t>(stream), "gram_flush64");
+}
+
+int gram_window_import(gram_ctx* ctx, const int32_t* ids, const int64_t* counts, const float* G_rows,
+                       int64_t n, void* stream)
+{
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (!c) return GRAM_ERR_ARG;
+    if (!c->dense)
+        return fail(c, GRAM_ERR_UNIMPLEMENTED, "gram_window_import: available for the dense buffer only");
+    if (n < 0 || n > c->cfg.vocab_n)
+        return fail(c, GRAM_ERR_ARG, "gram_window_import: n = %lld outside [0, vocab_n]", (long long)n);
+    if (n > 0 && (!ids || !counts)) return fail(c, GRAM_ERR_ARG, "gram_window_import: NULL pointer");
+    import_dense(c, ids, reinterpret_cast<const long long*>(counts), G_rows, n, static_cast<hipStream_t>(stream));
+    if (int rc = launch_status(c, "gram_window_import")) return rc;
+    c->window_imported = true;
     return GRAM_OK;
 }
 

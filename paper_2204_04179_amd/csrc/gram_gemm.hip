@@ -1024,7 +1024,7 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
         const int sb_ = (sl_begin + ((SLAB) < last ? (SLAB) : last)) * WK;                          \
         _Pragma("unroll") for (int t = 0; t < RW / 2; ++t) {                                        \
             const int slot = sb_ + a_row + 2 * t;                                                   \
-            ids_next[t] = (slot < U && slot >= row_begin) ? id_of_slot[slot] : pad_id;              \
+            ids_next[t] = (slot < U && slot >= row_begin) ? (id_of_slot ? id_of_slot[slot] : slot) : pad_id; \
         }                                                                                           \
     }
 #define GRAM_LOAD(SET, SLAB)                                                                        \
@@ -1145,7 +1145,7 @@ __global__ __launch_bounds__(kBlock) void k_wgrad_f32(
     ke += row_begin;
     float acc = 0.f;
     for (int sidx = kb; sidx < ke; ++sidx) {
-        const int id = id_of_slot[sidx];
+        const int id = id_of_slot ? id_of_slot[sidx] : sidx;
         if (id != pad_id) acc = fmaf(X[(int64_t)id * d_in + i], G[(int64_t)sidx * d + c], acc);
     }
     partial[((int64_t)z * d_in + i) * d + c] = acc;
@@ -1183,7 +1183,8 @@ bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t firs
 {
     const int d_in = c->cfg.d_in, d = c->cfg.d;
     int S = c->wg_splits;
-    // the rows contracted over: the persistent buffer, or the caller's (ids, rows) pairs
+    // the rows contracted over: the persistent buffer (id_of_slot is NULL for the dense layout:
+    // the item of row r is r), or the caller's (ids, rows) pairs
     const int64_t cap = other ? other->n_max : c->cap_total;
     const int* ids = other ? other->ids : c->id_of_slot;
     const float* rows = other ? other->rows : c->G;
@@ -1194,7 +1195,7 @@ bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t firs
     if (c->cfg.xw_dtype == GRAM_BF16) {
         // a short window does not need all the ranges: at least 8 slabs of 32 buffer rows each
         // (from the host's bound on the rows in the buffer), still a multiple of 8
-        int64_t rows_bound = other ? cap : (c->window_positions < cap ? c->window_positions : cap);
+        int64_t rows_bound = (other || c->dense) ? cap : (c->window_positions < cap ? c->window_positions : cap);
         if (rows_bound > row_end - row_begin) rows_bound = row_end - row_begin;
         const int64_t slabs_bound = rows_bound / TK + 1;
         int64_t want = slabs_bound / 8 / 8 * 8;

@@ -60,6 +60,7 @@ struct Ctx {
     gram_config cfg;
     int64_t cap_u;        // min(max_positions, vocab_n): upper bound of U per step
     int64_t cap_total;    // rows of the persistent buffer
+    bool dense = false;   // buffer_layout == GRAM_BUFFER_DENSE: row of an item = its ID, no slot map
     int64_t cap_chunk;    // max(cap_u, cap_total): upper bound of a content-encoder batch
     int key_bits;         // bits needed for an ID
 
@@ -82,6 +83,8 @@ struct Ctx {
     float* G = nullptr;         // [cap_total, d] persistent per-item gradient
     float* E_ws = nullptr;      // [cap_u, d] representations when the caller passes E = NULL
     double* loss_part = nullptr; // [cap_chunk / kPseudoRows + 1] per-block sums of the pseudo-loss
+    long long* cnt64 = nullptr; // [N] occurrences of each ID in the window (dense layout only)
+    int* dense_sums = nullptr;  // [N / kScanTile + 1] items per tile of IDs (dense layout only)
     int* chunk_ids = nullptr;   // [cap_chunk] checked copy of a content-encoder batch's item IDs
     float* seg_first = nullptr; // [tiles_seg, d] partial sums of segments entering a tile
     float* seg_last = nullptr;  // [tiles_seg, d] partial sums of segments leaving a tile
@@ -107,6 +110,7 @@ struct Ctx {
     const int* last_uniq = nullptr;      // outputs of the most recent gram_unique (identity only)
     const int* last_inverse = nullptr;
     bool unique_consumed = false;  // the current batch was already accumulated
+    bool window_imported = false;  // a saved state was merged into this window (dense layout)
     int64_t cur_m = 0;
     int32_t steps_done = 0;
     int64_t window_positions = 0;  // positions accumulated in this window: bounds the buffer rows
@@ -165,6 +169,10 @@ void pseudo_miss(Ctx* c, float* R, const float* Ht, int64_t n, double* loss_dev,
 void assign_slots(Ctx* c, hipStream_t s);
 void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s);
 void flush_export(Ctx* c, int* uniq_total, int* counts_total, float* G_total, int* u_total_dev,
+                  hipStream_t s);
+void flush_dense(Ctx* c, int* uniq_total, int* counts_total, long long* counts64_total, float* G_total,
+                 int* u_total_dev, hipStream_t s);
+void import_dense(Ctx* c, const int* ids, const long long* counts, const float* rows, int64_t n,
                   hipStream_t s);
 void fill_i32(int* p, int64_t n, int v, hipStream_t s);
 

@@ -465,10 +465,34 @@ __global__ __launch_bounds__(kSlotSmallThreads) void k_slot_small(
 
 constexpr int64_t kSmallBatch = 8 * kScanTile;   // positions up to which one-block variants are used
 
+// Dense-by-vocabulary buffer: the row of an item is its ID, so there is nothing to hand out; the
+// row is always added to (rows outside a window are zero) and the 64-bit count of the item grows.
+__global__ __launch_bounds__(kBlock) void k_slot_dense(const int* __restrict__ uniq_ws,
+                                                       const int* __restrict__ offsets,
+                                                       int* __restrict__ scal,
+                                                       long long* __restrict__ cnt64,
+                                                       int* __restrict__ seg_slot, int vocab_n)
+{
+    const int j = blockIdx.x * kBlock + threadIdx.x;
+    if (j == 0) {
+        scal[kSLongCount] = 0;
+        scal[kSUTotal] = vocab_n;      // rows the weight gradient contracts over: all of them
+    }
+    if (j >= scal[kSU]) return;
+    const int id = uniq_ws[j];         // distinct within a batch: no two threads meet on a count
+    seg_slot[j] = id;
+    cnt64[id] += offsets[j + 1] - offsets[j];
+}
+
 void assign_slots(Ctx* c, hipStream_t s)
 {
     int64_t bound = c->cur_m < c->cap_u ? c->cur_m : c->cap_u;
     if (bound < 1) bound = 1;
+    if (c->dense) {
+        launch(c, KID_SLOT_EMIT, k_slot_dense, dim3((unsigned)((bound + kBlock - 1) / kBlock)), dim3(kBlock), s,
+               c->uniq_ws, c->offsets, c->scal, c->cnt64, c->seg_slot, c->cfg.vocab_n);
+        return;
+    }
     const int first_step = c->steps_done == 0 ? 1 : 0;
     if (bound <= kSmallBatch) {
         launch(c, KID_SLOT_EMIT, k_slot_small, dim3(1), dim3(kSlotSmallThreads), s, c->uniq_ws, c->offsets, c->slot_of,
@@ -766,6 +790,132 @@ void flush_export(Ctx* c, int* uniq_total, int* counts_total, float* G_total, in
         launch(c, KID_FLUSH_META, k_flush_meta, dim3((unsigned)blocks), dim3(kBlock), s, sorted_ids,
                sorted_slots, c->cnt_of_slot, c->slot_of, uniq_total, counts_total, c->scal, u_total_dev, 0);
     }
+}
+
+// ---- dense-by-vocabulary buffer: end of the window, and resuming one --------------------
+//
+// The items of the window are those with a non-zero count.  Tiles of kScanTile IDs are counted,
+// then every tile finds its place from the counts of the tiles before it and writes its items'
+// IDs (ascending by construction) and counts, clearing the counts; a third kernel copies the
+// items' rows out and zeroes them, which is what makes "always add" correct in the next window.
+
+__global__ __launch_bounds__(kBlock) void k_dense_count(const long long* __restrict__ cnt64,
+                                                        int vocab_n, int* __restrict__ tile_sums)
+{
+    __shared__ int sm[kWavesPerBlock];
+    const int i0 = blockIdx.x * kScanTile + threadIdx.x * 4;
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (i0 + i < vocab_n) s += cnt64[i0 + i] != 0 ? 1 : 0;
+    const int tot = block_sum(s, sm);
+    if (threadIdx.x == 0) tile_sums[blockIdx.x] = tot;
+}
+
+__global__ __launch_bounds__(kBlock) void k_dense_emit(
+    long long* __restrict__ cnt64, int vocab_n, const int* __restrict__ tile_sums,
+    int* __restrict__ list, int* __restrict__ uniq_total, int* __restrict__ counts_total,
+    long long* __restrict__ counts64_total, int* __restrict__ scal, int* __restrict__ u_total_dev)
+{
+    __shared__ int sm[kWavesPerBlock];
+    int pre = 0;
+    for (int t = threadIdx.x; t < (int)blockIdx.x; t += kBlock) pre += tile_sums[t];
+    pre = block_sum(pre, sm);
+    const int i0 = blockIdx.x * kScanTile + threadIdx.x * 4;
+    long long cnt[4];
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        cnt[i] = i0 + i < vocab_n ? cnt64[i0 + i] : 0;
+        s += cnt[i] != 0 ? 1 : 0;
+    }
+    int total;
+    int at = pre + block_excl_scan(s, &total, sm);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (cnt[i] != 0) {
+            list[at] = i0 + i;
+            if (uniq_total) uniq_total[at] = i0 + i;
+            if (counts_total) counts_total[at] = cnt[i] > 0x7fffffffLL ? 0x7fffffff : (int)cnt[i];
+            if (counts64_total) counts64_total[at] = cnt[i];
+            cnt64[i0 + i] = 0;
+            ++at;
+        }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        if (u_total_dev) *u_total_dev = pre + total;
+        scal[kSFlushN] = pre + total;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_dense_rows(const int* __restrict__ list,
+                                                       const int* __restrict__ scal,
+                                                       f32x4* __restrict__ G, int cols4,
+                                                       f32x4* __restrict__ G_total)
+{
+    const int64_t total = (int64_t)scal[kSFlushN] * cols4;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * kBlock) {
+        const int64_t r = i / cols4;
+        const int cc = (int)(i % cols4);
+        f32x4* src = G + (int64_t)list[r] * cols4 + cc;
+        if (G_total) __builtin_nontemporal_store(*src, G_total + i);
+        *src = zero;
+    }
+}
+
+void flush_dense(Ctx* c, int* uniq_total, int* counts_total, long long* counts64_total, float* G_total,
+                 int* u_total_dev, hipStream_t s)
+{
+    const int n = c->cfg.vocab_n;
+    const int tiles = (n + kScanTile - 1) / kScanTile;
+    int* list = c->keys[0];
+    launch(c, KID_FLUSH_META, k_dense_count, dim3(tiles), dim3(kBlock), s, c->cnt64, n, c->dense_sums);
+    launch(c, KID_FLUSH_META, k_dense_emit, dim3(tiles), dim3(kBlock), s, c->cnt64, n, c->dense_sums, list,
+           uniq_total, counts_total, counts64_total, c->scal, u_total_dev);
+    int64_t blocks = ((int64_t)n * (c->cfg.d / 4) + kBlock - 1) / kBlock;
+    if (blocks > 2048) blocks = 2048;
+    launch(c, KID_FLUSH_ROWS, k_dense_rows, dim3((unsigned)blocks), dim3(kBlock), s, list, c->scal,
+           reinterpret_cast<f32x4*>(c->G), c->cfg.d / 4, reinterpret_cast<f32x4*>(G_total));
+}
+
+// A saved window state merged into the buffer: counts and rows of the listed (distinct) items are
+// added.  An ID outside [0, N) latches the range error and is skipped.
+__global__ __launch_bounds__(kBlock) void k_dense_import(const int* __restrict__ ids,
+                                                         const long long* __restrict__ counts,
+                                                         const f32x4* __restrict__ rows, int n,
+                                                         int vocab_n, int cols4,
+                                                         long long* __restrict__ cnt64,
+                                                         f32x4* __restrict__ G, int* __restrict__ scal)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) scal[kSUTotal] = vocab_n;
+    const int64_t total = (int64_t)n * cols4;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * kBlock) {
+        const int64_t r = i / cols4;
+        const int cc = (int)(i % cols4);
+        const int id = ids[r];
+        if (id < 0 || id >= vocab_n) {
+            if (cc == 0) atomicOr(&scal[kSErr], kErrBitRange);
+            continue;
+        }
+        if (cc == 0) cnt64[id] += counts[r];
+        if (rows) {
+            f32x4* dst = G + (int64_t)id * cols4 + cc;
+            *dst = *dst + rows[i];
+        }
+    }
+}
+
+void import_dense(Ctx* c, const int* ids, const long long* counts, const float* rows, int64_t n,
+                  hipStream_t s)
+{
+    int64_t blocks = (n * (c->cfg.d / 4) + kBlock - 1) / kBlock;
+    if (blocks > 2048) blocks = 2048;
+    if (blocks < 1) blocks = 1;
+    launch(c, KID_FLUSH_ROWS, k_dense_import, dim3((unsigned)blocks), dim3(kBlock), s, ids, counts,
+           reinterpret_cast<const f32x4*>(rows), (int)n, c->cfg.vocab_n, c->cfg.d / 4, c->cnt64,
+           reinterpret_cast<f32x4*>(c->G), c->scal);
 }
 
 }  // namespace gram

@@ -22,6 +22,7 @@ STATUS_NAMES = {OK: "GRAM_OK", ERR_ARG: "GRAM_ERR_ARG", ERR_CAPACITY: "GRAM_ERR_
 EXPORTS = ("gram_workspace_bytes", "gram_create", "gram_destroy", "gram_unique", "gram_encode_gather",
            "gram_grad_accumulate", "gram_pseudo_target", "gram_gather", "gram_encoder_wgrad",
            "gram_encoder_wgrad_chunk", "gram_pseudo_loss_grad", "gram_flush",
+           "gram_flush64", "gram_window_import",
            "gram_check", "gram_last_error",
            "gram_kernel_count", "gram_kernel_name", "gram_light_max", "gram_profile_enable",
            "gram_profile_read")
@@ -30,7 +31,7 @@ EXPORTS = ("gram_workspace_bytes", "gram_create", "gram_destroy", "gram_unique",
 class GramConfig(C.Structure):
     _fields_ = [("vocab_n", C.c_int32), ("d_in", C.c_int32), ("d", C.c_int32),
                 ("max_positions", C.c_int64), ("k_steps", C.c_int32), ("pad_id", C.c_int32),
-                ("u_total_cap", C.c_int64), ("xw_dtype", C.c_int32)]
+                ("u_total_cap", C.c_int64), ("xw_dtype", C.c_int32), ("buffer_layout", C.c_int32)]
 
 
 class GramError(RuntimeError):
@@ -75,6 +76,10 @@ def load():
     L.gram_encoder_wgrad.argtypes = [vp, vp, vp, vp]
     L.gram_flush.restype = C.c_int
     L.gram_flush.argtypes = [vp, vp, vp, vp, vp, i32p, vp]
+    L.gram_flush64.restype = C.c_int
+    L.gram_flush64.argtypes = [vp, vp, vp, vp, vp, i32p, vp]
+    L.gram_window_import.restype = C.c_int
+    L.gram_window_import.argtypes = [vp, vp, vp, vp, C.c_int64, vp]
     L.gram_check.restype = C.c_int
     L.gram_check.argtypes = [vp, vp]
     L.gram_last_error.restype = C.c_char_p
@@ -93,9 +98,10 @@ def load():
     return L
 
 
-def make_config(vocab_n, d_in, d, max_positions, k_steps=1, pad_id=0, u_total_cap=0, xw_dtype=BF16):
+def make_config(vocab_n, d_in, d, max_positions, k_steps=1, pad_id=0, u_total_cap=0, xw_dtype=BF16,
+                buffer_layout=0):
     return GramConfig(int(vocab_n), int(d_in), int(d), int(max_positions), int(k_steps), int(pad_id),
-                      int(u_total_cap), int(xw_dtype))
+                      int(u_total_cap), int(xw_dtype), int(buffer_layout))
 
 
 def workspace_bytes(cfg: GramConfig) -> int:
@@ -187,6 +193,18 @@ class Gram:
                                       _ptr(u_total_dev), C.byref(u_host) if want_host_u else None,
                                       _stream(stream)))
         return u_host.value if want_host_u else None
+
+    def flush64(self, uniq_total=None, counts_total=None, G_total=None, u_total_dev=None,
+                want_host_u=False, stream=None):
+        u_host = C.c_int32(-1)
+        self._ck(self._lib.gram_flush64(self._h, _ptr(uniq_total), _ptr(counts_total), _ptr(G_total),
+                                        _ptr(u_total_dev), C.byref(u_host) if want_host_u else None,
+                                        _stream(stream)))
+        return u_host.value if want_host_u else None
+
+    def window_import(self, ids, counts, G_rows, n, stream=None):
+        self._ck(self._lib.gram_window_import(self._h, _ptr(ids), _ptr(counts), _ptr(G_rows), int(n),
+                                              _stream(stream)))
 
     def light_max(self):
         return int(self._lib.gram_light_max())

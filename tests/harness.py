@@ -15,7 +15,8 @@ def to_dev(a, torch):
 
 def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=None, u_total_cap=0,
                keep_H=True, keep_E=True, want_G=True, gram_obj=None, X_dev=None, W_dev=None,
-               pass_E=True, foreign_buffers=False, profile=None, pseudo=False, wgrad_chunks=None):
+               pass_E=True, foreign_buffers=False, profile=None, pseudo=False, wgrad_chunks=None,
+               dense=False, resume=None):
     """batches: list of (ids int32 [m], dH float32 [m,d]).  Returns dict with per-step
     uniq/inverse/counts/E/H and the window's uniq_total/counts_total/G_total/dW.
     pass_E=False calls gram_encode_gather with E = NULL (no "E" in the result);
@@ -24,7 +25,10 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
     (result key "profile": name -> (launches, ms)).  pseudo=True also calls gram_pseudo_target
     and gram_gather after each accumulate (step keys "Ht", "loss", "H_tilde").  wgrad_chunks: list of
     (first_row, n_rows); before the full weight gradient each chunk is taken alone (key "dW_chunks")
-    and all of them accumulated into one matrix (key "dW_chunked")."""
+    and all of them accumulated into one matrix (key "dW_chunked").  dense=True selects the
+    one-row-per-ID buffer and exports through gram_flush64 (counts_total is then int64);
+    resume=(ids, counts int64, G rows float32) is merged into the window with gram_window_import
+    before the first step."""
     import torch
     from paper_2204_04179_amd import gram
 
@@ -32,7 +36,7 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
     xw = gram.F32 if X.dtype == np.float32 else gram.BF16
     K = k_steps or len(batches)
     M_max = max_positions or max(1, max(b[0].size for b in batches))
-    cfg = gram.make_config(vocab_n, d_in, d, M_max, K, pad_id, u_total_cap, xw)
+    cfg = gram.make_config(vocab_n, d_in, d, M_max, K, pad_id, u_total_cap, xw, 1 if dense else 0)
     g = gram_obj or gram.Gram(cfg)
     if profile:
         g.profile_enable(profile, max_launches=256)
@@ -40,6 +44,9 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
     Wd = W_dev if W_dev is not None else to_dev(W, torch)
     cap_u = max(1, min(M_max, vocab_n))
     steps = []
+    if resume is not None:
+        r_ids, r_cnt, r_G = (torch.from_numpy(np.ascontiguousarray(a)).cuda() for a in resume)
+        g.window_import(r_ids, r_cnt, r_G, r_ids.numel())
     for k, (ids, dH) in enumerate(batches):
         m = int(ids.size)
         ids_d = torch.from_numpy(np.ascontiguousarray(ids.reshape(-1))).cuda()
@@ -87,12 +94,12 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
         chunk_out = dict(dW_chunks=[t.cpu().numpy() for t in singles], dW_chunked=acc.cpu().numpy())
     dW = torch.full((d_in, d), float("nan"), device="cuda")
     g.encoder_wgrad(Xd, dW)
-    cap_total = u_total_cap or max(1, min(K * M_max, vocab_n))
+    cap_total = vocab_n if dense else (u_total_cap or max(1, min(K * M_max, vocab_n)))
     ut = torch.full((cap_total,), -7, dtype=torch.int32, device="cuda")
-    ct = torch.full((cap_total,), -7, dtype=torch.int32, device="cuda")
+    ct = torch.full((cap_total,), -7, dtype=torch.int64 if dense else torch.int32, device="cuda")
     Gt = torch.full((cap_total, d), float("nan"), device="cuda") if want_G else None
     utd = torch.zeros(1, dtype=torch.int32, device="cuda")
-    n = g.flush(ut, ct, Gt, utd, want_host_u=True)
+    n = (g.flush64 if dense else g.flush)(ut, ct, Gt, utd, want_host_u=True)
     torch.cuda.synchronize()
     out = dict(steps=steps, dW=dW.cpu().numpy(), U_total=n, **chunk_out, uniq_total=ut[:n].cpu().numpy(),
                counts_total=ct[:n].cpu().numpy(), gram=g, X_dev=Xd, W_dev=Wd)

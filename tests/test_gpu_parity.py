@@ -552,6 +552,133 @@ def test_long_window_reaches_the_whole_vocabulary():
     assert_close(out["dW"], ref["dW"], 1e-5, "dW")
 
 
+# ---------------------------------------------- dense-by-vocabulary buffer (long windows) --
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_dense_buffer_window_matches_oracle(bf16):
+    """One row per ID instead of the slot table (Section 4.2 at epoch scale): every output of a
+    multi-step window, pseudo-targets, weight gradient whole and in ID ranges, and a second window
+    on the same context (the rows of the first must be zero again)."""
+    class W_:                      # name only, for the report line of full_window_check
+        name = f"dense bf16={bf16}"
+    K, n, d_in, d = 3, 1500, 64, 40
+    probs = [small_problem(600 + k, 4000 + 300 * k, n, d_in=d_in, d=d, bf16=bf16) for k in range(K)]
+    X, W = probs[0][1], probs[0][2]
+    batches = [(p[0], p[3]) for p in probs]
+    dt = wl.BF16 if bf16 else wl.F32
+    chunks = [(0, 100), (100, 37), (137, 1000), (1137, 100000), (5000, 3)]
+    say(W_.name)
+    out = run_window(X, W, batches, vocab_n=n, k_steps=K, max_positions=5000, dense=True, pseudo=True,
+                     wgrad_chunks=chunks)
+    assert out["counts_total"].dtype == np.int64
+    ref = full_window_check(W_, batches, X, W, out, TOL[dt], TOL_SUM[dt])
+    mm = orc.GramMulti(X, W)
+    for k, (ids, dH) in enumerate(batches):
+        st_ref = mm.step(ids, dH)
+        Ht_ref, loss_ref = orc.pseudo_target(st_ref["E"], mm.rows(st_ref["uniq"]))
+        assert_close(out["steps"][k]["Ht"], Ht_ref, TOL_SUM[dt], f"Ht step {k}")
+        assert abs(out["steps"][k]["loss"] - loss_ref) <= TOL_SUM[dt] * loss_ref
+    scale = np.abs(ref["dW"]).max()
+    for (a, nrows), got in zip(chunks, out["dW_chunks"]):
+        sel = (ref["uniq"] >= a) & (ref["uniq"] < a + nrows)
+        want = orc.wgrad(ref["uniq"][sel], X, ref["G"][sel], 0) if sel.any() else np.zeros_like(ref["dW"])
+        assert np.abs(got - want).max() <= TOL[dt] * scale, (a, nrows)
+    assert_close(out["dW_chunked"], ref["dW"], TOL[dt], "sum of ID ranges")
+    # second window, other batches first: nothing of the first window may be left in the rows
+    again = run_window(X, W, batches[::-1], vocab_n=n, k_steps=K, max_positions=5000, dense=True,
+                       gram_obj=out["gram"])
+    full_window_check(W_, batches[::-1], X, W, again, TOL[dt], TOL_SUM[dt])
+
+
+def test_dense_buffer_on_a_paper_shaped_multi_step_workload():
+    w = wl.get("kt_multi")
+    X, W = wl.features(w), wl.weights(w)
+    batches = [(wl.ids(w, k).reshape(-1), wl.upstream_grad(w, k)) for k in range(w.K)]
+    say("dense kt_multi")
+    out = run_window(X, W, batches, vocab_n=w.N, k_steps=w.K, dense=True)
+    full_window_check(w, batches, X, W, out, TOL[w.xw_dtype], TOL_SUM[w.xw_dtype])
+
+
+def test_dense_buffer_window_saved_and_resumed_and_wide_counts():
+    """A window exported after two steps (gram_flush64), merged back (gram_window_import) and
+    continued ends like the uninterrupted window; counts beyond 2^31 stay exact in 64 bits and
+    saturate in gram_flush."""
+    import torch
+    from paper_2204_04179_amd import gram
+    K, n, d_in, d = 4, 700, 16, 8
+    probs = [small_problem(700 + k, 2000, n, d_in=d_in, d=d) for k in range(K)]
+    X, W = probs[0][1], probs[0][2]
+    batches = [(p[0], p[3]) for p in probs]
+    say("dense save / resume")
+    first = run_window(X, W, batches[:2], vocab_n=n, k_steps=K, max_positions=2000, dense=True)
+    saved = (first["uniq_total"], first["counts_total"], first["G_total"])
+    second = run_window(X, W, batches[2:], vocab_n=n, k_steps=K, max_positions=2000, dense=True,
+                        gram_obj=first["gram"], resume=saved)
+    mm = orc.GramMulti(X, W)
+    for ids, dH in batches:
+        mm.step(ids, dH)
+    ref = mm.finish()
+    np.testing.assert_array_equal(second["uniq_total"], ref["uniq"])
+    np.testing.assert_array_equal(second["counts_total"], ref["counts"])
+    assert_close(second["G_total"], ref["G"], 1e-5, "G after resume")
+    assert_close(second["dW"], ref["dW"], 1e-5, "dW after resume")
+    # a resumed window alone (no further step) can take its weight gradient and be exported
+    g = first["gram"]
+    big_ids = torch.tensor([0, 7, 699], dtype=torch.int32, device="cuda")
+    big_cnt = torch.tensor([2 ** 31 + 5, 2 ** 40, 3], dtype=torch.int64, device="cuda")
+    rows = torch.arange(3 * d, dtype=torch.float32, device="cuda").reshape(3, d)
+    rows[0] = 0.0                                                  # the padding item's row is zero
+    g.window_import(big_ids, big_cnt, rows, 3)
+    dW = torch.full((d_in, d), float("nan"), device="cuda")
+    g.encoder_wgrad(first["X_dev"], dW)
+    want = orc.wgrad(np.array([0, 7, 699], np.int32), X, rows.cpu().numpy().astype(np.float64), 0)
+    assert_close(dW.cpu().numpy(), want, 1e-5, "dW of an imported window")
+    # one more step on top, then the 64-bit export
+    ids = np.array([7, 0, 0, 9, 0], np.int32)
+    after = run_window(X, W, [(ids, np.ones((5, d), np.float32))], vocab_n=n, k_steps=K, max_positions=2000,
+                       dense=True, gram_obj=g)
+    assert after["uniq_total"].tolist() == [0, 7, 9, 699]
+    assert after["counts_total"].tolist() == [2 ** 31 + 8, 2 ** 40 + 1, 1, 3]
+    np.testing.assert_array_equal(after["G_total"][1], rows[1].cpu().numpy() + 1.0)
+    assert not after["G_total"][0].any()                           # the padding item keeps a zero row ...
+    # ... and the 32-bit export saturates
+    g.window_import(big_ids, big_cnt, None, 3)
+    u = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    c32 = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    assert g.flush(u, c32, None, None, want_host_u=True) == 3
+    assert c32[:3].tolist() == [2 ** 31 - 1, 2 ** 31 - 1, 3] and u[:3].tolist() == [0, 7, 699]
+    assert g.flush64(u, None, None, None, want_host_u=True) == 0   # empty again
+
+
+def test_dense_buffer_argument_errors():
+    import torch
+    from paper_2204_04179_amd import gram
+    with pytest.raises(gram.GramError):
+        gram.Gram(gram.make_config(100, 16, 8, 50, 1, 0, 5, gram.F32, 1))        # one row per ID: no other capacity
+    with pytest.raises(gram.GramError):
+        gram.Gram(gram.make_config(100, 16, 8, 50, 1, 0, 0, gram.F32, 2))        # unknown layout
+    slots = gram.Gram(gram.make_config(100, 16, 8, 50, 1, 0, 0, gram.F32))
+    u = torch.zeros(100, dtype=torch.int32, device="cuda")
+    c64 = torch.zeros(100, dtype=torch.int64, device="cuda")
+    for fn in (lambda: slots.flush64(u, c64), lambda: slots.window_import(u, c64, None, 1)):
+        with pytest.raises(gram.GramError) as e:
+            fn()
+        assert e.value.status == gram.ERR_UNIMPLEMENTED
+    dense = gram.Gram(gram.make_config(100, 16, 8, 50, 1, 0, 0, gram.F32, 1))
+    with pytest.raises(gram.GramError) as e:
+        dense.window_import(u, c64, None, 101)
+    assert e.value.status == gram.ERR_ARG
+    u[3] = 100                                                                   # outside [0, N): skipped, latched
+    c64[:] = 1
+    dense.window_import(u[3:4], c64[3:4], None, 1)
+    with pytest.raises(gram.GramError) as e:
+        dense.check()
+    assert e.value.status == gram.ERR_RANGE
+    assert dense.flush64(u, c64, None, None, want_host_u=True) == 0
+    slots.close()
+    dense.close()
+
+
 def test_flush_variants_and_back_to_back_windows():
     """gram_flush with and without the G export gives the same IDs and counts; a second flush of an
     empty window returns nothing; a context runs window after window with one- and multi-step
