@@ -24,7 +24,9 @@
  * is the end-to-end gradient (Proposition), a central difference of an
  * independently written pseudo-loss matches it, a Newton step from it solves
  * a consistent regression exactly, and it vanishes at the regression's
- * solution.
+ * solution; two-layer encoder: central differences of an independently
+ * written loss, the closed form of an all-active (linear) case, gradients
+ * once per unique item == once per interaction.
  * No function here is "parity unpinned".
  */
 #include <stdint.h>
@@ -403,4 +405,88 @@ int oracle_pseudo_loss_grad(const int32_t *item, int64_t n_items, int32_t vocab_
         }
     *loss = total;
     return oracle_wgrad(item, n_items, vocab_n, pad_id, X, xw_dtype, d_in, d, miss, dW);
+}
+
+/*
+ * A deeper stand-in for the content encoder: two dense layers with a rectifier,
+ *   z_j = X[item[j],:] . W1      a_j = max(z_j, 0)      h_j = a_j . W2,
+ * W1 [d_in, d_hid], W2 [d_hid, d].  Nothing in the method depends on the encoder
+ * being linear (Eq. 4 takes any CE; the Proposition holds for any f); the hidden
+ * activation a_j is what a training framework keeps for the backward pass, once
+ * per listed item: per unique item under GRAM, per interaction end to end (the
+ * memory argument of the section on GPU memory consumption).
+ * A padding item gets zero rows.  A1 (nullable) [n, d_hid], E [n, d].
+ */
+int oracle_mlp_encode(const int32_t *item, int64_t n_items, int32_t vocab_n, int32_t pad_id,
+                      const void *X, const void *W1, const void *W2, int xw_dtype, int32_t d_in,
+                      int32_t d_hid, int32_t d, double *A1, double *E)
+{
+    if (n_items < 0 || d_in <= 0 || d_hid <= 0 || d <= 0) return -1;
+    for (int64_t j = 0; j < n_items; ++j)
+        if (item[j] < 0 || item[j] >= vocab_n) return -2;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < n_items; ++j) {
+        double *a = (double *)calloc((size_t)d_hid, sizeof *a);
+        double *e = E + j * d;
+        for (int32_t c = 0; c < d; ++c) e[c] = 0.0;
+        if (item[j] != pad_id) {
+            for (int32_t k = 0; k < d_in; ++k) {
+                double x = xw_at(X, xw_dtype, (int64_t)item[j] * d_in + k);
+                for (int32_t q = 0; q < d_hid; ++q) a[q] += x * xw_at(W1, xw_dtype, (int64_t)k * d_hid + q);
+            }
+            for (int32_t q = 0; q < d_hid; ++q) {
+                if (a[q] < 0.0) a[q] = 0.0;
+                for (int32_t c = 0; c < d; ++c) e[c] += a[q] * xw_at(W2, xw_dtype, (int64_t)q * d + c);
+            }
+        }
+        if (A1) memcpy(A1 + j * d_hid, a, (size_t)d_hid * sizeof *a);
+        free(a);
+    }
+    return 0;
+}
+
+/*
+ * Backward pass of the same encoder for the listed items, given the gradient
+ * with respect to each item's output, R [n, d] (the accumulated gradient G of
+ * Eq. 6, or the regression miss of Eq. 7):
+ *   dW2 = sum_j a_j^T R_j       da_j = R_j . W2^T       dz_j = da_j where z_j > 0, else 0
+ *   dW1 = sum_j X[item[j],:]^T dz_j
+ * Items are visited in ascending j; a padding item is skipped.
+ */
+int oracle_mlp_grad(const int32_t *item, int64_t n_items, int32_t vocab_n, int32_t pad_id,
+                    const void *X, const void *W1, const void *W2, int xw_dtype, int32_t d_in,
+                    int32_t d_hid, int32_t d, const double *R, double *dW1, double *dW2)
+{
+    if (n_items < 0 || d_in <= 0 || d_hid <= 0 || d <= 0) return -1;
+    for (int64_t j = 0; j < n_items; ++j)
+        if (item[j] < 0 || item[j] >= vocab_n) return -2;
+    memset(dW1, 0, (size_t)d_in * d_hid * sizeof *dW1);
+    memset(dW2, 0, (size_t)d_hid * d * sizeof *dW2);
+    double *z = (double *)malloc((size_t)d_hid * sizeof *z);
+    double *dz = (double *)malloc((size_t)d_hid * sizeof *dz);
+    if (!z || !dz) { free(z); free(dz); return -1; }
+    for (int64_t j = 0; j < n_items; ++j) {
+        if (item[j] == pad_id) continue;
+        const double *r = R + j * d;
+        for (int32_t q = 0; q < d_hid; ++q) z[q] = 0.0;
+        for (int32_t k = 0; k < d_in; ++k) {
+            double x = xw_at(X, xw_dtype, (int64_t)item[j] * d_in + k);
+            for (int32_t q = 0; q < d_hid; ++q) z[q] += x * xw_at(W1, xw_dtype, (int64_t)k * d_hid + q);
+        }
+        for (int32_t q = 0; q < d_hid; ++q) {
+            double a = z[q] > 0.0 ? z[q] : 0.0;
+            double da = 0.0;
+            for (int32_t c = 0; c < d; ++c) {
+                dW2[(int64_t)q * d + c] += a * r[c];
+                da += r[c] * xw_at(W2, xw_dtype, (int64_t)q * d + c);
+            }
+            dz[q] = z[q] > 0.0 ? da : 0.0;
+        }
+        for (int32_t k = 0; k < d_in; ++k) {
+            double x = xw_at(X, xw_dtype, (int64_t)item[j] * d_in + k);
+            for (int32_t q = 0; q < d_hid; ++q) dW1[(int64_t)k * d_hid + q] += x * dz[q];
+        }
+    }
+    free(z); free(dz);
+    return 0;
 }

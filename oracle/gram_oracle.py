@@ -73,6 +73,12 @@ def lib():
         L.oracle_buffer_size.argtypes = [vp]
         L.oracle_buffer_add.restype = C.c_int
         L.oracle_buffer_add.argtypes = [vp, i32p, i32p, f64p, C.c_int64]
+        L.oracle_mlp_encode.restype = C.c_int
+        L.oracle_mlp_encode.argtypes = [i32p, C.c_int64, C.c_int32, C.c_int32, vp, vp, vp, C.c_int, C.c_int32,
+                                        C.c_int32, C.c_int32, f64p, f64p]
+        L.oracle_mlp_grad.restype = C.c_int
+        L.oracle_mlp_grad.argtypes = [i32p, C.c_int64, C.c_int32, C.c_int32, vp, vp, vp, C.c_int, C.c_int32,
+                                      C.c_int32, C.c_int32, f64p, f64p, f64p]
         L.oracle_buffer_add64.restype = C.c_int
         L.oracle_buffer_add64.argtypes = [vp, i32p, i64p, f64p, C.c_int64]
         L.oracle_buffer_export.restype = C.c_int
@@ -232,6 +238,77 @@ def pseudo_loss_grad(item, X, W, Ht, pad_id=0):
                                          _p(miss, C.c_double), C.byref(loss), _p(dW, C.c_double)),
            "pseudo_loss_grad")
     return miss, loss.value, dW
+
+
+def _mlp_args(item, X, W1, W2):
+    item = np.ascontiguousarray(item, dtype=np.int32).reshape(-1)
+    X, W1, W2 = np.ascontiguousarray(X), np.ascontiguousarray(W1), np.ascontiguousarray(W2)
+    dt = _xw_dtype(X)
+    assert _xw_dtype(W1) == dt and _xw_dtype(W2) == dt
+    assert X.shape[1] == W1.shape[0] and W1.shape[1] == W2.shape[0]
+    return item, X, W1, W2, dt
+
+
+def mlp_encode(item, X, W1, W2, pad_id=0):
+    """Two-layer stand-in encoder, h = max(x.W1, 0).W2, once per listed item.
+    Returns float64 (A1 [n, d_hid] hidden activations, E [n, d])."""
+    item, X, W1, W2, dt = _mlp_args(item, X, W1, W2)
+    (d_in, d_hid), d = W1.shape, W2.shape[1]
+    A1 = np.empty((item.size, d_hid), np.float64)
+    E = np.empty((item.size, d), np.float64)
+    _check(lib().oracle_mlp_encode(_p(item, C.c_int32), item.size, X.shape[0], pad_id, X.ctypes.data,
+                                   W1.ctypes.data, W2.ctypes.data, dt, d_in, d_hid, d,
+                                   _p(A1, C.c_double), _p(E, C.c_double)), "mlp_encode")
+    return A1, E
+
+
+def mlp_grad(item, X, W1, W2, R, pad_id=0):
+    """Backward pass of the two-layer encoder for the listed items given dL/dh rows R [n, d].
+    Returns float64 (dW1 [d_in, d_hid], dW2 [d_hid, d])."""
+    item, X, W1, W2, dt = _mlp_args(item, X, W1, W2)
+    (d_in, d_hid), d = W1.shape, W2.shape[1]
+    R = np.ascontiguousarray(R, dtype=np.float64)
+    assert R.shape == (item.size, d)
+    dW1 = np.empty((d_in, d_hid), np.float64)
+    dW2 = np.empty((d_hid, d), np.float64)
+    _check(lib().oracle_mlp_grad(_p(item, C.c_int32), item.size, X.shape[0], pad_id, X.ctypes.data,
+                                 W1.ctypes.data, W2.ctypes.data, dt, d_in, d_hid, d, _p(R, C.c_double),
+                                 _p(dW1, C.c_double), _p(dW2, C.c_double)), "mlp_grad")
+    return dW1, dW2
+
+
+def mlp_e2e(ids, X, W1, W2, dH, pad_id=0):
+    """End-to-end baseline with the two-layer encoder: forward and backward once per interaction
+    (Section 3.3).  Returns float64 (H [M, d], dW1, dW2)."""
+    ids = np.ascontiguousarray(ids, dtype=np.int32).reshape(-1)
+    d = W2.shape[1]
+    _, H = mlp_encode(ids, X, W1, W2, pad_id)
+    dW1, dW2 = mlp_grad(ids, X, W1, W2, np.asarray(dH, np.float32).reshape(-1, d).astype(np.float64), pad_id)
+    return H, dW1, dW2
+
+
+def mlp_gram_single(ids, X, W1, W2, dH, pad_id=0):
+    """Single-step GRAM with the two-layer encoder: encode, keep activations and back-propagate
+    once per unique item (Algorithm 1 with N = 1)."""
+    ids = np.ascontiguousarray(ids, dtype=np.int32).reshape(-1)
+    uniq, inverse, counts = unique(ids, X.shape[0])
+    A1, E = mlp_encode(uniq, X, W1, W2, pad_id)
+    H = gather(E, inverse)
+    G = grad_accumulate(dH, inverse, uniq, pad_id)
+    dW1, dW2 = mlp_grad(uniq, X, W1, W2, G, pad_id)
+    return dict(uniq=uniq, inverse=inverse, counts=counts, A1=A1, E=E, H=H, G=G, dW1=dW1, dW2=dW2)
+
+
+def mlp_pseudo_loss_grad(item, X, W1, W2, Ht, pad_id=0):
+    """One content-encoder batch of Algorithm 1 step 4 with the two-layer encoder: miss = h - Ht at the
+    current weights (zero for padding), pseudo-loss of Eq. 7, and its gradients.
+    Returns float64 (miss, loss, dW1, dW2)."""
+    item = np.ascontiguousarray(item, dtype=np.int32).reshape(-1)
+    _, E = mlp_encode(item, X, W1, W2, pad_id)
+    miss = E - np.ascontiguousarray(Ht, dtype=np.float64)
+    miss[item == pad_id] = 0.0
+    dW1, dW2 = mlp_grad(item, X, W1, W2, miss, pad_id)
+    return miss, 0.5 * float(np.sum(miss * miss)), dW1, dW2
 
 
 def e2e(ids, X, W, dH, pad_id=0):

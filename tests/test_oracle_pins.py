@@ -500,6 +500,92 @@ def test_encoder_batch_handles_bf16_weights_exactly():
         np.testing.assert_array_equal(u, v)
 
 
+# ------------------------------------------------- two-layer stand-in encoder --
+
+def mlp_problem(seed, m=60, n=19, d_in=5, d_hid=7, d=3, bf16=False):
+    rng = np.random.default_rng(seed)
+    ids = rng.integers(1, n, size=m).astype(np.int32)
+    ids[rng.random(m) < 0.15] = 0
+    X = rng.standard_normal((n, d_in)).astype(np.float32)
+    W1 = rng.standard_normal((d_in, d_hid)).astype(np.float32)
+    W2 = rng.standard_normal((d_hid, d)).astype(np.float32)
+    if bf16:
+        X, W1, W2 = (wl.f32_to_bf16_bits(a) for a in (X, W1, W2))
+    dH = rng.standard_normal((m, d)).astype(np.float32)
+    return ids, X, W1, W2, dH
+
+
+def test_mlp_encoder_matches_numpy_and_reduces_to_the_linear_encoder():
+    ids, X, W1, W2, dH = mlp_problem(90)
+    A1, E = orc.mlp_encode(ids, X, W1, W2)
+    live = ids != 0
+    Z = X[ids].astype(np.float64) @ W1.astype(np.float64)
+    np.testing.assert_allclose(A1[live], np.maximum(Z, 0)[live], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(E[live], (np.maximum(Z, 0) @ W2.astype(np.float64))[live], rtol=0, atol=1e-12)
+    assert not E[~live].any() and not A1[~live].any()
+    # all pre-activations positive (non-negative features and first-layer weights): the rectifier is the
+    # identity, the encoder is linear with W = W1 W2, and the gradients have the closed forms below
+    Xp, W1p = np.abs(X) + 0.1, np.abs(W1) + 0.1
+    Xp[0] = 0
+    _, Ep = orc.mlp_encode(ids, Xp, W1p, W2)
+    Wlin = W1p.astype(np.float64) @ W2.astype(np.float64)
+    np.testing.assert_allclose(Ep[live], (Xp[ids].astype(np.float64) @ Wlin)[live], rtol=0, atol=1e-10)
+    R = dH.astype(np.float64)
+    dW1, dW2 = orc.mlp_grad(ids, Xp, W1p, W2, R)
+    Xl, Rl = Xp[ids][live].astype(np.float64), R[live]
+    np.testing.assert_allclose(dW2, (Xl @ W1p.astype(np.float64)).T @ Rl, rtol=0, atol=1e-9)
+    np.testing.assert_allclose(dW1, Xl.T @ (Rl @ W2.astype(np.float64).T), rtol=0, atol=1e-9)
+
+
+def test_mlp_gradients_are_the_derivative_of_an_independent_loss():
+    """L(W1, W2) = sum_p <dH[p], h(ids[p])> written out with numpy; central differences in every
+    entry of W1 and W2 (exact up to rounding where no pre-activation changes sign within the step)."""
+    ids, X, W1, W2, dH = mlp_problem(91)
+    live = ids != 0
+    Xd = X[ids][live].astype(np.float64)
+    Gd = dH[live].astype(np.float64)
+
+    def loss(A, B):
+        return float(np.sum(Gd * (np.maximum(Xd @ A, 0) @ B)))
+
+    A0, B0 = W1.astype(np.float64), W2.astype(np.float64)
+    eps = 2.0 ** -20
+    assert np.abs(Xd @ A0).min() > 100 * eps * np.abs(Xd).max()       # no sign change inside a step
+    _, dW1, dW2 = orc.mlp_e2e(ids, X, W1, W2, dH)
+    for W, dW, first in ((A0, dW1, True), (B0, dW2, False)):
+        for i in range(W.shape[0]):
+            for c in range(W.shape[1]):
+                Wp, Wm = W.copy(), W.copy()
+                Wp[i, c] += eps
+                Wm[i, c] -= eps
+                num = ((loss(Wp, B0) - loss(Wm, B0)) if first else (loss(A0, Wp) - loss(A0, Wm))) / (2 * eps)
+                assert abs(num - dW[i, c]) <= 1e-6 * max(1.0, abs(num)), (first, i, c)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_mlp_gram_equals_end_to_end(bf16):
+    """Section 4.1 / Proposition for an encoder that is not linear: one backward pass per unique item
+    with the summed gradient gives the per-interaction gradients; representations agree exactly."""
+    ids, X, W1, W2, dH = mlp_problem(92, m=200, n=23, bf16=bf16)
+    H, dW1, dW2 = orc.mlp_e2e(ids, X, W1, W2, dH)
+    r = orc.mlp_gram_single(ids, X, W1, W2, dH)
+    np.testing.assert_array_equal(r["H"], H)
+    np.testing.assert_allclose(r["dW1"], dW1, rtol=0, atol=1e-10 * np.abs(dW1).max())
+    np.testing.assert_allclose(r["dW2"], dW2, rtol=0, atol=1e-10 * np.abs(dW2).max())
+    # step 4 as a regression: targets taken at the same weights give the same gradients again
+    Ht, _ = orc.pseudo_target(r["E"], r["G"])
+    miss, loss, gW1, gW2 = orc.mlp_pseudo_loss_grad(r["uniq"], X, W1, W2, Ht)
+    np.testing.assert_allclose(gW1, dW1, rtol=0, atol=1e-9 * np.abs(dW1).max())
+    np.testing.assert_allclose(gW2, dW2, rtol=0, atol=1e-9 * np.abs(dW2).max())
+    assert abs(loss - 0.5 * np.sum(r["G"][r["uniq"] != 0] ** 2)) <= 1e-9 * loss
+    # planted slip: the gate taken from the output gradient instead of the pre-activation
+    A1 = r["A1"]
+    da = r["G"] @ widen(W2).T
+    bad = X[r["uniq"]].astype(np.float64).T @ (da * (da > 0)) if not bf16 else None
+    if bad is not None:
+        assert np.abs(bad - dW1).max() > 1e-3 * np.abs(dW1).max()
+
+
 # -------------------------------------------------- planted-mistake checks --
 
 def test_pins_catch_planted_mistakes():
