@@ -695,7 +695,7 @@ static void launch_gemm_nt(Ctx* c, int kid, const uint16_t* A, int64_t lda, int6
                            const int* row_ids, const int* m_dev, int m_host, int64_t m_bound,
                            const uint16_t* B, int64_t ldb, int64_t b_rows, int n, const int* k_dev,
                            int k_host, int splits, float* C, int64_t ldc, int64_t split_stride,
-                           hipStream_t s, const ScatterArgs* scatter = nullptr)
+                           hipStream_t s, const ScatterArgs* scatter = nullptr, int pad_id = -1)
 {
     static bool attr_set = false;
     if (!attr_set) {
@@ -719,16 +719,16 @@ static void launch_gemm_nt(Ctx* c, int kid, const uint16_t* A, int64_t lda, int6
     if (scatter)
         launch_smem(c, kid, k_gemm_nt_bf16<GATHER, kGemmWaves, GATHER>, dim3((unsigned)blocks),
                     dim3(kGemmWaves * 64), GATHER ? RSMEM_SC : RSMEM, s, A, lda, (uint32_t)a_bytes, row_ids,
-                    m_dev, m_host, B, ldb, (uint32_t)b_bytes, n, k_dev, k_host, splits, c->cfg.pad_id,
+                    m_dev, m_host, B, ldb, (uint32_t)b_bytes, n, k_dev, k_host, splits, pad_id,
                     n_tiles, C, ldc, split_stride, *scatter);
     else if (a_bytes < window && b_bytes < window)
         launch_smem(c, kid, k_gemm_nt_bf16<GATHER, kGemmWaves, false>, dim3((unsigned)blocks),
                     dim3(kGemmWaves * 64), RSMEM, s, A, lda, (uint32_t)a_bytes, row_ids, m_dev, m_host, B,
-                    ldb, (uint32_t)b_bytes, n, k_dev, k_host, splits, c->cfg.pad_id, n_tiles, C, ldc,
+                    ldb, (uint32_t)b_bytes, n, k_dev, k_host, splits, pad_id, n_tiles, C, ldc,
                     split_stride, none);
     else
         launch_smem(c, kid, k_gemm_nt_bf16_dma<GATHER>, dim3((unsigned)blocks), dim3(kBlock), TSMEM, s, A,
-                    lda, row_ids, m_dev, m_host, B, ldb, n, k_dev, k_host, splits, c->cfg.pad_id, n_tiles,
+                    lda, row_ids, m_dev, m_host, B, ldb, n, k_dev, k_host, splits, pad_id, n_tiles,
                     C, ldc, split_stride);
 }
 
@@ -835,43 +835,57 @@ __global__ __launch_bounds__(kBlock) void k_encode_f32(
     E[(int64_t)j * d + c] = acc;
 }
 
+// Wt[cols, rows] = W[rows, cols]^T for a bf16 matrix whose rows count is a multiple of 8.
+void transpose_weight(Ctx* c, const void* W, int rows, int cols, void* Wt, hipStream_t s)
+{
+    // 16-byte row chunks of W^T never straddle its end because rows is a multiple of 8
+    if (cols % 8 == 0) {
+        const int tiles = ((rows + TT - 1) / TT) * ((cols + TT - 1) / TT);
+        launch(c, KID_TRANSPOSE_U16, k_transpose_x, dim3(tiles < 1024 ? tiles : 1024), dim3(kBlock), s,
+               static_cast<const uint16_t*>(W), (const int*)nullptr, c->scal, rows, cols, -1,
+               static_cast<uint16_t*>(Wt), (int64_t)rows);
+    } else {
+        launch(c, KID_TRANSPOSE_U16, k_transpose_u16, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(kBlock), s,
+               static_cast<const uint16_t*>(W), rows, cols, static_cast<uint16_t*>(Wt));
+    }
+}
+
+bool gemm_rows_bf16(Ctx* c, const void* A, int64_t a_rows, int k, const int* row_ids, int pad_id,
+                    const int* n_dev, int64_t rows_max, const void* Bt, int n_out, float* C, hipStream_t s,
+                    float* H_scatter, bool caller_wants_C)
+{
+    if (rows_max <= 0) return false;
+    const int64_t window = (int64_t)1 << 32;
+    const int64_t tile_bound = ((rows_max + TM - 1) / TM) * ((n_out + TN - 1) / TN);
+    if (tile_bound >= c->num_cus && k % TK == 0) {
+        // Fusing the gather pays when there are tiles for every CU: with a handful of tiles the
+        // position stores of a tile run on one CU while a separate gather spreads over all.
+        const bool fuse = H_scatter && a_rows * k * 2 < window;
+        const ScatterArgs sc = {c->offsets, c->perm, H_scatter, (int64_t)n_out, caller_wants_C ? 1 : 0};
+        launch_gemm_nt<true>(c, KID_ENCODE_BF16, static_cast<const uint16_t*>(A), k, a_rows, row_ids, n_dev,
+                             0, rows_max, static_cast<const uint16_t*>(Bt), k, n_out, n_out, nullptr, k, 1,
+                             C, n_out, 0, s, fuse ? &sc : nullptr, pad_id);
+        return fuse;
+    }
+    launch(c, KID_ENCODE_BF16, k_encode_bf16, dim3((n_out + BN - 1) / BN, (unsigned)((rows_max + BM - 1) / BM)),
+           dim3(kBlock), s, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(Bt), row_ids, n_dev,
+           k, n_out, pad_id, C);
+    return false;
+}
+
 bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const int* u_dev,
                     int64_t rows_max, float* E, hipStream_t s, float* H_scatter, bool caller_wants_E)
 {
     if (rows_max <= 0) return false;
     const int d_in = c->cfg.d_in, d = c->cfg.d;
     if (c->cfg.xw_dtype == GRAM_BF16) {
-        // W^T; d_in is a multiple of 8, so 16-byte row chunks of W^T never straddle its end
-        if (d % 8 == 0) {
-            const int tiles = ((d_in + TT - 1) / TT) * ((d + TT - 1) / TT);
-            launch(c, KID_TRANSPOSE_U16, k_transpose_x, dim3(tiles < 1024 ? tiles : 1024), dim3(kBlock), s,
-                   static_cast<const uint16_t*>(W), (const int*)nullptr, c->scal, d_in, d, -1,
-                   static_cast<uint16_t*>(c->Wt), (int64_t)d_in);
-        } else {
-            launch(c, KID_TRANSPOSE_U16, k_transpose_u16, dim3((d + 31) / 32, (d_in + 31) / 32), dim3(kBlock), s,
-                   static_cast<const uint16_t*>(W), d_in, d, static_cast<uint16_t*>(c->Wt));
-        }
-        const int64_t window = (int64_t)1 << 32;
-        const int64_t tile_bound = ((rows_max + TM - 1) / TM) * ((d + TN - 1) / TN);
-        if (tile_bound >= c->num_cus && d_in % TK == 0) {
-            // Fusing the gather pays when there are tiles for every CU: with a handful of tiles the
-            // position stores of a tile run on one CU while a separate gather spreads over all.
-            const bool fuse = H_scatter && (int64_t)c->cfg.vocab_n * d_in * 2 < window;
-            const ScatterArgs sc = {c->offsets, c->perm, H_scatter, (int64_t)d, caller_wants_E ? 1 : 0};
-            launch_gemm_nt<true>(c, KID_ENCODE_BF16, static_cast<const uint16_t*>(X), d_in, c->cfg.vocab_n,
-                                 uniq, u_dev, 0, rows_max, static_cast<const uint16_t*>(c->Wt), d_in, d, d,
-                                 nullptr, d_in, 1, E, d, 0, s, fuse ? &sc : nullptr);
-            return fuse;
-        } else {
-            launch(c, KID_ENCODE_BF16, k_encode_bf16, dim3((d + BN - 1) / BN, (unsigned)((rows_max + BM - 1) / BM)),
-                   dim3(kBlock), s, static_cast<const uint16_t*>(X),
-                   static_cast<const uint16_t*>(c->Wt), uniq, u_dev, d_in, d, c->cfg.pad_id, E);
-        }
-    } else {
-        launch(c, KID_ENCODE_F32, k_encode_f32, dim3((d + 63) / 64, (unsigned)((rows_max + 3) / 4)),
-               dim3(kBlock), s, static_cast<const float*>(X), static_cast<const float*>(W), uniq, u_dev,
-               d_in, d, c->cfg.pad_id, E);
+        transpose_weight(c, W, d_in, d, c->Wt, s);
+        return gemm_rows_bf16(c, X, c->cfg.vocab_n, d_in, uniq, c->cfg.pad_id, u_dev, rows_max, c->Wt, d, E, s,
+                              H_scatter, caller_wants_E);
     }
+    launch(c, KID_ENCODE_F32, k_encode_f32, dim3((d + 63) / 64, (unsigned)((rows_max + 3) / 4)),
+           dim3(kBlock), s, static_cast<const float*>(X), static_cast<const float*>(W), uniq, u_dev,
+           d_in, d, c->cfg.pad_id, E);
     return false;
 }
 
@@ -1168,8 +1182,13 @@ __global__ __launch_bounds__(kBlock) void k_wgrad_reduce(const float4* __restric
 
 int wgrad_splits_for(const gram_config& cfg)
 {
-    if (cfg.xw_dtype != GRAM_BF16) return 4;
-    const int tiles = ((cfg.d_in + TM - 1) / TM) * ((cfg.d + TN - 1) / TN);
+    return wgrad_splits_dims(cfg.d_in, cfg.d, cfg.xw_dtype == GRAM_BF16);
+}
+
+int wgrad_splits_dims(int d_in, int d, bool bf16)
+{
+    if (!bf16) return 4;
+    const int tiles = ((d_in + TM - 1) / TM) * ((d + TN - 1) / TN);
     int s = 256 / tiles / 8 * 8;      // one block per CU; a multiple of 8 (one K range per XCD)
     if (s < 8) s = 8;
     if (s > 64) s = 64;
@@ -1181,8 +1200,11 @@ int64_t wgrad_pitch_for(int64_t cap_total) { return (cap_total + TT - 1) / TT * 
 bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t first_row, int64_t n_rows,
                    bool accumulate, const WgradRows* other)
 {
-    const int d_in = c->cfg.d_in, d = c->cfg.d;
-    int S = c->wg_splits;
+    const int d_in = other && other->d_in ? other->d_in : c->cfg.d_in;
+    const int d = other && other->d ? other->d : c->cfg.d;
+    const int64_t x_rows = other && other->x_rows ? other->x_rows : c->cfg.vocab_n;
+    const int pad_id = other && other->d_in ? other->pad_id : c->cfg.pad_id;
+    int S = other && other->d_in ? wgrad_splits_dims(d_in, d, c->cfg.xw_dtype == GRAM_BF16) : c->wg_splits;
     // the rows contracted over: the persistent buffer (id_of_slot is NULL for the dense layout:
     // the item of row r is r), or the caller's (ids, rows) pairs
     const int64_t cap = other ? other->n_max : c->cap_total;
@@ -1201,7 +1223,7 @@ bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t firs
         int64_t want = slabs_bound / 8 / 8 * 8;
         if (want < 8) want = 8;
         if (want < S) S = (int)want;
-        const int64_t x_bytes = (int64_t)c->cfg.vocab_n * d_in * 2, g_bytes = cap * d * 4;
+        const int64_t x_bytes = x_rows * d_in * 2, g_bytes = cap * d * 4;
         const int64_t window = ((int64_t)1 << 32) - 16;
         if (x_bytes < window && g_bytes < window) {
             static bool attr_set = false;
@@ -1213,7 +1235,7 @@ bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t firs
             const int tiles = ((d_in + 255) / 256) * ((d + 255) / 256);
             launch_smem(c, KID_WGRAD_BF16, k_wgrad_tn_bf16<kWgradWaves>, dim3((unsigned)(tiles * S)), dim3(kWgradWaves * 64), WSMEM, s,
                         static_cast<const uint16_t*>(X), (uint32_t)x_bytes, ids, rows, (uint32_t)g_bytes,
-                        rows_dev, d_in, d, c->cfg.pad_id, S, c->wg_partial, row_begin, row_end);
+                        rows_dev, d_in, d, pad_id, S, c->wg_partial, row_begin, row_end);
         } else {
             if (chunked) return false;      // the transposed copies cover the whole buffer only
             // operands beyond the 4 GiB buffer window: transposed bf16 copies + the NT kernel
@@ -1226,7 +1248,7 @@ bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t firs
         }
     } else {
         launch(c, KID_WGRAD_F32, k_wgrad_f32, dim3((d + 63) / 64, (d_in + 3) / 4, S), dim3(kBlock), s,
-               static_cast<const float*>(X), ids, rows, rows_dev, d_in, d, c->cfg.pad_id, S,
+               static_cast<const float*>(X), ids, rows, rows_dev, d_in, d, pad_id, S,
                c->wg_partial, row_begin, row_end);
     }
     const int64_t n4 = (int64_t)d_in * d / 4;

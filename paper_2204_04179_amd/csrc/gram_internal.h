@@ -184,11 +184,16 @@ bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
                     int64_t rows_max, float* E, hipStream_t s, float* H_scatter, bool caller_wants_E);
 // Rows the weight gradient contracts over when they are not the persistent buffer's: row j pairs
 // item ids[j] with rows[j,:] (float32, d columns); *n_dev rows are held, at most n_max.
+// With d_in != 0 the contraction also takes its shape from here instead of the context: the
+// matrix passed as X is [x_rows, d_in] (bf16), rows[] has d columns, dW is [d_in, d]; ids == NULL
+// pairs rows[j] with row j of X; pad_id < 0: no row is skipped.
 struct WgradRows {
     const int* ids;
     const float* rows;
     const int* n_dev;
     int64_t n_max;
+    int64_t x_rows = 0;
+    int d_in = 0, d = 0, pad_id = -1;
 };
 // Weight gradient over the buffer rows [first_row, first_row + n_rows) (clipped to the rows held),
 // or over the rows of `other`, written to dW or added to it.  Returns false if the range is a
@@ -196,6 +201,15 @@ struct WgradRows {
 bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t first_row, int64_t n_rows,
                    bool accumulate, const WgradRows* other = nullptr);
 int wgrad_splits_for(const gram_config& cfg);
+int wgrad_splits_dims(int d_in, int d, bool bf16);
+// bf16 helpers the two-layer encoder shares with the linear one.
+void transpose_weight(Ctx* c, const void* W, int rows, int cols, void* Wt, hipStream_t s);
+// C[j,:] = A[row_ids[j],:k] . Bt^T for j < *n_dev (A bf16 [a_rows, k], Bt bf16 [n_out, k], C float32
+// [., n_out]); a row whose ID equals pad_id is zero.  Same return value and fused-gather rule as
+// encode_forward.
+bool gemm_rows_bf16(Ctx* c, const void* A, int64_t a_rows, int k, const int* row_ids, int pad_id,
+                    const int* n_dev, int64_t rows_max, const void* Bt, int n_out, float* C, hipStream_t s,
+                    float* H_scatter, bool caller_wants_C);
 int64_t wgrad_pitch_for(int64_t cap_total);
 
 }  // namespace gram
