@@ -400,6 +400,67 @@ def long_window_leg(K=32, windows=3):
     return out
 
 
+def mlp_leg(r, d_hid=1024, chunk_rows=32768, windows=3):
+    """Outside the timed steps: the same windows with the two-layer stand-in encoder
+    (h = max(x.W1, 0).W2): forward with the hidden activations kept once per unique item, accumulate,
+    and at the window's end the backward pass over the window's items in content-encoder batches."""
+    import torch
+    from paper_2204_04179_amd import gram, workloads as wl
+    w = r.w
+    rng = np.random.default_rng(12345)
+    def bf(a):
+        b = wl.f32_to_bf16_bits(a.astype(np.float32))
+        return torch.from_numpy(b.view(np.int16)).cuda().view(torch.bfloat16)
+    W1 = bf(rng.standard_normal((w.d_in, d_hid)) / np.sqrt(w.d_in))
+    W2 = bf(rng.standard_normal((d_hid, w.d)) / np.sqrt(d_hid))
+    g = gram.Gram(gram.make_config(w.N, w.d_in, w.d, w.M, w.K, 0, 0, gram.BF16, 0, d_hid))
+    cap_u = min(w.M, w.N)
+    A1 = torch.empty(cap_u, d_hid, dtype=torch.bfloat16, device="cuda")
+    dW1 = torch.empty(w.d_in, d_hid, device="cuda")
+    dW2 = torch.empty(d_hid, w.d, device="cuda")
+    work = torch.empty(g.mlp_batch_bytes(chunk_rows), dtype=torch.uint8, device="cuda")
+    G_t = r.G_t if r.G_t is not None else torch.empty(r.uniq_t.numel(), w.d, device="cuda")
+    names = ["encode_bf16", "mlp_act", "mlp_gate", "wgrad_bf16", "wgrad_reduce", "gather_heavy", "transpose_w"]
+
+    def window(backward=True):
+        for k in range(w.K):
+            g.unique(r.ids[k], r.uniq, r.inverse, r.counts, r.u_dev)
+            g.mlp_encode_gather(r.X, W1, W2, r.uniq, r.inverse, r.u_dev, r.M, A1, None, r.H)
+            g.grad_accumulate(r.dH[k], r.M, k)
+        g.flush(r.uniq_t, r.counts_t, G_t, r.u_t)
+        if backward:
+            for i, a in enumerate(range(0, r.U_total, chunk_rows)):
+                n = min(chunk_rows, r.U_total - a)
+                g.mlp_backward(r.X, W1, W2, r.uniq_t[a:a + n], G_t[a:a + n], None, n, work, dW1, dW2, i > 0)
+
+    window()
+    torch.cuda.synchronize()
+    t = {}
+    for key, bw in (("with_backward", True), ("forward_only", False)):
+        t0 = time.perf_counter()
+        for _ in range(windows):
+            window(bw)
+        torch.cuda.synchronize()
+        t[key] = (time.perf_counter() - t0) / windows
+    g.profile_enable(names, max_launches=4096)
+    window()
+    prof = g.profile_read()
+    g.profile_enable([])
+    g.close()
+    U_avg = sum(s["U"] for s in r.stats) / len(r.stats)
+    fwd_flops = 2 * U_avg * d_hid * (w.d_in + w.d)
+    bwd_flops = 2 * r.U_total * d_hid * (2 * w.d_in + 2 * w.d)       # recompute z, dW2, dA, dW1
+    us_bwd = 1e6 * (t["with_backward"] - t["forward_only"])
+    return {"d_hidden": d_hid, "chunk_rows": chunk_rows,
+            "us_per_step_forward_accumulate": 1e6 * t["forward_only"] / w.K,
+            "us_per_window_backward": us_bwd,
+            "backward_tflops": bwd_flops / (us_bwd * 1e-6) / 1e12,
+            "forward_flops_per_step": fwd_flops,
+            "kernels_us_per_window": {k: round(1e3 * v[1], 1) for k, v in prof.items()},
+            "activation_bytes_per_step": {"per_unique_item": int(U_avg * d_hid * 2), "per_interaction": int(w.M * d_hid * 2)},
+            "backward_workspace_bytes": {"per_batch": int(work.numel()), "whole_window_at_once": int(work.numel() / chunk_rows * r.U_total)}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -410,7 +471,7 @@ def main():
                     help="comma-separated workloads reported under 'also' ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-export-G", action="store_true", help="gram_flush without the G_total copy")
-    ap.add_argument("--legs", default="pseudo_target,chunked_wgrad,encoder_batches,long_window",
+    ap.add_argument("--legs", default="pseudo_target,chunked_wgrad,encoder_batches,mlp,long_window",
                     help="extra measurements outside the timed steps (profiling runs drop chunked_wgrad so that "
                          "the weight-gradient kernel's statistics cover the timed windows only)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -487,6 +548,8 @@ def main():
         out["next_rows"]["chunked_wgrad"] = chunked_wgrad_leg(r)
     if "encoder_batches" in legs and w.xw_dtype != wl.F32:
         out["next_rows"]["encoder_batches"] = encoder_batches_leg(r)
+    if "mlp" in legs and w.xw_dtype != wl.F32:
+        out["next_rows"]["mlp_encoder"] = mlp_leg(r)
     out["paper_context"] = "paper: Single-step ~4x, Multi-step up to 146x faster than E2E, whole training runs on A100"
     del r
     torch.cuda.empty_cache()

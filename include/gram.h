@@ -93,6 +93,9 @@ typedef struct gram_config {
     int64_t u_total_cap;   /* rows of the persistent buffer; 0 => min(K*M_max, N)      */
     int32_t xw_dtype;      /* gram_dtype of X and W                                    */
     int32_t buffer_layout; /* gram_buffer_layout; DENSE: u_total_cap must be 0 or N    */
+    int32_t d_hidden;      /* 0: linear stand-in encoder.  > 0: width of the hidden
+                              layer of the two-layer stand-in (gram_mlp_*; bf16 only,
+                              d_hidden and d multiples of 8)                           */
 } gram_config;
 
 /* Bytes of device memory gram_create would allocate for cfg (0 if cfg is invalid). */
@@ -152,6 +155,49 @@ int gram_encode_gather(gram_ctx* ctx, const void* X, const void* W, const int32_
  * No float atomics are used: every buffer row has one writer and a fixed
  * summation order. */
 int gram_grad_accumulate(gram_ctx* ctx, const float* dH, int64_t m, int32_t step_k, void* stream);
+
+/* ---- A deeper stand-in encoder -----------------------------------------------
+ * Eq. 4 takes any content encoder and the Proposition (Eq. 1-3) holds for any f.
+ * With cfg.d_hidden > 0 the context also offers a two-layer encoder
+ *   z = x . W1      a = max(z, 0)      h = a . W2,     W1 [d_in, d_hidden], W2 [d_hidden, d]
+ * so that what the paper's section on GPU memory consumption is about can be
+ * measured: the activation a, which the backward pass needs, is kept once per
+ * unique item (bf16) instead of once per interaction.  gram_unique,
+ * gram_grad_accumulate, gram_pseudo_target, gram_gather and gram_flush are used as
+ * with the linear encoder; the two calls below replace gram_encode_gather and the
+ * weight-gradient calls.  bf16 features and weights only.
+ *
+ * gram_mlp_encode_gather: Algorithm 1 step 1 with the two-layer encoder.
+ *   W1, W2   DEVICE bf16       A1  DEVICE [>= U, d_hidden] bf16, nullable  out: the
+ *                              hidden activations of the unique items (zero row for
+ *                              the padding ID); other arguments as gram_encode_gather
+ * gram_mlp_batch_bytes: bytes of `work` that gram_mlp_backward needs for n items
+ *   (n * (6 d_hidden + 6 d), each of four parts rounded up to 256 bytes).
+ * gram_mlp_backward: Algorithm 1 step 4 for one content-encoder batch of items.
+ *   The activations are recomputed from the CURRENT weights (W1), so the call
+ *   keeps nothing between batches but the caller's `work`.  Exactly one of
+ *     G_rows  DEVICE [n,d]  dL/dh of each listed item (rows of gram_flush's
+ *                           G_total: by the Proposition the result is the
+ *                           end-to-end gradient when the weights have not moved)
+ *     Ht      DEVICE [n,d]  stored pseudo-targets: the miss h - Ht at the current
+ *                           weights is back-propagated and loss_dev (nullable)
+ *                           receives the pseudo-loss of Eq. 7
+ *   is given.  dW2 (+)= sum_j a_j^T r_j;  dz_j = (r_j . W2^T) where a_j > 0;
+ *   dW1 (+)= sum_j X[ids[j],:]^T dz_j.  r and dz are rounded to bf16 as they enter
+ *   the matrix cores.
+ *   ids      DEVICE [n] int32 (range-checked like gram_pseudo_loss_grad's)
+ *   n        0 <= n <= max(min(max_positions, N), rows of the buffer)
+ *   work     DEVICE, gram_mlp_batch_bytes(ctx, n) bytes, 256-byte aligned
+ *   dW1      DEVICE [d_in, d_hidden]   dW2  DEVICE [d_hidden, d]   float32 out;
+ *            accumulate = 0 overwrites both, else adds
+ * GRAM_ERR_UNIMPLEMENTED when X or a batch matrix exceeds 4 GiB. */
+int gram_mlp_encode_gather(gram_ctx* ctx, const void* X, const void* W1, const void* W2,
+                           const int32_t* uniq, const int32_t* inverse, const int32_t* u_dev, int64_t m,
+                           void* A1, float* E, float* H, void* stream);
+int64_t gram_mlp_batch_bytes(const gram_ctx* ctx, int64_t n);
+int gram_mlp_backward(gram_ctx* ctx, const void* X, const void* W1, const void* W2, const int32_t* ids,
+                      const float* G_rows, const float* Ht, int64_t n, void* work, float* dW1,
+                      float* dW2, int32_t accumulate, double* loss_dev, void* stream);
 
 /* Pseudo-targets of the items of the current batch (Algorithm 1 step 3, Eq. 6:
  * the representation is moved by one plain gradient step of rate 1, Section 4.3)

@@ -12,7 +12,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libgram.so")
-SOURCES = ["gram_api.hip", "gram_sort.hip", "gram_stream.hip", "gram_gemm.hip"]
+SOURCES = ["gram_api.hip", "gram_sort.hip", "gram_stream.hip", "gram_gemm.hip", "gram_mlp.hip"]
 HEADERS = [os.path.join(CSRC, "gram_internal.h"), os.path.join(ROOT, "include", "gram.h")]
 ARCH = "gfx950"
 FLAGS = [

@@ -71,6 +71,9 @@ const char* validate(const gram_config* cfg, Derived* dv)
     if (cfg->u_total_cap < 0) return "u_total_cap must be >= 0";
     if (cfg->buffer_layout != GRAM_BUFFER_SLOTS && cfg->buffer_layout != GRAM_BUFFER_DENSE)
         return "buffer_layout must be GRAM_BUFFER_SLOTS or GRAM_BUFFER_DENSE";
+    if (cfg->d_hidden < 0) return "d_hidden must be >= 0 (0 = linear encoder)";
+    if (cfg->d_hidden > 0 && (cfg->xw_dtype != GRAM_BF16 || cfg->d_hidden % 8 != 0 || cfg->d % 8 != 0))
+        return "the two-layer encoder needs bf16 features and d_hidden, d multiples of 8";
     const bool dense = cfg->buffer_layout == GRAM_BUFFER_DENSE;
     if (dense && cfg->u_total_cap != 0 && cfg->u_total_cap != cfg->vocab_n)
         return "the dense buffer has one row per ID: u_total_cap must be 0 or vocab_n";
@@ -129,7 +132,20 @@ int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
     float* seg_first = (float*)take(dv.tiles_seg * d * 4);
     float* seg_last = (float*)take(dv.tiles_seg * d * 4);
     void* Wt = take(cfg.xw_dtype == GRAM_BF16 ? d * d_in * 2 : 1);
-    float* wg_partial = (float*)take((int64_t)dv.splits * d_in * d * 4);
+    const int64_t dh = cfg.d_hidden;
+    int64_t partial_elems = (int64_t)dv.splits * d_in * d;
+    if (dh > 0) {
+        const int64_t bottom = (int64_t)wgrad_splits_dims((int)d_in, (int)dh, true) * d_in * dh;
+        const int64_t top = (int64_t)wgrad_splits_dims((int)dh, (int)d, true) * dh * d;
+        if (bottom > partial_elems) partial_elems = bottom;
+        if (top > partial_elems) partial_elems = top;
+    }
+    float* wg_partial = (float*)take(partial_elems * 4);
+    void* W1t = take(dh > 0 ? dh * d_in * 2 : 1);
+    void* W2t = take(dh > 0 ? d * dh * 2 : 1);
+    float* Z_ws = (float*)take(dh > 0 ? dv.cap_u * dh * 4 : 1);
+    void* A1_ws = take(dh > 0 ? dv.cap_u * dh * 2 : 1);
+    int* iota = (int*)take(dh > 0 ? dv.cap_chunk * 4 : 1);
     const bool bf = cfg.xw_dtype == GRAM_BF16;
     const int64_t ldt = wgrad_pitch_for(dv.cap_total);
     uint16_t* XT = (uint16_t*)take(bf && !dense ? d_in * ldt * 2 : 1);   // wide-address path only:
@@ -142,6 +158,7 @@ int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
         c->cnt_of_slot = cnt_of_slot; c->cnt64 = cnt64; c->dense_sums = dense_sums; c->G = G; c->E_ws = E_ws; c->loss_part = loss_part; c->chunk_ids = chunk_ids; c->seg_first = seg_first;
         c->seg_last = seg_last; c->Wt = Wt; c->wg_partial = wg_partial;
         c->XT = XT; c->GT = GT; c->ldt = ldt;
+        c->W1t = W1t; c->W2t = W2t; c->Z_ws = Z_ws; c->A1_ws = A1_ws; c->iota = iota;
     }
     return off;
 }
@@ -220,6 +237,7 @@ int gram_create(gram_ctx** out, const gram_config* cfg)
         return rc;
     }
     fill_i32(c->scal, 64, 0, nullptr);
+    if (cfg->d_hidden > 0) iota_i32(c->iota, c->cap_chunk, nullptr);
     if (c->dense) {
         // rows and counts are zero outside a window; gram_flush restores that for what it exports
         fill_i32(reinterpret_cast<int*>(c->G), (int64_t)cfg->vocab_n * cfg->d, 0, nullptr);
@@ -317,6 +335,67 @@ int gram_encode_gather(gram_ctx* ctx, const void* X, const void* W, const int32_
     else
         gather_rows(c, Ep, inverse, m, H, s);
     return launch_status(c, "gram_encode_gather");
+}
+
+int gram_mlp_encode_gather(gram_ctx* ctx, const void* X, const void* W1, const void* W2, const int32_t* uniq,
+                           const int32_t* inverse, const int32_t* u_dev, int64_t m, void* A1, float* E,
+                           float* H, void* stream)
+{
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (!c) return GRAM_ERR_ARG;
+    if (c->cfg.d_hidden <= 0)
+        return fail(c, GRAM_ERR_ARG, "gram_mlp_encode_gather: the context was created with d_hidden = 0");
+    if (!c->have_unique)
+        return fail(c, GRAM_ERR_SEQUENCE, "gram_mlp_encode_gather: no preceding gram_unique");
+    if (m != c->cur_m)
+        return fail(c, GRAM_ERR_ARG, "gram_mlp_encode_gather: m = %lld differs from the last gram_unique (%lld)",
+                    (long long)m, (long long)c->cur_m);
+    if (m > 0 && (!X || !W1 || !W2 || !uniq || !inverse || !H))
+        return fail(c, GRAM_ERR_ARG, "gram_mlp_encode_gather: NULL pointer");
+    if ((int64_t)c->cfg.vocab_n * c->cfg.d_in * 2 >= ((int64_t)1 << 32) - 16)
+        return fail(c, GRAM_ERR_UNIMPLEMENTED, "gram_mlp_encode_gather: not available when X exceeds 4 GiB");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (m == 0) return GRAM_OK;
+    float* Ep = E ? E : c->E_ws;
+    const int* up = u_dev ? u_dev : c->scal + kSU;
+    const bool own = uniq == c->last_uniq && inverse == c->last_inverse;
+    if (mlp_forward(c, X, W1, W2, uniq, up, m < c->cap_u ? m : c->cap_u, A1, Ep, s, own ? H : nullptr, E != nullptr))
+        gather_heavy(c, Ep, m, H, s);
+    else
+        gather_rows(c, Ep, inverse, m, H, s);
+    return launch_status(c, "gram_mlp_encode_gather");
+}
+
+int64_t gram_mlp_batch_bytes(const gram_ctx* ctx, int64_t n)
+{
+    const Ctx* c = reinterpret_cast<const Ctx*>(ctx);
+    if (!c || c->cfg.d_hidden <= 0 || n < 0) return 0;
+    return mlp_batch_bytes(c, n);
+}
+
+int gram_mlp_backward(gram_ctx* ctx, const void* X, const void* W1, const void* W2, const int32_t* ids,
+                      const float* G_rows, const float* Ht, int64_t n, void* work, float* dW1, float* dW2,
+                      int32_t accumulate, double* loss_dev, void* stream)
+{
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (!c) return GRAM_ERR_ARG;
+    if (c->cfg.d_hidden <= 0)
+        return fail(c, GRAM_ERR_ARG, "gram_mlp_backward: the context was created with d_hidden = 0");
+    if (n < 0 || n > c->cap_chunk)
+        return fail(c, GRAM_ERR_ARG, "gram_mlp_backward: n = %lld outside [0, %lld]", (long long)n,
+                    (long long)c->cap_chunk);
+    if ((G_rows != nullptr) == (Ht != nullptr) && n > 0)
+        return fail(c, GRAM_ERR_ARG, "gram_mlp_backward: give exactly one of G_rows and Ht");
+    if (!X || !W1 || !W2 || !dW1 || !dW2 || (n > 0 && (!ids || !work)))
+        return fail(c, GRAM_ERR_ARG, "gram_mlp_backward: NULL pointer");
+    const int64_t window = ((int64_t)1 << 32) - 16;
+    const int64_t widest = c->cfg.d_hidden > c->cfg.d ? c->cfg.d_hidden : c->cfg.d;
+    if ((int64_t)c->cfg.vocab_n * c->cfg.d_in * 2 >= window || n * widest * 4 >= window)
+        return fail(c, GRAM_ERR_UNIMPLEMENTED, "gram_mlp_backward: not available when X or a batch matrix exceeds 4 GiB");
+    if (!mlp_backward(c, X, W1, W2, ids, G_rows, Ht, n, work, dW1, dW2, accumulate != 0, Ht ? loss_dev : nullptr,
+                      static_cast<hipStream_t>(stream)))
+        return fail(c, GRAM_ERR_UNIMPLEMENTED, "gram_mlp_backward: batch too large for the buffer window");
+    return launch_status(c, "gram_mlp_backward");
 }
 
 int gram_grad_accumulate(gram_ctx* ctx, const float* dH, int64_t m, int32_t step_k, void* stream)
@@ -478,7 +557,7 @@ static const char* const kKernelNames[KID_COUNT] = {
     "transpose_w", "encode_bf16", "encode_f32", "gather_rows", "slot_count", "slot_emit", "seg_reduce",
     "seg_combine", "wgrad_bf16", "wgrad_f32", "wgrad_reduce", "transpose_x", "transpose_g", "flush_meta",
     "flush_rows", "unique_small", "gather_heavy", "pseudo_target", "pseudo_loss", "chunk_ids",
-    "pseudo_miss"};
+    "pseudo_miss", "mlp_act", "mlp_gate"};
 
 int gram_kernel_count(void) { return KID_COUNT; }
 

@@ -40,7 +40,7 @@ enum KernelId {
     KID_UNIQUE_EMPTY, KID_TRANSPOSE_U16, KID_ENCODE_BF16, KID_ENCODE_F32, KID_GATHER_ROWS,
     KID_SLOT_COUNT, KID_SLOT_EMIT, KID_SEG_REDUCE, KID_SEG_COMBINE, KID_WGRAD_BF16, KID_WGRAD_F32,
     KID_WGRAD_REDUCE, KID_TRANSPOSE_X, KID_TRANSPOSE_G, KID_FLUSH_META, KID_FLUSH_ROWS, KID_UNIQUE_SMALL,
-    KID_GATHER_HEAVY, KID_PSEUDO_TARGET, KID_PSEUDO_LOSS, KID_CHUNK_IDS, KID_PSEUDO_MISS, KID_COUNT
+    KID_GATHER_HEAVY, KID_PSEUDO_TARGET, KID_PSEUDO_LOSS, KID_CHUNK_IDS, KID_PSEUDO_MISS, KID_MLP_ACT, KID_MLP_GATE, KID_COUNT
 };
 
 struct ProfSlot {
@@ -89,6 +89,12 @@ struct Ctx {
     float* seg_first = nullptr; // [tiles_seg, d] partial sums of segments entering a tile
     float* seg_last = nullptr;  // [tiles_seg, d] partial sums of segments leaving a tile
     void* Wt = nullptr;         // [d, d_in] transposed weight (bf16 path)
+    // two-layer encoder (cfg.d_hidden > 0) only:
+    void* W1t = nullptr;        // [d_hidden, d_in] bf16
+    void* W2t = nullptr;        // [d, d_hidden] bf16
+    float* Z_ws = nullptr;      // [cap_u, d_hidden] pre-activations of the current batch
+    void* A1_ws = nullptr;      // [cap_u, d_hidden] bf16 activations when the caller keeps none
+    int* iota = nullptr;        // [cap_chunk] 0, 1, 2, ...: row list of a matrix that needs no gather
     float* wg_partial = nullptr;// [splits, d_in, d] split-K partials of the weight gradient
     uint16_t* XT = nullptr;     // [d_in, ldt] bf16 features of the buffer's items, transposed (bf16 path)
     uint16_t* GT = nullptr;     // [d, ldt] bf16 copy of G, transposed (bf16 path)
@@ -175,6 +181,7 @@ void flush_dense(Ctx* c, int* uniq_total, int* counts_total, long long* counts64
 void import_dense(Ctx* c, const int* ids, const long long* counts, const float* rows, int64_t n,
                   hipStream_t s);
 void fill_i32(int* p, int64_t n, int v, hipStream_t s);
+void iota_i32(int* p, int64_t n, hipStream_t s);
 
 // ---- gram_gemm.hip -------------------------------------------------------
 // Returns true when H_scatter was given and the contraction's epilogue has already written H
@@ -200,6 +207,18 @@ struct WgradRows {
 // proper chunk, or `other` is given, and an operand is beyond 4 GiB (nothing is launched).
 bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t first_row, int64_t n_rows,
                    bool accumulate, const WgradRows* other = nullptr);
+// ---- gram_mlp.hip --------------------------------------------------------
+// Forward of the two-layer encoder for the unique items of the batch; A1 (nullable) receives the
+// bf16 hidden activations.  Return value as encode_forward.
+bool mlp_forward(Ctx* c, const void* X, const void* W1, const void* W2, const int* uniq, const int* u_dev,
+                 int64_t rows_max, void* A1, float* E, hipStream_t s, float* H_scatter, bool caller_wants_E);
+int64_t mlp_batch_bytes(const Ctx* c, int64_t n);
+// Backward of the two-layer encoder over the listed items from output-gradient rows (`rows`) or,
+// with Ht, from the regression miss against stored targets (then loss_dev may receive Eq. 7).
+bool mlp_backward(Ctx* c, const void* X, const void* W1, const void* W2, const int* ids, const float* rows,
+                  const float* Ht, int64_t n, void* work, float* dW1, float* dW2, bool accumulate,
+                  double* loss_dev, hipStream_t s);
+
 int wgrad_splits_for(const gram_config& cfg);
 int wgrad_splits_dims(int d_in, int d, bool bf16);
 // bf16 helpers the two-layer encoder shares with the linear one.

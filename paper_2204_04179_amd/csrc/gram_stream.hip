@@ -78,6 +78,20 @@ void fill_i32(int* p, int64_t n, int v, hipStream_t s)
     hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)blocks), dim3(kBlock), 0, s, p, n, v);
 }
 
+__global__ __launch_bounds__(kBlock) void k_iota_i32(int* __restrict__ p, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (int64_t)gridDim.x * kBlock)
+        p[i] = (int)i;
+}
+
+void iota_i32(int* p, int64_t n, hipStream_t s)
+{
+    if (n <= 0) return;
+    int64_t blocks = (n + kBlock - 1) / kBlock;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_iota_i32, dim3((unsigned)blocks), dim3(kBlock), 0, s, p, n);
+}
+
 // ---- gather: H[p,:] = E[inverse[p],:] ---------------------------------------
 
 // A block copies `rows_per_block` consecutive positions (about 32 KiB), so its

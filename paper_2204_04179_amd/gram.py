@@ -22,7 +22,8 @@ STATUS_NAMES = {OK: "GRAM_OK", ERR_ARG: "GRAM_ERR_ARG", ERR_CAPACITY: "GRAM_ERR_
 EXPORTS = ("gram_workspace_bytes", "gram_create", "gram_destroy", "gram_unique", "gram_encode_gather",
            "gram_grad_accumulate", "gram_pseudo_target", "gram_gather", "gram_encoder_wgrad",
            "gram_encoder_wgrad_chunk", "gram_pseudo_loss_grad", "gram_flush",
-           "gram_flush64", "gram_window_import",
+           "gram_flush64", "gram_window_import", "gram_mlp_encode_gather", "gram_mlp_batch_bytes",
+           "gram_mlp_backward",
            "gram_check", "gram_last_error",
            "gram_kernel_count", "gram_kernel_name", "gram_light_max", "gram_profile_enable",
            "gram_profile_read")
@@ -31,7 +32,8 @@ EXPORTS = ("gram_workspace_bytes", "gram_create", "gram_destroy", "gram_unique",
 class GramConfig(C.Structure):
     _fields_ = [("vocab_n", C.c_int32), ("d_in", C.c_int32), ("d", C.c_int32),
                 ("max_positions", C.c_int64), ("k_steps", C.c_int32), ("pad_id", C.c_int32),
-                ("u_total_cap", C.c_int64), ("xw_dtype", C.c_int32), ("buffer_layout", C.c_int32)]
+                ("u_total_cap", C.c_int64), ("xw_dtype", C.c_int32), ("buffer_layout", C.c_int32),
+                ("d_hidden", C.c_int32)]
 
 
 class GramError(RuntimeError):
@@ -76,6 +78,12 @@ def load():
     L.gram_encoder_wgrad.argtypes = [vp, vp, vp, vp]
     L.gram_flush.restype = C.c_int
     L.gram_flush.argtypes = [vp, vp, vp, vp, vp, i32p, vp]
+    L.gram_mlp_encode_gather.restype = C.c_int
+    L.gram_mlp_encode_gather.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_int64, vp, vp, vp, vp]
+    L.gram_mlp_batch_bytes.restype = C.c_int64
+    L.gram_mlp_batch_bytes.argtypes = [vp, C.c_int64]
+    L.gram_mlp_backward.restype = C.c_int
+    L.gram_mlp_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_int64, vp, vp, vp, C.c_int32, vp, vp]
     L.gram_flush64.restype = C.c_int
     L.gram_flush64.argtypes = [vp, vp, vp, vp, vp, i32p, vp]
     L.gram_window_import.restype = C.c_int
@@ -99,9 +107,9 @@ def load():
 
 
 def make_config(vocab_n, d_in, d, max_positions, k_steps=1, pad_id=0, u_total_cap=0, xw_dtype=BF16,
-                buffer_layout=0):
+                buffer_layout=0, d_hidden=0):
     return GramConfig(int(vocab_n), int(d_in), int(d), int(max_positions), int(k_steps), int(pad_id),
-                      int(u_total_cap), int(xw_dtype), int(buffer_layout))
+                      int(u_total_cap), int(xw_dtype), int(buffer_layout), int(d_hidden))
 
 
 def workspace_bytes(cfg: GramConfig) -> int:
@@ -193,6 +201,20 @@ class Gram:
                                       _ptr(u_total_dev), C.byref(u_host) if want_host_u else None,
                                       _stream(stream)))
         return u_host.value if want_host_u else None
+
+    def mlp_encode_gather(self, X, W1, W2, uniq, inverse, u_dev, m, A1, E, H, stream=None):
+        self._ck(self._lib.gram_mlp_encode_gather(self._h, _ptr(X), _ptr(W1), _ptr(W2), _ptr(uniq), _ptr(inverse),
+                                                  _ptr(u_dev), int(m), _ptr(A1), _ptr(E), _ptr(H),
+                                                  _stream(stream)))
+
+    def mlp_batch_bytes(self, n):
+        return int(self._lib.gram_mlp_batch_bytes(self._h, int(n)))
+
+    def mlp_backward(self, X, W1, W2, ids, G_rows, Ht, n, work, dW1, dW2, accumulate=False, loss_dev=None,
+                     stream=None):
+        self._ck(self._lib.gram_mlp_backward(self._h, _ptr(X), _ptr(W1), _ptr(W2), _ptr(ids), _ptr(G_rows),
+                                             _ptr(Ht), int(n), _ptr(work), _ptr(dW1), _ptr(dW2),
+                                             1 if accumulate else 0, _ptr(loss_dev), _stream(stream)))
 
     def flush64(self, uniq_total=None, counts_total=None, G_total=None, u_total_dev=None,
                 want_host_u=False, stream=None):

@@ -552,6 +552,157 @@ def test_long_window_reaches_the_whole_vocabulary():
     assert_close(out["dW"], ref["dW"], 1e-5, "dW")
 
 
+# ------------------------------------------------------- two-layer stand-in encoder --
+
+def mlp_weights(seed, n, d_in, d_hid, d):
+    rng = np.random.default_rng(seed)
+    X = wl.f32_to_bf16_bits(rng.standard_normal((n, d_in)).astype(np.float32))
+    W1 = wl.f32_to_bf16_bits((rng.standard_normal((d_in, d_hid)) / np.sqrt(d_in)).astype(np.float32))
+    W2 = wl.f32_to_bf16_bits((rng.standard_normal((d_hid, d)) / np.sqrt(d_hid)).astype(np.float32))
+    return X, W1, W2
+
+
+def run_mlp_step(X, W1, W2, ids, dH, vocab_n, batches_of, targets=None, W_now=None):
+    """One single-step window with the two-layer encoder through the library: forward, accumulate,
+    flush, then the backward pass over the window's items in batches of the given sizes (from the
+    accumulated gradient rows, or from `targets` [U, d] at the weights W_now)."""
+    import torch
+    from paper_2204_04179_amd import gram
+    from harness import to_dev
+    (d_in, d_hid), d = W1.shape, W2.shape[1]
+    m = ids.size
+    g = gram.Gram(gram.make_config(vocab_n, d_in, d, m, 1, 0, 0, gram.BF16, 0, d_hid))
+    Xd, W1d, W2d = to_dev(X, torch), to_dev(W1, torch), to_dev(W2, torch)
+    cap_u = min(m, vocab_n)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    uniq, counts, inverse = torch.full((cap_u,), -7, **i32), torch.empty(cap_u, **i32), torch.empty(m, **i32)
+    u_dev = torch.zeros(1, **i32)
+    A1 = torch.full((cap_u, d_hid), float("nan"), dtype=torch.bfloat16, device="cuda")
+    E = torch.full((cap_u, d), float("nan"), device="cuda")
+    H = torch.full((m, d), float("nan"), device="cuda")
+    U = g.unique(torch.from_numpy(ids).cuda(), uniq, inverse, counts, u_dev, want_host_u=True)
+    g.mlp_encode_gather(Xd, W1d, W2d, uniq, inverse, u_dev, m, A1, E, H)
+    g.grad_accumulate(torch.from_numpy(dH).cuda(), m, 0)
+    ut, ct = torch.empty(cap_u, **i32), torch.empty(cap_u, **i32)
+    Gt = torch.empty(cap_u, d, device="cuda")
+    assert g.flush(ut, ct, Gt, None, want_host_u=True) == U
+    if W_now is not None:
+        W1d, W2d = to_dev(W_now[0], torch), to_dev(W_now[1], torch)
+    Ht = torch.from_numpy(targets.astype(np.float32)).cuda() if targets is not None else None
+    dW1 = torch.full((d_in, d_hid), float("nan"), device="cuda")
+    dW2 = torch.full((d_hid, d), float("nan"), device="cuda")
+    work = torch.empty(max(1, g.mlp_batch_bytes(max(batches_of))), dtype=torch.uint8, device="cuda")
+    losses, a = [], 0
+    for i, n in enumerate(batches_of):
+        loss = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda")
+        g.mlp_backward(Xd, W1d, W2d, ut[a:a + n], None if Ht is not None else Gt[a:a + n],
+                       Ht[a:a + n] if Ht is not None else None, n, work, dW1, dW2, accumulate=i > 0,
+                       loss_dev=loss)
+        losses.append(float(loss.item()))
+        a += n
+    g.check()
+    assert a == U
+    out = dict(U=U, uniq=uniq[:U].cpu().numpy(), inverse=inverse.cpu().numpy(),
+               A1=A1[:U].float().cpu().numpy(), A1_tail_untouched=bool(torch.isnan(A1[U:].float()).all()),
+               E=E[:U].cpu().numpy(), H=H.cpu().numpy(), G=Gt[:U].cpu().numpy(), dW1=dW1.cpu().numpy(),
+               dW2=dW2.cpu().numpy(), losses=losses)
+    g.close()
+    return out
+
+
+def test_mlp_encoder_step_matches_oracle_and_end_to_end():
+    """Forward with kept activations, accumulate, and the backward pass in ragged batches of items:
+    against the oracle's per-unique-item run and its per-interaction (end-to-end) gradients."""
+    n, d_in, d_hid, d = 2500, 32, 48, 24
+    X, W1, W2 = mlp_weights(800, n, d_in, d_hid, d)
+    ids, _, _, dH = small_problem(801, 7000, n, d_in=8, d=d)
+    say("two-layer encoder, small")
+    ref = orc.mlp_gram_single(ids, X, W1, W2, dH)
+    U = ref["uniq"].size
+    out = run_mlp_step(X, W1, W2, ids, dH, n, [500, 1, 0, U - 501])
+    np.testing.assert_array_equal(out["uniq"], ref["uniq"])
+    np.testing.assert_array_equal(out["inverse"], ref["inverse"])
+    assert out["A1_tail_untouched"]
+    assert_close(out["A1"], ref["A1"], 2.0 ** -8, "A1 (kept in bf16)")
+    assert_close(out["E"], ref["E"], TOL[wl.BF16], "E")
+    np.testing.assert_array_equal(out["H"], out["E"][out["inverse"]])
+    pad = ref["uniq"] == 0
+    assert pad.any() and not out["A1"][pad].any() and not out["E"][pad].any()
+    assert_close(out["G"], ref["G"], TOL_SUM[wl.BF16], "G")
+    _, dW1_e2e, dW2_e2e = orc.mlp_e2e(ids, X, W1, W2, dH)
+    assert_close(out["dW1"], dW1_e2e, TOL[wl.BF16], "dW1 vs end-to-end")
+    assert_close(out["dW2"], dW2_e2e, TOL[wl.BF16], "dW2 vs end-to-end")
+
+
+def test_mlp_encoder_step_with_tiles_for_every_compute_unit():
+    """Sizes at which both contractions of the forward (the second with the fused gather) and all
+    three of the backward run in the 256x256 kernels."""
+    n, d_in, d_hid, d = 90000, 32, 256, 128
+    X, W1, W2 = mlp_weights(802, n, d_in, d_hid, d)
+    rng = np.random.default_rng(803)
+    m = 72000
+    ids = rng.permutation(np.arange(1, n))[:m].astype(np.int32)      # nearly all distinct ...
+    ids[:3000] = rng.integers(1, 50, size=3000)                      # ... a few heavy items ...
+    ids[rng.random(m) < 0.02] = 0                                    # ... and padding
+    dH = rng.standard_normal((m, d)).astype(np.float32)
+    say("two-layer encoder, large")
+    ref = orc.mlp_gram_single(ids, X, W1, W2, dH)
+    U = ref["uniq"].size
+    assert U > 65536
+    out = run_mlp_step(X, W1, W2, ids, dH, n, [U])
+    assert_close(out["E"], ref["E"], TOL[wl.BF16], "E")
+    np.testing.assert_array_equal(out["H"], out["E"][out["inverse"]])
+    assert_close(out["dW1"], ref["dW1"], TOL[wl.BF16], "dW1")
+    assert_close(out["dW2"], ref["dW2"], TOL[wl.BF16], "dW2")
+
+
+def test_mlp_encoder_regression_towards_stored_targets():
+    """Algorithm 1 step 4 (Eq. 7) with the two-layer encoder at weights that have moved."""
+    n, d_in, d_hid, d = 1200, 64, 40, 16
+    X, W1, W2 = mlp_weights(804, n, d_in, d_hid, d)
+    _, V1, V2 = mlp_weights(805, n, d_in, d_hid, d)
+    ids, _, _, dH = small_problem(806, 3000, n, d_in=8, d=d)
+    uniq = np.unique(ids)
+    Ht = np.random.default_rng(807).standard_normal((uniq.size, d)).astype(np.float32)
+    say("two-layer encoder, regression")
+    out = run_mlp_step(X, W1, W2, ids, dH, n, [300, uniq.size - 300], targets=Ht, W_now=(V1, V2))
+    miss, loss, dW1, dW2 = orc.mlp_pseudo_loss_grad(uniq, X, V1, V2, Ht.astype(np.float64))
+    assert abs(sum(out["losses"]) - loss) <= TOL[wl.BF16] * loss
+    assert_close(out["dW1"], dW1, TOL[wl.BF16], "dW1")
+    assert_close(out["dW2"], dW2, TOL[wl.BF16], "dW2")
+
+
+def test_mlp_encoder_argument_errors():
+    import torch
+    from paper_2204_04179_amd import gram
+    with pytest.raises(gram.GramError):
+        gram.Gram(gram.make_config(100, 16, 8, 50, 1, 0, 0, gram.F32, 0, 16))     # bf16 only
+    with pytest.raises(gram.GramError):
+        gram.Gram(gram.make_config(100, 16, 8, 50, 1, 0, 0, gram.BF16, 0, 12))    # d_hidden % 8
+    lin = gram.Gram(gram.make_config(100, 16, 8, 50, 1, 0, 0, gram.BF16))
+    mlp = gram.Gram(gram.make_config(100, 16, 8, 50, 1, 0, 0, gram.BF16, 0, 16))
+    z = torch.zeros(4096, device="cuda")
+    ids = torch.zeros(8, dtype=torch.int32, device="cuda")
+    assert lin.mlp_batch_bytes(8) == 0 and mlp.mlp_batch_bytes(8) == 5 * 256
+
+    def status(fn):
+        with pytest.raises(gram.GramError) as e:
+            fn()
+        return e.value.status
+
+    assert status(lambda: lin.mlp_backward(z, z, z, ids, z, None, 8, z, z, z)) == gram.ERR_ARG
+    assert status(lambda: mlp.mlp_backward(z, z, z, ids, z, z, 8, z, z, z)) == gram.ERR_ARG      # both sources
+    assert status(lambda: mlp.mlp_backward(z, z, z, ids, None, None, 8, z, z, z)) == gram.ERR_ARG
+    assert status(lambda: mlp.mlp_backward(z, z, z, ids, z, None, 101, z, z, z)) == gram.ERR_ARG
+    assert status(lambda: mlp.mlp_encode_gather(z, z, z, ids, ids, None, 8, None, None, z)) == gram.ERR_SEQUENCE
+    dW1, dW2 = torch.ones(16, 16, device="cuda"), torch.ones(16, 8, device="cuda")
+    mlp.mlp_backward(z, z, z, None, None, None, 0, None, dW1, dW2)                                # empty batch
+    mlp.check()
+    assert not bool(dW1.any()) and not bool(dW2.any())
+    lin.close()
+    mlp.close()
+
+
 # ---------------------------------------------- dense-by-vocabulary buffer (long windows) --
 
 @pytest.mark.parametrize("bf16", [False, True])
