@@ -424,7 +424,7 @@ def mlp_leg(r, d_hid=1024, chunk_rows=32768, windows=3):
     dW2 = torch.empty(d_hid, w.d, device="cuda")
     work = torch.empty(g.mlp_batch_bytes(chunk_rows), dtype=torch.uint8, device="cuda")
     G_t = r.G_t if r.G_t is not None else torch.empty(r.uniq_t.numel(), w.d, device="cuda")
-    names = ["encode_bf16", "mlp_act", "mlp_gate", "wgrad_bf16", "wgrad_reduce", "gather_heavy", "transpose_w"]
+    names = ["encode_bf16", "mlp_to_bf16", "wgrad_bf16", "wgrad_reduce", "gather_heavy", "transpose_w"]
 
     def window(backward=True):
         for k in range(w.K):

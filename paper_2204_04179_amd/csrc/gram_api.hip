@@ -143,7 +143,6 @@ int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
     float* wg_partial = (float*)take(partial_elems * 4);
     void* W1t = take(dh > 0 ? dh * d_in * 2 : 1);
     void* W2t = take(dh > 0 ? d * dh * 2 : 1);
-    float* Z_ws = (float*)take(dh > 0 ? dv.cap_u * dh * 4 : 1);
     void* A1_ws = take(dh > 0 ? dv.cap_u * dh * 2 : 1);
     int* iota = (int*)take(dh > 0 ? dv.cap_chunk * 4 : 1);
     const bool bf = cfg.xw_dtype == GRAM_BF16;
@@ -158,7 +157,7 @@ int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
         c->cnt_of_slot = cnt_of_slot; c->cnt64 = cnt64; c->dense_sums = dense_sums; c->G = G; c->E_ws = E_ws; c->loss_part = loss_part; c->chunk_ids = chunk_ids; c->seg_first = seg_first;
         c->seg_last = seg_last; c->Wt = Wt; c->wg_partial = wg_partial;
         c->XT = XT; c->GT = GT; c->ldt = ldt;
-        c->W1t = W1t; c->W2t = W2t; c->Z_ws = Z_ws; c->A1_ws = A1_ws; c->iota = iota;
+        c->W1t = W1t; c->W2t = W2t; c->A1_ws = A1_ws; c->iota = iota;
     }
     return off;
 }
@@ -487,8 +486,14 @@ int gram_pseudo_loss_grad(gram_ctx* ctx, const void* X, const void* W, const int
         return fail(c, GRAM_ERR_UNIMPLEMENTED, "gram_pseudo_loss_grad: not available when X or R exceeds 4 GiB");
     hipStream_t s = static_cast<hipStream_t>(stream);
     chunk_ids_prepare(c, ids, n, s);
-    encode_forward(c, X, W, c->chunk_ids, c->scal + kSChunkN, n, R, s, nullptr, true);
-    pseudo_miss(c, R, Ht, n, loss_dev, s);
+    if (c->cfg.xw_dtype == GRAM_BF16) {
+        // the contraction subtracts the targets as it stores; only the loss needs another pass
+        encode_forward(c, X, W, c->chunk_ids, c->scal + kSChunkN, n, R, s, nullptr, true, kEpiMinus, Ht);
+        pseudo_miss(c, R, nullptr, n, loss_dev, s);
+    } else {
+        encode_forward(c, X, W, c->chunk_ids, c->scal + kSChunkN, n, R, s, nullptr, true);
+        pseudo_miss(c, R, Ht, n, loss_dev, s);
+    }
     const WgradRows rows = {c->chunk_ids, R, c->scal + kSChunkN, n};
     if (!encoder_wgrad(c, X, dW, s, 0, n, accumulate != 0, &rows))
         return fail(c, GRAM_ERR_UNIMPLEMENTED, "gram_pseudo_loss_grad: batch too large for the buffer window");
@@ -557,7 +562,7 @@ static const char* const kKernelNames[KID_COUNT] = {
     "transpose_w", "encode_bf16", "encode_f32", "gather_rows", "slot_count", "slot_emit", "seg_reduce",
     "seg_combine", "wgrad_bf16", "wgrad_f32", "wgrad_reduce", "transpose_x", "transpose_g", "flush_meta",
     "flush_rows", "unique_small", "gather_heavy", "pseudo_target", "pseudo_loss", "chunk_ids",
-    "pseudo_miss", "mlp_act", "mlp_gate"};
+    "pseudo_miss", "mlp_to_bf16"};
 
 int gram_kernel_count(void) { return KID_COUNT; }
 

@@ -42,6 +42,41 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     return (uint16_t)(u >> 16);
 }
 
+// What a contraction kernel does with an output element before storing it (template parameter
+// EPI of the kernels below).  `aux` has the row pitch of C.
+//   kEpiPlain      C = v                                   (float32)
+//   kEpiReluBf16   C = bf16(max(v, 0))                     (C is a bf16 matrix)
+//   kEpiMinus      C = v - aux                             (aux float32: stored targets)
+//   kEpiGate       C = v where aux > 0, else 0             (aux bf16: kept activations)
+// A row flagged `zero` (the padding item) is stored as zeros in every mode.
+
+// The aux value of an element is fetched ahead of the stores (epi_load for a group of elements,
+// then epi_store for the group), so that the loads of a group are in flight together.
+template <int EPI>
+__device__ __forceinline__ float epi_load(const void* __restrict__ aux, int64_t at)
+{
+    if (EPI == kEpiMinus) return static_cast<const float*>(aux)[at];
+    if (EPI == kEpiGate) {
+        const uint16_t a = static_cast<const uint16_t*>(aux)[at];
+        return ((a & 0x8000u) || !(a & 0x7fffu)) ? 0.f : 1.f;               // positive bf16 only
+    }
+    return 0.f;
+}
+
+template <int EPI>
+__device__ __forceinline__ void epi_store(float* __restrict__ C, int64_t at, float v, float a, bool zero)
+{
+    if (EPI == kEpiReluBf16) {
+        reinterpret_cast<uint16_t*>(C)[at] = (zero || !(v > 0.f)) ? (uint16_t)0 : f32_to_bf16_rne(v);
+    } else if (EPI == kEpiMinus) {
+        C[at] = zero ? 0.f : v - a;
+    } else if (EPI == kEpiGate) {
+        C[at] = (zero || a == 0.f) ? 0.f : v;
+    } else {
+        C[at] = zero ? 0.f : v;
+    }
+}
+
 // ---- small forward kernel: latency first ------------------------------------------
 //
 // Batches whose unique items give the 256x256 kernel fewer tiles than there are CUs (and any
@@ -69,9 +104,11 @@ __global__ __launch_bounds__(kBlock) void k_transpose_u16(const uint16_t* __rest
 
 __device__ __forceinline__ uint4 and4(uint4 v, uint32_t m) { return make_uint4(v.x & m, v.y & m, v.z & m, v.w & m); }
 
+template <int EPI>
 __global__ __launch_bounds__(kBlock) void k_encode_bf16(
     const uint16_t* __restrict__ X, const uint16_t* __restrict__ Wt, const int* __restrict__ uniq,
-    const int* __restrict__ u_dev, int d_in, int d, int pad_id, float* __restrict__ E)
+    const int* __restrict__ u_dev, int d_in, int d, int pad_id, float* __restrict__ E,
+    const void* __restrict__ aux)
 {
     __shared__ __attribute__((aligned(16))) uint16_t sA[2][BM * LDS_STRIDE];
     __shared__ __attribute__((aligned(16))) uint16_t sB[2][BN * LDS_STRIDE];
@@ -158,10 +195,16 @@ __global__ __launch_bounds__(kBlock) void k_encode_bf16(
 
     // accumulator element r of a lane sits at (row, col) = ((r / 4) * 8 + (lane / 32) * 4 + r % 4, lane % 32)
     const int cc = n0 + wn * 32 + (lane & 31);
+    float av[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int j = m0 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        if (j < U && cc < d) E[(int64_t)j * d + cc] = uniq[j] == pad_id ? 0.f : acc[r];
+        av[r] = (j < U && cc < d) ? epi_load<EPI>(aux, (int64_t)j * d + cc) : 0.f;
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int j = m0 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        if (j < U && cc < d) epi_store<EPI>(E, (int64_t)j * d + cc, acc[r], av[r], uniq[j] == pad_id);
     }
 }
 
@@ -415,12 +458,13 @@ struct ScatterArgs {
     int write_all;        // also store every row to C (the caller asked for E)
 };
 
-template <bool GATHER, int NW, bool SCATTER>
+template <bool GATHER, int NW, bool SCATTER, int EPI = kEpiPlain>
 __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
     const uint16_t* __restrict__ A, int64_t lda, uint32_t a_bytes, const int* __restrict__ row_ids,
     const int* __restrict__ m_dev, int m_host, const uint16_t* __restrict__ B, int64_t ldb,
     uint32_t b_bytes, int n, const int* __restrict__ k_dev, int k_host, int splits, int pad_id,
-    int n_tiles, float* __restrict__ C, int64_t ldc, int64_t split_stride, ScatterArgs sc)
+    int n_tiles, float* __restrict__ C, int64_t ldc, int64_t split_stride, ScatterArgs sc,
+    const void* __restrict__ aux)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     __shared__ int s_pad_row;
@@ -654,29 +698,50 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
         }
     } else if (m0 + TM <= M && n0 + TN <= n) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i) {
+            float av[16][NT];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int lr = wm * 128 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                float* row = C + (int64_t)(m0 + lr) * ldc + n0 + wn * (NT * 32) + (lane & 31);
+                const int64_t at = (int64_t)(m0 + lr) * ldc + n0 + wn * (NT * 32) + (lane & 31);
+#pragma unroll
+                for (int jj = 0; jj < NT; ++jj) av[r][jj] = epi_load<EPI>(aux, at + jj * 32);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int lr = wm * 128 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                const int64_t at = (int64_t)(m0 + lr) * ldc + n0 + wn * (NT * 32) + (lane & 31);
                 const bool zero = lr == pad_row;
 #pragma unroll
-                for (int jj = 0; jj < NT; ++jj) row[jj * 32] = zero ? 0.f : acc[i][jj][r];
+                for (int jj = 0; jj < NT; ++jj) epi_store<EPI>(C, at + jj * 32, acc[i][jj][r], av[r][jj], zero);
             }
+        }
     } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i) {
+            float av[16][NT];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int lr = wm * 128 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                const int64_t at = (int64_t)(m0 + lr) * ldc + n0 + wn * (NT * 32) + (lane & 31);
+#pragma unroll
+                for (int jj = 0; jj < NT; ++jj)
+                    av[r][jj] = (m0 + lr < M && n0 + wn * (NT * 32) + jj * 32 + (lane & 31) < n)
+                                    ? epi_load<EPI>(aux, at + jj * 32) : 0.f;
+            }
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int lr = wm * 128 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
                 if (m0 + lr < M) {
-                    float* row = C + (int64_t)(m0 + lr) * ldc + n0 + wn * (NT * 32) + (lane & 31);
+                    const int64_t at = (int64_t)(m0 + lr) * ldc + n0 + wn * (NT * 32) + (lane & 31);
                     const bool zero = lr == pad_row;
 #pragma unroll
                     for (int jj = 0; jj < NT; ++jj)
-                        if (n0 + wn * (NT * 32) + jj * 32 + (lane & 31) < n) row[jj * 32] = zero ? 0.f : acc[i][jj][r];
+                        if (n0 + wn * (NT * 32) + jj * 32 + (lane & 31) < n)
+                            epi_store<EPI>(C, at + jj * 32, acc[i][jj][r], av[r][jj], zero);
                 }
             }
+        }
     }
 }
 #undef GRAM_FRAGS
@@ -690,12 +755,33 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
 constexpr int kGemmWaves = 8;
 
 // a_rows / b_rows: rows of the matrices A and B as allocated (A: all rows that row_ids may name).
+// epi != kEpiPlain (with its `aux` matrix) is available for gathered, unsplit, unfused launches
+// whose operands lie below 4 GiB.
+template <int EPI>
+static void launch_gemm_nt_epi(Ctx* c, int kid, unsigned blocks, hipStream_t s, const uint16_t* A, int64_t lda,
+                               uint32_t a_bytes, const int* row_ids, const int* m_dev, int m_host,
+                               const uint16_t* B, int64_t ldb, uint32_t b_bytes, int n, int k_host, int pad_id,
+                               int n_tiles, float* C, int64_t ldc, const void* aux)
+{
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16<true, kGemmWaves, false, EPI>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)RSMEM);
+        attr_set = true;
+    }
+    const ScatterArgs none = {nullptr, nullptr, nullptr, 0, 0};
+    launch_smem(c, kid, k_gemm_nt_bf16<true, kGemmWaves, false, EPI>, dim3(blocks), dim3(kGemmWaves * 64), RSMEM,
+                s, A, lda, a_bytes, row_ids, m_dev, m_host, B, ldb, b_bytes, n, (const int*)nullptr, k_host, 1,
+                pad_id, n_tiles, C, ldc, (int64_t)0, none, aux);
+}
+
 template <bool GATHER>
 static void launch_gemm_nt(Ctx* c, int kid, const uint16_t* A, int64_t lda, int64_t a_rows,
                            const int* row_ids, const int* m_dev, int m_host, int64_t m_bound,
                            const uint16_t* B, int64_t ldb, int64_t b_rows, int n, const int* k_dev,
                            int k_host, int splits, float* C, int64_t ldc, int64_t split_stride,
-                           hipStream_t s, const ScatterArgs* scatter = nullptr, int pad_id = -1)
+                           hipStream_t s, const ScatterArgs* scatter = nullptr, int pad_id = -1,
+                           int epi = kEpiPlain, const void* aux = nullptr)
 {
     static bool attr_set = false;
     if (!attr_set) {
@@ -716,16 +802,27 @@ static void launch_gemm_nt(Ctx* c, int kid, const uint16_t* A, int64_t lda, int6
     const int64_t a_bytes = a_rows * lda * 2, b_bytes = b_rows * ldb * 2;
     const int64_t window = (int64_t)1 << 32;
     const ScatterArgs none = {nullptr, nullptr, nullptr, 0, 0};
-    if (scatter)
+    if (epi != kEpiPlain) {
+        // callers keep to the conditions stated above
+        if (epi == kEpiReluBf16)
+            launch_gemm_nt_epi<kEpiReluBf16>(c, kid, (unsigned)blocks, s, A, lda, (uint32_t)a_bytes, row_ids, m_dev,
+                                              m_host, B, ldb, (uint32_t)b_bytes, n, k_host, pad_id, n_tiles, C, ldc, aux);
+        else if (epi == kEpiMinus)
+            launch_gemm_nt_epi<kEpiMinus>(c, kid, (unsigned)blocks, s, A, lda, (uint32_t)a_bytes, row_ids, m_dev,
+                                          m_host, B, ldb, (uint32_t)b_bytes, n, k_host, pad_id, n_tiles, C, ldc, aux);
+        else
+            launch_gemm_nt_epi<kEpiGate>(c, kid, (unsigned)blocks, s, A, lda, (uint32_t)a_bytes, row_ids, m_dev,
+                                         m_host, B, ldb, (uint32_t)b_bytes, n, k_host, pad_id, n_tiles, C, ldc, aux);
+    } else if (scatter)
         launch_smem(c, kid, k_gemm_nt_bf16<GATHER, kGemmWaves, GATHER>, dim3((unsigned)blocks),
                     dim3(kGemmWaves * 64), GATHER ? RSMEM_SC : RSMEM, s, A, lda, (uint32_t)a_bytes, row_ids,
                     m_dev, m_host, B, ldb, (uint32_t)b_bytes, n, k_dev, k_host, splits, pad_id,
-                    n_tiles, C, ldc, split_stride, *scatter);
+                    n_tiles, C, ldc, split_stride, *scatter, (const void*)nullptr);
     else if (a_bytes < window && b_bytes < window)
         launch_smem(c, kid, k_gemm_nt_bf16<GATHER, kGemmWaves, false>, dim3((unsigned)blocks),
                     dim3(kGemmWaves * 64), RSMEM, s, A, lda, (uint32_t)a_bytes, row_ids, m_dev, m_host, B,
                     ldb, (uint32_t)b_bytes, n, k_dev, k_host, splits, pad_id, n_tiles, C, ldc,
-                    split_stride, none);
+                    split_stride, none, (const void*)nullptr);
     else
         launch_smem(c, kid, k_gemm_nt_bf16_dma<GATHER>, dim3((unsigned)blocks), dim3(kBlock), TSMEM, s, A,
                     lda, row_ids, m_dev, m_host, B, ldb, n, k_dev, k_host, splits, pad_id, n_tiles,
@@ -852,7 +949,7 @@ void transpose_weight(Ctx* c, const void* W, int rows, int cols, void* Wt, hipSt
 
 bool gemm_rows_bf16(Ctx* c, const void* A, int64_t a_rows, int k, const int* row_ids, int pad_id,
                     const int* n_dev, int64_t rows_max, const void* Bt, int n_out, float* C, hipStream_t s,
-                    float* H_scatter, bool caller_wants_C)
+                    float* H_scatter, bool caller_wants_C, int epi, const void* aux)
 {
     if (rows_max <= 0) return false;
     const int64_t window = (int64_t)1 << 32;
@@ -860,28 +957,41 @@ bool gemm_rows_bf16(Ctx* c, const void* A, int64_t a_rows, int k, const int* row
     if (tile_bound >= c->num_cus && k % TK == 0) {
         // Fusing the gather pays when there are tiles for every CU: with a handful of tiles the
         // position stores of a tile run on one CU while a separate gather spreads over all.
-        const bool fuse = H_scatter && a_rows * k * 2 < window;
+        const bool fuse = H_scatter && epi == kEpiPlain && a_rows * k * 2 < window;
         const ScatterArgs sc = {c->offsets, c->perm, H_scatter, (int64_t)n_out, caller_wants_C ? 1 : 0};
         launch_gemm_nt<true>(c, KID_ENCODE_BF16, static_cast<const uint16_t*>(A), k, a_rows, row_ids, n_dev,
                              0, rows_max, static_cast<const uint16_t*>(Bt), k, n_out, n_out, nullptr, k, 1,
-                             C, n_out, 0, s, fuse ? &sc : nullptr, pad_id);
+                             C, n_out, 0, s, fuse ? &sc : nullptr, pad_id, epi, aux);
         return fuse;
     }
-    launch(c, KID_ENCODE_BF16, k_encode_bf16, dim3((n_out + BN - 1) / BN, (unsigned)((rows_max + BM - 1) / BM)),
-           dim3(kBlock), s, static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(Bt), row_ids, n_dev,
-           k, n_out, pad_id, C);
+    const dim3 grid((n_out + BN - 1) / BN, (unsigned)((rows_max + BM - 1) / BM));
+    const uint16_t* a16 = static_cast<const uint16_t*>(A);
+    const uint16_t* b16 = static_cast<const uint16_t*>(Bt);
+    if (epi == kEpiReluBf16)
+        launch(c, KID_ENCODE_BF16, k_encode_bf16<kEpiReluBf16>, grid, dim3(kBlock), s, a16, b16, row_ids, n_dev, k,
+               n_out, pad_id, C, aux);
+    else if (epi == kEpiMinus)
+        launch(c, KID_ENCODE_BF16, k_encode_bf16<kEpiMinus>, grid, dim3(kBlock), s, a16, b16, row_ids, n_dev, k,
+               n_out, pad_id, C, aux);
+    else if (epi == kEpiGate)
+        launch(c, KID_ENCODE_BF16, k_encode_bf16<kEpiGate>, grid, dim3(kBlock), s, a16, b16, row_ids, n_dev, k,
+               n_out, pad_id, C, aux);
+    else
+        launch(c, KID_ENCODE_BF16, k_encode_bf16<kEpiPlain>, grid, dim3(kBlock), s, a16, b16, row_ids, n_dev, k,
+               n_out, pad_id, C, aux);
     return false;
 }
 
 bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const int* u_dev,
-                    int64_t rows_max, float* E, hipStream_t s, float* H_scatter, bool caller_wants_E)
+                    int64_t rows_max, float* E, hipStream_t s, float* H_scatter, bool caller_wants_E, int epi,
+                    const void* aux)
 {
     if (rows_max <= 0) return false;
     const int d_in = c->cfg.d_in, d = c->cfg.d;
     if (c->cfg.xw_dtype == GRAM_BF16) {
         transpose_weight(c, W, d_in, d, c->Wt, s);
         return gemm_rows_bf16(c, X, c->cfg.vocab_n, d_in, uniq, c->cfg.pad_id, u_dev, rows_max, c->Wt, d, E, s,
-                              H_scatter, caller_wants_E);
+                              H_scatter, caller_wants_E, epi, aux);
     }
     launch(c, KID_ENCODE_F32, k_encode_f32, dim3((d + 63) / 64, (unsigned)((rows_max + 3) / 4)),
            dim3(kBlock), s, static_cast<const float*>(X), static_cast<const float*>(W), uniq, u_dev,

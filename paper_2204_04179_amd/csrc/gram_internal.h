@@ -40,7 +40,7 @@ enum KernelId {
     KID_UNIQUE_EMPTY, KID_TRANSPOSE_U16, KID_ENCODE_BF16, KID_ENCODE_F32, KID_GATHER_ROWS,
     KID_SLOT_COUNT, KID_SLOT_EMIT, KID_SEG_REDUCE, KID_SEG_COMBINE, KID_WGRAD_BF16, KID_WGRAD_F32,
     KID_WGRAD_REDUCE, KID_TRANSPOSE_X, KID_TRANSPOSE_G, KID_FLUSH_META, KID_FLUSH_ROWS, KID_UNIQUE_SMALL,
-    KID_GATHER_HEAVY, KID_PSEUDO_TARGET, KID_PSEUDO_LOSS, KID_CHUNK_IDS, KID_PSEUDO_MISS, KID_MLP_ACT, KID_MLP_GATE, KID_COUNT
+    KID_GATHER_HEAVY, KID_PSEUDO_TARGET, KID_PSEUDO_LOSS, KID_CHUNK_IDS, KID_PSEUDO_MISS, KID_MLP_TO_BF16, KID_COUNT
 };
 
 struct ProfSlot {
@@ -92,7 +92,6 @@ struct Ctx {
     // two-layer encoder (cfg.d_hidden > 0) only:
     void* W1t = nullptr;        // [d_hidden, d_in] bf16
     void* W2t = nullptr;        // [d, d_hidden] bf16
-    float* Z_ws = nullptr;      // [cap_u, d_hidden] pre-activations of the current batch
     void* A1_ws = nullptr;      // [cap_u, d_hidden] bf16 activations when the caller keeps none
     int* iota = nullptr;        // [cap_chunk] 0, 1, 2, ...: row list of a matrix that needs no gather
     float* wg_partial = nullptr;// [splits, d_in, d] split-K partials of the weight gradient
@@ -169,8 +168,8 @@ void gather_heavy(Ctx* c, const float* E, int64_t m, float* H, hipStream_t s);
 void pseudo_target(Ctx* c, const float* E, float* Ht, double* loss_dev, hipStream_t s);
 // Checked copy of a content-encoder batch's IDs into c->chunk_ids and its size into scal[kSChunkN].
 void chunk_ids_prepare(Ctx* c, const int* ids, int64_t n, hipStream_t s);
-// R[j,:] -= Ht[j,:] for the n rows of the batch in c->chunk_ids (zero for the padding item) and,
-// with loss_dev, 1/2 of the sum of the squares of the result.
+// With Ht: R[j,:] -= Ht[j,:] for the n rows of the batch in c->chunk_ids (zero for the padding
+// item); without: R is taken as it is.  With loss_dev, 1/2 of the sum of the squares of R.
 void pseudo_miss(Ctx* c, float* R, const float* Ht, int64_t n, double* loss_dev, hipStream_t s);
 void assign_slots(Ctx* c, hipStream_t s);
 void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s);
@@ -187,8 +186,12 @@ void iota_i32(int* p, int64_t n, hipStream_t s);
 // Returns true when H_scatter was given and the contraction's epilogue has already written H
 // for every item with at most kLightMax positions (gather_heavy must follow); false when only E
 // was written (gather_rows must follow).
+// epi (bf16 contexts only; see the enum): what the contraction does with an output element
+// before storing it; a mode other than kEpiPlain excludes the fused gather.
+enum { kEpiPlain = 0, kEpiReluBf16 = 1, kEpiMinus = 2, kEpiGate = 3 };
 bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const int* u_dev,
-                    int64_t rows_max, float* E, hipStream_t s, float* H_scatter, bool caller_wants_E);
+                    int64_t rows_max, float* E, hipStream_t s, float* H_scatter, bool caller_wants_E,
+                    int epi = kEpiPlain, const void* aux = nullptr);
 // Rows the weight gradient contracts over when they are not the persistent buffer's: row j pairs
 // item ids[j] with rows[j,:] (float32, d columns); *n_dev rows are held, at most n_max.
 // With d_in != 0 the contraction also takes its shape from here instead of the context: the
@@ -223,12 +226,13 @@ int wgrad_splits_for(const gram_config& cfg);
 int wgrad_splits_dims(int d_in, int d, bool bf16);
 // bf16 helpers the two-layer encoder shares with the linear one.
 void transpose_weight(Ctx* c, const void* W, int rows, int cols, void* Wt, hipStream_t s);
-// C[j,:] = A[row_ids[j],:k] . Bt^T for j < *n_dev (A bf16 [a_rows, k], Bt bf16 [n_out, k], C float32
-// [., n_out]); a row whose ID equals pad_id is zero.  Same return value and fused-gather rule as
-// encode_forward.
+// C[j,:] = epi(A[row_ids[j],:k] . Bt^T) for j < *n_dev (A bf16 [a_rows, k], Bt bf16 [n_out, k], C
+// float32 [., n_out], or bf16 for kEpiReluBf16); a row whose ID equals pad_id is zero.  kEpiMinus
+// subtracts the float32 matrix aux, kEpiGate keeps the value where the bf16 matrix aux is positive
+// (both [., n_out]).  Same return value and fused-gather rule as encode_forward.
 bool gemm_rows_bf16(Ctx* c, const void* A, int64_t a_rows, int k, const int* row_ids, int pad_id,
                     const int* n_dev, int64_t rows_max, const void* Bt, int n_out, float* C, hipStream_t s,
-                    float* H_scatter, bool caller_wants_C);
+                    float* H_scatter, bool caller_wants_C, int epi = kEpiPlain, const void* aux = nullptr);
 int64_t wgrad_pitch_for(int64_t cap_total);
 
 }  // namespace gram

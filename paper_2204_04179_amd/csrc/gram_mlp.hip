@@ -4,7 +4,8 @@
 // activation a is what has to be kept for the backward pass, and under GRAM it is kept once
 // per unique item instead of once per interaction (the paper's section on GPU memory
 // consumption).  Both contractions run in the kernels of the linear encoder (gram_gemm.hip);
-// this file adds the element-wise kernels between them and the order of the launches.
+// the rectifier and its gate are applied by those kernels as they store (epilogue modes); this
+// file adds the one remaining element-wise kernel and the order of the launches.
 #include "gram_internal.h"
 
 namespace gram {
@@ -20,8 +21,7 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-// out = bf16(RELU ? max(in, 0) : in) for the first *n_dev rows of `cols4` float4 columns.
-template <bool RELU>
+// out = bf16(in) for the first *n_dev rows of `cols4` float4 columns (round to nearest even).
 __global__ __launch_bounds__(kBlock) void k_to_bf16(const f32x4* __restrict__ in,
                                                     const int* __restrict__ n_dev, int cols4,
                                                     uint2* __restrict__ out)
@@ -29,34 +29,8 @@ __global__ __launch_bounds__(kBlock) void k_to_bf16(const f32x4* __restrict__ in
     const int64_t total = (int64_t)*n_dev * cols4;
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
          i += (int64_t)gridDim.x * kBlock) {
-        f32x4 v = in[i];
-        if (RELU) {
-            v.x = v.x > 0.f ? v.x : 0.f;
-            v.y = v.y > 0.f ? v.y : 0.f;
-            v.z = v.z > 0.f ? v.z : 0.f;
-            v.w = v.w > 0.f ? v.w : 0.f;
-        }
+        const f32x4 v = in[i];
         out[i] = make_uint2(pack2(v.x, v.y), pack2(v.z, v.w));
-    }
-}
-
-// dZ = dA where the kept activation is positive, else 0 (in place on dA).  The gate reads the
-// bf16 activation the forward pass kept, so forward and backward agree on which units are active.
-__global__ __launch_bounds__(kBlock) void k_relu_gate(f32x4* __restrict__ dA,
-                                                      const uint2* __restrict__ A1,
-                                                      const int* __restrict__ n_dev, int cols4)
-{
-    const int64_t total = (int64_t)*n_dev * cols4;
-    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
-         i += (int64_t)gridDim.x * kBlock) {
-        const uint2 a = A1[i];
-        f32x4 v = dA[i];
-        // a positive bf16 has a clear sign bit and a non-zero magnitude
-        if ((a.x & 0x8000u) || !(a.x & 0x7fffu)) v.x = 0.f;
-        if ((a.x & 0x80000000u) || !(a.x & 0x7fff0000u)) v.y = 0.f;
-        if ((a.y & 0x8000u) || !(a.y & 0x7fffu)) v.z = 0.f;
-        if ((a.y & 0x80000000u) || !(a.y & 0x7fff0000u)) v.w = 0.f;
-        dA[i] = v;
     }
 }
 
@@ -74,10 +48,9 @@ bool mlp_forward(Ctx* c, const void* X, const void* W1, const void* W2, const in
     const int d_in = c->cfg.d_in, dh = c->cfg.d_hidden, d = c->cfg.d;
     void* a1 = A1 ? A1 : c->A1_ws;
     transpose_weight(c, W1, d_in, dh, c->W1t, s);
-    gemm_rows_bf16(c, X, c->cfg.vocab_n, d_in, uniq, c->cfg.pad_id, u_dev, rows_max, c->W1t, dh, c->Z_ws, s,
-                   nullptr, true);
-    launch(c, KID_MLP_ACT, k_to_bf16<true>, dim3(blocks_for(rows_max, dh / 4)), dim3(kBlock), s,
-           reinterpret_cast<const f32x4*>(c->Z_ws), u_dev, dh / 4, reinterpret_cast<uint2*>(a1));
+    // the first contraction stores a = bf16(max(z, 0)) directly: z itself is never written
+    gemm_rows_bf16(c, X, c->cfg.vocab_n, d_in, uniq, c->cfg.pad_id, u_dev, rows_max, c->W1t, dh,
+                   static_cast<float*>(a1), s, nullptr, true, kEpiReluBf16, nullptr);
     transpose_weight(c, W2, dh, d, c->W2t, s);
     // rows of A1 are in the order of uniq: the identity list stands in for the gather, and no row is
     // "padding" by its index (the padding item's activation row is zero already)
@@ -99,7 +72,7 @@ bool mlp_backward(Ctx* c, const void* X, const void* W1, const void* W2, const i
     const int d_in = c->cfg.d_in, dh = c->cfg.d_hidden, d = c->cfg.d;
     auto up = [](int64_t v) { return (v + 255) / 256 * 256; };
     char* w = static_cast<char*>(work);
-    float* Z = reinterpret_cast<float*>(w);                  // [n, dh] pre-activations, later dL/dz
+    float* Z = reinterpret_cast<float*>(w);                  // [n, dh] dL/dz
     void* A1 = w + up(n * dh * 4);                           // [n, dh] bf16 activations
     float* R = reinterpret_cast<float*>(w + up(n * dh * 4) + up(n * dh * 2));          // [n, d]
     void* Rb = w + up(n * dh * 4) + up(n * dh * 2) + up(n * d * 4);                    // [n, d] bf16
@@ -108,10 +81,8 @@ bool mlp_backward(Ctx* c, const void* X, const void* W1, const void* W2, const i
     chunk_ids_prepare(c, ids, n, s);
     if (n > 0) {
         transpose_weight(c, W1, d_in, dh, c->W1t, s);
-        gemm_rows_bf16(c, X, c->cfg.vocab_n, d_in, c->chunk_ids, c->cfg.pad_id, n_dev, n, c->W1t, dh, Z, s,
-                       nullptr, true);
-        launch(c, KID_MLP_ACT, k_to_bf16<true>, dim3(blocks_for(n, dh / 4)), dim3(kBlock), s,
-               reinterpret_cast<const f32x4*>(Z), n_dev, dh / 4, reinterpret_cast<uint2*>(A1));
+        gemm_rows_bf16(c, X, c->cfg.vocab_n, d_in, c->chunk_ids, c->cfg.pad_id, n_dev, n, c->W1t, dh,
+                       static_cast<float*>(A1), s, nullptr, true, kEpiReluBf16, nullptr);
     }
     const float* Rsrc = rows;
     if (Ht) {
@@ -128,11 +99,11 @@ bool mlp_backward(Ctx* c, const void* X, const void* W1, const void* W2, const i
     if (!encoder_wgrad(c, A1, dW2, s, 0, n, accumulate, &top)) return false;
     if (n > 0) {
         // dA = R . W2^T: W2 [dh, d] is already the K-contiguous second operand of that product
-        launch(c, KID_MLP_ACT, k_to_bf16<false>, dim3(blocks_for(n, d / 4)), dim3(kBlock), s,
+        launch(c, KID_MLP_TO_BF16, k_to_bf16, dim3(blocks_for(n, d / 4)), dim3(kBlock), s,
                reinterpret_cast<const f32x4*>(Rsrc), n_dev, d / 4, reinterpret_cast<uint2*>(Rb));
-        gemm_rows_bf16(c, Rb, n, d, c->iota, -1, n_dev, n, W2, dh, Z, s, nullptr, true);
-        launch(c, KID_MLP_GATE, k_relu_gate, dim3(blocks_for(n, dh / 4)), dim3(kBlock), s,
-               reinterpret_cast<f32x4*>(Z), reinterpret_cast<const uint2*>(A1), n_dev, dh / 4);
+        // the gate of the rectifier is applied as the product is stored: dZ = dA where the kept
+        // activation is positive, so forward and backward agree on which units are active
+        gemm_rows_bf16(c, Rb, n, d, c->iota, -1, n_dev, n, W2, dh, Z, s, nullptr, true, kEpiGate, A1);
     }
     // dW1 = X[ids]^T dZ
     const WgradRows bottom = {c->chunk_ids, Z, n_dev, n, c->cfg.vocab_n, d_in, dh, c->cfg.pad_id};

@@ -290,10 +290,11 @@ void chunk_ids_prepare(Ctx* c, const int* ids, int64_t n, hipStream_t s)
            c->cfg.vocab_n, c->cfg.pad_id >= 0 ? c->cfg.pad_id : 0, c->chunk_ids, c->scal);
 }
 
-// R[j,:] holds the encoder's output for item j of the batch; it becomes the regression miss
-// R[j,:] - Ht[j,:] (zero for the padding item), and the block's share of sum |miss|^2 goes to
-// partial[] exactly as in k_pseudo_target (double per thread, fixed tree, k_pseudo_loss adds
-// the blocks in index order).
+// With Ht: R[j,:] holds the encoder's output for item j of the batch and becomes the regression
+// miss R[j,:] - Ht[j,:] (zero for the padding item).  Without: R already holds the miss (the
+// contraction subtracted the targets as it stored).  Either way the block's share of sum |miss|^2
+// goes to partial[] exactly as in k_pseudo_target (double per thread, fixed tree, k_pseudo_loss
+// adds the blocks in index order).
 __global__ __launch_bounds__(kBlock) void k_pseudo_miss(f32x4* __restrict__ R,
                                                         const f32x4* __restrict__ Ht,
                                                         const int* __restrict__ ids, int n, int pad_id,
@@ -307,9 +308,14 @@ __global__ __launch_bounds__(kBlock) void k_pseudo_miss(f32x4* __restrict__ R,
     for (int e = threadIdx.x; e < total; e += kBlock) {
         const int r = e / cols4, cq = e - r * cols4;
         const int64_t at = (int64_t)(j0 + r) * cols4 + cq;
-        f32x4 m = {0.f, 0.f, 0.f, 0.f};
-        if (ids[j0 + r] != pad_id) m = R[at] - __builtin_nontemporal_load(&Ht[at]);
-        R[at] = m;
+        f32x4 m;
+        if (Ht) {
+            m = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (ids[j0 + r] != pad_id) m = R[at] - __builtin_nontemporal_load(&Ht[at]);
+            R[at] = m;
+        } else {
+            m = R[at];
+        }
         sum += (double)m.x * m.x + (double)m.y * m.y + (double)m.z * m.z + (double)m.w * m.w;
     }
     s_sum[threadIdx.x] = sum;
@@ -323,6 +329,7 @@ __global__ __launch_bounds__(kBlock) void k_pseudo_miss(f32x4* __restrict__ R,
 
 void pseudo_miss(Ctx* c, float* R, const float* Ht, int64_t n, double* loss_dev, hipStream_t s)
 {
+    if (!Ht && !loss_dev) return;       // nothing to subtract, nothing to sum
     const int64_t blocks = (n + kPseudoRows - 1) / kPseudoRows;
     if (blocks > 0)
         launch(c, KID_PSEUDO_MISS, k_pseudo_miss, dim3((unsigned)blocks), dim3(kBlock), s,
@@ -431,7 +438,8 @@ __global__ __launch_bounds__(kSlotSmallThreads) void k_slot_small(
     const int u = scal[kSU];
     int run_base = first_step ? 0 : scal[kSUTotal];             // a flush leaves the old count behind
     bool overflow = false;
-    for (int j0 = threadIdx.x * 4; j0 - threadIdx.x * 4 < u; j0 += kSlotSmallThreads * 4) {   // uniform trip count
+    const int t4 = (int)threadIdx.x * 4;
+    for (int j0 = t4; j0 - t4 < u; j0 += kSlotSmallThreads * 4) {   // uniform trip count
         int id[4], old[4], sflag = 0;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
