@@ -55,6 +55,33 @@ def test_workspace_query_validates_the_config():
     assert gram.workspace_bytes(gram.make_config(100, 30, 32, 64, 1, 0, 0, gram.F32)) > 0
 
 
+def test_workspace_query_for_the_dense_buffer_and_the_two_layer_encoder():
+    base = gram.make_config(20000, 768, 256, 51200, 8, 0, 0, gram.BF16)
+    dense = gram.make_config(20000, 768, 256, 51200, 8, 0, 0, gram.BF16, 1)
+    assert 0 < gram.workspace_bytes(dense) < gram.workspace_bytes(base)      # no slot map, no transposed copies
+    assert gram.workspace_bytes(gram.make_config(20000, 768, 256, 51200, 8, 0, 20000, gram.BF16, 1)) > 0
+    mlp = gram.make_config(20000, 768, 256, 51200, 8, 0, 0, gram.BF16, 0, 512)
+    assert gram.workspace_bytes(mlp) > gram.workspace_bytes(base)
+    bad = [
+        gram.make_config(20000, 768, 256, 51200, 8, 0, 500, gram.BF16, 1),       # dense: one row per ID, no other size
+        gram.make_config(20000, 768, 256, 51200, 8, 0, 0, gram.BF16, 2),         # unknown layout
+        gram.make_config(1 << 22, 768, 256, 51200, 8, 0, 0, gram.BF16, 1),       # dense: X beyond 4 GiB
+        gram.make_config(1 << 21, 64, 1024, 51200, 8, 0, 0, gram.BF16, 1),       # dense: N x d x 4 beyond 4 GiB
+        gram.make_config(20000, 768, 256, 51200, 8, 0, 0, gram.BF16, 0, -8),     # negative hidden width
+        gram.make_config(20000, 768, 256, 51200, 8, 0, 0, gram.BF16, 0, 100),    # hidden width not a multiple of 8
+        gram.make_config(20000, 768, 252, 51200, 8, 0, 0, gram.BF16, 0, 512),    # two-layer: d not a multiple of 8
+        gram.make_config(20000, 768, 256, 51200, 8, 0, 0, gram.F32, 0, 512),     # two-layer: bf16 only
+    ]
+    for cfg in bad:
+        assert gram.workspace_bytes(cfg) == 0
+    lib = gram.load()
+    assert lib.gram_mlp_batch_bytes(None, 100) == 0
+    assert lib.gram_flush64(None, None, None, None, None, None, None) == gram.ERR_ARG
+    assert lib.gram_window_import(None, None, None, None, 0, None) == gram.ERR_ARG
+    assert lib.gram_pseudo_loss_grad(None, None, None, None, None, 0, None, None, 0, None, None) == gram.ERR_ARG
+    assert lib.gram_mlp_backward(None, None, None, None, None, None, None, 0, None, None, None, 0, None, None) == gram.ERR_ARG
+
+
 def test_kernel_names_and_null_context_errors():
     lib = gram.load()
     n = lib.gram_kernel_count()
