@@ -147,8 +147,13 @@ int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
     int* iota = (int*)take(dh > 0 ? dv.cap_chunk * 4 : 1);
     const bool bf = cfg.xw_dtype == GRAM_BF16;
     const int64_t ldt = wgrad_pitch_for(dv.cap_total);
-    uint16_t* XT = (uint16_t*)take(bf && !dense ? d_in * ldt * 2 : 1);   // wide-address path only:
-    uint16_t* GT = (uint16_t*)take(bf && !dense ? d * ldt * 2 : 1);      // never taken by a dense buffer
+    // transposed copies for the wide-address weight gradient: needed only when X or the buffer lies
+    // beyond the 4 GiB a buffer descriptor can address (the same test encoder_wgrad applies)
+    const int64_t window = ((int64_t)1 << 32) - 16;
+    const bool wide = bf && !dense &&
+                      ((int64_t)cfg.vocab_n * d_in * 2 >= window || dv.cap_total * d * 4 >= window);
+    uint16_t* XT = (uint16_t*)take(wide ? d_in * ldt * 2 : 1);
+    uint16_t* GT = (uint16_t*)take(wide ? d * ldt * 2 : 1);
     if (c && base) {
         c->scal = scal; c->keys[0] = keys0; c->keys[1] = keys1; c->vals[0] = vals0; c->vals[1] = vals1;
         c->table = table; c->gtot = gtot; c->tile_sums = tile_sums; c->offsets = offsets;
