@@ -830,6 +830,66 @@ def test_dense_buffer_argument_errors():
     dense.close()
 
 
+def test_window_captured_in_a_hip_graph_replays_like_eager():
+    """The calls only enqueue kernels (no memset nodes, no host read-backs unless asked for), so a
+    whole window can be captured once and replayed; every replay, with eager work and
+    synchronisations in between, must reproduce the eager window bit for bit."""
+    import torch
+    from paper_2204_04179_amd import gram
+    from harness import to_dev
+    K, n, d_in, d, m = 2, 3000, 64, 32, 9000
+    probs = [small_problem(900 + k, m, n, d_in=d_in, d=d, bf16=True) for k in range(K)]
+    X, W = to_dev(probs[0][1], torch), to_dev(probs[0][2], torch)
+    ids = [torch.from_numpy(p[0]).cuda() for p in probs]
+    dH = [torch.from_numpy(p[3]).cuda() for p in probs]
+    g = gram.Gram(gram.make_config(n, d_in, d, m, K, 0, 0, gram.BF16))
+    i32 = dict(dtype=torch.int32, device="cuda")
+    uniq, counts, inverse, u_dev = torch.empty(n, **i32), torch.empty(n, **i32), torch.empty(m, **i32), torch.zeros(1, **i32)
+    H = torch.empty(m, d, device="cuda")
+    dW = torch.empty(d_in, d, device="cuda")
+    ut, ct, Gt, n_t = torch.empty(n, **i32), torch.empty(n, **i32), torch.empty(n, d, device="cuda"), torch.zeros(1, **i32)
+    outs = (H, dW, ut, ct, Gt, n_t)
+
+    def window():
+        for k in range(K):
+            g.unique(ids[k], uniq, inverse, counts, u_dev)
+            g.encode_gather(X, W, uniq, inverse, u_dev, m, None, H)
+            g.grad_accumulate(dH[k], m, k)
+        g.encoder_wgrad(X, dW)
+        g.flush(ut, ct, Gt, n_t)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        u = int(n_t.item())
+        return [t.clone() if t is not ut and t is not ct and t is not Gt else t[:u].clone() for t in outs]
+
+    say("graph capture of a window")
+    window()
+    eager = snapshot()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        window()                                   # warm-up on a capture-capable stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        window()
+    for rep in range(3):
+        for t in outs:
+            t.zero_()                              # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(eager, got):
+            assert torch.equal(a, b), f"replay {rep}"
+    window()                                       # and eager again after the replays
+    for a, b in zip(eager, snapshot()):
+        assert torch.equal(a, b)
+    g.check()
+    g.close()
+
+
 def test_flush_variants_and_back_to_back_windows():
     """gram_flush with and without the G export gives the same IDs and counts; a second flush of an
     empty window returns nothing; a context runs window after window with one- and multi-step
