@@ -465,6 +465,40 @@ def mlp_leg(r, d_hid=1024, chunk_rows=32768, windows=3):
             "backward_workspace_bytes": {"per_batch": int(work.numel()), "whole_window_at_once": int(work.numel() / chunk_rows * r.U_total)}}
 
 
+def bf16_h_leg(r, windows=5):
+    """Outside the timed steps: the same windows with the per-position output H stored in bf16
+    (h_dtype), i.e. half the bytes of the step's largest output."""
+    import torch
+    from paper_2204_04179_amd import gram
+    w = r.w
+    g = gram.Gram(gram.make_config(w.N, w.d_in, w.d, w.M, w.K, 0, 0, gram.BF16, 0, 0, gram.BF16))
+    H16 = torch.empty(w.M, w.d, dtype=torch.bfloat16, device="cuda")
+
+    def window():
+        for k in range(w.K):
+            g.unique(r.ids[k], r.uniq, r.inverse, r.counts, r.u_dev)
+            g.encode_gather(r.X, r.Wt, r.uniq, r.inverse, r.u_dev, r.M, None, H16)
+            g.grad_accumulate(r.dH[k], r.M, k)
+        g.encoder_wgrad(r.X, r.dW)
+        g.flush(r.uniq_t, r.counts_t, r.G_t, r.u_t)
+
+    window()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(windows):
+        window()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    g.profile_enable(["encode_bf16", "gather_heavy", "gather_rows"], max_launches=64 * w.K)
+    window()
+    prof = g.profile_read()
+    g.profile_enable([])
+    g.close()
+    steps = windows * w.K
+    return {"ms_per_step": 1e3 * dt / steps, "value": r.M_valid_per_step * steps / dt, "unit": "occurrences/s",
+            "kernels_avg_us": {k: round(1e3 * v[1] / v[0], 1) for k, v in prof.items()}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -475,7 +509,7 @@ def main():
                     help="comma-separated workloads reported under 'also' ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-export-G", action="store_true", help="gram_flush without the G_total copy")
-    ap.add_argument("--legs", default="pseudo_target,chunked_wgrad,encoder_batches,mlp,long_window",
+    ap.add_argument("--legs", default="pseudo_target,chunked_wgrad,encoder_batches,mlp,bf16_h,long_window",
                     help="extra measurements outside the timed steps (profiling runs drop chunked_wgrad so that "
                          "the weight-gradient kernel's statistics cover the timed windows only)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -552,6 +586,8 @@ def main():
         out["next_rows"]["chunked_wgrad"] = chunked_wgrad_leg(r)
     if "encoder_batches" in legs and w.xw_dtype != wl.F32:
         out["next_rows"]["encoder_batches"] = encoder_batches_leg(r)
+    if "bf16_h" in legs and w.xw_dtype != wl.F32:
+        out["next_rows"]["bf16_positions_output"] = bf16_h_leg(r)
     if "mlp" in legs and w.xw_dtype != wl.F32:
         out["next_rows"]["mlp_encoder"] = mlp_leg(r)
     out["paper_context"] = "paper: Single-step ~4x, Multi-step up to 146x faster than E2E, whole training runs on A100"

@@ -96,6 +96,10 @@ typedef struct gram_config {
     int32_t d_hidden;      /* 0: linear stand-in encoder.  > 0: width of the hidden
                               layer of the two-layer stand-in (gram_mlp_*; bf16 only,
                               d_hidden and d multiples of 8)                           */
+    int32_t h_dtype;       /* gram_dtype of H, the per-position output of the forward:
+                              GRAM_F32 (0), or GRAM_BF16: each value is rounded to
+                              nearest even as it is stored (half the bytes of the
+                              step's largest output); E stays float32                  */
 } gram_config;
 
 /* Bytes of device memory gram_create would allocate for cfg (0 if cfg is invalid). */
@@ -131,8 +135,8 @@ int gram_unique(gram_ctx* ctx, const int32_t* ids, int64_t m, int32_t* uniq, int
  *   m        the m of that gram_unique
  *   E        DEVICE [>= min(m,N), d], nullable   out: E[j,:] = X[uniq[j],:].W,
  *            zero row for the padding ID; NULL keeps E in the workspace
- *   H        DEVICE [m,d]      out: H[p,:] = E[inverse[p],:] (zero at padding);
- *            16-byte aligned
+ *   H        DEVICE [m,d] of cfg.h_dtype   out: H[p,:] = E[inverse[p],:] (zero at
+ *            padding), rounded to nearest even when h_dtype is bf16; 16-byte aligned
  * Requires a preceding gram_unique on this context (GRAM_ERR_SEQUENCE).
  * When uniq and inverse are the very buffers that gram_unique wrote, large bf16
  * batches take a fused path: the contraction stores each representation
@@ -142,7 +146,7 @@ int gram_unique(gram_ctx* ctx, const int32_t* ids, int64_t m, int32_t* uniq, int
  * kernel.  Any other uniq / inverse pair takes the two-kernel path (encode to
  * E, then gather).  The results are identical. */
 int gram_encode_gather(gram_ctx* ctx, const void* X, const void* W, const int32_t* uniq,
-                       const int32_t* inverse, const int32_t* u_dev, int64_t m, float* E, float* H,
+                       const int32_t* inverse, const int32_t* u_dev, int64_t m, float* E, void* H,
                        void* stream);
 
 /* Per-unique-item gradient (Algorithm 1 step 3): for the batch of the last
@@ -193,7 +197,7 @@ int gram_grad_accumulate(gram_ctx* ctx, const float* dH, int64_t m, int32_t step
  * GRAM_ERR_UNIMPLEMENTED when X or a batch matrix exceeds 4 GiB. */
 int gram_mlp_encode_gather(gram_ctx* ctx, const void* X, const void* W1, const void* W2,
                            const int32_t* uniq, const int32_t* inverse, const int32_t* u_dev, int64_t m,
-                           void* A1, float* E, float* H, void* stream);
+                           void* A1, float* E, void* H, void* stream);
 int64_t gram_mlp_batch_bytes(const gram_ctx* ctx, int64_t n);
 int gram_mlp_backward(gram_ctx* ctx, const void* X, const void* W1, const void* W2, const int32_t* ids,
                       const float* G_rows, const float* Ht, int64_t n, void* work, float* dW1,
@@ -218,8 +222,8 @@ int gram_pseudo_target(gram_ctx* ctx, const float* E, float* Ht, double* loss_de
  * representations in later steps of a window (Section 4.3: item vectors as
  * trainable embeddings).
  *   src      DEVICE [>= U, d]   inverse  DEVICE [m], values < U
- *   H        DEVICE [m, d]      16-byte aligned pointers */
-int gram_gather(gram_ctx* ctx, const float* src, const int32_t* inverse, int64_t m, float* H,
+ *   H        DEVICE [m, d] of cfg.h_dtype      16-byte aligned pointers */
+int gram_gather(gram_ctx* ctx, const float* src, const int32_t* inverse, int64_t m, void* H,
                 void* stream);
 
 /* Encoder weight gradient over all items accumulated in the window

@@ -71,6 +71,7 @@ const char* validate(const gram_config* cfg, Derived* dv)
     if (cfg->u_total_cap < 0) return "u_total_cap must be >= 0";
     if (cfg->buffer_layout != GRAM_BUFFER_SLOTS && cfg->buffer_layout != GRAM_BUFFER_DENSE)
         return "buffer_layout must be GRAM_BUFFER_SLOTS or GRAM_BUFFER_DENSE";
+    if (cfg->h_dtype != GRAM_F32 && cfg->h_dtype != GRAM_BF16) return "h_dtype must be GRAM_F32 or GRAM_BF16";
     if (cfg->d_hidden < 0) return "d_hidden must be >= 0 (0 = linear encoder)";
     if (cfg->d_hidden > 0 && (cfg->xw_dtype != GRAM_BF16 || cfg->d_hidden % 8 != 0 || cfg->d % 8 != 0))
         return "the two-layer encoder needs bf16 features and d_hidden, d multiples of 8";
@@ -315,7 +316,7 @@ int gram_unique(gram_ctx* ctx, const int32_t* ids, int64_t m, int32_t* uniq, int
 }
 
 int gram_encode_gather(gram_ctx* ctx, const void* X, const void* W, const int32_t* uniq,
-                       const int32_t* inverse, const int32_t* u_dev, int64_t m, float* E, float* H,
+                       const int32_t* inverse, const int32_t* u_dev, int64_t m, float* E, void* H,
                        void* stream)
 {
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
@@ -343,7 +344,7 @@ int gram_encode_gather(gram_ctx* ctx, const void* X, const void* W, const int32_
 
 int gram_mlp_encode_gather(gram_ctx* ctx, const void* X, const void* W1, const void* W2, const int32_t* uniq,
                            const int32_t* inverse, const int32_t* u_dev, int64_t m, void* A1, float* E,
-                           float* H, void* stream)
+                           void* H, void* stream)
 {
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     if (!c) return GRAM_ERR_ARG;
@@ -437,7 +438,7 @@ int gram_pseudo_target(gram_ctx* ctx, const float* E, float* Ht, double* loss_de
     return launch_status(c, "gram_pseudo_target");
 }
 
-int gram_gather(gram_ctx* ctx, const float* src, const int32_t* inverse, int64_t m, float* H, void* stream)
+int gram_gather(gram_ctx* ctx, const float* src, const int32_t* inverse, int64_t m, void* H, void* stream)
 {
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     if (!c) return GRAM_ERR_ARG;

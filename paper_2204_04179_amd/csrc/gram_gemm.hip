@@ -24,16 +24,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void lds_void;
 
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-
-// two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
-{
-    const f32x2 v = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
-
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
 {
     uint32_t u = __float_as_uint(f);
@@ -453,9 +443,10 @@ constexpr uint32_t kBufferFlags = 0x00027000;   // raw buffer: 32-bit elements, 
 struct ScatterArgs {
     const int* seg_off;   // [U + 1]
     const int* perm;      // [m] positions in sorted order
-    float* H;             // [m, ldh]
+    void* H;              // [m, ldh] float32, or bf16 with h_bf16
     int64_t ldh;
     int write_all;        // also store every row to C (the caller asked for E)
+    int h_bf16;           // H holds bf16: values are rounded to nearest even as they are stored
 };
 
 template <bool GATHER, int NW, bool SCATTER, int EPI = kEpiPlain>
@@ -689,10 +680,20 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
                     if (col_ok) *reinterpret_cast<f32x4*>(C + (int64_t)(m0 + lr) * ldc + n0 + lane * 4) = v[u];
                     if (cnt > kLightMax) continue;
                 }
-                for (int t = 0; t < cnt; ++t) {
-                    const int pos = __builtin_amdgcn_readlane(pv[i * RPW + u], t);
-                    if (col_ok)
-                        __builtin_nontemporal_store(v[u], reinterpret_cast<f32x4*>(sc.H + (int64_t)pos * sc.ldh + n0 + lane * 4));
+                if (sc.h_bf16) {
+                    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                    const u32x2 h = {pack_bf16x2(v[u].x, v[u].y), pack_bf16x2(v[u].z, v[u].w)};
+                    for (int t = 0; t < cnt; ++t) {
+                        const int pos = __builtin_amdgcn_readlane(pv[i * RPW + u], t);
+                        if (col_ok)
+                            __builtin_nontemporal_store(h, reinterpret_cast<u32x2*>(static_cast<uint16_t*>(sc.H) + (int64_t)pos * sc.ldh + n0 + lane * 4));
+                    }
+                } else {
+                    for (int t = 0; t < cnt; ++t) {
+                        const int pos = __builtin_amdgcn_readlane(pv[i * RPW + u], t);
+                        if (col_ok)
+                            __builtin_nontemporal_store(v[u], reinterpret_cast<f32x4*>(static_cast<float*>(sc.H) + (int64_t)pos * sc.ldh + n0 + lane * 4));
+                    }
                 }
             }
         }
@@ -769,7 +770,7 @@ static void launch_gemm_nt_epi(Ctx* c, int kid, unsigned blocks, hipStream_t s, 
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)RSMEM);
         attr_set = true;
     }
-    const ScatterArgs none = {nullptr, nullptr, nullptr, 0, 0};
+    const ScatterArgs none = {nullptr, nullptr, nullptr, 0, 0, 0};
     launch_smem(c, kid, k_gemm_nt_bf16<true, kGemmWaves, false, EPI>, dim3(blocks), dim3(kGemmWaves * 64), RSMEM,
                 s, A, lda, a_bytes, row_ids, m_dev, m_host, B, ldb, b_bytes, n, (const int*)nullptr, k_host, 1,
                 pad_id, n_tiles, C, ldc, (int64_t)0, none, aux);
@@ -801,7 +802,7 @@ static void launch_gemm_nt(Ctx* c, int kid, const uint16_t* A, int64_t lda, int6
         blocks = ((m_bound + TM - 1) / TM) * n_tiles * splits;
     const int64_t a_bytes = a_rows * lda * 2, b_bytes = b_rows * ldb * 2;
     const int64_t window = (int64_t)1 << 32;
-    const ScatterArgs none = {nullptr, nullptr, nullptr, 0, 0};
+    const ScatterArgs none = {nullptr, nullptr, nullptr, 0, 0, 0};
     if (epi != kEpiPlain) {
         // callers keep to the conditions stated above
         if (epi == kEpiReluBf16)
@@ -949,7 +950,7 @@ void transpose_weight(Ctx* c, const void* W, int rows, int cols, void* Wt, hipSt
 
 bool gemm_rows_bf16(Ctx* c, const void* A, int64_t a_rows, int k, const int* row_ids, int pad_id,
                     const int* n_dev, int64_t rows_max, const void* Bt, int n_out, float* C, hipStream_t s,
-                    float* H_scatter, bool caller_wants_C, int epi, const void* aux)
+                    void* H_scatter, bool caller_wants_C, int epi, const void* aux)
 {
     if (rows_max <= 0) return false;
     const int64_t window = (int64_t)1 << 32;
@@ -958,7 +959,8 @@ bool gemm_rows_bf16(Ctx* c, const void* A, int64_t a_rows, int k, const int* row
         // Fusing the gather pays when there are tiles for every CU: with a handful of tiles the
         // position stores of a tile run on one CU while a separate gather spreads over all.
         const bool fuse = H_scatter && epi == kEpiPlain && a_rows * k * 2 < window;
-        const ScatterArgs sc = {c->offsets, c->perm, H_scatter, (int64_t)n_out, caller_wants_C ? 1 : 0};
+        const ScatterArgs sc = {c->offsets, c->perm, H_scatter, (int64_t)n_out, caller_wants_C ? 1 : 0,
+                               c->cfg.h_dtype == GRAM_BF16 ? 1 : 0};
         launch_gemm_nt<true>(c, KID_ENCODE_BF16, static_cast<const uint16_t*>(A), k, a_rows, row_ids, n_dev,
                              0, rows_max, static_cast<const uint16_t*>(Bt), k, n_out, n_out, nullptr, k, 1,
                              C, n_out, 0, s, fuse ? &sc : nullptr, pad_id, epi, aux);
@@ -983,7 +985,7 @@ bool gemm_rows_bf16(Ctx* c, const void* A, int64_t a_rows, int k, const int* row
 }
 
 bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const int* u_dev,
-                    int64_t rows_max, float* E, hipStream_t s, float* H_scatter, bool caller_wants_E, int epi,
+                    int64_t rows_max, float* E, hipStream_t s, void* H_scatter, bool caller_wants_E, int epi,
                     const void* aux)
 {
     if (rows_max <= 0) return false;

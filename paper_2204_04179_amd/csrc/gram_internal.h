@@ -27,6 +27,15 @@ constexpr int kPseudoRows = 8;          // unique items per block of the pseudo-
 constexpr int kFixCols4 = 16;           // float4 columns per block of the long-segment combine
 constexpr int kFixLanes = kBlock / kFixCols4;
 
+// two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    typedef float f32x2_ __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_ __attribute__((ext_vector_type(2)));
+    const f32x2_ v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_));
+}
+
 // Device scalars (ctx->scal[...]).
 enum Scalar { kSU = 0, kSUTotal, kSErr, kSUBase, kSLongCount, kSFlushN, kSChunkN, kSCount };
 
@@ -163,8 +172,9 @@ bool unique_small(Ctx* c, const int* ids, int n, int fix_key, int* uniq, int* in
                   int* u_out, hipStream_t s);
 
 // ---- gram_stream.hip -----------------------------------------------------
-void gather_rows(Ctx* c, const float* E, const int* inverse, int64_t m, float* H, hipStream_t s);
-void gather_heavy(Ctx* c, const float* E, int64_t m, float* H, hipStream_t s);
+// H has the context's h_dtype (float32, or bf16 rounded to nearest even).
+void gather_rows(Ctx* c, const float* E, const int* inverse, int64_t m, void* H, hipStream_t s);
+void gather_heavy(Ctx* c, const float* E, int64_t m, void* H, hipStream_t s);
 void pseudo_target(Ctx* c, const float* E, float* Ht, double* loss_dev, hipStream_t s);
 // Checked copy of a content-encoder batch's IDs into c->chunk_ids and its size into scal[kSChunkN].
 void chunk_ids_prepare(Ctx* c, const int* ids, int64_t n, hipStream_t s);
@@ -190,7 +200,7 @@ void iota_i32(int* p, int64_t n, hipStream_t s);
 // before storing it; a mode other than kEpiPlain excludes the fused gather.
 enum { kEpiPlain = 0, kEpiReluBf16 = 1, kEpiMinus = 2, kEpiGate = 3 };
 bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const int* u_dev,
-                    int64_t rows_max, float* E, hipStream_t s, float* H_scatter, bool caller_wants_E,
+                    int64_t rows_max, float* E, hipStream_t s, void* H_scatter, bool caller_wants_E,
                     int epi = kEpiPlain, const void* aux = nullptr);
 // Rows the weight gradient contracts over when they are not the persistent buffer's: row j pairs
 // item ids[j] with rows[j,:] (float32, d columns); *n_dev rows are held, at most n_max.
@@ -214,7 +224,7 @@ bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t firs
 // Forward of the two-layer encoder for the unique items of the batch; A1 (nullable) receives the
 // bf16 hidden activations.  Return value as encode_forward.
 bool mlp_forward(Ctx* c, const void* X, const void* W1, const void* W2, const int* uniq, const int* u_dev,
-                 int64_t rows_max, void* A1, float* E, hipStream_t s, float* H_scatter, bool caller_wants_E);
+                 int64_t rows_max, void* A1, float* E, hipStream_t s, void* H_scatter, bool caller_wants_E);
 int64_t mlp_batch_bytes(const Ctx* c, int64_t n);
 // Backward of the two-layer encoder over the listed items from output-gradient rows (`rows`) or,
 // with Ht, from the regression miss against stored targets (then loss_dev may receive Eq. 7).
@@ -232,7 +242,7 @@ void transpose_weight(Ctx* c, const void* W, int rows, int cols, void* Wt, hipSt
 // (both [., n_out]).  Same return value and fused-gather rule as encode_forward.
 bool gemm_rows_bf16(Ctx* c, const void* A, int64_t a_rows, int k, const int* row_ids, int pad_id,
                     const int* n_dev, int64_t rows_max, const void* Bt, int n_out, float* C, hipStream_t s,
-                    float* H_scatter, bool caller_wants_C, int epi = kEpiPlain, const void* aux = nullptr);
+                    void* H_scatter, bool caller_wants_C, int epi = kEpiPlain, const void* aux = nullptr);
 int64_t wgrad_pitch_for(int64_t cap_total);
 
 }  // namespace gram

@@ -11,16 +11,6 @@
 namespace gram {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-
-// two floats -> packed bf16 pair, round to nearest even
-__device__ __forceinline__ uint32_t pack2(float lo, float hi)
-{
-    const f32x2 v = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
-
 // out = bf16(in) for the first *n_dev rows of `cols4` float4 columns (round to nearest even).
 __global__ __launch_bounds__(kBlock) void k_to_bf16(const f32x4* __restrict__ in,
                                                     const int* __restrict__ n_dev, int cols4,
@@ -30,7 +20,7 @@ __global__ __launch_bounds__(kBlock) void k_to_bf16(const f32x4* __restrict__ in
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
          i += (int64_t)gridDim.x * kBlock) {
         const f32x4 v = in[i];
-        out[i] = make_uint2(pack2(v.x, v.y), pack2(v.z, v.w));
+        out[i] = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
     }
 }
 
@@ -42,7 +32,7 @@ static unsigned blocks_for(int64_t rows_max, int cols4)
 }
 
 bool mlp_forward(Ctx* c, const void* X, const void* W1, const void* W2, const int* uniq, const int* u_dev,
-                 int64_t rows_max, void* A1, float* E, hipStream_t s, float* H_scatter, bool caller_wants_E)
+                 int64_t rows_max, void* A1, float* E, hipStream_t s, void* H_scatter, bool caller_wants_E)
 {
     if (rows_max <= 0) return false;
     const int d_in = c->cfg.d_in, dh = c->cfg.d_hidden, d = c->cfg.d;

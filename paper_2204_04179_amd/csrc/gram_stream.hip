@@ -101,16 +101,29 @@ void iota_i32(int* p, int64_t n, hipStream_t s)
 // and keep ordinary cached loads, which measured faster than streaming ones.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kGatherUnroll = 8;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+// One group of 4 columns of a row of H: float32 as it is, or rounded to bf16 (HB).
+template <bool HB>
+__device__ __forceinline__ void store_h4(void* __restrict__ H, int64_t group, f32x4 v)
+{
+    if (HB) {
+        const u32x2 h = {pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
+        __builtin_nontemporal_store(h, static_cast<u32x2*>(H) + group);
+    } else {
+        __builtin_nontemporal_store(v, static_cast<f32x4*>(H) + group);
+    }
+}
+
+template <bool HB>
 __global__ __launch_bounds__(kBlock) void k_gather_rows(const f32x4* __restrict__ E,
                                                         const int* __restrict__ inverse, int64_t m,
-                                                        int cols4, f32x4* __restrict__ H,
+                                                        int cols4, void* __restrict__ H,
                                                         int rows_per_block)
 {
     const int64_t p0 = (int64_t)blockIdx.x * rows_per_block;
     const int rows = (int)(p0 + rows_per_block < m ? rows_per_block : m - p0);
     const int total = rows * cols4;
-    f32x4* out = H + p0 * cols4;
     for (int e0 = 0; e0 < total; e0 += kBlock * kGatherUnroll) {
         int64_t src[kGatherUnroll];
 #pragma unroll
@@ -125,31 +138,35 @@ __global__ __launch_bounds__(kBlock) void k_gather_rows(const f32x4* __restrict_
             if (src[u] >= 0) v[u] = E[src[u]];
 #pragma unroll
         for (int u = 0; u < kGatherUnroll; ++u)
-            if (src[u] >= 0) __builtin_nontemporal_store(v[u], &out[e0 + u * kBlock + threadIdx.x]);
+            if (src[u] >= 0) store_h4<HB>(H, p0 * cols4 + e0 + u * kBlock + threadIdx.x, v[u]);
     }
 }
 
-void gather_rows(Ctx* c, const float* E, const int* inverse, int64_t m, float* H, hipStream_t s)
+void gather_rows(Ctx* c, const float* E, const int* inverse, int64_t m, void* H, hipStream_t s)
 {
     if (m == 0) return;
     const int cols4 = c->cfg.d / 4;
     int rows_per_block = (kGatherUnroll * kBlock + cols4 - 1) / cols4;
     if (rows_per_block < 1) rows_per_block = 1;
     const int64_t blocks = (m + rows_per_block - 1) / rows_per_block;
-    launch(c, KID_GATHER_ROWS, k_gather_rows, dim3((unsigned)blocks), dim3(kBlock), s,
-           reinterpret_cast<const f32x4*>(E), inverse, m, cols4, reinterpret_cast<f32x4*>(H),
-           rows_per_block);
+    if (c->cfg.h_dtype == GRAM_BF16)
+        launch(c, KID_GATHER_ROWS, k_gather_rows<true>, dim3((unsigned)blocks), dim3(kBlock), s,
+               reinterpret_cast<const f32x4*>(E), inverse, m, cols4, H, rows_per_block);
+    else
+        launch(c, KID_GATHER_ROWS, k_gather_rows<false>, dim3((unsigned)blocks), dim3(kBlock), s,
+               reinterpret_cast<const f32x4*>(E), inverse, m, cols4, H, rows_per_block);
 }
 
 // Second half of the fused forward: items with more than kLightMax positions were written to
 // E only; their rows are copied to their positions here.  Blocks walk the SORTED order (all
 // positions of an item adjacent), 64 rows each, and leave at once when none of their rows
 // belongs to such an item, so the row of E being copied stays in cache across many blocks.
+template <bool HB>
 __global__ __launch_bounds__(kBlock) void k_gather_heavy(const f32x4* __restrict__ E,
                                                          const int* __restrict__ seg_of_row,
                                                          const int* __restrict__ offsets,
                                                          const int* __restrict__ perm, int64_t m,
-                                                         int cols4, f32x4* __restrict__ H,
+                                                         int cols4, void* __restrict__ H,
                                                          int rows_per_block)
 {
     __shared__ int s_src[64], s_dst[64];
@@ -175,20 +192,23 @@ __global__ __launch_bounds__(kBlock) void k_gather_heavy(const f32x4* __restrict
                 v = E[(int64_t)j * cols4 + cp];
                 cur = j;
             }
-            __builtin_nontemporal_store(v, &H[(int64_t)s_dst[row] * cols4 + cp]);
+            store_h4<HB>(H, (int64_t)s_dst[row] * cols4 + cp, v);
         }
     }
 }
 
-void gather_heavy(Ctx* c, const float* E, int64_t m, float* H, hipStream_t s)
+void gather_heavy(Ctx* c, const float* E, int64_t m, void* H, hipStream_t s)
 {
     if (m == 0) return;
     const int cols4 = c->cfg.d / 4;
     const int rows_per_block = 64;      // the size of the kernel's row tables
     const int64_t blocks = (m + rows_per_block - 1) / rows_per_block;
-    launch(c, KID_GATHER_HEAVY, k_gather_heavy, dim3((unsigned)blocks), dim3(kBlock), s,
-           reinterpret_cast<const f32x4*>(E), c->seg_of_row, c->offsets, c->perm, m, cols4,
-           reinterpret_cast<f32x4*>(H), rows_per_block);
+    if (c->cfg.h_dtype == GRAM_BF16)
+        launch(c, KID_GATHER_HEAVY, k_gather_heavy<true>, dim3((unsigned)blocks), dim3(kBlock), s,
+               reinterpret_cast<const f32x4*>(E), c->seg_of_row, c->offsets, c->perm, m, cols4, H, rows_per_block);
+    else
+        launch(c, KID_GATHER_HEAVY, k_gather_heavy<false>, dim3((unsigned)blocks), dim3(kBlock), s,
+               reinterpret_cast<const f32x4*>(E), c->seg_of_row, c->offsets, c->perm, m, cols4, H, rows_per_block);
 }
 
 // ---- pseudo-targets (Algorithm 1 step 3, Eq. 6) and the pseudo-loss (Eq. 7) -------------

@@ -33,7 +33,7 @@ class GramConfig(C.Structure):
     _fields_ = [("vocab_n", C.c_int32), ("d_in", C.c_int32), ("d", C.c_int32),
                 ("max_positions", C.c_int64), ("k_steps", C.c_int32), ("pad_id", C.c_int32),
                 ("u_total_cap", C.c_int64), ("xw_dtype", C.c_int32), ("buffer_layout", C.c_int32),
-                ("d_hidden", C.c_int32)]
+                ("d_hidden", C.c_int32), ("h_dtype", C.c_int32)]
 
 
 class GramError(RuntimeError):
@@ -107,9 +107,9 @@ def load():
 
 
 def make_config(vocab_n, d_in, d, max_positions, k_steps=1, pad_id=0, u_total_cap=0, xw_dtype=BF16,
-                buffer_layout=0, d_hidden=0):
+                buffer_layout=0, d_hidden=0, h_dtype=F32):
     return GramConfig(int(vocab_n), int(d_in), int(d), int(max_positions), int(k_steps), int(pad_id),
-                      int(u_total_cap), int(xw_dtype), int(buffer_layout), int(d_hidden))
+                      int(u_total_cap), int(xw_dtype), int(buffer_layout), int(d_hidden), int(h_dtype))
 
 
 def workspace_bytes(cfg: GramConfig) -> int:

@@ -16,7 +16,7 @@ def to_dev(a, torch):
 def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=None, u_total_cap=0,
                keep_H=True, keep_E=True, want_G=True, gram_obj=None, X_dev=None, W_dev=None,
                pass_E=True, foreign_buffers=False, profile=None, pseudo=False, wgrad_chunks=None,
-               dense=False, resume=None):
+               dense=False, resume=None, h_bf16=False):
     """batches: list of (ids int32 [m], dH float32 [m,d]).  Returns dict with per-step
     uniq/inverse/counts/E/H and the window's uniq_total/counts_total/G_total/dW.
     pass_E=False calls gram_encode_gather with E = NULL (no "E" in the result);
@@ -28,7 +28,7 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
     and all of them accumulated into one matrix (key "dW_chunked").  dense=True selects the
     one-row-per-ID buffer and exports through gram_flush64 (counts_total is then int64);
     resume=(ids, counts int64, G rows float32) is merged into the window with gram_window_import
-    before the first step."""
+    before the first step.  h_bf16=True asks for H in bf16 (returned widened to float32)."""
     import torch
     from paper_2204_04179_amd import gram
 
@@ -36,7 +36,9 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
     xw = gram.F32 if X.dtype == np.float32 else gram.BF16
     K = k_steps or len(batches)
     M_max = max_positions or max(1, max(b[0].size for b in batches))
-    cfg = gram.make_config(vocab_n, d_in, d, M_max, K, pad_id, u_total_cap, xw, 1 if dense else 0)
+    cfg = gram.make_config(vocab_n, d_in, d, M_max, K, pad_id, u_total_cap, xw, 1 if dense else 0, 0,
+                           gram.BF16 if h_bf16 else gram.F32)
+    h_dt = torch.bfloat16 if h_bf16 else torch.float32
     g = gram_obj or gram.Gram(cfg)
     if profile:
         g.profile_enable(profile, max_launches=256)
@@ -56,7 +58,7 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
         inverse = torch.full((max(1, m),), -7, dtype=torch.int32, device="cuda")
         u_dev = torch.zeros(1, dtype=torch.int32, device="cuda")
         E = torch.full((cap_u, d), float("nan"), device="cuda")
-        H = torch.full((max(1, m), d), float("nan"), device="cuda")
+        H = torch.full((max(1, m), d), float("nan"), dtype=h_dt, device="cuda")
         U = g.unique(ids_d, uniq, inverse, counts, u_dev, want_host_u=True)
         assert int(u_dev.item()) == U
         uq, inv = (uniq.clone(), inverse.clone()) if foreign_buffers else (uniq, inverse)
@@ -65,7 +67,7 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
         if pseudo:
             Ht = torch.full((cap_u, d), float("nan"), device="cuda")
             loss = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda")
-            H2 = torch.full((max(1, m), d), float("nan"), device="cuda")
+            H2 = torch.full((max(1, m), d), float("nan"), dtype=h_dt, device="cuda")
             g.pseudo_target(E, Ht, loss)
             g.gather(Ht, inverse, m, H2)
         torch.cuda.synchronize()
@@ -75,9 +77,9 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
         if keep_E and pass_E:
             st["E"] = E[:U].cpu().numpy()
         if keep_H:
-            st["H"] = H[:m].cpu().numpy()
+            st["H"] = H[:m].float().cpu().numpy()
         if pseudo:
-            st["Ht"], st["loss"], st["H_tilde"] = Ht[:U].cpu().numpy(), float(loss.item()), H2[:m].cpu().numpy()
+            st["Ht"], st["loss"], st["H_tilde"] = Ht[:U].cpu().numpy(), float(loss.item()), H2[:m].float().cpu().numpy()
             st["Ht_tail_untouched"] = bool(torch.isnan(Ht[U:]).all().item())
         st["H_dev"], st["E_dev"], st["inverse_dev"] = H, E, inverse
         steps.append(st)

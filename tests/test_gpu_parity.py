@@ -830,6 +830,42 @@ def test_dense_buffer_argument_errors():
     dense.close()
 
 
+def bf16_round(a):
+    """float32 array rounded to bf16 (nearest even) and widened again."""
+    return wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(np.ascontiguousarray(a, dtype=np.float32)))
+
+
+@pytest.mark.parametrize("case", ["small", "fused", "fused_with_E", "foreign"])
+def test_positions_output_in_bf16(case):
+    """h_dtype = bf16: every way the forward reaches the positions (gather kernel, fused epilogue for
+    light items + copy kernel for heavy ones, gram_gather of pseudo-targets) stores exactly the
+    nearest-even bf16 of the float32 representation; E, G and dW are untouched by the option."""
+    if case == "small":
+        n, m, d_in, d = 2500, 7000, 32, 24
+        ids = None
+    else:
+        n, m, d_in, d = 70000, 70000, 64, 256
+        rng = np.random.default_rng(41)
+        ids = rng.integers(1, 3000, size=m).astype(np.int32)
+        ids[: m // 2] = rng.integers(1, n, size=m // 2)
+        ids[rng.random(m) < 0.05] = 0
+    ids, X, W, dH = small_problem(42, m, n, d_in=d_in, d=d, bf16=True, ids=ids)
+    say(f"bf16 H, {case}")
+    kw = dict(pass_E=case != "fused", foreign_buffers=case == "foreign", pseudo=case in ("small", "fused_with_E"))
+    out = run_window(X, W, [(ids, dH)], vocab_n=n, h_bf16=True, **kw)
+    base = run_window(X, W, [(ids, dH)], vocab_n=n, **kw)
+    st, st0 = out["steps"][0], base["steps"][0]
+    ref = orc.gram_single(ids, X, W, dH)
+    np.testing.assert_array_equal(st["H"], bf16_round(st0["H"]))            # pure rounding of the same values
+    assert_close(st["H"], ref["H"], 2.0 ** -8, "H (bf16)")
+    assert np.all(st["H"][ids == 0] == 0.0)
+    if "E" in st:
+        np.testing.assert_array_equal(st["E"], st0["E"])
+    if kw["pseudo"]:
+        np.testing.assert_array_equal(st["H_tilde"], bf16_round(st["Ht"])[ref["inverse"]])
+    assert out["G_total"].tobytes() == base["G_total"].tobytes() and out["dW"].tobytes() == base["dW"].tobytes()
+
+
 def test_window_captured_in_a_hip_graph_replays_like_eager():
     """The calls only enqueue kernels (no memset nodes, no host read-backs unless asked for), so a
     whole window can be captured once and replayed; every replay, with eager work and
