@@ -443,13 +443,14 @@ constexpr uint32_t kBufferFlags = 0x00027000;   // raw buffer: 32-bit elements, 
 struct ScatterArgs {
     const int* seg_off;   // [U + 1]
     const int* perm;      // [m] positions in sorted order
-    void* H;              // [m, ldh] float32, or bf16 with h_bf16
+    void* H;              // [m, ldh] float32, or bf16 with h_bf16 (selects the kernel's HB variant)
     int64_t ldh;
     int write_all;        // also store every row to C (the caller asked for E)
-    int h_bf16;           // H holds bf16: values are rounded to nearest even as they are stored
+    int h_bf16;
 };
 
-template <bool GATHER, int NW, bool SCATTER, int EPI = kEpiPlain>
+// HB (with SCATTER): H holds bf16, values are rounded to nearest even as they are stored.
+template <bool GATHER, int NW, bool SCATTER, int EPI = kEpiPlain, bool HB = false>
 __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
     const uint16_t* __restrict__ A, int64_t lda, uint32_t a_bytes, const int* __restrict__ row_ids,
     const int* __restrict__ m_dev, int m_host, const uint16_t* __restrict__ B, int64_t ldb,
@@ -680,7 +681,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
                     if (col_ok) *reinterpret_cast<f32x4*>(C + (int64_t)(m0 + lr) * ldc + n0 + lane * 4) = v[u];
                     if (cnt > kLightMax) continue;
                 }
-                if (sc.h_bf16) {
+                if (HB) {
                     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
                     const u32x2 h = {pack_bf16x2(v[u].x, v[u].y), pack_bf16x2(v[u].z, v[u].w)};
                     for (int t = 0; t < cnt; ++t) {
@@ -790,6 +791,8 @@ static void launch_gemm_nt(Ctx* c, int kid, const uint16_t* A, int64_t lda, int6
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)RSMEM);
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16<GATHER, kGemmWaves, GATHER>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)(GATHER ? RSMEM_SC : RSMEM));
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16<GATHER, kGemmWaves, GATHER, kEpiPlain, GATHER>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)(GATHER ? RSMEM_SC : RSMEM));
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16_dma<GATHER>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)TSMEM);
         attr_set = true;
@@ -814,7 +817,12 @@ static void launch_gemm_nt(Ctx* c, int kid, const uint16_t* A, int64_t lda, int6
         else
             launch_gemm_nt_epi<kEpiGate>(c, kid, (unsigned)blocks, s, A, lda, (uint32_t)a_bytes, row_ids, m_dev,
                                          m_host, B, ldb, (uint32_t)b_bytes, n, k_host, pad_id, n_tiles, C, ldc, aux);
-    } else if (scatter)
+    } else if (scatter && scatter->h_bf16)
+        launch_smem(c, kid, k_gemm_nt_bf16<GATHER, kGemmWaves, GATHER, kEpiPlain, GATHER>, dim3((unsigned)blocks),
+                    dim3(kGemmWaves * 64), GATHER ? RSMEM_SC : RSMEM, s, A, lda, (uint32_t)a_bytes, row_ids,
+                    m_dev, m_host, B, ldb, (uint32_t)b_bytes, n, k_dev, k_host, splits, pad_id,
+                    n_tiles, C, ldc, split_stride, *scatter, (const void*)nullptr);
+    else if (scatter)
         launch_smem(c, kid, k_gemm_nt_bf16<GATHER, kGemmWaves, GATHER>, dim3((unsigned)blocks),
                     dim3(kGemmWaves * 64), GATHER ? RSMEM_SC : RSMEM, s, A, lda, (uint32_t)a_bytes, row_ids,
                     m_dev, m_host, B, ldb, (uint32_t)b_bytes, n, k_dev, k_host, splits, pad_id,
