@@ -240,9 +240,9 @@ def cpu_baseline(r, target_s=12.0):
     # the cost per history falls as the sample grows (more repeats per unique item), so the sample is
     # grown in up to three rounds towards target_s of oracle time
     for _ in range(3):
-        if rows >= w.B or t >= target_s / 2:
+        if rows >= w.B or t >= 0.8 * target_s:
             break
-        rows = int(min(w.B, max(rows + 1, rows * target_s / max(t, 1e-3) * 0.8)))
+        rows = int(min(w.B, max(rows + 1, rows * target_s / max(t, 1e-3))))
         t, occ = run(rows)
     return dict(value=occ / t, unit="occurrences/s", cores=orc.num_threads(), kind="oracle",
                 sample=f"first {rows} of {w.B} histories of each of the K={w.K} steps of one window "
