@@ -490,3 +490,43 @@ int oracle_mlp_grad(const int32_t *item, int64_t n_items, int32_t vocab_n, int32
     free(z); free(dz);
     return 0;
 }
+
+/*
+ * Selected entries of the two-layer encoder's weight gradients, for sizes where
+ * the full backward pass is too slow on a CPU:
+ *   out1[t] = dW1[i1[t], q1[t]] = sum_j X[item[j], i1] * [z_j[q1] > 0] * (R_j . W2[q1,:])
+ *   out2[t] = dW2[q2[t], c2[t]] = sum_j max(z_j[q2], 0) * R[j, c2]
+ * with z_j[q] = X[item[j],:] . W1[:,q]; padding items are skipped.
+ */
+int oracle_mlp_grad_entries(const int32_t *item, int64_t n_items, int32_t vocab_n, int32_t pad_id,
+                            const void *X, const void *W1, const void *W2, int xw_dtype, int32_t d_in,
+                            int32_t d_hid, int32_t d, const double *R, const int32_t *i1,
+                            const int32_t *q1, int64_t n1, double *out1, const int32_t *q2,
+                            const int32_t *c2, int64_t n2, double *out2)
+{
+    for (int64_t j = 0; j < n_items; ++j)
+        if (item[j] < 0 || item[j] >= vocab_n) return -2;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t t = 0; t < n1 + n2; ++t) {
+        const int first = t < n1;
+        const int32_t q = first ? q1[t] : q2[t - n1];
+        double acc = 0.0;
+        for (int64_t j = 0; j < n_items; ++j) {
+            if (item[j] == pad_id) continue;
+            double z = 0.0;
+            for (int32_t k = 0; k < d_in; ++k)
+                z += xw_at(X, xw_dtype, (int64_t)item[j] * d_in + k) * xw_at(W1, xw_dtype, (int64_t)k * d_hid + q);
+            if (first) {
+                if (z > 0.0) {
+                    double da = 0.0;
+                    for (int32_t c = 0; c < d; ++c) da += R[j * d + c] * xw_at(W2, xw_dtype, (int64_t)q * d + c);
+                    acc += xw_at(X, xw_dtype, (int64_t)item[j] * d_in + i1[t]) * da;
+                }
+            } else if (z > 0.0) {
+                acc += z * R[j * d + c2[t - n1]];
+            }
+        }
+        if (first) out1[t] = acc; else out2[t - n1] = acc;
+    }
+    return 0;
+}

@@ -79,6 +79,10 @@ def lib():
         L.oracle_mlp_grad.restype = C.c_int
         L.oracle_mlp_grad.argtypes = [i32p, C.c_int64, C.c_int32, C.c_int32, vp, vp, vp, C.c_int, C.c_int32,
                                       C.c_int32, C.c_int32, f64p, f64p, f64p]
+        L.oracle_mlp_grad_entries.restype = C.c_int
+        L.oracle_mlp_grad_entries.argtypes = [i32p, C.c_int64, C.c_int32, C.c_int32, vp, vp, vp, C.c_int, C.c_int32,
+                                              C.c_int32, C.c_int32, f64p, i32p, i32p, C.c_int64, f64p, i32p, i32p,
+                                              C.c_int64, f64p]
         L.oracle_buffer_add64.restype = C.c_int
         L.oracle_buffer_add64.argtypes = [vp, i32p, i64p, f64p, C.c_int64]
         L.oracle_buffer_export.restype = C.c_int
@@ -275,6 +279,22 @@ def mlp_grad(item, X, W1, W2, R, pad_id=0):
                                  W1.ctypes.data, W2.ctypes.data, dt, d_in, d_hid, d, _p(R, C.c_double),
                                  _p(dW1, C.c_double), _p(dW2, C.c_double)), "mlp_grad")
     return dW1, dW2
+
+
+def mlp_grad_entries(item, X, W1, W2, R, i1, q1, q2, c2, pad_id=0):
+    """float64 (dW1[i1[t], q1[t]], dW2[q2[t], c2[t]]) of mlp_grad without forming the matrices."""
+    item, X, W1, W2, dt = _mlp_args(item, X, W1, W2)
+    (d_in, d_hid), d = W1.shape, W2.shape[1]
+    R = np.ascontiguousarray(R, dtype=np.float64)
+    assert R.shape == (item.size, d)
+    i1, q1, q2, c2 = (np.ascontiguousarray(a, dtype=np.int32) for a in (i1, q1, q2, c2))
+    out1, out2 = np.empty(i1.size, np.float64), np.empty(q2.size, np.float64)
+    _check(lib().oracle_mlp_grad_entries(_p(item, C.c_int32), item.size, X.shape[0], pad_id, X.ctypes.data,
+                                         W1.ctypes.data, W2.ctypes.data, dt, d_in, d_hid, d, _p(R, C.c_double),
+                                         _p(i1, C.c_int32), _p(q1, C.c_int32), i1.size, _p(out1, C.c_double),
+                                         _p(q2, C.c_int32), _p(c2, C.c_int32), q2.size, _p(out2, C.c_double)),
+           "mlp_grad_entries")
+    return out1, out2
 
 
 def mlp_e2e(ids, X, W1, W2, dH, pad_id=0):

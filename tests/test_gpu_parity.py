@@ -70,14 +70,24 @@ def test_paper_shaped_workloads_match_oracle(name):
         assert_close(ref["dW"], dW_e2e, 1e-12, "oracle GRAM vs oracle E2E")
 
 
+_STRESS = {}
+
+
+def stress_inputs():
+    """(workload, X, W) of the stress configuration, drawn once per test process (2 GB, half a minute)."""
+    if not _STRESS:
+        w = wl.get("stress")
+        _STRESS["v"] = (w, wl.features(w), wl.weights(w))
+    return _STRESS["v"]
+
+
 def test_stress_workload_sampled_against_oracle():
     """Full-size large configuration in the launch shape the benchmark times;
     integer outputs are compared in full, float outputs on sampled rows/entries
     the oracle computes one by one, plus size-independent properties."""
     import torch
-    w = wl.get("stress")
+    w, X, W = stress_inputs()
     say(f"workload stress: M={w.M} N={w.N} d_in={w.d_in} d={w.d} K={w.K}")
-    X, W = wl.features(w), wl.weights(w)
     say("   inputs drawn")
     rng = np.random.default_rng(7)
     batches = [(wl.ids(w, k).reshape(-1), wl.upstream_grad(w, k)) for k in range(w.K)]
@@ -112,6 +122,71 @@ def test_stress_workload_sampled_against_oracle():
     err = np.abs(dW[rows, cols] - ref).max() / scale
     say(f"   U_total={ids_t.size} G err={e[0]:.2e} dW sampled err={err:.2e}")
     assert np.all(np.isfinite(dW)) and err <= TOL[wl.BF16]
+
+
+def test_encoder_update_rows_at_the_stress_shape_sampled_against_oracle():
+    """The content-encoder batch calls in the launch configuration the benchmark times (stress
+    vocabulary and widths, batches of 32,768 items): outputs are compared on sampled rows and
+    entries that the oracle computes one by one."""
+    import torch
+    from paper_2204_04179_amd import gram
+    from harness import to_dev
+    w, X, W = stress_inputs()
+    say("stress-shaped encoder batches: inputs drawn")
+    rng = np.random.default_rng(11)
+    n = 32768
+    items = np.sort(rng.choice(np.arange(0, w.N), size=n, replace=False)).astype(np.int32)
+    items[0] = 0                                                   # the padding item is in the batch
+    Xd, Wd = to_dev(X, torch), to_dev(W, torch)
+    items_d = torch.from_numpy(items).cuda()
+    rows_s = np.sort(rng.choice(n, size=96, replace=False))
+    cols_s = np.sort(rng.choice(w.d, size=24, replace=False))
+    W_sub = np.ascontiguousarray(W[:, cols_s])
+
+    # --- linear encoder: regression towards stored targets
+    Ht = rng.standard_normal((n, w.d)).astype(np.float32)
+    g = gram.Gram(gram.make_config(w.N, w.d_in, w.d, w.M, w.K, 0, 0, gram.BF16))
+    R = torch.full((n, w.d), float("nan"), device="cuda")
+    dW = torch.full((w.d_in, w.d), float("nan"), device="cuda")
+    g.pseudo_loss_grad(Xd, Wd, items_d, torch.from_numpy(Ht).cuda(), n, R, dW)
+    g.check()
+    miss_rows = orc.pseudo_loss_grad(items[rows_s], X, W, Ht[rows_s].astype(np.float64))[0]
+    assert_close(R[torch.from_numpy(rows_s).cuda()].cpu().numpy(), miss_rows, TOL_SUM[wl.BF16], "R sample")
+    miss_cols = orc.encode(items, X, W_sub, 0) - Ht[:, cols_s].astype(np.float64)   # all items, sampled columns
+    miss_cols[items == 0] = 0.0
+    ii = rng.integers(0, w.d_in, size=600).astype(np.int32)
+    cc = rng.integers(0, cols_s.size, size=600).astype(np.int32)
+    ref = orc.wgrad_entries(items, X, miss_cols, 0, ii, cc)
+    got = dW.cpu().numpy()[ii, cols_s[cc]]
+    err = np.abs(got - ref).max() / np.abs(ref).max()
+    say(f"   linear: dW sampled err={err:.2e}")
+    assert err <= TOL[wl.BF16]
+    g.close()
+    del R, dW
+
+    # --- two-layer encoder: backward from gradient rows
+    d_hid = 1024
+    W1 = wl.f32_to_bf16_bits((rng.standard_normal((w.d_in, d_hid)) / np.sqrt(w.d_in)).astype(np.float32))
+    W2 = wl.f32_to_bf16_bits((rng.standard_normal((d_hid, w.d)) / np.sqrt(d_hid)).astype(np.float32))
+    G_rows = rng.standard_normal((n, w.d)).astype(np.float32)
+    G_rows[0] = 0.0
+    g = gram.Gram(gram.make_config(w.N, w.d_in, w.d, w.M, w.K, 0, 0, gram.BF16, 0, d_hid))
+    work = torch.empty(g.mlp_batch_bytes(n), dtype=torch.uint8, device="cuda")
+    dW1 = torch.full((w.d_in, d_hid), float("nan"), device="cuda")
+    dW2 = torch.full((d_hid, w.d), float("nan"), device="cuda")
+    g.mlp_backward(Xd, to_dev(W1, torch), to_dev(W2, torch), items_d, torch.from_numpy(G_rows).cuda(), None, n,
+                   work, dW1, dW2)
+    g.check()
+    k = 160
+    i1, q1 = rng.integers(0, w.d_in, size=k), rng.integers(0, d_hid, size=k)
+    q2, c2 = rng.integers(0, d_hid, size=k), rng.integers(0, w.d, size=k)
+    r1, r2 = orc.mlp_grad_entries(items, X, W1, W2, G_rows.astype(np.float64), i1, q1, q2, c2)
+    e1 = np.abs(dW1.cpu().numpy()[i1, q1] - r1).max() / np.abs(r1).max()
+    e2 = np.abs(dW2.cpu().numpy()[q2, c2] - r2).max() / np.abs(r2).max()
+    say(f"   two-layer: dW1 sampled err={e1:.2e} dW2 sampled err={e2:.2e}")
+    assert e1 <= TOL[wl.BF16] and e2 <= TOL[wl.BF16]
+    assert bool(torch.isfinite(dW1).all()) and bool(torch.isfinite(dW2).all())
+    g.close()
 
 
 # ---------------------------------------------------------------- edge cases --

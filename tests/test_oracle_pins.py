@@ -562,6 +562,16 @@ def test_mlp_gradients_are_the_derivative_of_an_independent_loss():
                 assert abs(num - dW[i, c]) <= 1e-6 * max(1.0, abs(num)), (first, i, c)
 
 
+def test_mlp_gradient_entries_are_entries_of_the_full_gradient():
+    ids, X, W1, W2, dH = mlp_problem(93, m=70, bf16=True)
+    dW1, dW2 = orc.mlp_grad(ids, X, W1, W2, dH.astype(np.float64))
+    ii, qq = np.meshgrid(np.arange(5), np.arange(7), indexing="ij")
+    q2, cc = np.meshgrid(np.arange(7), np.arange(3), indexing="ij")
+    e1, e2 = orc.mlp_grad_entries(ids, X, W1, W2, dH.astype(np.float64), ii.ravel(), qq.ravel(), q2.ravel(), cc.ravel())
+    np.testing.assert_allclose(e1.reshape(5, 7), dW1, rtol=0, atol=1e-12 * np.abs(dW1).max())
+    np.testing.assert_allclose(e2.reshape(7, 3), dW2, rtol=0, atol=1e-12 * np.abs(dW2).max())
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 def test_mlp_gram_equals_end_to_end(bf16):
     """Section 4.1 / Proposition for an encoder that is not linear: one backward pass per unique item
