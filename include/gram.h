@@ -25,6 +25,13 @@
  *   gram_pseudo_loss_grad step 4 as a regression towards stored pseudo-targets,
  *                         one content-encoder batch at a time, at the encoder's
  *                         current weights (optional)
+ *   gram_encoder_wgrad_chunk  the weight gradient over a range of the window's
+ *                         items (content-encoder batches; optional)
+ *   gram_flush64, gram_window_import   64-bit counts and save / resume of a
+ *                         window kept in the dense one-row-per-ID buffer
+ *                         (cfg.buffer_layout; windows of epoch length)
+ *   gram_mlp_encode_gather, gram_mlp_backward   steps 1 and 4 with a two-layer
+ *                         stand-in encoder (cfg.d_hidden > 0)
  *
  * Memory.  Every pointer marked DEVICE is memory of the current HIP device,
  * owned by the caller (the library never frees, reallocates or keeps it beyond
