@@ -515,6 +515,18 @@ def mlp_problem(seed, m=60, n=19, d_in=5, d_hid=7, d=3, bf16=False):
     return ids, X, W1, W2, dH
 
 
+def test_mlp_hand_example(golden_dir):
+    ex = json.load(open(os.path.join(golden_dir, "mlp_hand_example.json")))
+    f32 = lambda k: np.array(ex[k], np.float32)
+    items = np.array(ex["items"], np.int32)
+    A1, E = orc.mlp_encode(items, f32("X"), f32("W1"), f32("W2"), ex["pad_id"])
+    np.testing.assert_array_equal(A1, np.array(ex["A1"], float))
+    np.testing.assert_array_equal(E, np.array(ex["E"], float))
+    dW1, dW2 = orc.mlp_grad(items, f32("X"), f32("W1"), f32("W2"), np.array(ex["R"], float), ex["pad_id"])
+    np.testing.assert_array_equal(dW1, np.array(ex["dW1"], float))
+    np.testing.assert_array_equal(dW2, np.array(ex["dW2"], float))
+
+
 def test_mlp_encoder_matches_numpy_and_reduces_to_the_linear_encoder():
     ids, X, W1, W2, dH = mlp_problem(90)
     A1, E = orc.mlp_encode(ids, X, W1, W2)
