@@ -876,6 +876,53 @@ def test_dense_buffer_window_saved_and_resumed_and_wide_counts():
     assert g.flush64(u, None, None, None, want_host_u=True) == 0   # empty again
 
 
+def test_dense_buffer_window_of_two_thousand_steps():
+    """An accumulation period in the thousands (the half-epoch / one-epoch periods of the
+    experiments): 2,000 mini-batches into the one-row-per-ID buffer, then one weight gradient and
+    one export, against the oracle's window."""
+    import torch
+    from paper_2204_04179_amd import gram
+    K, n, d_in, d, m = 2000, 3000, 16, 8, 512
+    rng = np.random.default_rng(950)
+    X = rng.standard_normal((n, d_in)).astype(np.float32)
+    W = (rng.standard_normal((d_in, d)) / 4).astype(np.float32)
+    ids_all = rng.zipf(1.3, size=(K, m)).astype(np.int64) % n          # popular items recur in every batch
+    ids_all[rng.random((K, m)) < 0.1] = 0
+    ids_all = ids_all.astype(np.int32)
+    dH_all = rng.standard_normal((K, m, d)).astype(np.float32)
+    say("dense window of 2000 steps")
+    g = gram.Gram(gram.make_config(n, d_in, d, m, K, 0, 0, gram.F32, 1))
+    Xd, Wd = torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda()
+    ids_d, dH_d = torch.from_numpy(ids_all).cuda(), torch.from_numpy(dH_all).cuda()
+    i32 = dict(dtype=torch.int32, device="cuda")
+    uniq, counts, inverse, u_dev = torch.empty(m, **i32), torch.empty(m, **i32), torch.empty(m, **i32), torch.zeros(1, **i32)
+    H = torch.empty(m, d, device="cuda")
+    for k in range(K):
+        g.unique(ids_d[k], uniq, inverse, counts, u_dev)
+        g.encode_gather(Xd, Wd, uniq, inverse, u_dev, m, None, H)
+        g.grad_accumulate(dH_d[k], m, k)
+    dW = torch.empty(d_in, d, device="cuda")
+    g.encoder_wgrad(Xd, dW)
+    ut, ct = torch.empty(n, **i32), torch.empty(n, dtype=torch.int64, device="cuda")
+    Gt = torch.empty(n, d, device="cuda")
+    u_total = g.flush64(ut, ct, Gt, None, want_host_u=True)
+    mm = orc.GramMulti(X, W)
+    for k in range(K):
+        uq, inv, cnt = orc.unique(ids_all[k], n)
+        Gk = orc.grad_accumulate(dH_all[k], inv, uq, 0)
+        orc._check(orc.lib().oracle_buffer_add(mm._buf, orc._p(uq, orc.C.c_int32), orc._p(cnt, orc.C.c_int32),
+                                               orc._p(Gk, orc.C.c_double), uq.size), "buffer_add")
+    ref = mm.finish()
+    assert u_total == ref["uniq"].size
+    np.testing.assert_array_equal(ut[:u_total].cpu().numpy(), ref["uniq"])
+    np.testing.assert_array_equal(ct[:u_total].cpu().numpy(), ref["counts"])
+    assert int(ref["counts"].sum()) == K * m
+    # 2,000 float32 additions per row in a fixed order against float64: a few 1e-6 relative at most
+    assert_close(Gt[:u_total].cpu().numpy(), ref["G"], 2e-5, "G after 2000 steps")
+    assert_close(dW.cpu().numpy(), ref["dW"], 2e-5, "dW after 2000 steps")
+    g.close()
+
+
 def test_dense_buffer_argument_errors():
     import torch
     from paper_2204_04179_amd import gram
