@@ -301,25 +301,28 @@ int gram_pseudo_loss_grad(gram_ctx* ctx, const void* X, const void* W, const int
 int gram_flush(gram_ctx* ctx, int32_t* uniq_total, int32_t* counts_total, float* G_total,
                int32_t* u_total_dev, int32_t* u_total_host, void* stream);
 
-/* gram_flush for the dense buffer with the counts in 64 bits (an epoch-long
- * window can meet one item, the padding item above all, more than 2^31 times;
- * gram_flush itself saturates such a count at INT32_MAX).  Same arguments
- * otherwise; the output buffers need room for N items.
- * GRAM_ERR_UNIMPLEMENTED for the slot-table layout. */
+/* gram_flush with the counts in 64 bits.  The dense buffer keeps 64-bit counts
+ * (an epoch-long window can meet one item, the padding item above all, more
+ * than 2^31 times; gram_flush itself saturates such a count at INT32_MAX); the
+ * slot table keeps 32-bit counts, which are widened here.  Same arguments
+ * otherwise; with the dense buffer the outputs need room for N items. */
 int gram_flush64(gram_ctx* ctx, int32_t* uniq_total, int64_t* counts_total, float* G_total,
                  int32_t* u_total_dev, int32_t* u_total_host, void* stream);
 
-/* Merge a saved window state into the dense buffer, e.g. what gram_flush64
- * exported before an interruption: counts[j] is added to the count of ids[j]
- * and, if given, G_rows[j,:] to its gradient row.  A window saved after some
+/* Merge a saved window state into the buffer, e.g. what gram_flush64 exported
+ * before an interruption: counts[j] is added to the count of ids[j] and, if
+ * given, G_rows[j,:] to its gradient row.  A window saved after some
  * steps, imported and continued ends like the uninterrupted window (Section
  * 4.2: the buffer is the whole state of a window).
  *   ids     DEVICE [n] int32    distinct IDs (any order); an ID outside [0,N)
  *                               latches GRAM_ERR_RANGE and is skipped
  *   counts  DEVICE [n] int64    G_rows  DEVICE [n,d], nullable
+ *   n       at most the rows of the buffer (N for the dense layout)
  * Does not count as a step (the next gram_grad_accumulate keeps its index) but
- * makes the window non-empty for gram_encoder_wgrad.
- * GRAM_ERR_UNIMPLEMENTED for the slot-table layout. */
+ * makes the window non-empty for gram_encoder_wgrad.  Slot table: items the
+ * window has not met take rows in list order (GRAM_ERR_CAPACITY latched when
+ * the buffer is full), counts saturate at INT32_MAX.  Uses the workspace of the
+ * content-encoder batch calls (gram_pseudo_loss_grad, gram_mlp_backward). */
 int gram_window_import(gram_ctx* ctx, const int32_t* ids, const int64_t* counts, const float* G_rows,
                        int64_t n, void* stream);
 

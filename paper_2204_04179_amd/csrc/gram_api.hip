@@ -514,7 +514,8 @@ static int flush_any(Ctx* c, int32_t* uniq_total, int32_t* counts_total, int64_t
         flush_dense(c, uniq_total, counts_total, reinterpret_cast<long long*>(counts64_total), G_total,
                     u_total_dev, s);
     else
-        flush_export(c, uniq_total, counts_total, G_total, u_total_dev, s);
+        flush_export(c, uniq_total, counts_total, reinterpret_cast<long long*>(counts64_total), G_total,
+                     u_total_dev, s);
     c->have_unique = false;     // the sort buffers were reused
     c->steps_done = 0;
     c->window_positions = 0;
@@ -541,8 +542,6 @@ int gram_flush64(gram_ctx* ctx, int32_t* uniq_total, int64_t* counts_total, floa
 {
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     if (!c) return GRAM_ERR_ARG;
-    if (!c->dense)
-        return fail(c, GRAM_ERR_UNIMPLEMENTED, "gram_flush64: 64-bit counts are kept by the dense buffer only");
     return flush_any(c, uniq_total, nullptr, counts_total, G_total, u_total_dev, u_total_host,
                      static_cast<hipStream_t>(stream), "gram_flush64");
 }
@@ -552,14 +551,18 @@ int gram_window_import(gram_ctx* ctx, const int32_t* ids, const int64_t* counts,
 {
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     if (!c) return GRAM_ERR_ARG;
-    if (!c->dense)
-        return fail(c, GRAM_ERR_UNIMPLEMENTED, "gram_window_import: available for the dense buffer only");
-    if (n < 0 || n > c->cfg.vocab_n)
-        return fail(c, GRAM_ERR_ARG, "gram_window_import: n = %lld outside [0, vocab_n]", (long long)n);
+    const int64_t n_max = c->dense ? c->cfg.vocab_n : c->cap_total;
+    if (n < 0 || n > n_max)
+        return fail(c, GRAM_ERR_ARG, "gram_window_import: n = %lld outside [0, %lld]", (long long)n,
+                    (long long)n_max);
     if (n > 0 && (!ids || !counts)) return fail(c, GRAM_ERR_ARG, "gram_window_import: NULL pointer");
-    import_dense(c, ids, reinterpret_cast<const long long*>(counts), G_rows, n, static_cast<hipStream_t>(stream));
+    if (c->dense)
+        import_dense(c, ids, reinterpret_cast<const long long*>(counts), G_rows, n, static_cast<hipStream_t>(stream));
+    else
+        import_slots(c, ids, reinterpret_cast<const long long*>(counts), G_rows, n, static_cast<hipStream_t>(stream));
     if (int rc = launch_status(c, "gram_window_import")) return rc;
     c->window_imported = true;
+    c->window_positions += n;      // host bound on the rows in the buffer (sizes the split-K of the weight gradient)
     return GRAM_OK;
 }
 

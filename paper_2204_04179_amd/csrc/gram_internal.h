@@ -124,7 +124,7 @@ struct Ctx {
     const int* last_uniq = nullptr;      // outputs of the most recent gram_unique (identity only)
     const int* last_inverse = nullptr;
     bool unique_consumed = false;  // the current batch was already accumulated
-    bool window_imported = false;  // a saved state was merged into this window (dense layout)
+    bool window_imported = false;  // a saved state was merged into this window
     int64_t cur_m = 0;
     int32_t steps_done = 0;
     int64_t window_positions = 0;  // positions accumulated in this window: bounds the buffer rows
@@ -183,7 +183,9 @@ void chunk_ids_prepare(Ctx* c, const int* ids, int64_t n, hipStream_t s);
 void pseudo_miss(Ctx* c, float* R, const float* Ht, int64_t n, double* loss_dev, hipStream_t s);
 void assign_slots(Ctx* c, hipStream_t s);
 void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s);
-void flush_export(Ctx* c, int* uniq_total, int* counts_total, float* G_total, int* u_total_dev,
+void flush_export(Ctx* c, int* uniq_total, int* counts_total, long long* counts64_total, float* G_total,
+                  int* u_total_dev, hipStream_t s);
+void import_slots(Ctx* c, const int* ids, const long long* counts, const float* rows, int64_t n,
                   hipStream_t s);
 void flush_dense(Ctx* c, int* uniq_total, int* counts_total, long long* counts64_total, float* G_total,
                  int* u_total_dev, hipStream_t s);

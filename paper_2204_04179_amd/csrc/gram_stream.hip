@@ -535,7 +535,7 @@ void assign_slots(Ctx* c, hipStream_t s)
                c->uniq_ws, c->offsets, c->scal, c->cnt64, c->seg_slot, c->cfg.vocab_n);
         return;
     }
-    const int first_step = c->steps_done == 0 ? 1 : 0;
+    const int first_step = (c->steps_done == 0 && !c->window_imported) ? 1 : 0;
     if (bound <= kSmallBatch) {
         launch(c, KID_SLOT_EMIT, k_slot_small, dim3(1), dim3(kSlotSmallThreads), s, c->uniq_ws, c->offsets, c->slot_of,
                c->id_of_slot, c->cnt_of_slot, c->seg_slot, c->scal, (int)c->cap_total, first_step);
@@ -746,22 +746,26 @@ void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s)
 
 __device__ __forceinline__ void flush_meta_row(int r, const int* sorted_ids, const int* sorted_slots,
                                                const int* cnt_of_slot, int* slot_of, int* uniq_total,
-                                               int* counts_total)
+                                               int* counts_total, long long* counts64_total)
 {
     const int id = sorted_ids[r];
+    const int cnt = cnt_of_slot[sorted_slots ? sorted_slots[r] : r];
     if (uniq_total) uniq_total[r] = id;
-    if (counts_total) counts_total[r] = cnt_of_slot[sorted_slots ? sorted_slots[r] : r];
+    if (counts_total) counts_total[r] = cnt;
+    if (counts64_total) counts64_total[r] = cnt;
     slot_of[id] = -1;
 }
 
 __global__ __launch_bounds__(kBlock) void k_flush_meta(
     const int* __restrict__ sorted_ids, const int* __restrict__ sorted_slots,
     const int* __restrict__ cnt_of_slot, int* __restrict__ slot_of, int* __restrict__ uniq_total,
-    int* __restrict__ counts_total, int* __restrict__ scal, int* __restrict__ u_total_dev, int n_zero)
+    int* __restrict__ counts_total, long long* __restrict__ counts64_total, int* __restrict__ scal,
+    int* __restrict__ u_total_dev, int n_zero)
 {
     const int n = n_zero ? 0 : scal[kSUTotal];
     for (int r = blockIdx.x * kBlock + threadIdx.x; r < n; r += gridDim.x * kBlock)
-        flush_meta_row(r, sorted_ids, sorted_slots, cnt_of_slot, slot_of, uniq_total, counts_total);
+        flush_meta_row(r, sorted_ids, sorted_slots, cnt_of_slot, slot_of, uniq_total, counts_total,
+                       counts64_total);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         if (u_total_dev) *u_total_dev = n;
         scal[kSFlushN] = n;
@@ -773,15 +777,16 @@ __global__ __launch_bounds__(kBlock) void k_flush_meta(
 __global__ __launch_bounds__(kBlock) void k_flush_rows(
     const int* __restrict__ sorted_ids, const int* __restrict__ sorted_slots,
     const int* __restrict__ cnt_of_slot, int* __restrict__ slot_of, int* __restrict__ uniq_total,
-    int* __restrict__ counts_total, const float4* __restrict__ G, int cols4,
-    float4* __restrict__ G_total, int* __restrict__ scal, int* __restrict__ u_total_dev,
-    int copy_blocks)
+    int* __restrict__ counts_total, long long* __restrict__ counts64_total,
+    const float4* __restrict__ G, int cols4, float4* __restrict__ G_total, int* __restrict__ scal,
+    int* __restrict__ u_total_dev, int copy_blocks)
 {
     const int n = scal[kSUTotal];
     if ((int)blockIdx.x >= copy_blocks) {
         const int mb = blockIdx.x - copy_blocks, nmb = gridDim.x - copy_blocks;
         for (int r = mb * kBlock + threadIdx.x; r < n; r += nmb * kBlock)
-            flush_meta_row(r, sorted_ids, sorted_slots, cnt_of_slot, slot_of, uniq_total, counts_total);
+            flush_meta_row(r, sorted_ids, sorted_slots, cnt_of_slot, slot_of, uniq_total, counts_total,
+                           counts64_total);
         if (mb == 0 && threadIdx.x == 0) {
             if (u_total_dev) *u_total_dev = n;
             scal[kSFlushN] = n;
@@ -799,19 +804,19 @@ __global__ __launch_bounds__(kBlock) void k_flush_rows(
     }
 }
 
-void flush_export(Ctx* c, int* uniq_total, int* counts_total, float* G_total, int* u_total_dev,
-                  hipStream_t s)
+void flush_export(Ctx* c, int* uniq_total, int* counts_total, long long* counts64_total, float* G_total,
+                  int* u_total_dev, hipStream_t s)
 {
-    if (c->steps_done == 0) {       // nothing accumulated since the last flush
+    if (c->steps_done == 0 && !c->window_imported) {       // nothing accumulated since the last flush
         launch(c, KID_FLUSH_META, k_flush_meta, dim3(1), dim3(kBlock), s, c->id_of_slot, (const int*)nullptr,
-               c->cnt_of_slot, c->slot_of, uniq_total, counts_total, c->scal, u_total_dev, 1);
+               c->cnt_of_slot, c->slot_of, uniq_total, counts_total, counts64_total, c->scal, u_total_dev, 1);
         return;
     }
     // After one step the buffer rows are already in ascending ID order (rows are handed out in
     // that order within a step); only later steps append out of order.
     const int* sorted_ids = c->id_of_slot;
     const int* sorted_slots = nullptr;
-    if (c->steps_done > 1) {
+    if (c->steps_done > 1 || c->window_imported) {
         const int r = radix_sort_pairs(c, c->id_of_slot, nullptr, 0, c->scal + kSUTotal, c->cap_total,
                                        false, 0, s);
         sorted_ids = c->keys[r];
@@ -823,15 +828,115 @@ void flush_export(Ctx* c, int* uniq_total, int* counts_total, float* G_total, in
         int64_t meta_blocks = (c->cap_total + kBlock - 1) / kBlock;
         if (meta_blocks > 64) meta_blocks = 64;
         launch(c, KID_FLUSH_ROWS, k_flush_rows, dim3((unsigned)(blocks + meta_blocks)), dim3(kBlock), s, sorted_ids,
-               sorted_slots, c->cnt_of_slot, c->slot_of, uniq_total, counts_total,
+               sorted_slots, c->cnt_of_slot, c->slot_of, uniq_total, counts_total, counts64_total,
                reinterpret_cast<const float4*>(c->G), c->cfg.d / 4, reinterpret_cast<float4*>(G_total), c->scal,
                u_total_dev, (int)blocks);
     } else {
         int64_t blocks = (c->cap_total + kBlock - 1) / kBlock;
         if (blocks > 1024) blocks = 1024;
         launch(c, KID_FLUSH_META, k_flush_meta, dim3((unsigned)blocks), dim3(kBlock), s, sorted_ids,
-               sorted_slots, c->cnt_of_slot, c->slot_of, uniq_total, counts_total, c->scal, u_total_dev, 0);
+               sorted_slots, c->cnt_of_slot, c->slot_of, uniq_total, counts_total, counts64_total, c->scal,
+               u_total_dev, 0);
     }
+}
+
+// ---- slot table: a saved window state merged into the buffer ----------------------------
+//
+// One block walks the listed items in tiles of 4096 exactly as k_slot_small walks the items of a
+// batch: an item the window has not met takes the next free row (in list order), an item it has
+// met keeps its row; the saved count is added (32-bit rows: a count beyond INT32_MAX saturates).
+// code[j] receives the row (kSlotNew set for a fresh row, -1 when the buffer is full or the ID is
+// outside [0, N)); k_import_rows then writes or adds the saved gradient rows.
+__global__ __launch_bounds__(kSlotSmallThreads) void k_slot_import(
+    const int* __restrict__ ids, const long long* __restrict__ counts, int n, int vocab_n,
+    int* __restrict__ slot_of, int* __restrict__ id_of_slot, int* __restrict__ cnt_of_slot,
+    int* __restrict__ code, int* __restrict__ scal, int cap_total, int first_touch)
+{
+    __shared__ int sm[kSlotSmallThreads / kWave];
+    int run_base = first_touch ? 0 : scal[kSUTotal];
+    int err = 0;
+    const int t4 = (int)threadIdx.x * 4;
+    for (int j0 = t4; j0 - t4 < n; j0 += kSlotSmallThreads * 4) {   // uniform trip count
+        int id[4], old[4], sflag = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            id[i] = -1;
+            old[i] = 0;
+            if (j0 + i < n) {
+                const int v = ids[j0 + i];
+                if (v >= 0 && v < vocab_n) {
+                    id[i] = v;
+                    old[i] = slot_of[v];
+                    sflag += old[i] < 0 ? 1 : 0;
+                } else {
+                    err |= kErrBitRange;
+                }
+            }
+        }
+        int total;
+        int run = run_base + block_excl_scan<kSlotSmallThreads / kWave>(sflag, &total, sm);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int j = j0 + i;
+            if (j >= n) continue;
+            if (id[i] < 0) {
+                code[j] = -1;
+                continue;
+            }
+            const long long c64 = counts[j];
+            if (old[i] < 0) {
+                const int slot = run++;
+                if (slot < cap_total) {
+                    slot_of[id[i]] = slot;
+                    id_of_slot[slot] = id[i];
+                    cnt_of_slot[slot] = c64 > 0x7fffffffLL ? 0x7fffffff : (int)c64;
+                    code[j] = slot | kSlotNew;
+                } else {
+                    code[j] = -1;
+                    err |= kErrBitCapacity;
+                }
+            } else {
+                const long long sum = (long long)cnt_of_slot[old[i]] + c64;
+                cnt_of_slot[old[i]] = sum > 0x7fffffffLL ? 0x7fffffff : (int)sum;
+                code[j] = old[i];
+            }
+        }
+        run_base += total;
+    }
+    if (err) atomicOr(&scal[kSErr], err);
+    if (threadIdx.x == 0) scal[kSUTotal] = run_base < cap_total ? run_base : cap_total;
+}
+
+__global__ __launch_bounds__(kBlock) void k_import_rows(const int* __restrict__ code,
+                                                        const f32x4* __restrict__ rows, int n,
+                                                        int cols4, f32x4* __restrict__ G)
+{
+    const int64_t total = (int64_t)n * cols4;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * kBlock) {
+        const int64_t r = i / cols4;
+        const int cc = (int)(i % cols4);
+        const int cd = code[r];
+        if (cd < 0) continue;
+        f32x4* dst = G + (int64_t)(cd & (kSlotNew - 1)) * cols4 + cc;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (rows) v = rows[i];
+        *dst = (cd & kSlotNew) ? v : *dst + v;
+    }
+}
+
+void import_slots(Ctx* c, const int* ids, const long long* counts, const float* rows, int64_t n,
+                  hipStream_t s)
+{
+    const int first_touch = (c->steps_done == 0 && !c->window_imported) ? 1 : 0;
+    launch(c, KID_SLOT_EMIT, k_slot_import, dim3(1), dim3(kSlotSmallThreads), s, ids, counts, (int)n,
+           c->cfg.vocab_n, c->slot_of, c->id_of_slot, c->cnt_of_slot, c->chunk_ids, c->scal,
+           (int)c->cap_total, first_touch);
+    if (n == 0) return;
+    int64_t blocks = (n * (c->cfg.d / 4) + kBlock - 1) / kBlock;
+    if (blocks > 2048) blocks = 2048;
+    launch(c, KID_FLUSH_ROWS, k_import_rows, dim3((unsigned)blocks), dim3(kBlock), s, c->chunk_ids,
+           reinterpret_cast<const f32x4*>(rows), (int)n, c->cfg.d / 4, reinterpret_cast<f32x4*>(c->G));
 }
 
 // ---- dense-by-vocabulary buffer: end of the window, and resuming one --------------------

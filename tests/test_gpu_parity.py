@@ -876,6 +876,52 @@ def test_dense_buffer_window_saved_and_resumed_and_wide_counts():
     assert g.flush64(u, None, None, None, want_host_u=True) == 0   # empty again
 
 
+def test_slot_table_window_saved_and_resumed():
+    """The same save / resume through the default slot-table buffer: export with widened counts
+    (gram_flush64), import into the emptied buffer, continue; items of the saved state keep their
+    sums, new items take rows behind them, and the export is in ascending ID order again."""
+    import torch
+    K, n, d_in, d = 4, 700, 16, 8
+    probs = [small_problem(720 + k, 2000, n, d_in=d_in, d=d) for k in range(K)]
+    X, W = probs[0][1], probs[0][2]
+    batches = [(p[0], p[3]) for p in probs]
+    say("slot table save / resume")
+    first = run_window(X, W, batches[:2], vocab_n=n, k_steps=K, max_positions=2000)
+    perm = np.random.default_rng(5).permutation(first["uniq_total"].size)        # any order of distinct IDs
+    saved = (first["uniq_total"][perm], first["counts_total"][perm].astype(np.int64), first["G_total"][perm])
+    second = run_window(X, W, batches[2:], vocab_n=n, k_steps=K, max_positions=2000, gram_obj=first["gram"],
+                        resume=saved)
+    mm = orc.GramMulti(X, W)
+    for ids, dH in batches:
+        mm.step(ids, dH)
+    ref = mm.finish()
+    np.testing.assert_array_equal(second["uniq_total"], ref["uniq"])
+    np.testing.assert_array_equal(second["counts_total"], ref["counts"])
+    assert_close(second["G_total"], ref["G"], 1e-5, "G after resume")
+    assert_close(second["dW"], ref["dW"], 1e-5, "dW after resume")
+    # an imported state alone: weight gradient and a 64-bit export with saturated 32-bit counts
+    g = first["gram"]
+    ids3 = torch.tensor([699, 7, 0], dtype=torch.int32, device="cuda")
+    cnt3 = torch.tensor([3, 2 ** 40, 2 ** 31 + 5], dtype=torch.int64, device="cuda")
+    rows = torch.arange(3 * d, dtype=torch.float32, device="cuda").reshape(3, d)
+    rows[2] = 0.0
+    g.window_import(ids3, cnt3, rows, 3)
+    g.window_import(ids3[:1], cnt3[:1], rows[:1], 1)                 # a second import meets item 699 again
+    dW = torch.full((d_in, d), float("nan"), device="cuda")
+    g.encoder_wgrad(first["X_dev"], dW)
+    r = rows.cpu().numpy().astype(np.float64)
+    r[0] *= 2
+    want = orc.wgrad(np.array([699, 7, 0], np.int32), X, r, 0)
+    assert_close(dW.cpu().numpy(), want, 1e-5, "dW of an imported window")
+    u = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    c64 = torch.full((n,), -7, dtype=torch.int64, device="cuda")
+    Gt = torch.full((n, d), float("nan"), device="cuda")
+    assert g.flush64(u, c64, Gt, None, want_host_u=True) == 3
+    assert u[:3].tolist() == [0, 7, 699] and c64[:3].tolist() == [2 ** 31 - 1, 2 ** 31 - 1, 6]
+    np.testing.assert_array_equal(Gt[:3].cpu().numpy(), np.stack([r[2], r[1], r[0]]).astype(np.float32))
+    assert g.flush(u, None, None, None, want_host_u=True) == 0
+
+
 def test_dense_buffer_window_of_two_thousand_steps():
     """An accumulation period in the thousands (the half-epoch / one-epoch periods of the
     experiments): 2,000 mini-batches into the one-row-per-ID buffer, then one weight gradient and
@@ -933,10 +979,9 @@ def test_dense_buffer_argument_errors():
     slots = gram.Gram(gram.make_config(100, 16, 8, 50, 1, 0, 0, gram.F32))
     u = torch.zeros(100, dtype=torch.int32, device="cuda")
     c64 = torch.zeros(100, dtype=torch.int64, device="cuda")
-    for fn in (lambda: slots.flush64(u, c64), lambda: slots.window_import(u, c64, None, 1)):
-        with pytest.raises(gram.GramError) as e:
-            fn()
-        assert e.value.status == gram.ERR_UNIMPLEMENTED
+    with pytest.raises(gram.GramError) as e:
+        slots.window_import(u, c64, None, 51)                                    # more items than buffer rows
+    assert e.value.status == gram.ERR_ARG
     dense = gram.Gram(gram.make_config(100, 16, 8, 50, 1, 0, 0, gram.F32, 1))
     with pytest.raises(gram.GramError) as e:
         dense.window_import(u, c64, None, 101)
