@@ -94,7 +94,15 @@ __global__ __launch_bounds__(kBlock) void k_transpose_u16(const uint16_t* __rest
 
 __device__ __forceinline__ uint4 and4(uint4 v, uint32_t m) { return make_uint4(v.x & m, v.y & m, v.z & m, v.w & m); }
 
-template <int EPI>
+// BDIRECT: the second operand is W [d_in, d] as the caller holds it (d a multiple of 8), not its
+// transpose: a slab of W is parked as 64 rows of k with 64 values of n each, and the MFMA fragments
+// (8 consecutive k for one n) come from the transposing LDS read of gfx950 (ds_read_b64_tr_b16;
+// see k_wgrad_tn_bf16 for its lane layout).  Saves the separate transpose launch, which matters
+// where this kernel is used: batches that are bound by launch latency.
+typedef short sv4i16 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) sv4i16 lds_sv4i16;
+
+template <int EPI, bool BDIRECT = false>
 __global__ __launch_bounds__(kBlock) void k_encode_bf16(
     const uint16_t* __restrict__ X, const uint16_t* __restrict__ Wt, const int* __restrict__ uniq,
     const int* __restrict__ u_dev, int d_in, int d, int pad_id, float* __restrict__ E,
@@ -122,9 +130,15 @@ __global__ __launch_bounds__(kBlock) void k_encode_bf16(
         const int j0 = m0 + lrow0 < U ? m0 + lrow0 : U - 1, j1 = m0 + lrow1 < U ? m0 + lrow1 : U - 1;
         pa0 = X + (int64_t)uniq[j0] * d_in;
         pa1 = X + (int64_t)uniq[j1] * d_in;
-        const int c0 = n0 + lrow0 < d ? n0 + lrow0 : d - 1, c1 = n0 + lrow1 < d ? n0 + lrow1 : d - 1;
-        pb0 = Wt + (int64_t)c0 * d_in;
-        pb1 = Wt + (int64_t)c1 * d_in;
+        if (BDIRECT) {
+            // chunk of 8 values of n at column n0 + kc0 of row k = slab start + lrow; a column past
+            // the matrix is fetched from column 0 (its products are never stored)
+            pb0 = pb1 = Wt + (n0 + kc0 < d ? n0 + kc0 : 0);
+        } else {
+            const int c0 = n0 + lrow0 < d ? n0 + lrow0 : d - 1, c1 = n0 + lrow1 < d ? n0 + lrow1 : d - 1;
+            pb0 = Wt + (int64_t)c0 * d_in;
+            pb1 = Wt + (int64_t)c1 * d_in;
+        }
     }
     uint4 a00, a01, b00, b01, a10, a11, b10, b11, a20, a21, b20, b21;     // three register sets
 #define GRAM_LOAD_SLAB(S, K0)                                                                       \
@@ -133,16 +147,25 @@ __global__ __launch_bounds__(kBlock) void k_encode_bf16(
         const int ks_ = k_ < d_in ? k_ : 0;                                                         \
         a##S##0 = *reinterpret_cast<const uint4*>(pa0 + ks_);                                       \
         a##S##1 = *reinterpret_cast<const uint4*>(pa1 + ks_);                                       \
-        b##S##0 = *reinterpret_cast<const uint4*>(pb0 + ks_);                                       \
-        b##S##1 = *reinterpret_cast<const uint4*>(pb1 + ks_);                                       \
+        if (BDIRECT) {                                                                              \
+            const int r0_ = (K0) + lrow0 < d_in ? (K0) + lrow0 : 0;                                 \
+            const int r1_ = (K0) + lrow1 < d_in ? (K0) + lrow1 : 0;                                 \
+            b##S##0 = *reinterpret_cast<const uint4*>(pb0 + (int64_t)r0_ * d);                      \
+            b##S##1 = *reinterpret_cast<const uint4*>(pb1 + (int64_t)r1_ * d);                      \
+        } else {                                                                                    \
+            b##S##0 = *reinterpret_cast<const uint4*>(pb0 + ks_);                                   \
+            b##S##1 = *reinterpret_cast<const uint4*>(pb1 + ks_);                                   \
+        }                                                                                           \
     }
 #define GRAM_PARK_SLAB(S, K0, BUF)                                                                  \
     {                                                                                               \
         const uint32_t keep_ = (K0) + kc0 < d_in ? 0xFFFFFFFFu : 0u;                                \
         *reinterpret_cast<uint4*>(&sA[BUF][lrow0 * LDS_STRIDE + kc0]) = and4(a##S##0, keep_);       \
         *reinterpret_cast<uint4*>(&sA[BUF][lrow1 * LDS_STRIDE + kc1]) = and4(a##S##1, keep_);       \
-        *reinterpret_cast<uint4*>(&sB[BUF][lrow0 * LDS_STRIDE + kc0]) = and4(b##S##0, keep_);       \
-        *reinterpret_cast<uint4*>(&sB[BUF][lrow1 * LDS_STRIDE + kc1]) = and4(b##S##1, keep_);       \
+        const uint32_t kb0_ = BDIRECT ? ((K0) + lrow0 < d_in ? 0xFFFFFFFFu : 0u) : keep_;           \
+        const uint32_t kb1_ = BDIRECT ? ((K0) + lrow1 < d_in ? 0xFFFFFFFFu : 0u) : keep_;           \
+        *reinterpret_cast<uint4*>(&sB[BUF][lrow0 * LDS_STRIDE + kc0]) = and4(b##S##0, kb0_);        \
+        *reinterpret_cast<uint4*>(&sB[BUF][lrow1 * LDS_STRIDE + kc1]) = and4(b##S##1, kb1_);        \
     }
 
     f32x16 acc;
@@ -151,7 +174,11 @@ __global__ __launch_bounds__(kBlock) void k_encode_bf16(
 
     const int nslab = (d_in + BK - 1) / BK;
     const int arow = (wm * 32 + (lane & 31)) * LDS_STRIDE + (lane >> 5) * 8;
-    const int brow = (wn * 32 + (lane & 31)) * LDS_STRIDE + (lane >> 5) * 8;
+    // BDIRECT: sB rows are k; group g = lane / 16 of a transposing read covers k rows
+    // (g / 2) * 8 + 4 h + j / 4 and columns wn * 32 + (g % 2) * 16 + 4 (j % 4) .. + 3, j = lane % 16
+    const int brow = BDIRECT ? (((lane >> 5) * 8 + ((lane & 15) >> 2)) * LDS_STRIDE + wn * 32 +
+                                ((lane >> 4) & 1) * 16 + (lane & 3) * 4)
+                             : ((wn * 32 + (lane & 31)) * LDS_STRIDE + (lane >> 5) * 8);
     // slab sl lives in register set sl % 3; in iteration sl the set of slab sl + 1 is parked in
     // the other LDS buffer and refilled with slab sl + 4.  Nothing is conditional (slabs past the
     // end park zeros), so the count of loads in flight is known at every wait.
@@ -163,7 +190,15 @@ __global__ __launch_bounds__(kBlock) void k_encode_bf16(
         const uint16_t* b_ = &sB[(SL) & 1][brow];                                                   \
         _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                    \
             const bf16x8 fa = *reinterpret_cast<const bf16x8*>(a_ + ks * 16);                       \
-            const bf16x8 fb = *reinterpret_cast<const bf16x8*>(b_ + ks * 16);                       \
+            bf16x8 fb;                                                                              \
+            if (BDIRECT) {                                                                          \
+                const uint16_t* t_ = b_ + ks * 16 * LDS_STRIDE;                                     \
+                const sv4i16 lo_ = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_sv4i16*)t_);        \
+                const sv4i16 hi_ = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_sv4i16*)(t_ + 4 * LDS_STRIDE)); \
+                fb = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo_, hi_, 0, 1, 2, 3, 4, 5, 6, 7)); \
+            } else {                                                                                \
+                fb = *reinterpret_cast<const bf16x8*>(b_ + ks * 16);                                \
+            }                                                                                       \
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc, 0, 0, 0);                    \
         }                                                                                           \
         __syncthreads();                                                                            \
@@ -956,14 +991,21 @@ void transpose_weight(Ctx* c, const void* W, int rows, int cols, void* Wt, hipSt
     }
 }
 
+// Batches that give the 256x256 kernel a tile for every CU (and a K that fits its slabs) take it;
+// the rest take the 64x64 latency-oriented kernel.
+static bool takes_big_kernel(const Ctx* c, int64_t rows_max, int n_out, int k)
+{
+    const int64_t tile_bound = ((rows_max + TM - 1) / TM) * ((n_out + TN - 1) / TN);
+    return tile_bound >= c->num_cus && k % TK == 0;
+}
+
 bool gemm_rows_bf16(Ctx* c, const void* A, int64_t a_rows, int k, const int* row_ids, int pad_id,
                     const int* n_dev, int64_t rows_max, const void* Bt, int n_out, float* C, hipStream_t s,
-                    void* H_scatter, bool caller_wants_C, int epi, const void* aux)
+                    void* H_scatter, bool caller_wants_C, int epi, const void* aux, const void* B_plain)
 {
     if (rows_max <= 0) return false;
     const int64_t window = (int64_t)1 << 32;
-    const int64_t tile_bound = ((rows_max + TM - 1) / TM) * ((n_out + TN - 1) / TN);
-    if (tile_bound >= c->num_cus && k % TK == 0) {
+    if (takes_big_kernel(c, rows_max, n_out, k)) {
         // Fusing the gather pays when there are tiles for every CU: with a handful of tiles the
         // position stores of a tile run on one CU while a separate gather spreads over all.
         const bool fuse = H_scatter && epi == kEpiPlain && a_rows * k * 2 < window;
@@ -977,6 +1019,17 @@ bool gemm_rows_bf16(Ctx* c, const void* A, int64_t a_rows, int k, const int* row
     const dim3 grid((n_out + BN - 1) / BN, (unsigned)((rows_max + BM - 1) / BM));
     const uint16_t* a16 = static_cast<const uint16_t*>(A);
     const uint16_t* b16 = static_cast<const uint16_t*>(Bt);
+    if (B_plain && n_out % 8 == 0 && (epi == kEpiPlain || epi == kEpiMinus)) {
+        // the kernel reads the untransposed operand itself
+        const uint16_t* w16 = static_cast<const uint16_t*>(B_plain);
+        if (epi == kEpiMinus)
+            launch(c, KID_ENCODE_BF16, k_encode_bf16<kEpiMinus, true>, grid, dim3(kBlock), s, a16, w16, row_ids,
+                   n_dev, k, n_out, pad_id, C, aux);
+        else
+            launch(c, KID_ENCODE_BF16, k_encode_bf16<kEpiPlain, true>, grid, dim3(kBlock), s, a16, w16, row_ids,
+                   n_dev, k, n_out, pad_id, C, aux);
+        return false;
+    }
     if (epi == kEpiReluBf16)
         launch(c, KID_ENCODE_BF16, k_encode_bf16<kEpiReluBf16>, grid, dim3(kBlock), s, a16, b16, row_ids, n_dev, k,
                n_out, pad_id, C, aux);
@@ -999,9 +1052,12 @@ bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
     if (rows_max <= 0) return false;
     const int d_in = c->cfg.d_in, d = c->cfg.d;
     if (c->cfg.xw_dtype == GRAM_BF16) {
-        transpose_weight(c, W, d_in, d, c->Wt, s);
+        // the small kernel can read W as it is (no transposed copy, one launch less)
+        const bool direct = !takes_big_kernel(c, rows_max, d, d_in) && d % 8 == 0 &&
+                            (epi == kEpiPlain || epi == kEpiMinus);
+        if (!direct) transpose_weight(c, W, d_in, d, c->Wt, s);
         return gemm_rows_bf16(c, X, c->cfg.vocab_n, d_in, uniq, c->cfg.pad_id, u_dev, rows_max, c->Wt, d, E, s,
-                              H_scatter, caller_wants_E, epi, aux);
+                              H_scatter, caller_wants_E, epi, aux, direct ? W : nullptr);
     }
     launch(c, KID_ENCODE_F32, k_encode_f32, dim3((d + 63) / 64, (unsigned)((rows_max + 3) / 4)),
            dim3(kBlock), s, static_cast<const float*>(X), static_cast<const float*>(W), uniq, u_dev,
