@@ -1094,8 +1094,11 @@ bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
 // receives column i of the 4 rows, i.e. 4 consecutive values of the contraction
 // index for one output row, which is the operand layout of
 // v_mfma_f32_32x32x16_bf16 (two such reads per 8-value fragment).
-// LDS rows are 512 bytes; 16-byte chunk p of row s sits at p ^ ((s & 3) << 1), so
-// the four rows of a group fall into four different 32-byte bank groups.
+// LDS rows are 512 bytes; 16-byte chunk p of row s sits at p ^ ((s & 3) << 2).  A half-wave of
+// such a read is two groups, i.e. 4 rows x 4 neighbouring chunks; with the row number XOR-ed
+// into bits 2-3 of the chunk index those 16 pieces land in 16 different chunk positions of the
+// 256-byte bank period: every bank once (XOR-ing bits 1-2 instead left half of the banks idle
+// and showed as bank conflicts in 37 % of the LDS cycles).
 // Loads go through buffer descriptors; a row past the end of the buffer, a
 // padding item or a column past the matrix edge is turned into an out-of-range
 // offset, for which the hardware returns zeros.
@@ -1131,7 +1134,10 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
     // register sets for loads in flight: two with one wave per SIMD (a load has two slabs to
     // land); one with two waves per SIMD, where the other wave covers the wait and the
     // registers are needed for the second wave to fit
-    constexpr int SETS = NW == 4 ? 2 : 1;
+    constexpr int SETS = 2;
+    // one set of fragment registers with two waves per SIMD (the other wave's MFMAs cover the LDS
+    // latency; the registers go to the second set of loads in flight instead), two with one
+    constexpr bool FRAG1 = NW == 8;
     const int wm = NW == 4 ? wave >> 1 : wave >> 2, wn = NW == 4 ? wave & 1 : wave & 3;
 
     // buffer rows [row_begin, U) take part (row_end clips U: the chunked call); slabs stay aligned
@@ -1170,16 +1176,25 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
     // fragment addresses (see the header comment): group g = lane / 16, j = lane % 16
     const int j16 = lane & 15, grp = lane >> 4;
     const int f_row = (grp >> 1) * 8 + (j16 >> 2);                   // + 16 ks + 4 h
-    const int f_x = ((j16 >> 2) & 3) << 1;
-    int f_off[4];
+    const int f_x = ((j16 >> 2) & 3) << 2;
+    // chunk index within the whole 512-byte row (the swizzle acts on it): the wave's quadrant starts
+    // at chunk 16 wm (A) / NT 4 wn (B)
+    int f_offA[4], f_offB[NT];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-        f_off[i] = f_row * WROWB + (((i * 4 + (grp & 1) * 2 + ((j16 & 3) >> 1)) ^ f_x) * 16) + (j16 & 1) * 8;
-    const int baseA = wm * 256, baseB = WOPB + wn * (NT * 64);             // byte offset of the wave's quadrant
+        f_offA[i] = f_row * WROWB + (((wm * 16 + i * 4 + (grp & 1) * 2 + ((j16 & 3) >> 1)) ^ f_x) * 16) + (j16 & 1) * 8;
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+        f_offB[i] = WOPB + f_row * WROWB +
+                    (((wn * (NT * 4) + i * 4 + (grp & 1) * 2 + ((j16 & 3) >> 1)) ^ f_x) * 16) + (j16 & 1) * 8;
 
-    bf16x8 fa[2][4], fb[2][NT];
+    bf16x8 fa[FRAG1 ? 1 : 2][4], fb[FRAG1 ? 1 : 2][NT];
     v4i32 ra[SETS][RW / 2], rg[SETS][RW];
-    int ids_next[RW / 2];
+    // item IDs: ids_next receives the load for the slab after next, ids_cur holds the ones the next
+    // data loads use.  The ID load is issued BEFORE the data loads of an iteration: memory operations
+    // return in order, so waiting for an ID load that was issued after them would drain them all
+    // and leave a single slab of loads in flight.
+    int ids_next[RW / 2], ids_cur[RW / 2];
 
 #define GRAM_TR(PTR) __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(PTR))
 #define GRAM_FRAGS(FS, STAGE, KS)                                                                   \
@@ -1187,13 +1202,13 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
         __builtin_amdgcn_s_setprio(1);                                                              \
         const unsigned char* sb_ = smem + (STAGE) * WSTAGEB + (KS) * 16 * WROWB;                    \
         _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                             \
-            const v4i16 a0 = GRAM_TR(sb_ + baseA + f_off[i]);                                       \
-            const v4i16 a1 = GRAM_TR(sb_ + baseA + f_off[i] + 4 * WROWB);                           \
+            const v4i16 a0 = GRAM_TR(sb_ + f_offA[i]);                                       \
+            const v4i16 a1 = GRAM_TR(sb_ + f_offA[i] + 4 * WROWB);                           \
             fa[FS][i] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7)); \
         }                                                                                           \
         _Pragma("unroll") for (int i = 0; i < NT; ++i) {                                            \
-            const v4i16 b0 = GRAM_TR(sb_ + baseB + f_off[i]);                                       \
-            const v4i16 b1 = GRAM_TR(sb_ + baseB + f_off[i] + 4 * WROWB);                           \
+            const v4i16 b0 = GRAM_TR(sb_ + f_offB[i]);                                       \
+            const v4i16 b1 = GRAM_TR(sb_ + f_offB[i] + 4 * WROWB);                           \
             fb[FS][i] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7)); \
         }                                                                                           \
     }
@@ -1217,13 +1232,15 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
             ids_next[t] = (slot < U && slot >= row_begin) ? (id_of_slot ? id_of_slot[slot] : slot) : pad_id; \
         }                                                                                           \
     }
+#define GRAM_IDS_TAKE                                                                               \
+    _Pragma("unroll") for (int t = 0; t < RW / 2; ++t) ids_cur[t] = ids_next[t];
 #define GRAM_LOAD(SET, SLAB)                                                                        \
     {                                                                                               \
         const int sb_ = (sl_begin + ((SLAB) < last ? (SLAB) : last)) * WK;                          \
         _Pragma("unroll") for (int t = 0; t < RW / 2; ++t) {                                        \
             const int kk = a_row + 2 * t;                                                           \
-            const int feat = i0 + ((a_pos ^ ((kk & 3) << 1)) * 8);                                  \
-            const int id = ids_next[t];                                                             \
+            const int feat = i0 + ((a_pos ^ ((kk & 3) << 2)) * 8);                                  \
+            const int id = ids_cur[t];                                                              \
             const bool ok = id != pad_id && feat < d_in && sb_ + kk < U && sb_ + kk >= row_begin;   \
             const uint32_t off = ok ? (uint32_t)(((int64_t)id * d_in + feat) * 2) : kOutOfRange;    \
             ra[(SET) % SETS][t] = __builtin_amdgcn_raw_buffer_load_b128(rsX, off, 0, 0);                     \
@@ -1244,46 +1261,73 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
             const v4i32 v = rg[(SET) % SETS][t];                                                             \
             const uint32_t lo = pack_bf16x2(__int_as_float(v.x), __int_as_float(v.y));              \
             const uint32_t hi = pack_bf16x2(__int_as_float(v.z), __int_as_float(v.w));              \
-            const int pos = (lane >> 1) ^ ((t & 3) << 1);        /* row RW w + t: (row & 3) == (t & 3) */ \
+            const int pos = (lane >> 1) ^ ((t & 3) << 2);        /* row RW w + t: (row & 3) == (t & 3) */ \
             *reinterpret_cast<uint2*>(pg_ + t * WROWB + pos * 16) = make_uint2(lo, hi);             \
         }                                                                                           \
     }
     // (fixed interleaving patterns measured slower here than the compiler's own order)
 #define GRAM_ITER(SL, P)                                                                            \
     {                                                                                               \
-        GRAM_FRAGS(1, (SL) & 1, 1)                                                                  \
+        GRAM_FRAGS(FRAG1 ? 0 : 1, (SL) & 1, 1)                                                      \
         GRAM_MMA(0)                                                                                 \
         GRAM_PARK(P, ((SL) + 1) & 1)                                                                \
         __syncthreads();                                                                            \
-        GRAM_LOAD(P, (SL) + 1 + SETS)                                                               \
+        GRAM_IDS_TAKE                                                                               \
         GRAM_IDS((SL) + 2 + SETS)                                                                   \
+        GRAM_LOAD(P, (SL) + 1 + SETS)                                                               \
         GRAM_FRAGS(0, ((SL) + 1) & 1, 0)                                                            \
-        GRAM_MMA(1)                                                                                 \
+        GRAM_MMA(FRAG1 ? 0 : 1)                                                                     \
+    }
+    // one fragment set: both k-steps of the slab, then the next slab's rows go to LDS
+#define GRAM_ITER1(SL, P)                                                                           \
+    {                                                                                               \
+        GRAM_FRAGS(0, (SL) & 1, 0)                                                                  \
+        GRAM_MMA(0)                                                                                 \
+        GRAM_FRAGS(0, (SL) & 1, 1)                                                                  \
+        GRAM_MMA(0)                                                                                 \
+        GRAM_PARK(P, ((SL) + 1) & 1)                                                                \
+        __syncthreads();                                                                            \
+        GRAM_IDS_TAKE                                                                               \
+        GRAM_IDS((SL) + 2 + SETS)                                                                   \
+        GRAM_LOAD(P, (SL) + 1 + SETS)                                                               \
     }
 
     if (nslab > 0) {
         const int last = nslab - 1;
         GRAM_IDS(0)
-        GRAM_LOAD(0, 0)
+        GRAM_IDS_TAKE
         GRAM_IDS(1)
-        if (SETS == 2) {
-            GRAM_LOAD(1, 1)
-            GRAM_IDS(2)
-        }
+        GRAM_LOAD(0, 0)
+        GRAM_IDS_TAKE
+        GRAM_IDS(2)
+        GRAM_LOAD(1, 1)
         GRAM_PARK(0, 0)
-        GRAM_LOAD(0, SETS)
+        GRAM_IDS_TAKE
         GRAM_IDS(SETS + 1)
+        GRAM_LOAD(0, SETS)
         __syncthreads();
-        GRAM_FRAGS(0, 0, 0)
         int sl = 0;
-        for (; sl + 1 < last; sl += 2) {
-            GRAM_ITER(sl, 1)          // (two sets) set 1 holds slab sl+1, set 0 holds slab sl+2
-            GRAM_ITER(sl + 1, 0)
+        if (FRAG1) {
+            for (; sl + 1 < last; sl += 2) {
+                GRAM_ITER1(sl, 1)         // set 1 holds slab sl+1, set 0 holds slab sl+2
+                GRAM_ITER1(sl + 1, 0)
+            }
+            if (sl < last) GRAM_ITER1(sl, 1)
+            GRAM_FRAGS(0, last & 1, 0)
+            GRAM_MMA(0)
+            GRAM_FRAGS(0, last & 1, 1)
+            GRAM_MMA(0)
+        } else {
+            GRAM_FRAGS(0, 0, 0)
+            for (; sl + 1 < last; sl += 2) {
+                GRAM_ITER(sl, 1)
+                GRAM_ITER(sl + 1, 0)
+            }
+            if (sl < last) GRAM_ITER(sl, 1)
+            GRAM_FRAGS(FRAG1 ? 0 : 1, last & 1, 1)
+            GRAM_MMA(0)
+            GRAM_MMA(FRAG1 ? 0 : 1)
         }
-        if (sl < last) GRAM_ITER(sl, 1)
-        GRAM_FRAGS(1, last & 1, 1)
-        GRAM_MMA(0)
-        GRAM_MMA(1)
     }
 
     // accumulator element r of a lane sits at (row, col) = ((r / 4) * 8 + (lane / 32) * 4 + r % 4, lane % 32)
@@ -1304,9 +1348,11 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
 #undef GRAM_FRAGS
 #undef GRAM_MMA
 #undef GRAM_IDS
+#undef GRAM_IDS_TAKE
 #undef GRAM_LOAD
 #undef GRAM_PARK
 #undef GRAM_ITER
+#undef GRAM_ITER1
 
 __device__ __forceinline__ void split_range(int u_total, int splits, int z, int* kb, int* ke)
 {
