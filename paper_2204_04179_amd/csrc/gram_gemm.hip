@@ -1131,13 +1131,9 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     constexpr int NT = NW == 4 ? 4 : 2;          // 32-column MFMA tiles per wave
     constexpr int RW = 32 / NW;                  // buffer rows of a slab this wave loads
-    // register sets for loads in flight: two with one wave per SIMD (a load has two slabs to
-    // land); one with two waves per SIMD, where the other wave covers the wait and the
-    // registers are needed for the second wave to fit
+    // two register sets for loads in flight: a load has two slabs of MFMAs to land (246 VGPRs
+    // with 8 waves, so two waves per SIMD still fit)
     constexpr int SETS = 2;
-    // one set of fragment registers with two waves per SIMD (the other wave's MFMAs cover the LDS
-    // latency; the registers go to the second set of loads in flight instead), two with one
-    constexpr bool FRAG1 = NW == 8;
     const int wm = NW == 4 ? wave >> 1 : wave >> 2, wn = NW == 4 ? wave & 1 : wave & 3;
 
     // buffer rows [row_begin, U) take part (row_end clips U: the chunked call); slabs stay aligned
@@ -1188,7 +1184,7 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
         f_offB[i] = WOPB + f_row * WROWB +
                     (((wn * (NT * 4) + i * 4 + (grp & 1) * 2 + ((j16 & 3) >> 1)) ^ f_x) * 16) + (j16 & 1) * 8;
 
-    bf16x8 fa[FRAG1 ? 1 : 2][4], fb[FRAG1 ? 1 : 2][NT];
+    bf16x8 fa[2][4], fb[2][NT];
     v4i32 ra[SETS][RW / 2], rg[SETS][RW];
     // item IDs: ids_next receives the load for the slab after next, ids_cur holds the ones the next
     // data loads use.  The ID load is issued BEFORE the data loads of an iteration: memory operations
@@ -1268,7 +1264,7 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
     // (fixed interleaving patterns measured slower here than the compiler's own order)
 #define GRAM_ITER(SL, P)                                                                            \
     {                                                                                               \
-        GRAM_FRAGS(FRAG1 ? 0 : 1, (SL) & 1, 1)                                                      \
+        GRAM_FRAGS(1, (SL) & 1, 1)                                                                  \
         GRAM_MMA(0)                                                                                 \
         GRAM_PARK(P, ((SL) + 1) & 1)                                                                \
         __syncthreads();                                                                            \
@@ -1276,20 +1272,7 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
         GRAM_IDS((SL) + 2 + SETS)                                                                   \
         GRAM_LOAD(P, (SL) + 1 + SETS)                                                               \
         GRAM_FRAGS(0, ((SL) + 1) & 1, 0)                                                            \
-        GRAM_MMA(FRAG1 ? 0 : 1)                                                                     \
-    }
-    // one fragment set: both k-steps of the slab, then the next slab's rows go to LDS
-#define GRAM_ITER1(SL, P)                                                                           \
-    {                                                                                               \
-        GRAM_FRAGS(0, (SL) & 1, 0)                                                                  \
-        GRAM_MMA(0)                                                                                 \
-        GRAM_FRAGS(0, (SL) & 1, 1)                                                                  \
-        GRAM_MMA(0)                                                                                 \
-        GRAM_PARK(P, ((SL) + 1) & 1)                                                                \
-        __syncthreads();                                                                            \
-        GRAM_IDS_TAKE                                                                               \
-        GRAM_IDS((SL) + 2 + SETS)                                                                   \
-        GRAM_LOAD(P, (SL) + 1 + SETS)                                                               \
+        GRAM_MMA(1)                                                                                 \
     }
 
     if (nslab > 0) {
@@ -1306,28 +1289,16 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
         GRAM_IDS(SETS + 1)
         GRAM_LOAD(0, SETS)
         __syncthreads();
+        GRAM_FRAGS(0, 0, 0)
         int sl = 0;
-        if (FRAG1) {
-            for (; sl + 1 < last; sl += 2) {
-                GRAM_ITER1(sl, 1)         // set 1 holds slab sl+1, set 0 holds slab sl+2
-                GRAM_ITER1(sl + 1, 0)
-            }
-            if (sl < last) GRAM_ITER1(sl, 1)
-            GRAM_FRAGS(0, last & 1, 0)
-            GRAM_MMA(0)
-            GRAM_FRAGS(0, last & 1, 1)
-            GRAM_MMA(0)
-        } else {
-            GRAM_FRAGS(0, 0, 0)
-            for (; sl + 1 < last; sl += 2) {
-                GRAM_ITER(sl, 1)
-                GRAM_ITER(sl + 1, 0)
-            }
-            if (sl < last) GRAM_ITER(sl, 1)
-            GRAM_FRAGS(FRAG1 ? 0 : 1, last & 1, 1)
-            GRAM_MMA(0)
-            GRAM_MMA(FRAG1 ? 0 : 1)
+        for (; sl + 1 < last; sl += 2) {
+            GRAM_ITER(sl, 1)          // set 1 holds slab sl+1, set 0 holds slab sl+2
+            GRAM_ITER(sl + 1, 0)
         }
+        if (sl < last) GRAM_ITER(sl, 1)
+        GRAM_FRAGS(1, last & 1, 1)
+        GRAM_MMA(0)
+        GRAM_MMA(1)
     }
 
     // accumulator element r of a lane sits at (row, col) = ((r / 4) * 8 + (lane / 32) * 4 + r % 4, lane % 32)
@@ -1352,7 +1323,6 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
 #undef GRAM_LOAD
 #undef GRAM_PARK
 #undef GRAM_ITER
-#undef GRAM_ITER1
 
 __device__ __forceinline__ void split_range(int u_total, int splits, int z, int* kb, int* ke)
 {
