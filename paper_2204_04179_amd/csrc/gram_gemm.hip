@@ -1195,7 +1195,6 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
 #define GRAM_TR(PTR) __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(PTR))
 #define GRAM_FRAGS(FS, STAGE, KS)                                                                   \
     {                                                                                               \
-        __builtin_amdgcn_s_setprio(1);                                                              \
         const unsigned char* sb_ = smem + (STAGE) * WSTAGEB + (KS) * 16 * WROWB;                    \
         _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                             \
             const v4i16 a0 = GRAM_TR(sb_ + f_offA[i]);                                       \
@@ -1208,16 +1207,12 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
             fb[FS][i] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7)); \
         }                                                                                           \
     }
-    // The fragment reads and the MFMA group of a k-step run at raised wave priority and are fenced
-    // off from the rest (s_setprio also stops the compiler from moving instructions across it):
-    // with two waves per SIMD the matrix pipe stays fed and the other wave's LDS and memory
-    // instructions fit into its shadow (517 -> 440 us on the stress window; most of the gain comes
-    // from the fence; the same in the forward kernel measured 4 % slower).
+    // (Raising the wave priority around the fragment reads and MFMAs of a k-step paid while a
+    // single slab of loads was in flight; with two it costs 4 %.)
 #define GRAM_MMA(FS)                                                                                \
     _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                   \
         _Pragma("unroll") for (int j = 0; j < NT; ++j)                                              \
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[FS][i], fb[FS][j], acc[i][j], 0, 0, 0); \
-    __builtin_amdgcn_s_setprio(0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[FS][i], fb[FS][j], acc[i][j], 0, 0, 0);
     // item IDs of the X rows this lane will fetch for slab SLAB (clamped: a slab past the end is
     // loaded but never multiplied)
 #define GRAM_IDS(SLAB)                                                                              \
