@@ -326,6 +326,29 @@ int gram_flush64(gram_ctx* ctx, int32_t* uniq_total, int64_t* counts_total, floa
 int gram_window_import(gram_ctx* ctx, const int32_t* ids, const int64_t* counts, const float* G_rows,
                        int64_t n, void* stream);
 
+/* gram_unique for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Needs no
+ * context: the scratch memory of the dedup kernels (sort buffers, digit tables,
+ * segment offsets; about 8.3 MB) is one array in the library's device image, which
+ * every GPU the library runs on holds until the process ends.  The call allocates
+ * nothing and never synchronises; it only enqueues kernels on `stream`.
+ *   ids, uniq, inverse, counts   DEVICE, as for gram_unique (uniq and counts with
+ *                                room for min(m, vocab_n) entries)
+ *   m        0 <= m <= GRAM_UNIQUE_STATIC_MAX_POSITIONS, else GRAM_ERR_CAPACITY
+ *   vocab_n  IDs are valid in [0, vocab_n)       pad_id  as gram_config.pad_id
+ *   u_dev    DEVICE [1]            out: U (required: there is no host copy)
+ *   err_dev  DEVICE [1], nullable  out: 0, or 1 if an ID outside [0, vocab_n) was
+ *                                  seen (such an ID is processed as the padding ID,
+ *                                  0 if there is none)
+ * Results are those of gram_unique, bit for bit.  All calls on one GPU share the
+ * one array, which keeps the last call's contents (the call clears what must start
+ * at zero itself): calls that overlap on one GPU, on different streams or host
+ * threads, race.  Errors are reported through the return value and
+ * gram_last_error(NULL). */
+#define GRAM_UNIQUE_STATIC_MAX_POSITIONS 262144
+int gram_unique_static(const int32_t* ids, int64_t m, int32_t vocab_n, int32_t pad_id, int32_t* uniq,
+                       int32_t* inverse, int32_t* counts, int32_t* u_dev, int32_t* err_dev, void* stream);
+
 /* Synchronise `stream` and return (and clear) any latched device error. */
 int gram_check(gram_ctx* ctx, void* stream);
 

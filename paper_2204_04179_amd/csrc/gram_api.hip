@@ -3,6 +3,7 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <mutex>
 #include <new>
 
 #include "gram_internal.h"
@@ -191,6 +192,69 @@ int sync_scalars(Ctx* c, hipStream_t s, const char* what)
                     (long long)c->cap_total);
     }
     return GRAM_OK;
+}
+
+}  // namespace
+
+// ---- gram_unique for callers that cannot allocate -----------------------------------
+//
+// The dedup kernels need scratch memory (radix ping-pong arrays, digit tables, segment
+// offsets).  gram_unique takes it from the context's workspace, which gram_create
+// allocates; this variant takes it from one array in the library's device image, so it
+// allocates nothing.  The array's name is a host-side stand-in, not a device address:
+// its device address is looked up once per device and only that pointer is used below.
+namespace {
+
+constexpr int64_t kStaticMax = GRAM_UNIQUE_STATIC_MAX_POSITIONS;
+constexpr int64_t static_align(int64_t v) { return (v + 255) / 256 * 256; }
+// digit table of the largest sort plan (see table_elems_for): 256 blocks + 1, 1024 bins
+constexpr int64_t kStaticTableElems = ((int64_t)1 << kMaxDigitBits) * 257;
+constexpr int64_t kStaticOffScal = 0;
+constexpr int64_t kStaticOffKeys0 = kStaticOffScal + static_align(64 * 4);
+constexpr int64_t kStaticOffKeys1 = kStaticOffKeys0 + static_align(kStaticMax * 4);
+constexpr int64_t kStaticOffVals0 = kStaticOffKeys1 + static_align(kStaticMax * 4);
+constexpr int64_t kStaticOffVals1 = kStaticOffVals0 + static_align(kStaticMax * 4);
+constexpr int64_t kStaticOffTable = kStaticOffVals1 + static_align(kStaticMax * 4);
+constexpr int64_t kStaticOffGtot = kStaticOffTable + static_align(kStaticTableElems * 4);
+constexpr int64_t kStaticOffTiles = kStaticOffGtot + static_align((1 << kMaxDigitBits) * 4);
+constexpr int64_t kStaticOffOffsets = kStaticOffTiles + static_align((kStaticMax / kScanTile + 2) * 4);
+constexpr int64_t kStaticOffSegOfRow = kStaticOffOffsets + static_align((kStaticMax + 2) * 4);
+constexpr int64_t kStaticOffUniqWs = kStaticOffSegOfRow + static_align(kStaticMax * 4);
+constexpr int64_t kStaticBytes = kStaticOffUniqWs + static_align(kStaticMax * 4);
+static_assert(kStaticBytes < ((int64_t)9 << 20), "the static scratch array is meant to stay below 9 MiB");
+
+constexpr int kStaticMaxDevices = 64;
+std::mutex g_static_mutex;
+unsigned char* g_static_ptr[kStaticMaxDevices] = {};
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+namespace {
+
+// Device address of `scratch` on the current device (looked up on the first call there).
+int static_scratch(unsigned char** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(nullptr, e, "gram_unique_static: hipGetDevice");
+    if (dev < 0 || dev >= kStaticMaxDevices)
+        return fail(nullptr, GRAM_ERR_ARG, "gram_unique_static: device index %d not supported", dev);
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_fail(nullptr, e, "gram_unique_static: hipGetSymbolAddress");
+        g_static_ptr[dev] = static_cast<unsigned char*>(p);
+    }
+    *out = g_static_ptr[dev];
+    return GRAM_OK;
+}
+
+__global__ void k_copy_scalar(const int* __restrict__ src, int* __restrict__ dst)
+{
+    if (threadIdx.x == 0) *dst = *src;
 }
 
 }  // namespace
@@ -617,6 +681,62 @@ int gram_profile_read(gram_ctx* ctx, int k, int64_t* launches, double* total_ms)
     }
     *launches = n;
     *total_ms = ms;
+    return GRAM_OK;
+}
+
+int gram_unique_static(const int32_t* ids, int64_t m, int32_t vocab_n, int32_t pad_id, int32_t* uniq,
+                       int32_t* inverse, int32_t* counts, int32_t* u_dev, int32_t* err_dev, void* stream)
+{
+    if (m < 0) return fail(nullptr, GRAM_ERR_ARG, "gram_unique_static: m < 0");
+    if (m > kStaticMax)
+        return fail(nullptr, GRAM_ERR_CAPACITY, "gram_unique_static: m = %lld exceeds the fixed maximum of %lld positions",
+                    (long long)m, (long long)kStaticMax);
+    if (vocab_n < 1 || pad_id >= vocab_n)
+        return fail(nullptr, GRAM_ERR_ARG, "gram_unique_static: vocab_n must be >= 1 and pad_id < vocab_n");
+    if (!u_dev || (m > 0 && (!ids || !uniq || !inverse || !counts)))
+        return fail(nullptr, GRAM_ERR_ARG, "gram_unique_static: NULL pointer");
+    unsigned char* base = nullptr;
+    if (int rc = static_scratch(&base)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    // A context on the stack whose workspace pointers lie in the static array: the kernels are
+    // the ones gram_unique runs.
+    Ctx c;
+    c.cfg = gram_config{};
+    c.cfg.vocab_n = vocab_n;
+    c.cfg.pad_id = pad_id;
+    c.cfg.max_positions = kStaticMax;
+    c.cap_u = kStaticMax < vocab_n ? kStaticMax : vocab_n;
+    c.key_bits = bits_for(vocab_n);
+    c.scal = reinterpret_cast<int*>(base + kStaticOffScal);
+    c.keys[0] = reinterpret_cast<int*>(base + kStaticOffKeys0);
+    c.keys[1] = reinterpret_cast<int*>(base + kStaticOffKeys1);
+    c.vals[0] = reinterpret_cast<int*>(base + kStaticOffVals0);
+    c.vals[1] = reinterpret_cast<int*>(base + kStaticOffVals1);
+    c.table = reinterpret_cast<int*>(base + kStaticOffTable);
+    c.gtot = reinterpret_cast<int*>(base + kStaticOffGtot);
+    c.tile_sums = reinterpret_cast<int*>(base + kStaticOffTiles);
+    c.offsets = reinterpret_cast<int*>(base + kStaticOffOffsets);
+    c.seg_of_row = reinterpret_cast<int*>(base + kStaticOffSegOfRow);
+    c.uniq_ws = reinterpret_cast<int*>(base + kStaticOffUniqWs);
+
+    // the array keeps the last call's contents: the error bits must start at zero (a fill kernel,
+    // so that the call can be captured in a HIP graph); everything else is written before it is read
+    fill_i32(c.scal, 64, 0, s);
+    if (m > 0) {
+        const int fix = pad_id >= 0 ? pad_id : 0;
+        if (!unique_small(&c, ids, (int)m, fix, uniq, inverse, counts, u_dev, s)) {
+            const int r = radix_sort_pairs(&c, ids, nullptr, (int)m, nullptr, m, true, fix, s);
+            c.sorted_keys = c.keys[r];
+            c.perm = c.vals[r];
+            unique_from_sorted(&c, (int)m, uniq, inverse, counts, u_dev, s);
+        }
+    } else {
+        unique_from_sorted(&c, 0, uniq, inverse, counts, u_dev, s);
+    }
+    if (err_dev) hipLaunchKernelGGL(k_copy_scalar, dim3(1), dim3(kWave), 0, s, c.scal + kSErr, err_dev);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(nullptr, e, "gram_unique_static");
     return GRAM_OK;
 }
 

@@ -23,7 +23,7 @@ EXPORTS = ("gram_workspace_bytes", "gram_create", "gram_destroy", "gram_unique",
            "gram_grad_accumulate", "gram_pseudo_target", "gram_gather", "gram_encoder_wgrad",
            "gram_encoder_wgrad_chunk", "gram_pseudo_loss_grad", "gram_flush",
            "gram_flush64", "gram_window_import", "gram_mlp_encode_gather", "gram_mlp_batch_bytes",
-           "gram_mlp_backward",
+           "gram_mlp_backward", "gram_unique_static",
            "gram_check", "gram_last_error",
            "gram_kernel_count", "gram_kernel_name", "gram_light_max", "gram_profile_enable",
            "gram_profile_read")
@@ -88,6 +88,8 @@ def load():
     L.gram_flush64.argtypes = [vp, vp, vp, vp, vp, i32p, vp]
     L.gram_window_import.restype = C.c_int
     L.gram_window_import.argtypes = [vp, vp, vp, vp, C.c_int64, vp]
+    L.gram_unique_static.restype = C.c_int
+    L.gram_unique_static.argtypes = [vp, C.c_int64, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp]
     L.gram_check.restype = C.c_int
     L.gram_check.argtypes = [vp, vp]
     L.gram_last_error.restype = C.c_char_p
@@ -132,6 +134,19 @@ def _stream(stream):
     if isinstance(stream, int):
         return stream
     return stream.cuda_stream
+
+
+UNIQUE_STATIC_MAX_POSITIONS = 262144
+
+
+def unique_static(ids, vocab_n, pad_id, uniq, inverse, counts, u_dev, err_dev=None, m=None, stream=None):
+    """gram_unique_static: the dedup step without a context and without any allocation."""
+    L = load()
+    rc = L.gram_unique_static(_ptr(ids), int(ids.numel() if m is None else m), int(vocab_n), int(pad_id),
+                              _ptr(uniq), _ptr(inverse), _ptr(counts), _ptr(u_dev), _ptr(err_dev),
+                              _stream(stream))
+    if rc != OK:
+        raise GramError(rc, (L.gram_last_error(None) or b"").decode())
 
 
 class Gram:
