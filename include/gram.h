@@ -87,7 +87,7 @@ typedef enum gram_dtype { GRAM_F32 = 0, GRAM_BF16 = 1 } gram_dtype;
  *   (Section 4.2 and the half-epoch / one-epoch alternation periods of the
  *   experiments), where the window reaches most of the vocabulary: the weight
  *   gradient then contracts over all N rows (rows of items the window has not
- *   met are zero).  Needs X and N*d*4 bytes below 4 GiB each for bf16. */
+ *   met are zero). */
 typedef enum gram_buffer_layout { GRAM_BUFFER_SLOTS = 0, GRAM_BUFFER_DENSE = 1 } gram_buffer_layout;
 
 typedef struct gram_config {
@@ -144,14 +144,18 @@ int gram_unique(gram_ctx* ctx, const int32_t* ids, int64_t m, int32_t* uniq, int
  *            zero row for the padding ID; NULL keeps E in the workspace
  *   H        DEVICE [m,d] of cfg.h_dtype   out: H[p,:] = E[inverse[p],:] (zero at
  *            padding), rounded to nearest even when h_dtype is bf16; 16-byte aligned
- * Requires a preceding gram_unique on this context (GRAM_ERR_SEQUENCE).
- * When uniq and inverse are the very buffers that gram_unique wrote, large bf16
- * batches take a fused path: the contraction stores each representation
- * straight to the positions of its item (using the sort order kept in the
- * context) and E is written only if the caller passes a buffer for it; an
- * item with more than gram_light_max() positions is copied to them by a second
- * kernel.  Any other uniq / inverse pair takes the two-kernel path (encode to
- * E, then gather).  The results are identical. */
+ * Requires a preceding gram_unique on this context (GRAM_ERR_SEQUENCE); uniq and
+ * inverse must hold what that call wrote, unmodified.
+ * When uniq and inverse are the very buffers that gram_unique wrote (same
+ * addresses), large bf16 batches take a fused path: the contraction stores each
+ * representation straight to the positions of its item and E is written only if
+ * the caller passes a buffer for it; an item with more than gram_light_max()
+ * positions is copied to them by a second kernel.  That path reads the unique
+ * list and the sort order from the context's own copies, not from the caller's
+ * buffers, so rows and positions always belong to the same dedup (the batch of
+ * the preceding gram_unique).  Any other uniq / inverse pair takes the
+ * two-kernel path (encode to E, then gather), which reads the caller's buffers.
+ * For unmodified buffers the results are identical. */
 int gram_encode_gather(gram_ctx* ctx, const void* X, const void* W, const int32_t* uniq,
                        const int32_t* inverse, const int32_t* u_dev, int64_t m, float* E, void* H,
                        void* stream);
@@ -200,8 +204,7 @@ int gram_grad_accumulate(gram_ctx* ctx, const float* dH, int64_t m, int32_t step
  *   n        0 <= n <= max(min(max_positions, N), rows of the buffer)
  *   work     DEVICE, gram_mlp_batch_bytes(ctx, n) bytes, 256-byte aligned
  *   dW1      DEVICE [d_in, d_hidden]   dW2  DEVICE [d_hidden, d]   float32 out;
- *            accumulate = 0 overwrites both, else adds
- * GRAM_ERR_UNIMPLEMENTED when X or a batch matrix exceeds 4 GiB. */
+ *            accumulate = 0 overwrites both, else adds */
 int gram_mlp_encode_gather(gram_ctx* ctx, const void* X, const void* W1, const void* W2,
                            const int32_t* uniq, const int32_t* inverse, const int32_t* u_dev, int64_t m,
                            void* A1, float* E, void* H, void* stream);
@@ -255,8 +258,7 @@ int gram_encoder_wgrad(gram_ctx* ctx, const void* X, float* dW, void* stream);
  * The chunks of a partition of the held rows add up to gram_encoder_wgrad's dW
  * (up to the order of the float32 sums).  No workspace grows with the chunk.
  * With the dense buffer the rows are the IDs themselves: the chunk is the ID
- * range [first_row, first_row + n_rows).
- * GRAM_ERR_UNIMPLEMENTED when X or the buffer exceeds 4 GiB. */
+ * range [first_row, first_row + n_rows). */
 int gram_encoder_wgrad_chunk(gram_ctx* ctx, const void* X, float* dW, int64_t first_row,
                              int64_t n_rows, int32_t accumulate, void* stream);
 
@@ -284,8 +286,7 @@ int gram_encoder_wgrad_chunk(gram_ctx* ctx, const void* X, float* dW, int64_t fi
  *   loss_dev DEVICE [1] double, nullable  out (summed in double, fixed order)
  * With bf16 features R is rounded to bf16 (nearest-even) as it enters the matrix
  * cores, like G in gram_encoder_wgrad.  Independent of the window's state: may
- * be called at any point.  GRAM_ERR_UNIMPLEMENTED when X or R exceeds 4 GiB.
- * 16-byte aligned pointers. */
+ * be called at any point.  16-byte aligned pointers. */
 int gram_pseudo_loss_grad(gram_ctx* ctx, const void* X, const void* W, const int32_t* ids,
                           const float* Ht, int64_t n, float* R, float* dW, int32_t accumulate,
                           double* loss_dev, void* stream);
@@ -301,11 +302,10 @@ int gram_pseudo_loss_grad(gram_ctx* ctx, const void* X, const void* W, const int
 int gram_flush(gram_ctx* ctx, int32_t* uniq_total, int32_t* counts_total, float* G_total,
                int32_t* u_total_dev, int32_t* u_total_host, void* stream);
 
-/* gram_flush with the counts in 64 bits.  The dense buffer keeps 64-bit counts
+/* gram_flush with the counts in 64 bits.  Both buffer layouts keep 64-bit counts
  * (an epoch-long window can meet one item, the padding item above all, more
- * than 2^31 times; gram_flush itself saturates such a count at INT32_MAX); the
- * slot table keeps 32-bit counts, which are widened here.  Same arguments
- * otherwise; with the dense buffer the outputs need room for N items. */
+ * than 2^31 times; gram_flush itself saturates such a count at INT32_MAX).  Same
+ * arguments otherwise; with the dense buffer the outputs need room for N items. */
 int gram_flush64(gram_ctx* ctx, int32_t* uniq_total, int64_t* counts_total, float* G_total,
                  int32_t* u_total_dev, int32_t* u_total_host, void* stream);
 
@@ -321,7 +321,7 @@ int gram_flush64(gram_ctx* ctx, int32_t* uniq_total, int64_t* counts_total, floa
  * Does not count as a step (the next gram_grad_accumulate keeps its index) but
  * makes the window non-empty for gram_encoder_wgrad.  Slot table: items the
  * window has not met take rows in list order (GRAM_ERR_CAPACITY latched when
- * the buffer is full), counts saturate at INT32_MAX.  Uses the workspace of the
+ * the buffer is full).  Uses the workspace of the
  * content-encoder batch calls (gram_pseudo_loss_grad, gram_mlp_backward). */
 int gram_window_import(gram_ctx* ctx, const int32_t* ids, const int64_t* counts, const float* G_rows,
                        int64_t n, void* stream);
@@ -371,7 +371,7 @@ const char* gram_kernel_name(int k);
  * from the contraction's epilogue (a benchmark needs it to count the bytes
  * each of the two forward kernels moves). */
 int gram_light_max(void);
-int gram_profile_enable(gram_ctx* ctx, uint32_t mask, int32_t max_launches);
+int gram_profile_enable(gram_ctx* ctx, uint64_t mask, int32_t max_launches);
 int gram_profile_read(gram_ctx* ctx, int k, int64_t* launches, double* total_ms);
 
 /* Message of the last failing call on ctx (or of the last failing gram_create

@@ -82,13 +82,7 @@ const char* validate(const gram_config* cfg, Derived* dv)
     dv->cap_u = cfg->max_positions < cfg->vocab_n ? cfg->max_positions : cfg->vocab_n;
     int64_t km = (int64_t)cfg->k_steps * cfg->max_positions;
     dv->cap_total = cfg->u_total_cap ? cfg->u_total_cap : (km < cfg->vocab_n ? km : cfg->vocab_n);
-    if (dense) {
-        dv->cap_total = cfg->vocab_n;
-        const int64_t window = ((int64_t)1 << 32) - 16;
-        if (cfg->xw_dtype == GRAM_BF16 && ((int64_t)cfg->vocab_n * cfg->d * 4 >= window ||
-                                           (int64_t)cfg->vocab_n * cfg->d_in * 2 >= window))
-            return "the dense buffer needs X and the N x d buffer below 4 GiB each";
-    }
+    if (dense) dv->cap_total = cfg->vocab_n;
     if (dv->cap_total >= ((int64_t)1 << 30)) return "persistent buffer rows must be < 2^30";
     dv->cap_chunk = dv->cap_u > dv->cap_total ? dv->cap_u : dv->cap_total;
     dv->n_sort_max = cfg->max_positions > dv->cap_total ? cfg->max_positions : dv->cap_total;
@@ -124,7 +118,7 @@ int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
     const bool dense = cfg.buffer_layout == GRAM_BUFFER_DENSE;
     int* slot_of = (int*)take(dense ? 1 : (int64_t)cfg.vocab_n * 4);
     int* id_of_slot = (int*)take(dense ? 1 : dv.cap_total * 4);
-    int* cnt_of_slot = (int*)take(dense ? 1 : dv.cap_total * 4);
+    long long* cnt_of_slot = (long long*)take(dense ? 1 : dv.cap_total * 8);
     long long* cnt64 = (long long*)take(dense ? (int64_t)cfg.vocab_n * 8 : 1);
     int* dense_sums = (int*)take(dense ? ((int64_t)cfg.vocab_n / kScanTile + 2) * 4 : 1);
     float* G = (float*)take(dv.cap_total * d * 4);
@@ -147,15 +141,6 @@ int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
     void* W2t = take(dh > 0 ? d * dh * 2 : 1);
     void* A1_ws = take(dh > 0 ? dv.cap_u * dh * 2 : 1);
     int* iota = (int*)take(dh > 0 ? dv.cap_chunk * 4 : 1);
-    const bool bf = cfg.xw_dtype == GRAM_BF16;
-    const int64_t ldt = wgrad_pitch_for(dv.cap_total);
-    // transposed copies for the wide-address weight gradient: needed only when X or the buffer lies
-    // beyond the 4 GiB a buffer descriptor can address (the same test encoder_wgrad applies)
-    const int64_t window = ((int64_t)1 << 32) - 16;
-    const bool wide = bf && !dense &&
-                      ((int64_t)cfg.vocab_n * d_in * 2 >= window || dv.cap_total * d * 4 >= window);
-    uint16_t* XT = (uint16_t*)take(wide ? d_in * ldt * 2 : 1);
-    uint16_t* GT = (uint16_t*)take(wide ? d * ldt * 2 : 1);
     if (c && base) {
         c->scal = scal; c->keys[0] = keys0; c->keys[1] = keys1; c->vals[0] = vals0; c->vals[1] = vals1;
         c->table = table; c->gtot = gtot; c->tile_sums = tile_sums; c->offsets = offsets;
@@ -163,7 +148,6 @@ int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
         c->long_list = long_list; c->slot_of = slot_of; c->id_of_slot = dense ? nullptr : id_of_slot;
         c->cnt_of_slot = cnt_of_slot; c->cnt64 = cnt64; c->dense_sums = dense_sums; c->G = G; c->E_ws = E_ws; c->loss_part = loss_part; c->chunk_ids = chunk_ids; c->seg_first = seg_first;
         c->seg_last = seg_last; c->Wt = Wt; c->wg_partial = wg_partial;
-        c->XT = XT; c->GT = GT; c->ldt = ldt;
         c->W1t = W1t; c->W2t = W2t; c->A1_ws = A1_ws; c->iota = iota;
     }
     return off;
@@ -397,9 +381,12 @@ int gram_encode_gather(gram_ctx* ctx, const void* X, const void* W, const int32_
     float* Ep = E ? E : c->E_ws;
     const int* up = u_dev ? u_dev : c->scal + kSU;
     // The fused epilogue walks the sorted order of the last dedup, so it applies only when the
-    // caller hands back that call's own outputs.
+    // caller hands back that call's own outputs.  It then takes the unique list from the context's
+    // copy as well: rows and positions come from one and the same dedup, whatever the caller's
+    // buffers hold by now.
     const bool own = uniq == c->last_uniq && inverse == c->last_inverse;
-    if (encode_forward(c, X, W, uniq, up, m < c->cap_u ? m : c->cap_u, Ep, s, own ? H : nullptr, E != nullptr))
+    if (encode_forward(c, X, W, own ? c->uniq_ws : uniq, own ? c->scal + kSU : up, m < c->cap_u ? m : c->cap_u, Ep,
+                       s, own ? H : nullptr, E != nullptr))
         gather_heavy(c, Ep, m, H, s);
     else
         gather_rows(c, Ep, inverse, m, H, s);
@@ -421,14 +408,13 @@ int gram_mlp_encode_gather(gram_ctx* ctx, const void* X, const void* W1, const v
                     (long long)m, (long long)c->cur_m);
     if (m > 0 && (!X || !W1 || !W2 || !uniq || !inverse || !H))
         return fail(c, GRAM_ERR_ARG, "gram_mlp_encode_gather: NULL pointer");
-    if ((int64_t)c->cfg.vocab_n * c->cfg.d_in * 2 >= ((int64_t)1 << 32) - 16)
-        return fail(c, GRAM_ERR_UNIMPLEMENTED, "gram_mlp_encode_gather: not available when X exceeds 4 GiB");
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (m == 0) return GRAM_OK;
     float* Ep = E ? E : c->E_ws;
     const int* up = u_dev ? u_dev : c->scal + kSU;
     const bool own = uniq == c->last_uniq && inverse == c->last_inverse;
-    if (mlp_forward(c, X, W1, W2, uniq, up, m < c->cap_u ? m : c->cap_u, A1, Ep, s, own ? H : nullptr, E != nullptr))
+    if (mlp_forward(c, X, W1, W2, own ? c->uniq_ws : uniq, own ? c->scal + kSU : up, m < c->cap_u ? m : c->cap_u, A1,
+                    Ep, s, own ? H : nullptr, E != nullptr))
         gather_heavy(c, Ep, m, H, s);
     else
         gather_rows(c, Ep, inverse, m, H, s);
@@ -457,13 +443,8 @@ int gram_mlp_backward(gram_ctx* ctx, const void* X, const void* W1, const void* 
         return fail(c, GRAM_ERR_ARG, "gram_mlp_backward: give exactly one of G_rows and Ht");
     if (!X || !W1 || !W2 || !dW1 || !dW2 || (n > 0 && (!ids || !work)))
         return fail(c, GRAM_ERR_ARG, "gram_mlp_backward: NULL pointer");
-    const int64_t window = ((int64_t)1 << 32) - 16;
-    const int64_t widest = c->cfg.d_hidden > c->cfg.d ? c->cfg.d_hidden : c->cfg.d;
-    if ((int64_t)c->cfg.vocab_n * c->cfg.d_in * 2 >= window || n * widest * 4 >= window)
-        return fail(c, GRAM_ERR_UNIMPLEMENTED, "gram_mlp_backward: not available when X or a batch matrix exceeds 4 GiB");
-    if (!mlp_backward(c, X, W1, W2, ids, G_rows, Ht, n, work, dW1, dW2, accumulate != 0, Ht ? loss_dev : nullptr,
-                      static_cast<hipStream_t>(stream)))
-        return fail(c, GRAM_ERR_UNIMPLEMENTED, "gram_mlp_backward: batch too large for the buffer window");
+    mlp_backward(c, X, W1, W2, ids, G_rows, Ht, n, work, dW1, dW2, accumulate != 0, Ht ? loss_dev : nullptr,
+                 static_cast<hipStream_t>(stream));
     return launch_status(c, "gram_mlp_backward");
 }
 
@@ -534,9 +515,7 @@ int gram_encoder_wgrad_chunk(gram_ctx* ctx, const void* X, float* dW, int64_t fi
     if (!X || !dW) return fail(c, GRAM_ERR_ARG, "gram_encoder_wgrad_chunk: NULL pointer");
     if (first_row < 0 || n_rows < 0)
         return fail(c, GRAM_ERR_ARG, "gram_encoder_wgrad_chunk: negative row range");
-    if (!encoder_wgrad(c, X, dW, static_cast<hipStream_t>(stream), first_row, n_rows, accumulate != 0))
-        return fail(c, GRAM_ERR_UNIMPLEMENTED,
-                    "gram_encoder_wgrad_chunk: chunks are not available when X or the buffer exceeds 4 GiB");
+    encoder_wgrad(c, X, dW, static_cast<hipStream_t>(stream), first_row, n_rows, accumulate != 0);
     return launch_status(c, "gram_encoder_wgrad_chunk");
 }
 
@@ -550,10 +529,6 @@ int gram_pseudo_loss_grad(gram_ctx* ctx, const void* X, const void* W, const int
                     (long long)c->cap_chunk);
     if (!X || !W || !dW || (n > 0 && (!ids || !Ht || !R)))
         return fail(c, GRAM_ERR_ARG, "gram_pseudo_loss_grad: NULL pointer");
-    const int64_t window = ((int64_t)1 << 32) - 16;
-    if (c->cfg.xw_dtype == GRAM_BF16 &&
-        ((int64_t)c->cfg.vocab_n * c->cfg.d_in * 2 >= window || n * c->cfg.d * 4 >= window))
-        return fail(c, GRAM_ERR_UNIMPLEMENTED, "gram_pseudo_loss_grad: not available when X or R exceeds 4 GiB");
     hipStream_t s = static_cast<hipStream_t>(stream);
     chunk_ids_prepare(c, ids, n, s);
     if (c->cfg.xw_dtype == GRAM_BF16) {
@@ -565,8 +540,7 @@ int gram_pseudo_loss_grad(gram_ctx* ctx, const void* X, const void* W, const int
         pseudo_miss(c, R, Ht, n, loss_dev, s);
     }
     const WgradRows rows = {c->chunk_ids, R, c->scal + kSChunkN, n};
-    if (!encoder_wgrad(c, X, dW, s, 0, n, accumulate != 0, &rows))
-        return fail(c, GRAM_ERR_UNIMPLEMENTED, "gram_pseudo_loss_grad: batch too large for the buffer window");
+    encoder_wgrad(c, X, dW, s, 0, n, accumulate != 0, &rows);
     return launch_status(c, "gram_pseudo_loss_grad");
 }
 
@@ -633,9 +607,9 @@ int gram_window_import(gram_ctx* ctx, const int32_t* ids, const int64_t* counts,
 static const char* const kKernelNames[KID_COUNT] = {
     "radix_hist", "radix_scan", "radix_scatter", "heads_count", "heads_emit", "counts", "unique_empty",
     "transpose_w", "encode_bf16", "encode_f32", "gather_rows", "slot_count", "slot_emit", "seg_reduce",
-    "seg_combine", "wgrad_bf16", "wgrad_f32", "wgrad_reduce", "transpose_x", "transpose_g", "flush_meta",
+    "seg_combine", "wgrad_bf16", "wgrad_f32", "wgrad_reduce", "flush_meta",
     "flush_rows", "unique_small", "gather_heavy", "pseudo_target", "pseudo_loss", "chunk_ids",
-    "pseudo_miss", "mlp_to_bf16"};
+    "pseudo_miss", "mlp_to_bf16", "encode_bf16_wide", "wgrad_bf16_wide"};
 
 int gram_kernel_count(void) { return KID_COUNT; }
 
@@ -643,7 +617,7 @@ int gram_light_max(void) { return kLightMax; }
 
 const char* gram_kernel_name(int k) { return (k >= 0 && k < KID_COUNT) ? kKernelNames[k] : ""; }
 
-int gram_profile_enable(gram_ctx* ctx, uint32_t mask, int32_t max_launches)
+int gram_profile_enable(gram_ctx* ctx, uint64_t mask, int32_t max_launches)
 {
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     if (!c) return GRAM_ERR_ARG;

@@ -12,9 +12,9 @@
 //   wgrad:   k_wgrad_tn_bf16 contracts over the rows of the gradient buffer, which
 //            is the slow dimension of both operands in memory, with transposing
 //            LDS reads; split-K over blocks, float32 partials added in split order.
-//   Operands beyond 4 GiB cannot be addressed through a buffer descriptor: the
-//   forward then takes k_gemm_nt_bf16_dma, the weight gradient transposed bf16
-//   copies (k_transpose_x / k_transpose_g) followed by k_gemm_nt_bf16.
+//   Operands are addressed through buffer descriptors (32-bit offsets, out-of-range
+//   reads return zero); matrices beyond the 4 GiB a descriptor can address take the
+//   WIDE variants of both kernels, which form 64-bit addresses per lane.
 // The float32 variants are plain FMA code for small problems.
 #include "gram_internal.h"
 
@@ -233,229 +233,30 @@ __global__ __launch_bounds__(kBlock) void k_encode_bf16(
     }
 }
 
-// ---- C[M,N] = A[M,K] . B[N,K]^T, bf16 in, fp32 out: direct-to-LDS variant -----------
+// ---- C[M,N] = A[M,K] . B[N,K]^T, bf16 in, fp32 out ---------------------------------
 //
-// (Used for operands beyond 4 GiB; see k_gemm_nt_bf16 below for the faster
-// register-staged variant.)
-// 256x256 block tile, 4 waves each owning a 128x128 quadrant (4x4 MFMA tiles,
-// 256 accumulator registers per lane).  K advances in slabs of 32 through a
-// ring of 4 LDS stages filled by direct global->LDS loads
-// (global_load_lds_dwordx4: lane l of a wave writes LDS bytes [16 l, 16 l + 16)
-// of a 1 KiB window, so a wave moves 16 rows x 64 bytes per instruction), ahead
-// of the multiply: gathered rows come from HBM with a latency longer than one
-// slab of MFMA work.
-// LDS rows are 64 bytes (4 chunks of 16); chunk c of row r sits at position
-// c ^ ((r >> 2) & 3), which spreads the 16-byte fragment reads of 16
-// consecutive rows over all banks.  The swizzle is applied by choosing which
-// global chunk each lane fetches.
-// Per slab: the fragment reads of k-step 1 overlap the MFMAs of k-step 0; then
-// one barrier publishes slab s+1 (and retires slab s-1, whose stage is refilled
-// with slab s+3), and the reads of slab s+1's first fragments overlap the MFMAs
-// of k-step 1.
-// Block indices are decoded so that the column tiles of one row tile run on the
-// same XCD (consecutive block indices are dealt round-robin to the 8 XCDs) and
-// share the strip of A through that XCD's L2.
-// GATHER: row j of A is A[row_ids[j]]; a row whose ID equals pad_id yields zeros.
-// Split-K: the K slabs are cut into `splits` contiguous ranges (1, or a multiple
-// of 8) and split z writes C + z * split_stride (an empty range writes zeros);
-// with M given on the host.
-constexpr int TM = 256, TN = 256, TK = 32, TSTAGES = 4;
+// 256x256 block tile, K in slabs of 32.  LDS rows are 64 bytes (4 chunks of 16); chunk c
+// of row r sits at position c ^ ((r >> 2) & 3), which spreads the 16-byte fragment reads of
+// 16 consecutive rows over all banks; the swizzle is applied by choosing which global chunk
+// each lane fetches.  Block indices are decoded so that the column tiles of one row tile run
+// on the same XCD (consecutive block indices are dealt round-robin to the 8 XCDs) and share
+// the strip of A through that XCD's L2.
+// Row j of A is A[row_ids[j]]; a row whose ID equals pad_id yields zeros.
+constexpr int TM = 256, TN = 256, TK = 32;
 constexpr int TROWB = TK * 2;                          // bytes per LDS row
 constexpr int TSTAGEB = (TM + TN) * TROWB;             // bytes per stage
-constexpr size_t TSMEM = (size_t)TSTAGES * TSTAGEB;
 
-// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane.
-__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base)
-{
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :: "v"(gptr), "s"(lds_base) : "memory");
-}
-// s_waitcnt vmcnt(n) only; the other counters are left unconstrained
-#define GRAM_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
-
-template <bool GATHER>
-__global__ __launch_bounds__(kBlock) void k_gemm_nt_bf16_dma(
-    const uint16_t* __restrict__ A, int64_t lda, const int* __restrict__ row_ids,
-    const int* __restrict__ m_dev, int m_host, const uint16_t* __restrict__ B, int64_t ldb, int n,
-    const int* __restrict__ k_dev, int k_host, int splits, int pad_id, int n_tiles,
-    float* __restrict__ C, int64_t ldc, int64_t split_stride)
-{
-    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-    __shared__ int s_pad_row;
-    const int M = m_dev ? *m_dev : m_host;
-    const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
-    int m0, n0, z;
-    if (splits == 1) {
-        // row tiles are dealt to XCDs; the column tiles of a row tile stay together
-        m0 = ((q / n_tiles) * 8 + xcd) * TM;
-        n0 = (q % n_tiles) * TN;
-        z = 0;
-    } else {
-        // all tiles of one K range stay on one XCD (splits is a multiple of 8)
-        const int tiles = ((M + TM - 1) / TM) * n_tiles;
-        z = xcd + 8 * (q / tiles);
-        m0 = ((q % tiles) / n_tiles) * TM;
-        n0 = ((q % tiles) % n_tiles) * TN;
-    }
-    if (m0 >= M || z >= splits) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    if (tid == 0) s_pad_row = -1;
-    __syncthreads();
-
-    // K range of this split, in slabs
-    const int ktot = k_dev ? *k_dev : k_host;
-    const int slabs_all = (ktot + TK - 1) / TK;
-    const int per = (slabs_all + splits - 1) / splits;
-    const int sl_begin = z * per;
-    int nslab = slabs_all - sl_begin;
-    if (nslab > per) nslab = per;
-    C += (int64_t)z * split_stride;
-
-    // loader: wave w fills row groups g = 4 w + t (16 rows each) of A and of B; lane l moves the
-    // chunk that belongs at position l & 3 of row 16 g + (l >> 2).  Rows past M / past n are
-    // clamped to a valid row: their products are never stored.
-    const int lrow = lane >> 2;
-    const int lchunk = (lane & 3) ^ ((lane >> 4) & 3);
-    const uint16_t* pa[4];
-    const uint16_t* pb[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int r = (wave * 4 + t) * 16 + lrow;
-        const int j = m0 + r < M ? m0 + r : M - 1;
-        if (GATHER) {
-            const int id = row_ids[j];
-            if (m0 + r < M && id == pad_id) s_pad_row = r;   // at most one row is the padding item
-            pa[t] = A + (int64_t)id * lda;
-        } else {
-            pa[t] = A + (int64_t)j * lda;
-        }
-        pa[t] += (int64_t)sl_begin * TK + lchunk * 8;
-        const int nn = n0 + r;
-        pb[t] = B + (int64_t)(nn < n ? nn : n - 1) * ldb + (int64_t)sl_begin * TK + lchunk * 8;
-    }
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void*)smem;
-    // this wave's first row group in A (wave-uniform, kept in a scalar register for M0)
-    const uint32_t wave_dst = __builtin_amdgcn_readfirstlane(lds0 + wave * 4 * 1024);
-
-    f32x16 acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    // fragment addresses: row = quadrant base + 32 i + (lane & 31); k-step ks reads logical chunk
-    // 2 ks + (lane >> 5), stored at that value ^ ((lane >> 2) & 3)
-    const int ph0 = (lane >> 5) ^ ((lane >> 2) & 3);
-    const int offA = (wm * 128 + (lane & 31)) * TROWB;
-    const int offB = (TM + wn * 128 + (lane & 31)) * TROWB;
-    const int c0 = ph0 * 16, c1 = (ph0 ^ 2) * 16;
-    bf16x8 fa[2][4], fb[2][4];
-#define GRAM_FRAGS(FS, STAGE, COFF)                                                                 \
-    {                                                                                               \
-        const unsigned char* sb_ = smem + (STAGE) * TSTAGEB;                                        \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                             \
-            fa[FS][i] = *reinterpret_cast<const bf16x8*>(sb_ + offA + i * 32 * TROWB + (COFF));     \
-            fb[FS][i] = *reinterpret_cast<const bf16x8*>(sb_ + offB + i * 32 * TROWB + (COFF));     \
-        }                                                                                           \
-    }
-#define GRAM_MMA(FS)                                                                                \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                   \
-        _Pragma("unroll") for (int j = 0; j < 4; ++j)                                               \
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[FS][i], fb[FS][j], acc[i][j], 0, 0, 0);
-#define GRAM_INTERLEAVE                                                                             \
-    _Pragma("unroll") for (int g = 0; g < 8; ++g) {                                                 \
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                          \
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                          \
-    }
-    // Slabs past the end are clamped to the last one: such loads land in a stage that is not read
-    // again, and they keep the count of loads in flight the same in every iteration.
-#define GRAM_ISSUE_CLAMPED(SLAB, STAGE_OF)                                                          \
-    {                                                                                               \
-        const uint32_t st_ = wave_dst + ((STAGE_OF) & (TSTAGES - 1)) * TSTAGEB;                     \
-        const int k_ = ((SLAB) < last ? (SLAB) : last) * TK;                                        \
-        _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                             \
-            dma16(pa[t] + k_, st_ + t * 1024);                                                      \
-            dma16(pb[t] + k_, st_ + TM * TROWB + t * 1024);                                         \
-        }                                                                                           \
-    }
-
-    if (nslab > 0) {
-        const int last = nslab - 1;
-        GRAM_ISSUE_CLAMPED(0, 0)
-        GRAM_ISSUE_CLAMPED(1, 1)
-        GRAM_ISSUE_CLAMPED(2, 2)
-        GRAM_WAIT_VM(16);     // 24 issued, the oldest 8 (slab 0) needed
-        __syncthreads();
-        GRAM_FRAGS(0, 0, c0)
-        for (int sl = 0; sl < last; ++sl) {
-            GRAM_FRAGS(1, sl & (TSTAGES - 1), c1)
-            GRAM_MMA(0)
-            GRAM_INTERLEAVE
-            GRAM_WAIT_VM(8);      // slab sl+1 has landed (this wave's part) ...
-            __syncthreads();      // ... and everybody's part; slab sl-1 is retired
-            GRAM_ISSUE_CLAMPED(sl + 3, sl + 3)
-            GRAM_FRAGS(0, (sl + 1) & (TSTAGES - 1), c0)
-            GRAM_MMA(1)
-            GRAM_INTERLEAVE
-        }
-        GRAM_FRAGS(1, last & (TSTAGES - 1), c1)
-        GRAM_MMA(0)
-        GRAM_INTERLEAVE
-        GRAM_MMA(1)
-        GRAM_WAIT_VM(0);
-    }
-
-    // accumulator element r of a lane sits at (row, col) = ((r / 4) * 8 + (lane / 32) * 4 + r % 4, lane % 32)
-    const int pad_row = GATHER ? s_pad_row : -1;
-    if (m0 + TM <= M && n0 + TN <= n) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int lr = wm * 128 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                float* row = C + (int64_t)(m0 + lr) * ldc + n0 + wn * 128 + (lane & 31);
-                const bool zero = lr == pad_row;
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) row[jj * 32] = zero ? 0.f : acc[i][jj][r];
-            }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int lr = wm * 128 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                if (m0 + lr < M) {
-                    float* row = C + (int64_t)(m0 + lr) * ldc + n0 + wn * 128 + (lane & 31);
-                    const bool zero = lr == pad_row;
-#pragma unroll
-                    for (int jj = 0; jj < 4; ++jj)
-                        if (n0 + wn * 128 + jj * 32 + (lane & 31) < n) row[jj * 32] = zero ? 0.f : acc[i][jj][r];
-                }
-            }
-    }
-}
-#undef GRAM_ISSUE_CLAMPED
-#undef GRAM_FRAGS
-#undef GRAM_MMA
-#undef GRAM_INTERLEAVE
-
-// ---- the same contraction with register-staged buffer loads ----------------------
-//
-// Measured on MI355X: a wave that issues direct-to-LDS loads stalls at issue for
-// as long as the memory pipe needs to take them (about 130 cycles per 1 KiB
-// instruction at 4 waves per CU), and with one wave per SIMD nothing else can
-// issue MFMAs meanwhile, so load time and MFMA time add up.  buffer_load_dwordx4
-// into registers issues in about 20 cycles and completes in the background at
-// the same 29 bytes per clock and CU.  This variant therefore loads slab s+3
-// into one of two register sets, parks slab s+1 in LDS (2 stages, same swizzled
-// layout) just before the barrier that publishes it, and interleaves the load,
-// LDS-write and fragment-read instructions with the MFMAs of the current slab.
-// Operands are addressed through buffer descriptors (base + 32-bit byte offset;
-// reads past the end return zero), which limits each operand to 4 GiB; larger
-// ones take k_gemm_nt_bf16_dma.
+// Register-staged loads.  Measured on MI355X: a wave that issues direct-to-LDS loads
+// stalls at issue for as long as the memory pipe needs to take them (about 130 cycles
+// per 1 KiB instruction at 4 waves per CU), so load time and MFMA time add up.
+// buffer_load_dwordx4 into registers issues in about 20 cycles and completes in the
+// background.  The kernel therefore loads slab s+3 into one of two register sets, parks
+// slab s+1 in LDS (2 stages) just before the barrier that publishes it, and interleaves
+// the load, LDS-write and fragment-read instructions with the MFMAs of the current slab.
+// Operands are addressed through buffer descriptors (base + 32-bit byte offset); a
+// matrix A beyond the 4 GiB such a descriptor can address takes the WIDE variant, whose
+// lanes keep 64-bit row pointers instead (every address it forms is a valid one: rows
+// past the end are clamped and K is a multiple of the slab).
 typedef int v4i32 __attribute__((ext_vector_type(4)));
 constexpr int RSTAGES = 2;
 constexpr size_t RSMEM = (size_t)RSTAGES * TSTAGEB;
@@ -485,30 +286,21 @@ struct ScatterArgs {
 };
 
 // HB (with SCATTER): H holds bf16, values are rounded to nearest even as they are stored.
-template <bool GATHER, int NW, bool SCATTER, int EPI = kEpiPlain, bool HB = false>
+template <bool GATHER, int NW, bool SCATTER, int EPI = kEpiPlain, bool HB = false, bool WIDE = false>
 __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
     const uint16_t* __restrict__ A, int64_t lda, uint32_t a_bytes, const int* __restrict__ row_ids,
-    const int* __restrict__ m_dev, int m_host, const uint16_t* __restrict__ B, int64_t ldb,
-    uint32_t b_bytes, int n, const int* __restrict__ k_dev, int k_host, int splits, int pad_id,
-    int n_tiles, float* __restrict__ C, int64_t ldc, int64_t split_stride, ScatterArgs sc,
+    const int* __restrict__ m_dev, const uint16_t* __restrict__ B, int64_t ldb, uint32_t b_bytes, int n,
+    int ktot, int pad_id, int n_tiles, float* __restrict__ C, int64_t ldc, ScatterArgs sc,
     const void* __restrict__ aux)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     __shared__ int s_pad_row;
-    const int M = m_dev ? *m_dev : m_host;
+    const int M = *m_dev;
+    // row tiles are dealt to the XCDs; the column tiles of a row tile stay together
     const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
-    int m0, n0, z;
-    if (splits == 1) {
-        m0 = ((q / n_tiles) * 8 + xcd) * TM;
-        n0 = (q % n_tiles) * TN;
-        z = 0;
-    } else {
-        const int tiles = ((M + TM - 1) / TM) * n_tiles;
-        z = xcd + 8 * (q / tiles);
-        m0 = ((q % tiles) / n_tiles) * TM;
-        n0 = ((q % tiles) % n_tiles) * TN;
-    }
-    if (m0 >= M || z >= splits) return;
+    const int m0 = ((q / n_tiles) * 8 + xcd) * TM;
+    const int n0 = (q % n_tiles) * TN;
+    if (m0 >= M) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     constexpr int NT = NW == 4 ? 4 : 2;          // 32-column MFMA tiles per wave
     constexpr int GA = 16 / NW;                  // 16-row groups of A (and of B) a wave loads per slab
@@ -516,13 +308,8 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
     if (tid == 0) s_pad_row = -1;
     __syncthreads();
 
-    const int ktot = k_dev ? *k_dev : k_host;
-    const int slabs_all = (ktot + TK - 1) / TK;
-    const int per = (slabs_all + splits - 1) / splits;
-    const int sl_begin = z * per;
-    int nslab = slabs_all - sl_begin;
-    if (nslab > per) nslab = per;
-    C += (int64_t)z * split_stride;
+    const int nslab = (ktot + TK - 1) / TK;
+    constexpr int sl_begin = 0;
 
     // loader: wave w moves row groups g = GA w + t (16 rows each) of A and of B; lane l moves the
     // chunk that belongs at position l & 3 of row 16 g + (l >> 2).  Rows past M / past n are
@@ -532,6 +319,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
     const int lrow = lane >> 2;
     const int lchunk = (lane & 3) ^ ((lane >> 4) & 3);
     uint32_t oa[GA], ob[GA];
+    const unsigned char* pa[WIDE ? GA : 1];
 #pragma unroll
     for (int t = 0; t < GA; ++t) {
         const int r = (wave * GA + t) * 16 + lrow;
@@ -543,6 +331,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
             rowA = id;
         }
         oa[t] = (uint32_t)((rowA * lda + (int64_t)sl_begin * TK + lchunk * 8) * 2);
+        if (WIDE) pa[t] = reinterpret_cast<const unsigned char*>(A) + (rowA * lda + (int64_t)sl_begin * TK + lchunk * 8) * 2;
         const int nn = n0 + r;
         ob[t] = (uint32_t)(((int64_t)(nn < n ? nn : n - 1) * ldb + (int64_t)sl_begin * TK + lchunk * 8) * 2);
     }
@@ -601,7 +390,8 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
     {                                                                                               \
         const uint32_t k_ = (uint32_t)(((SLAB) < last ? (SLAB) : last) * (TK * 2));                 \
         _Pragma("unroll") for (int t = 0; t < GA; ++t) {                                            \
-            ra[SET][t] = __builtin_amdgcn_raw_buffer_load_b128(rsA, oa[t] + k_, 0, 0);              \
+            if (WIDE) ra[SET][t] = *reinterpret_cast<const v4i32*>(pa[t] + k_);                      \
+            else ra[SET][t] = __builtin_amdgcn_raw_buffer_load_b128(rsA, oa[t] + k_, 0, 0);         \
             rb[SET][t] = __builtin_amdgcn_raw_buffer_load_b128(rsB, ob[t] + k_, 0, 0);              \
         }                                                                                           \
     }
@@ -791,112 +581,74 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
 
 constexpr int kGemmWaves = 8;
 
-// a_rows / b_rows: rows of the matrices A and B as allocated (A: all rows that row_ids may name).
-// epi != kEpiPlain (with its `aux` matrix) is available for gathered, unsplit, unfused launches
-// whose operands lie below 4 GiB.
-template <int EPI>
-static void launch_gemm_nt_epi(Ctx* c, int kid, unsigned blocks, hipStream_t s, const uint16_t* A, int64_t lda,
-                               uint32_t a_bytes, const int* row_ids, const int* m_dev, int m_host,
-                               const uint16_t* B, int64_t ldb, uint32_t b_bytes, int n, int k_host, int pad_id,
-                               int n_tiles, float* C, int64_t ldc, const void* aux)
+template <bool SCATTER, int EPI, bool HB, bool WIDE>
+static void launch_gemm_variant(Ctx* c, int kid, unsigned blocks, hipStream_t s, const uint16_t* A, int64_t lda,
+                                int64_t a_bytes, const int* row_ids, const int* m_dev, const uint16_t* B,
+                                int64_t ldb, int64_t b_bytes, int n, int k, int pad_id, int n_tiles, float* C,
+                                int64_t ldc, const ScatterArgs& sc, const void* aux)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16<true, kGemmWaves, false, EPI>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)RSMEM);
-        attr_set = true;
-    }
-    const ScatterArgs none = {nullptr, nullptr, nullptr, 0, 0, 0};
-    launch_smem(c, kid, k_gemm_nt_bf16<true, kGemmWaves, false, EPI>, dim3(blocks), dim3(kGemmWaves * 64), RSMEM,
-                s, A, lda, a_bytes, row_ids, m_dev, m_host, B, ldb, b_bytes, n, (const int*)nullptr, k_host, 1,
-                pad_id, n_tiles, C, ldc, (int64_t)0, none, aux);
+    constexpr auto kern = k_gemm_nt_bf16<true, kGemmWaves, SCATTER, EPI, HB, WIDE>;
+    constexpr size_t smem = SCATTER ? RSMEM_SC : RSMEM;
+    ensure_dynamic_lds<kern>((int)smem);
+    // the descriptor of a WIDE operand is not used; any size that fits its field will do
+    launch_smem(c, kid, kern, dim3(blocks), dim3(kGemmWaves * 64), smem, s, A, lda,
+                (uint32_t)(WIDE ? 0 : a_bytes), row_ids, m_dev, B, ldb, (uint32_t)b_bytes, n, k, pad_id, n_tiles, C,
+                ldc, sc, aux);
 }
 
-template <bool GATHER>
-static void launch_gemm_nt(Ctx* c, int kid, const uint16_t* A, int64_t lda, int64_t a_rows,
-                           const int* row_ids, const int* m_dev, int m_host, int64_t m_bound,
-                           const uint16_t* B, int64_t ldb, int64_t b_rows, int n, const int* k_dev,
-                           int k_host, int splits, float* C, int64_t ldc, int64_t split_stride,
-                           hipStream_t s, const ScatterArgs* scatter = nullptr, int pad_id = -1,
-                           int epi = kEpiPlain, const void* aux = nullptr)
+// C[j,:] = epi(A[row_ids[j],:k] . B^T) for j < *m_dev <= m_bound with the 256x256 kernel.
+// a_rows / b_rows: rows of the matrices A and B as allocated (A: all rows that row_ids may
+// name).  A may lie beyond 4 GiB for the plain epilogue (with or without the fused gather);
+// the other epilogue modes and B need buffer descriptors (callers check).
+static void launch_gemm_nt(Ctx* c, const uint16_t* A, int64_t lda, int64_t a_rows, const int* row_ids,
+                           const int* m_dev, int64_t m_bound, const uint16_t* B, int64_t ldb, int64_t b_rows,
+                           int n, int k, float* C, int64_t ldc, hipStream_t s, const ScatterArgs* scatter,
+                           int pad_id, int epi, const void* aux)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16<GATHER, kGemmWaves, false>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)RSMEM);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16<GATHER, kGemmWaves, GATHER>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)(GATHER ? RSMEM_SC : RSMEM));
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16<GATHER, kGemmWaves, GATHER, kEpiPlain, GATHER>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)(GATHER ? RSMEM_SC : RSMEM));
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_nt_bf16_dma<GATHER>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)TSMEM);
-        attr_set = true;
-    }
     const int n_tiles = (n + TN - 1) / TN;
-    int64_t blocks;
-    if (splits == 1)
-        blocks = (((m_bound + TM - 1) / TM + 7) / 8 * 8) * n_tiles;
-    else
-        blocks = ((m_bound + TM - 1) / TM) * n_tiles * splits;
+    const unsigned blocks = (unsigned)((((m_bound + TM - 1) / TM + 7) / 8 * 8) * n_tiles);
     const int64_t a_bytes = a_rows * lda * 2, b_bytes = b_rows * ldb * 2;
-    const int64_t window = (int64_t)1 << 32;
+    const bool wide = a_bytes >= kBufferWindow;
+    const int kid = wide ? KID_ENCODE_BF16_WIDE : KID_ENCODE_BF16;
     const ScatterArgs none = {nullptr, nullptr, nullptr, 0, 0, 0};
-    if (epi != kEpiPlain) {
-        // callers keep to the conditions stated above
-        if (epi == kEpiReluBf16)
-            launch_gemm_nt_epi<kEpiReluBf16>(c, kid, (unsigned)blocks, s, A, lda, (uint32_t)a_bytes, row_ids, m_dev,
-                                              m_host, B, ldb, (uint32_t)b_bytes, n, k_host, pad_id, n_tiles, C, ldc, aux);
-        else if (epi == kEpiMinus)
-            launch_gemm_nt_epi<kEpiMinus>(c, kid, (unsigned)blocks, s, A, lda, (uint32_t)a_bytes, row_ids, m_dev,
-                                          m_host, B, ldb, (uint32_t)b_bytes, n, k_host, pad_id, n_tiles, C, ldc, aux);
-        else
-            launch_gemm_nt_epi<kEpiGate>(c, kid, (unsigned)blocks, s, A, lda, (uint32_t)a_bytes, row_ids, m_dev,
-                                         m_host, B, ldb, (uint32_t)b_bytes, n, k_host, pad_id, n_tiles, C, ldc, aux);
-    } else if (scatter && scatter->h_bf16)
-        launch_smem(c, kid, k_gemm_nt_bf16<GATHER, kGemmWaves, GATHER, kEpiPlain, GATHER>, dim3((unsigned)blocks),
-                    dim3(kGemmWaves * 64), GATHER ? RSMEM_SC : RSMEM, s, A, lda, (uint32_t)a_bytes, row_ids,
-                    m_dev, m_host, B, ldb, (uint32_t)b_bytes, n, k_dev, k_host, splits, pad_id,
-                    n_tiles, C, ldc, split_stride, *scatter, (const void*)nullptr);
-    else if (scatter)
-        launch_smem(c, kid, k_gemm_nt_bf16<GATHER, kGemmWaves, GATHER>, dim3((unsigned)blocks),
-                    dim3(kGemmWaves * 64), GATHER ? RSMEM_SC : RSMEM, s, A, lda, (uint32_t)a_bytes, row_ids,
-                    m_dev, m_host, B, ldb, (uint32_t)b_bytes, n, k_dev, k_host, splits, pad_id,
-                    n_tiles, C, ldc, split_stride, *scatter, (const void*)nullptr);
-    else if (a_bytes < window && b_bytes < window)
-        launch_smem(c, kid, k_gemm_nt_bf16<GATHER, kGemmWaves, false>, dim3((unsigned)blocks),
-                    dim3(kGemmWaves * 64), RSMEM, s, A, lda, (uint32_t)a_bytes, row_ids, m_dev, m_host, B,
-                    ldb, (uint32_t)b_bytes, n, k_dev, k_host, splits, pad_id, n_tiles, C, ldc,
-                    split_stride, none, (const void*)nullptr);
-    else
-        launch_smem(c, kid, k_gemm_nt_bf16_dma<GATHER>, dim3((unsigned)blocks), dim3(kBlock), TSMEM, s, A,
-                    lda, row_ids, m_dev, m_host, B, ldb, n, k_dev, k_host, splits, pad_id, n_tiles,
-                    C, ldc, split_stride);
+#define GRAM_GO(SC, EPI, HB, WIDE, ARGS)                                                            \
+    launch_gemm_variant<SC, EPI, HB, WIDE>(c, kid, blocks, s, A, lda, a_bytes, row_ids, m_dev, B, ldb, b_bytes, n, \
+                                           k, pad_id, n_tiles, C, ldc, ARGS, aux)
+    if (epi == kEpiReluBf16) GRAM_GO(false, kEpiReluBf16, false, false, none);
+    else if (epi == kEpiMinus) GRAM_GO(false, kEpiMinus, false, false, none);
+    else if (epi == kEpiGate) GRAM_GO(false, kEpiGate, false, false, none);
+    else if (scatter && scatter->h_bf16) {
+        if (wide) GRAM_GO(true, kEpiPlain, true, true, *scatter);
+        else GRAM_GO(true, kEpiPlain, true, false, *scatter);
+    } else if (scatter) {
+        if (wide) GRAM_GO(true, kEpiPlain, false, true, *scatter);
+        else GRAM_GO(true, kEpiPlain, false, false, *scatter);
+    } else {
+        if (wide) GRAM_GO(false, kEpiPlain, false, true, none);
+        else GRAM_GO(false, kEpiPlain, false, false, none);
+    }
+#undef GRAM_GO
 }
 
-// ---- 64x64 bf16 transposes through LDS (16-byte global accesses both ways) ---------
+// ---- 64x64 bf16 transpose through LDS (16-byte global accesses both ways) ----------
 
 constexpr int TT = 64;   // transpose tile edge
 
-// id_of_slot == NULL: plain transpose of the first `rows_host` rows (used for W -> W^T).
-__global__ __launch_bounds__(kBlock) void k_transpose_x(
-    const uint16_t* __restrict__ X, const int* __restrict__ id_of_slot, const int* __restrict__ scal,
-    int rows_host, int d_in, int pad_id, uint16_t* __restrict__ XT, int64_t ldt)
+// Wt[cols, rows] = W[rows, cols]^T; rows and cols multiples of 8.
+__global__ __launch_bounds__(kBlock) void k_transpose_w(const uint16_t* __restrict__ W, int rows, int cols,
+                                                        uint16_t* __restrict__ Wt)
 {
-    __shared__ uint16_t tile[TT][TT + 2];     // [buffer row][feature]
-    const int U = id_of_slot ? scal[kSUTotal] : rows_host;
-    const int s_tiles = (U + TT - 1) / TT, i_tiles = (d_in + TT - 1) / TT;
-    for (int t = blockIdx.x; t < s_tiles * i_tiles; t += gridDim.x) {
-        const int s0 = (t / i_tiles) * TT, i0 = (t % i_tiles) * TT;
+    __shared__ uint16_t tile[TT][TT + 2];     // [row of W][column of W]
+    const int r_tiles = (rows + TT - 1) / TT, c_tiles = (cols + TT - 1) / TT;
+    for (int t = blockIdx.x; t < r_tiles * c_tiles; t += gridDim.x) {
+        const int r0 = (t / c_tiles) * TT, c0 = (t % c_tiles) * TT;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int cid = threadIdx.x + h * kBlock;
             const int row = cid >> 3, ch = (cid & 7) * 8;
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (s0 + row < U && i0 + ch < d_in) {
-                const int id = id_of_slot ? id_of_slot[s0 + row] : s0 + row;
-                if (!id_of_slot || id != pad_id)
-                    v = *reinterpret_cast<const uint4*>(X + (int64_t)id * d_in + i0 + ch);
-            }
+            if (r0 + row < rows && c0 + ch < cols)
+                v = *reinterpret_cast<const uint4*>(W + (int64_t)(r0 + row) * cols + c0 + ch);
             const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int e = 0; e < 8; ++e) tile[row][ch + e] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
@@ -906,51 +658,12 @@ __global__ __launch_bounds__(kBlock) void k_transpose_x(
         for (int h = 0; h < 2; ++h) {
             const int cid = threadIdx.x + h * kBlock;
             const int r = cid >> 3, ch = (cid & 7) * 8;
-            // a plain transpose (no zero padding of the row tail) stops at the last real row
-            if (i0 + r < d_in && (id_of_slot || s0 + ch < U)) {
+            if (c0 + r < cols && r0 + ch < rows) {
                 uint32_t w[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
                     w[e] = (uint32_t)tile[ch + 2 * e][r] | ((uint32_t)tile[ch + 2 * e + 1][r] << 16);
-                *reinterpret_cast<uint4*>(XT + (int64_t)(i0 + r) * ldt + s0 + ch) = make_uint4(w[0], w[1], w[2], w[3]);
-            }
-        }
-        __syncthreads();
-    }
-}
-
-__global__ __launch_bounds__(kBlock) void k_transpose_g(const float* __restrict__ G,
-                                                        const int* __restrict__ scal, int d,
-                                                        uint16_t* __restrict__ GT, int64_t ldt)
-{
-    __shared__ uint16_t tile[TT][TT + 2];     // [buffer row][column]
-    const int U = scal[kSUTotal];
-    const int s_tiles = (U + TT - 1) / TT, c_tiles = (d + TT - 1) / TT;
-    for (int t = blockIdx.x; t < s_tiles * c_tiles; t += gridDim.x) {
-        const int s0 = (t / c_tiles) * TT, cc0 = (t % c_tiles) * TT;
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            const int cid = threadIdx.x + h * kBlock;
-            const int row = cid >> 4, ch = (cid & 15) * 4;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (s0 + row < U && cc0 + ch < d)
-                v = *reinterpret_cast<const float4*>(G + (int64_t)(s0 + row) * d + cc0 + ch);
-            tile[row][ch + 0] = f32_to_bf16_rne(v.x);
-            tile[row][ch + 1] = f32_to_bf16_rne(v.y);
-            tile[row][ch + 2] = f32_to_bf16_rne(v.z);
-            tile[row][ch + 3] = f32_to_bf16_rne(v.w);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int cid = threadIdx.x + h * kBlock;
-            const int r = cid >> 3, ch = (cid & 7) * 8;
-            if (cc0 + r < d) {
-                uint32_t w[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    w[e] = (uint32_t)tile[ch + 2 * e][r] | ((uint32_t)tile[ch + 2 * e + 1][r] << 16);
-                *reinterpret_cast<uint4*>(GT + (int64_t)(cc0 + r) * ldt + s0 + ch) = make_uint4(w[0], w[1], w[2], w[3]);
+                *reinterpret_cast<uint4*>(Wt + (int64_t)(c0 + r) * rows + r0 + ch) = make_uint4(w[0], w[1], w[2], w[3]);
             }
         }
         __syncthreads();
@@ -982,9 +695,8 @@ void transpose_weight(Ctx* c, const void* W, int rows, int cols, void* Wt, hipSt
     // 16-byte row chunks of W^T never straddle its end because rows is a multiple of 8
     if (cols % 8 == 0) {
         const int tiles = ((rows + TT - 1) / TT) * ((cols + TT - 1) / TT);
-        launch(c, KID_TRANSPOSE_U16, k_transpose_x, dim3(tiles < 1024 ? tiles : 1024), dim3(kBlock), s,
-               static_cast<const uint16_t*>(W), (const int*)nullptr, c->scal, rows, cols, -1,
-               static_cast<uint16_t*>(Wt), (int64_t)rows);
+        launch(c, KID_TRANSPOSE_U16, k_transpose_w, dim3(tiles < 1024 ? tiles : 1024), dim3(kBlock), s,
+               static_cast<const uint16_t*>(W), rows, cols, static_cast<uint16_t*>(Wt));
     } else {
         launch(c, KID_TRANSPOSE_U16, k_transpose_u16, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(kBlock), s,
                static_cast<const uint16_t*>(W), rows, cols, static_cast<uint16_t*>(Wt));
@@ -992,10 +704,12 @@ void transpose_weight(Ctx* c, const void* W, int rows, int cols, void* Wt, hipSt
 }
 
 // Batches that give the 256x256 kernel a tile for every CU (and a K that fits its slabs) take it;
-// the rest take the 64x64 latency-oriented kernel.
-static bool takes_big_kernel(const Ctx* c, int64_t rows_max, int n_out, int k)
+// the rest take the 64x64 latency-oriented kernel, which addresses its operands through plain
+// pointers and therefore also serves the epilogue modes when A lies beyond 4 GiB.
+static bool takes_big_kernel(const Ctx* c, int64_t rows_max, int n_out, int k, int64_t a_rows, int epi)
 {
     const int64_t tile_bound = ((rows_max + TM - 1) / TM) * ((n_out + TN - 1) / TN);
+    if (epi != kEpiPlain && a_rows * k * 2 >= kBufferWindow) return false;
     return tile_bound >= c->num_cus && k % TK == 0;
 }
 
@@ -1004,16 +718,15 @@ bool gemm_rows_bf16(Ctx* c, const void* A, int64_t a_rows, int k, const int* row
                     void* H_scatter, bool caller_wants_C, int epi, const void* aux, const void* B_plain)
 {
     if (rows_max <= 0) return false;
-    const int64_t window = (int64_t)1 << 32;
-    if (takes_big_kernel(c, rows_max, n_out, k)) {
+    if (takes_big_kernel(c, rows_max, n_out, k, a_rows, epi)) {
         // Fusing the gather pays when there are tiles for every CU: with a handful of tiles the
         // position stores of a tile run on one CU while a separate gather spreads over all.
-        const bool fuse = H_scatter && epi == kEpiPlain && a_rows * k * 2 < window;
+        const bool fuse = H_scatter && epi == kEpiPlain;
         const ScatterArgs sc = {c->offsets, c->perm, H_scatter, (int64_t)n_out, caller_wants_C ? 1 : 0,
                                c->cfg.h_dtype == GRAM_BF16 ? 1 : 0};
-        launch_gemm_nt<true>(c, KID_ENCODE_BF16, static_cast<const uint16_t*>(A), k, a_rows, row_ids, n_dev,
-                             0, rows_max, static_cast<const uint16_t*>(Bt), k, n_out, n_out, nullptr, k, 1,
-                             C, n_out, 0, s, fuse ? &sc : nullptr, pad_id, epi, aux);
+        launch_gemm_nt(c, static_cast<const uint16_t*>(A), k, a_rows, row_ids, n_dev, rows_max,
+                       static_cast<const uint16_t*>(Bt), k, n_out, n_out, k, C, n_out, s, fuse ? &sc : nullptr,
+                       pad_id, epi, aux);
         return fuse;
     }
     const dim3 grid((n_out + BN - 1) / BN, (unsigned)((rows_max + BM - 1) / BM));
@@ -1053,7 +766,7 @@ bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
     const int d_in = c->cfg.d_in, d = c->cfg.d;
     if (c->cfg.xw_dtype == GRAM_BF16) {
         // the small kernel can read W as it is (no transposed copy, one launch less)
-        const bool direct = !takes_big_kernel(c, rows_max, d, d_in) && d % 8 == 0 &&
+        const bool direct = !takes_big_kernel(c, rows_max, d, d_in, c->cfg.vocab_n, epi) && d % 8 == 0 &&
                             (epi == kEpiPlain || epi == kEpiMinus);
         if (!direct) transpose_weight(c, W, d_in, d, c->Wt, s);
         return gemm_rows_bf16(c, X, c->cfg.vocab_n, d_in, uniq, c->cfg.pad_id, u_dev, rows_max, c->Wt, d, E, s,
@@ -1073,14 +786,6 @@ bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
 // partials in range order.  The ranges depend only on the number of rows in
 // the buffer, so the result is reproducible.
 //
-// Wide-address path only (an operand beyond 4 GiB): both operands have the
-// contraction index (buffer row) as their slow dimension in memory, so they are
-// first transposed into workspace by the two transpose kernels above,
-//   XT[i][s] = X[item_s][i]            (gather + transpose, zero for padding)
-//   GT[c][s] = bf16(G[s][c])           (round to nearest even + transpose)
-// with rows padded by zeros up to a multiple of 64 buffer rows, and contracted by
-// k_gemm_nt_bf16.
-
 // ---- weight gradient without transposed copies ---------------------------------------
 //
 // dW[i,c] = sum_s X[item_s, i] * bf16(G[s, c]): both operands have the contraction
@@ -1101,7 +806,8 @@ bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
 // and showed as bank conflicts in 37 % of the LDS cycles).
 // Loads go through buffer descriptors; a row past the end of the buffer, a
 // padding item or a column past the matrix edge is turned into an out-of-range
-// offset, for which the hardware returns zeros.
+// offset, for which the hardware returns zeros.  WIDE (an operand beyond the 4 GiB
+// of a descriptor): plain 64-bit addresses, and such a load is skipped instead.
 // Same pipeline as k_gemm_nt_bf16: register-staged loads, two LDS stages, one
 // barrier per slab of 32 buffer rows; split-K with one K range per XCD.
 typedef short v4i16 __attribute__((ext_vector_type(4)));
@@ -1116,7 +822,7 @@ constexpr uint32_t kOutOfRange = 0xFFFFFFF0u;
 constexpr int kWgradWaves = 8;
 
 // NW = waves per block: 4 (128x128 each) or 8 (128x64 each, two per SIMD).
-template <int NW>
+template <int NW, bool WIDE = false>
 __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
     const uint16_t* __restrict__ X, uint32_t x_bytes, const int* __restrict__ id_of_slot,
     const float* __restrict__ G, uint32_t g_bytes, const int* __restrict__ rows_dev, int d_in, int d,
@@ -1233,13 +939,26 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
             const int feat = i0 + ((a_pos ^ ((kk & 3) << 2)) * 8);                                  \
             const int id = ids_cur[t];                                                              \
             const bool ok = id != pad_id && feat < d_in && sb_ + kk < U && sb_ + kk >= row_begin;   \
-            const uint32_t off = ok ? (uint32_t)(((int64_t)id * d_in + feat) * 2) : kOutOfRange;    \
-            ra[(SET) % SETS][t] = __builtin_amdgcn_raw_buffer_load_b128(rsX, off, 0, 0);                     \
+            if (WIDE) {                                                                             \
+                v4i32 v_ = {0, 0, 0, 0};                                                            \
+                if (ok) v_ = *reinterpret_cast<const v4i32*>(X + (int64_t)id * d_in + feat);        \
+                ra[(SET) % SETS][t] = v_;                                                           \
+            } else {                                                                                \
+                const uint32_t off = ok ? (uint32_t)(((int64_t)id * d_in + feat) * 2) : kOutOfRange; \
+                ra[(SET) % SETS][t] = __builtin_amdgcn_raw_buffer_load_b128(rsX, off, 0, 0);        \
+            }                                                                                       \
         }                                                                                           \
         _Pragma("unroll") for (int t = 0; t < RW; ++t) {                                            \
             const int slot = sb_ + wave * RW + t;                                                    \
-            const uint32_t off = (g_col_ok && slot < U && slot >= row_begin) ? (uint32_t)(((int64_t)slot * d + g_col) * 4) : kOutOfRange; \
-            rg[(SET) % SETS][t] = __builtin_amdgcn_raw_buffer_load_b128(rsG, off, 0, 0);                     \
+            const bool okg = g_col_ok && slot < U && slot >= row_begin;                             \
+            if (WIDE) {                                                                             \
+                v4i32 v_ = {0, 0, 0, 0};                                                            \
+                if (okg) v_ = *reinterpret_cast<const v4i32*>(G + (int64_t)slot * d + g_col);       \
+                rg[(SET) % SETS][t] = v_;                                                           \
+            } else {                                                                                \
+                const uint32_t off = okg ? (uint32_t)(((int64_t)slot * d + g_col) * 4) : kOutOfRange; \
+                rg[(SET) % SETS][t] = __builtin_amdgcn_raw_buffer_load_b128(rsG, off, 0, 0);        \
+            }                                                                                       \
         }                                                                                           \
     }
 #define GRAM_PARK(SET, STAGE)                                                                       \
@@ -1382,9 +1101,7 @@ int wgrad_splits_dims(int d_in, int d, bool bf16)
     return s;
 }
 
-int64_t wgrad_pitch_for(int64_t cap_total) { return (cap_total + TT - 1) / TT * TT + TT; }
-
-bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t first_row, int64_t n_rows,
+void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t first_row, int64_t n_rows,
                    bool accumulate, const WgradRows* other)
 {
     const int d_in = other && other->d_in ? other->d_in : c->cfg.d_in;
@@ -1398,7 +1115,6 @@ bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t firs
     const int* ids = other ? other->ids : c->id_of_slot;
     const float* rows = other ? other->rows : c->G;
     const int* rows_dev = other ? other->n_dev : c->scal + kSUTotal;
-    const bool chunked = other || first_row > 0 || n_rows < cap;
     const int row_begin = (int)(first_row < cap ? first_row : cap);
     const int row_end = (int)(n_rows < cap - row_begin ? row_begin + n_rows : cap);
     if (c->cfg.xw_dtype == GRAM_BF16) {
@@ -1411,27 +1127,19 @@ bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t firs
         if (want < 8) want = 8;
         if (want < S) S = (int)want;
         const int64_t x_bytes = x_rows * d_in * 2, g_bytes = cap * d * 4;
-        const int64_t window = ((int64_t)1 << 32) - 16;
-        if (x_bytes < window && g_bytes < window) {
-            static bool attr_set = false;
-            if (!attr_set) {
-                (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_wgrad_tn_bf16<kWgradWaves>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)WSMEM);
-                attr_set = true;
-            }
-            const int tiles = ((d_in + 255) / 256) * ((d + 255) / 256);
-            launch_smem(c, KID_WGRAD_BF16, k_wgrad_tn_bf16<kWgradWaves>, dim3((unsigned)(tiles * S)), dim3(kWgradWaves * 64), WSMEM, s,
+        const int tiles = ((d_in + 255) / 256) * ((d + 255) / 256);
+        if (x_bytes < kBufferWindow && g_bytes < kBufferWindow) {
+            constexpr auto kern = k_wgrad_tn_bf16<kWgradWaves, false>;
+            ensure_dynamic_lds<kern>((int)WSMEM);
+            launch_smem(c, KID_WGRAD_BF16, kern, dim3((unsigned)(tiles * S)), dim3(kWgradWaves * 64), WSMEM, s,
                         static_cast<const uint16_t*>(X), (uint32_t)x_bytes, ids, rows, (uint32_t)g_bytes,
                         rows_dev, d_in, d, pad_id, S, c->wg_partial, row_begin, row_end);
         } else {
-            if (chunked) return false;      // the transposed copies cover the whole buffer only
-            // operands beyond the 4 GiB buffer window: transposed bf16 copies + the NT kernel
-            launch(c, KID_TRANSPOSE_X, k_transpose_x, dim3(1024), dim3(kBlock), s,
-                   static_cast<const uint16_t*>(X), c->id_of_slot, c->scal, 0, d_in, c->cfg.pad_id, c->XT, c->ldt);
-            launch(c, KID_TRANSPOSE_G, k_transpose_g, dim3(1024), dim3(kBlock), s, c->G, c->scal, d, c->GT,
-                   c->ldt);
-            launch_gemm_nt<false>(c, KID_WGRAD_BF16, c->XT, c->ldt, d_in, nullptr, nullptr, d_in, d_in, c->GT,
-                                  c->ldt, d, d, c->scal + kSUTotal, 0, S, c->wg_partial, d, (int64_t)d_in * d, s);
+            constexpr auto kern = k_wgrad_tn_bf16<kWgradWaves, true>;
+            ensure_dynamic_lds<kern>((int)WSMEM);
+            launch_smem(c, KID_WGRAD_BF16_WIDE, kern, dim3((unsigned)(tiles * S)), dim3(kWgradWaves * 64), WSMEM, s,
+                        static_cast<const uint16_t*>(X), 0u, ids, rows, 0u, rows_dev, d_in, d, pad_id, S,
+                        c->wg_partial, row_begin, row_end);
         }
     } else {
         launch(c, KID_WGRAD_F32, k_wgrad_f32, dim3((d + 63) / 64, (d_in + 3) / 4, S), dim3(kBlock), s,
@@ -1441,7 +1149,6 @@ bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t firs
     const int64_t n4 = (int64_t)d_in * d / 4;
     launch(c, KID_WGRAD_REDUCE, k_wgrad_reduce, dim3((unsigned)((n4 + kBlock - 1) / kBlock)), dim3(kBlock), s,
            reinterpret_cast<const float4*>(c->wg_partial), n4, S, reinterpret_cast<float4*>(dW), accumulate ? 1 : 0);
-    return true;
 }
 
 }  // namespace gram

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include <string>
 #include <utility>
 #include <vector>
@@ -26,6 +27,9 @@ constexpr int kSlotNew = 1 << 30;       // flag in seg_slot: the buffer row is c
 constexpr int kPseudoRows = 8;          // unique items per block of the pseudo-target kernel
 constexpr int kFixCols4 = 16;           // float4 columns per block of the long-segment combine
 constexpr int kFixLanes = kBlock / kFixCols4;
+// A buffer descriptor addresses base + 32-bit byte offset: matrices of at least this many bytes
+// take the kernels' wide-address variants.
+constexpr int64_t kBufferWindow = ((int64_t)1 << 32) - 16;
 
 // two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
@@ -48,9 +52,12 @@ enum KernelId {
     KID_RADIX_HIST = 0, KID_RADIX_SCAN, KID_RADIX_SCATTER, KID_HEADS_COUNT, KID_HEADS_EMIT, KID_COUNTS,
     KID_UNIQUE_EMPTY, KID_TRANSPOSE_U16, KID_ENCODE_BF16, KID_ENCODE_F32, KID_GATHER_ROWS,
     KID_SLOT_COUNT, KID_SLOT_EMIT, KID_SEG_REDUCE, KID_SEG_COMBINE, KID_WGRAD_BF16, KID_WGRAD_F32,
-    KID_WGRAD_REDUCE, KID_TRANSPOSE_X, KID_TRANSPOSE_G, KID_FLUSH_META, KID_FLUSH_ROWS, KID_UNIQUE_SMALL,
-    KID_GATHER_HEAVY, KID_PSEUDO_TARGET, KID_PSEUDO_LOSS, KID_CHUNK_IDS, KID_PSEUDO_MISS, KID_MLP_TO_BF16, KID_COUNT
+    KID_WGRAD_REDUCE, KID_FLUSH_META, KID_FLUSH_ROWS, KID_UNIQUE_SMALL,
+    KID_GATHER_HEAVY, KID_PSEUDO_TARGET, KID_PSEUDO_LOSS, KID_CHUNK_IDS, KID_PSEUDO_MISS, KID_MLP_TO_BF16,
+    KID_ENCODE_BF16_WIDE, KID_WGRAD_BF16_WIDE, KID_COUNT
 };
+
+static_assert(KID_COUNT <= 64, "the profiling mask has 64 bits");
 
 struct ProfSlot {
     hipEvent_t start, stop;
@@ -88,7 +95,7 @@ struct Ctx {
     int* long_list = nullptr;   // [tiles_seg] head tiles of the long segments of the current batch
     int* slot_of = nullptr;     // [N] buffer row of an ID, -1 = absent
     int* id_of_slot = nullptr;  // [cap_total]
-    int* cnt_of_slot = nullptr; // [cap_total]
+    long long* cnt_of_slot = nullptr; // [cap_total] occurrences of the item of each row in the window
     float* G = nullptr;         // [cap_total, d] persistent per-item gradient
     float* E_ws = nullptr;      // [cap_u, d] representations when the caller passes E = NULL
     double* loss_part = nullptr; // [cap_chunk / kPseudoRows + 1] per-block sums of the pseudo-loss
@@ -104,9 +111,6 @@ struct Ctx {
     void* A1_ws = nullptr;      // [cap_u, d_hidden] bf16 activations when the caller keeps none
     int* iota = nullptr;        // [cap_chunk] 0, 1, 2, ...: row list of a matrix that needs no gather
     float* wg_partial = nullptr;// [splits, d_in, d] split-K partials of the weight gradient
-    uint16_t* XT = nullptr;     // [d_in, ldt] bf16 features of the buffer's items, transposed (bf16 path)
-    uint16_t* GT = nullptr;     // [d, ldt] bf16 copy of G, transposed (bf16 path)
-    int64_t ldt = 0;            // row pitch of XT / GT in elements
     int wg_splits = 1;
     int num_cus = 256;          // compute units of the device (one contraction block each)
 
@@ -115,7 +119,7 @@ struct Ctx {
     int* perm = nullptr;
 
     // --- optional per-kernel event timing ---
-    uint32_t prof_mask = 0;            // bit k set: time launches of kernel k
+    uint64_t prof_mask = 0;            // bit k set: time launches of kernel k
     std::vector<ProfSlot> prof_pool;   // events created once by gram_profile_enable
     size_t prof_used = 0;
 
@@ -131,6 +135,21 @@ struct Ctx {
     int* h_pinned = nullptr;    // [4] pinned host scratch for small read-backs
     std::string last_error;
 };
+
+// A kernel that uses more than 64 KiB of dynamic LDS needs its limit raised before its first
+// launch on a device.  Raising it twice is harmless, so threads that race here only repeat the
+// call; the flag is per kernel (template argument) and per device (bit).
+template <auto Kernel>
+inline void ensure_dynamic_lds(int bytes)
+{
+    static std::atomic<uint64_t> done{0};
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return;
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    done.fetch_or(bit, std::memory_order_release);
+}
 
 // Launch a kernel; with profiling enabled for `kid`, bracket it with two events
 // on the same stream.
@@ -218,9 +237,8 @@ struct WgradRows {
     int d_in = 0, d = 0, pad_id = -1;
 };
 // Weight gradient over the buffer rows [first_row, first_row + n_rows) (clipped to the rows held),
-// or over the rows of `other`, written to dW or added to it.  Returns false if the range is a
-// proper chunk, or `other` is given, and an operand is beyond 4 GiB (nothing is launched).
-bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t first_row, int64_t n_rows,
+// or over the rows of `other`, written to dW or added to it.
+void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t first_row, int64_t n_rows,
                    bool accumulate, const WgradRows* other = nullptr);
 // ---- gram_mlp.hip --------------------------------------------------------
 // Forward of the two-layer encoder for the unique items of the batch; A1 (nullable) receives the
@@ -230,7 +248,7 @@ bool mlp_forward(Ctx* c, const void* X, const void* W1, const void* W2, const in
 int64_t mlp_batch_bytes(const Ctx* c, int64_t n);
 // Backward of the two-layer encoder over the listed items from output-gradient rows (`rows`) or,
 // with Ht, from the regression miss against stored targets (then loss_dev may receive Eq. 7).
-bool mlp_backward(Ctx* c, const void* X, const void* W1, const void* W2, const int* ids, const float* rows,
+void mlp_backward(Ctx* c, const void* X, const void* W1, const void* W2, const int* ids, const float* rows,
                   const float* Ht, int64_t n, void* work, float* dW1, float* dW2, bool accumulate,
                   double* loss_dev, hipStream_t s);
 
@@ -248,6 +266,5 @@ bool gemm_rows_bf16(Ctx* c, const void* A, int64_t a_rows, int k, const int* row
                     const int* n_dev, int64_t rows_max, const void* Bt, int n_out, float* C, hipStream_t s,
                     void* H_scatter, bool caller_wants_C, int epi = kEpiPlain, const void* aux = nullptr,
                     const void* B_plain = nullptr);
-int64_t wgrad_pitch_for(int64_t cap_total);
 
 }  // namespace gram

@@ -55,7 +55,7 @@ int64_t mlp_batch_bytes(const Ctx* c, int64_t n)
     return up(n * dh * 4) + up(n * dh * 2) + up(n * d * 4) + up(n * d * 2);
 }
 
-bool mlp_backward(Ctx* c, const void* X, const void* W1, const void* W2, const int* ids, const float* rows,
+void mlp_backward(Ctx* c, const void* X, const void* W1, const void* W2, const int* ids, const float* rows,
                   const float* Ht, int64_t n, void* work, float* dW1, float* dW2, bool accumulate,
                   double* loss_dev, hipStream_t s)
 {
@@ -86,7 +86,7 @@ bool mlp_backward(Ctx* c, const void* X, const void* W1, const void* W2, const i
     }
     // dW2 = A1^T R: the kept activations play the part of the features, row j with row j
     const WgradRows top = {nullptr, Rsrc, n_dev, n, n > 0 ? n : 1, dh, d, -1};
-    if (!encoder_wgrad(c, A1, dW2, s, 0, n, accumulate, &top)) return false;
+    encoder_wgrad(c, A1, dW2, s, 0, n, accumulate, &top);
     if (n > 0) {
         // dA = R . W2^T: W2 [dh, d] is already the K-contiguous second operand of that product
         launch(c, KID_MLP_TO_BF16, k_to_bf16, dim3(blocks_for(n, d / 4)), dim3(kBlock), s,
@@ -97,7 +97,7 @@ bool mlp_backward(Ctx* c, const void* X, const void* W1, const void* W2, const i
     }
     // dW1 = X[ids]^T dZ
     const WgradRows bottom = {c->chunk_ids, Z, n_dev, n, c->cfg.vocab_n, d_in, dh, c->cfg.pad_id};
-    return encoder_wgrad(c, X, dW1, s, 0, n, accumulate, &bottom);
+    encoder_wgrad(c, X, dW1, s, 0, n, accumulate, &bottom);
 }
 
 }  // namespace gram

@@ -594,12 +594,7 @@ bool unique_small(Ctx* c, const int* ids, int n, int fix_key, int* uniq, int* in
                   int* u_out, hipStream_t s)
 {
     if (n <= 0 || n > kSmallMaxN) return false;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_unique_small),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmallLds);
-        attr_set = true;
-    }
+    ensure_dynamic_lds<k_unique_small>((int)kSmallLds);
     c->sorted_keys = c->keys[0];
     c->perm = c->vals[0];
     launch_smem(c, KID_UNIQUE_SMALL, k_unique_small, dim3(1), dim3(kSmallThreads), kSmallLds, s, ids, n,

@@ -391,7 +391,7 @@ __global__ __launch_bounds__(kBlock) void k_slot_count(const int* __restrict__ u
 
 __global__ __launch_bounds__(kBlock) void k_slot_emit(
     const int* __restrict__ uniq_ws, const int* __restrict__ offsets, int* __restrict__ slot_of,
-    int* __restrict__ id_of_slot, int* __restrict__ cnt_of_slot, int* __restrict__ seg_slot,
+    int* __restrict__ id_of_slot, long long* __restrict__ cnt_of_slot, int* __restrict__ seg_slot,
     int* __restrict__ scal, const int* __restrict__ tile_sums, int cap_total)
 {
     __shared__ int sm[kWavesPerBlock];
@@ -451,7 +451,7 @@ __global__ __launch_bounds__(kBlock) void k_slot_emit(
 constexpr int kSlotSmallThreads = 1024;
 __global__ __launch_bounds__(kSlotSmallThreads) void k_slot_small(
     const int* __restrict__ uniq_ws, const int* __restrict__ offsets, int* __restrict__ slot_of,
-    int* __restrict__ id_of_slot, int* __restrict__ cnt_of_slot, int* __restrict__ seg_slot,
+    int* __restrict__ id_of_slot, long long* __restrict__ cnt_of_slot, int* __restrict__ seg_slot,
     int* __restrict__ scal, int cap_total, int first_step)
 {
     __shared__ int sm[kSlotSmallThreads / kWave];
@@ -745,20 +745,20 @@ void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s)
 // the first step of the next window starts from zero by itself.  `n_zero`: the window is empty.
 
 __device__ __forceinline__ void flush_meta_row(int r, const int* sorted_ids, const int* sorted_slots,
-                                               const int* cnt_of_slot, int* slot_of, int* uniq_total,
+                                               const long long* cnt_of_slot, int* slot_of, int* uniq_total,
                                                int* counts_total, long long* counts64_total)
 {
     const int id = sorted_ids[r];
-    const int cnt = cnt_of_slot[sorted_slots ? sorted_slots[r] : r];
+    const long long cnt = cnt_of_slot[sorted_slots ? sorted_slots[r] : r];
     if (uniq_total) uniq_total[r] = id;
-    if (counts_total) counts_total[r] = cnt;
+    if (counts_total) counts_total[r] = cnt > 0x7fffffffLL ? 0x7fffffff : (int)cnt;     // the 32-bit export saturates
     if (counts64_total) counts64_total[r] = cnt;
     slot_of[id] = -1;
 }
 
 __global__ __launch_bounds__(kBlock) void k_flush_meta(
     const int* __restrict__ sorted_ids, const int* __restrict__ sorted_slots,
-    const int* __restrict__ cnt_of_slot, int* __restrict__ slot_of, int* __restrict__ uniq_total,
+    const long long* __restrict__ cnt_of_slot, int* __restrict__ slot_of, int* __restrict__ uniq_total,
     int* __restrict__ counts_total, long long* __restrict__ counts64_total, int* __restrict__ scal,
     int* __restrict__ u_total_dev, int n_zero)
 {
@@ -776,7 +776,7 @@ __global__ __launch_bounds__(kBlock) void k_flush_meta(
 // slot map (kept out of the copy loop: their scattered accesses would stall the copying waves).
 __global__ __launch_bounds__(kBlock) void k_flush_rows(
     const int* __restrict__ sorted_ids, const int* __restrict__ sorted_slots,
-    const int* __restrict__ cnt_of_slot, int* __restrict__ slot_of, int* __restrict__ uniq_total,
+    const long long* __restrict__ cnt_of_slot, int* __restrict__ slot_of, int* __restrict__ uniq_total,
     int* __restrict__ counts_total, long long* __restrict__ counts64_total,
     const float4* __restrict__ G, int cols4, float4* __restrict__ G_total, int* __restrict__ scal,
     int* __restrict__ u_total_dev, int copy_blocks)
@@ -844,12 +844,12 @@ void flush_export(Ctx* c, int* uniq_total, int* counts_total, long long* counts6
 //
 // One block walks the listed items in tiles of 4096 exactly as k_slot_small walks the items of a
 // batch: an item the window has not met takes the next free row (in list order), an item it has
-// met keeps its row; the saved count is added (32-bit rows: a count beyond INT32_MAX saturates).
+// met keeps its row; the saved count is added (64-bit counts, as in the dense layout).
 // code[j] receives the row (kSlotNew set for a fresh row, -1 when the buffer is full or the ID is
 // outside [0, N)); k_import_rows then writes or adds the saved gradient rows.
 __global__ __launch_bounds__(kSlotSmallThreads) void k_slot_import(
     const int* __restrict__ ids, const long long* __restrict__ counts, int n, int vocab_n,
-    int* __restrict__ slot_of, int* __restrict__ id_of_slot, int* __restrict__ cnt_of_slot,
+    int* __restrict__ slot_of, int* __restrict__ id_of_slot, long long* __restrict__ cnt_of_slot,
     int* __restrict__ code, int* __restrict__ scal, int cap_total, int first_touch)
 {
     __shared__ int sm[kSlotSmallThreads / kWave];
@@ -889,15 +889,14 @@ __global__ __launch_bounds__(kSlotSmallThreads) void k_slot_import(
                 if (slot < cap_total) {
                     slot_of[id[i]] = slot;
                     id_of_slot[slot] = id[i];
-                    cnt_of_slot[slot] = c64 > 0x7fffffffLL ? 0x7fffffff : (int)c64;
+                    cnt_of_slot[slot] = c64;
                     code[j] = slot | kSlotNew;
                 } else {
                     code[j] = -1;
                     err |= kErrBitCapacity;
                 }
             } else {
-                const long long sum = (long long)cnt_of_slot[old[i]] + c64;
-                cnt_of_slot[old[i]] = sum > 0x7fffffffLL ? 0x7fffffff : (int)sum;
+                cnt_of_slot[old[i]] += c64;
                 code[j] = old[i];
             }
         }

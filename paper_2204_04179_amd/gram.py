@@ -101,7 +101,7 @@ def load():
     L.gram_kernel_name.restype = C.c_char_p
     L.gram_kernel_name.argtypes = [C.c_int]
     L.gram_profile_enable.restype = C.c_int
-    L.gram_profile_enable.argtypes = [vp, C.c_uint32, C.c_int32]
+    L.gram_profile_enable.argtypes = [vp, C.c_uint64, C.c_int32]
     L.gram_profile_read.restype = C.c_int
     L.gram_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_double)]
     _lib = L

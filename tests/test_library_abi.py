@@ -65,8 +65,6 @@ def test_workspace_query_for_the_dense_buffer_and_the_two_layer_encoder():
     bad = [
         gram.make_config(20000, 768, 256, 51200, 8, 0, 500, gram.BF16, 1),       # dense: one row per ID, no other size
         gram.make_config(20000, 768, 256, 51200, 8, 0, 0, gram.BF16, 2),         # unknown layout
-        gram.make_config(1 << 22, 768, 256, 51200, 8, 0, 0, gram.BF16, 1),       # dense: X beyond 4 GiB
-        gram.make_config(1 << 21, 64, 1024, 51200, 8, 0, 0, gram.BF16, 1),       # dense: N x d x 4 beyond 4 GiB
         gram.make_config(20000, 768, 256, 51200, 8, 0, 0, gram.BF16, 0, -8),     # negative hidden width
         gram.make_config(20000, 768, 256, 51200, 8, 0, 0, gram.BF16, 0, 100),    # hidden width not a multiple of 8
         gram.make_config(20000, 768, 252, 51200, 8, 0, 0, gram.BF16, 0, 512),    # two-layer: d not a multiple of 8
@@ -74,6 +72,9 @@ def test_workspace_query_for_the_dense_buffer_and_the_two_layer_encoder():
     ]
     for cfg in bad:
         assert gram.workspace_bytes(cfg) == 0
+    # matrices beyond the 4 GiB of a buffer descriptor are served by wide-address kernel variants
+    assert gram.workspace_bytes(gram.make_config(1 << 22, 768, 256, 51200, 8, 0, 0, gram.BF16, 1)) > (1 << 32)
+    assert gram.workspace_bytes(gram.make_config(1 << 21, 64, 1024, 51200, 8, 0, 0, gram.BF16, 1)) > (1 << 33)
     lib = gram.load()
     assert lib.gram_mlp_batch_bytes(None, 100) == 0
     assert lib.gram_flush64(None, None, None, None, None, None, None) == gram.ERR_ARG
