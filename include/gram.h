@@ -27,6 +27,7 @@
  *                         current weights (optional)
  *   gram_encoder_wgrad_chunk  the weight gradient over a range of the window's
  *                         items (content-encoder batches; optional)
+ *   gram_window_end       gram_encoder_wgrad + gram_flush reading the buffer once
  *   gram_flush64, gram_window_import   64-bit counts and save / resume of a
  *                         window kept in the dense one-row-per-ID buffer
  *                         (cfg.buffer_layout; windows of epoch length)
@@ -308,6 +309,22 @@ int gram_flush(gram_ctx* ctx, int32_t* uniq_total, int32_t* counts_total, float*
  * arguments otherwise; with the dense buffer the outputs need room for N items. */
 int gram_flush64(gram_ctx* ctx, int32_t* uniq_total, int64_t* counts_total, float* G_total,
                  int32_t* u_total_dev, int32_t* u_total_host, void* stream);
+
+/* gram_encoder_wgrad followed by gram_flush as one call, for the end of a window
+ * (Algorithm 1 step 4 and the "t mod N" reset after it): same arguments, same
+ * outputs as the two calls in that order.  With the slot-table buffer, bf16
+ * features and operands below 4 GiB the weight-gradient kernel writes each buffer
+ * row to its place in G_total while it holds the row for the contraction, so the
+ * buffer is read once instead of twice; G_total then holds the same float32 rows
+ * as gram_flush would write, and dW the same sums in the same order.  Otherwise
+ * the call runs the two steps one after the other.
+ *   X, dW          as for gram_encoder_wgrad
+ *   uniq_total, counts_total, G_total, u_total_dev, u_total_host
+ *                  as for gram_flush
+ * Requires at least one accumulated step (GRAM_ERR_SEQUENCE). */
+int gram_window_end(gram_ctx* ctx, const void* X, float* dW, int32_t* uniq_total,
+                    int32_t* counts_total, float* G_total, int32_t* u_total_dev,
+                    int32_t* u_total_host, void* stream);
 
 /* Merge a saved window state into the buffer, e.g. what gram_flush64 exported
  * before an interruption: counts[j] is added to the count of ids[j] and, if

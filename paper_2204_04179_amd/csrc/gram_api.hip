@@ -584,6 +584,39 @@ int gram_flush64(gram_ctx* ctx, int32_t* uniq_total, int64_t* counts_total, floa
                      static_cast<hipStream_t>(stream), "gram_flush64");
 }
 
+int gram_window_end(gram_ctx* ctx, const void* X, float* dW, int32_t* uniq_total, int32_t* counts_total,
+                    float* G_total, int32_t* u_total_dev, int32_t* u_total_host, void* stream)
+{
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (!c) return GRAM_ERR_ARG;
+    if (c->steps_done < 1 && !c->window_imported)
+        return fail(c, GRAM_ERR_SEQUENCE, "gram_window_end: no step accumulated in this window");
+    if (!X || !dW) return fail(c, GRAM_ERR_ARG, "gram_window_end: NULL pointer");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // The fused form: the weight-gradient kernel holds every buffer row in registers on its way
+    // into LDS and writes it to its place in the export from there, so the rows are read once.
+    const bool fused = !c->dense && G_total && c->cfg.xw_dtype == GRAM_BF16 &&
+                       (int64_t)c->cfg.vocab_n * c->cfg.d_in * 2 < kBufferWindow &&
+                       c->cap_total * (int64_t)c->cfg.d * 4 < kBufferWindow;
+    if (!fused) {
+        encoder_wgrad(c, X, dW, s, 0, c->cap_total, false);
+        return flush_any(c, uniq_total, counts_total, nullptr, G_total, u_total_dev, u_total_host, s,
+                         "gram_window_end");
+    }
+    const int* ranks = flush_meta_and_ranks(c, uniq_total, counts_total, u_total_dev, s);
+    encoder_wgrad(c, X, dW, s, 0, c->cap_total, false, nullptr, G_total, ranks);
+    c->have_unique = false;     // the sort buffers were reused
+    c->steps_done = 0;
+    c->window_positions = 0;
+    c->window_imported = false;
+    if (int rc = launch_status(c, "gram_window_end")) return rc;
+    if (u_total_host) {
+        if (int rc = sync_scalars(c, s, "gram_window_end")) return rc;
+        *u_total_host = c->h_pinned[kSFlushN];
+    }
+    return GRAM_OK;
+}
+
 int gram_window_import(gram_ctx* ctx, const int32_t* ids, const int64_t* counts, const float* G_rows,
                        int64_t n, void* stream)
 {

@@ -822,11 +822,20 @@ constexpr uint32_t kOutOfRange = 0xFFFFFFF0u;
 constexpr int kWgradWaves = 8;
 
 // NW = waves per block: 4 (128x128 each) or 8 (128x64 each, two per SIMD).
-template <int NW, bool WIDE = false>
+// EXPORT: the end of a window also copies the buffer rows out in ascending-ID order
+// (gram_flush); this kernel has every row of G in registers anyway, so it writes row s to
+// G_total[rank_of_slot[s]] (rank_of_slot NULL: the buffer is in that order already) and the
+// export kernel's second read of the buffer is saved.  The feature tiles that share a slab of G
+// share its rows: tile f writes the rows t of a wave with t % f_tiles == f.
+struct WgradExport {
+    float* G_total;            // [rows held, d]
+    const int* rank_of_slot;   // [rows held] or NULL
+};
+template <int NW, bool WIDE = false, bool EXPORT = false>
 __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
     const uint16_t* __restrict__ X, uint32_t x_bytes, const int* __restrict__ id_of_slot,
     const float* __restrict__ G, uint32_t g_bytes, const int* __restrict__ rows_dev, int d_in, int d,
-    int pad_id, int splits, float* __restrict__ partial, int row_begin, int row_end)
+    int pad_id, int splits, float* __restrict__ partial, int row_begin, int row_end, WgradExport ex)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const int tiles_c = (d + 255) / 256, tiles = ((d_in + 255) / 256) * tiles_c;
@@ -892,6 +901,15 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
 
     bf16x8 fa[2][4], fb[2][NT];
     v4i32 ra[SETS][RW / 2], rg[SETS][RW];
+    // (EXPORT) rk[set]: lane t < RW holds the output row of the t-th buffer row of the slab in that
+    // set, -1 if the row is not to be written; fetched BEFORE the slab's data loads (see below)
+    int rk[EXPORT ? SETS : 1];
+    bool ex_mine[RW];
+    {
+        const int f_tiles = (d_in + 255) / 256, f_idx = i0 / 256;
+#pragma unroll
+        for (int t = 0; t < RW; ++t) ex_mine[t] = EXPORT && (t % f_tiles) == f_idx;
+    }
     // item IDs: ids_next receives the load for the slab after next, ids_cur holds the ones the next
     // data loads use.  The ID load is issued BEFORE the data loads of an iteration: memory operations
     // return in order, so waiting for an ID load that was issued after them would drain them all
@@ -934,6 +952,11 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
 #define GRAM_LOAD(SET, SLAB)                                                                        \
     {                                                                                               \
         const int sb_ = (sl_begin + ((SLAB) < last ? (SLAB) : last)) * WK;                          \
+        if (EXPORT) {                                                                               \
+            const int slot = sb_ + wave * RW + lane;                                                \
+            const bool okr = lane < RW && slot < U && slot >= row_begin;                            \
+            rk[(SET) % SETS] = okr ? (ex.rank_of_slot ? ex.rank_of_slot[slot] : slot) : -1;         \
+        }                                                                                           \
         _Pragma("unroll") for (int t = 0; t < RW / 2; ++t) {                                        \
             const int kk = a_row + 2 * t;                                                           \
             const int feat = i0 + ((a_pos ^ ((kk & 3) << 2)) * 8);                                  \
@@ -973,6 +996,11 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
             const uint32_t hi = pack_bf16x2(__int_as_float(v.z), __int_as_float(v.w));              \
             const int pos = (lane >> 1) ^ ((t & 3) << 2);        /* row RW w + t: (row & 3) == (t & 3) */ \
             *reinterpret_cast<uint2*>(pg_ + t * WROWB + pos * 16) = make_uint2(lo, hi);             \
+            if (EXPORT && ex_mine[t]) {                                                             \
+                const int r_ = __builtin_amdgcn_readlane(rk[(SET) % SETS], t);                      \
+                if (r_ >= 0 && g_col_ok)                                                            \
+                    __builtin_nontemporal_store(v, reinterpret_cast<v4i32*>(ex.G_total + (int64_t)r_ * d + g_col)); \
+            }                                                                                       \
         }                                                                                           \
     }
     // (fixed interleaving patterns measured slower here than the compiler's own order)
@@ -1101,9 +1129,10 @@ int wgrad_splits_dims(int d_in, int d, bool bf16)
     return s;
 }
 
-void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t first_row, int64_t n_rows,
-                   bool accumulate, const WgradRows* other)
+bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t first_row, int64_t n_rows,
+                   bool accumulate, const WgradRows* other, float* export_G, const int* rank_of_slot)
 {
+    bool exported = false;
     const int d_in = other && other->d_in ? other->d_in : c->cfg.d_in;
     const int d = other && other->d ? other->d : c->cfg.d;
     const int64_t x_rows = other && other->x_rows ? other->x_rows : c->cfg.vocab_n;
@@ -1128,18 +1157,27 @@ void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t firs
         if (want < S) S = (int)want;
         const int64_t x_bytes = x_rows * d_in * 2, g_bytes = cap * d * 4;
         const int tiles = ((d_in + 255) / 256) * ((d + 255) / 256);
-        if (x_bytes < kBufferWindow && g_bytes < kBufferWindow) {
+        const WgradExport no_export = {nullptr, nullptr};
+        if (x_bytes < kBufferWindow && g_bytes < kBufferWindow && export_G && !other) {
+            constexpr auto kern = k_wgrad_tn_bf16<kWgradWaves, false, true>;
+            ensure_dynamic_lds<kern>((int)WSMEM);
+            const WgradExport ex = {export_G, rank_of_slot};
+            launch_smem(c, KID_WGRAD_BF16, kern, dim3((unsigned)(tiles * S)), dim3(kWgradWaves * 64), WSMEM, s,
+                        static_cast<const uint16_t*>(X), (uint32_t)x_bytes, ids, rows, (uint32_t)g_bytes,
+                        rows_dev, d_in, d, pad_id, S, c->wg_partial, row_begin, row_end, ex);
+            exported = true;
+        } else if (x_bytes < kBufferWindow && g_bytes < kBufferWindow) {
             constexpr auto kern = k_wgrad_tn_bf16<kWgradWaves, false>;
             ensure_dynamic_lds<kern>((int)WSMEM);
             launch_smem(c, KID_WGRAD_BF16, kern, dim3((unsigned)(tiles * S)), dim3(kWgradWaves * 64), WSMEM, s,
                         static_cast<const uint16_t*>(X), (uint32_t)x_bytes, ids, rows, (uint32_t)g_bytes,
-                        rows_dev, d_in, d, pad_id, S, c->wg_partial, row_begin, row_end);
+                        rows_dev, d_in, d, pad_id, S, c->wg_partial, row_begin, row_end, no_export);
         } else {
             constexpr auto kern = k_wgrad_tn_bf16<kWgradWaves, true>;
             ensure_dynamic_lds<kern>((int)WSMEM);
             launch_smem(c, KID_WGRAD_BF16_WIDE, kern, dim3((unsigned)(tiles * S)), dim3(kWgradWaves * 64), WSMEM, s,
                         static_cast<const uint16_t*>(X), 0u, ids, rows, 0u, rows_dev, d_in, d, pad_id, S,
-                        c->wg_partial, row_begin, row_end);
+                        c->wg_partial, row_begin, row_end, no_export);
         }
     } else {
         launch(c, KID_WGRAD_F32, k_wgrad_f32, dim3((d + 63) / 64, (d_in + 3) / 4, S), dim3(kBlock), s,
@@ -1149,6 +1187,7 @@ void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t firs
     const int64_t n4 = (int64_t)d_in * d / 4;
     launch(c, KID_WGRAD_REDUCE, k_wgrad_reduce, dim3((unsigned)((n4 + kBlock - 1) / kBlock)), dim3(kBlock), s,
            reinterpret_cast<const float4*>(c->wg_partial), n4, S, reinterpret_cast<float4*>(dW), accumulate ? 1 : 0);
+    return exported;
 }
 
 }  // namespace gram

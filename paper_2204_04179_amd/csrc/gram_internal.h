@@ -204,6 +204,7 @@ void assign_slots(Ctx* c, hipStream_t s);
 void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s);
 void flush_export(Ctx* c, int* uniq_total, int* counts_total, long long* counts64_total, float* G_total,
                   int* u_total_dev, hipStream_t s);
+const int* flush_meta_and_ranks(Ctx* c, int* uniq_total, int* counts_total, int* u_total_dev, hipStream_t s);
 void import_slots(Ctx* c, const int* ids, const long long* counts, const float* rows, int64_t n,
                   hipStream_t s);
 void flush_dense(Ctx* c, int* uniq_total, int* counts_total, long long* counts64_total, float* G_total,
@@ -238,8 +239,12 @@ struct WgradRows {
 };
 // Weight gradient over the buffer rows [first_row, first_row + n_rows) (clipped to the rows held),
 // or over the rows of `other`, written to dW or added to it.
-void encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t first_row, int64_t n_rows,
-                   bool accumulate, const WgradRows* other = nullptr);
+// export_G (buffer rows, bf16, whole window only): the kernel also writes buffer row s to
+// export_G[rank_of_slot[s], :] (rank_of_slot NULL: to row s).  Returns false, and does not export,
+// when that variant does not apply (float32 features, an operand beyond 4 GiB).
+bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t first_row, int64_t n_rows,
+                   bool accumulate, const WgradRows* other = nullptr, float* export_G = nullptr,
+                   const int* rank_of_slot = nullptr);
 // ---- gram_mlp.hip --------------------------------------------------------
 // Forward of the two-layer encoder for the unique items of the batch; A1 (nullable) receives the
 // bf16 hidden activations.  Return value as encode_forward.

@@ -756,16 +756,20 @@ __device__ __forceinline__ void flush_meta_row(int r, const int* sorted_ids, con
     slot_of[id] = -1;
 }
 
+// rank_of_slot (nullable, needs sorted_slots): receives, for every buffer row, its place in
+// ascending-ID order, for a weight-gradient kernel that writes the rows out itself.
 __global__ __launch_bounds__(kBlock) void k_flush_meta(
     const int* __restrict__ sorted_ids, const int* __restrict__ sorted_slots,
     const long long* __restrict__ cnt_of_slot, int* __restrict__ slot_of, int* __restrict__ uniq_total,
     int* __restrict__ counts_total, long long* __restrict__ counts64_total, int* __restrict__ scal,
-    int* __restrict__ u_total_dev, int n_zero)
+    int* __restrict__ u_total_dev, int n_zero, int* __restrict__ rank_of_slot)
 {
     const int n = n_zero ? 0 : scal[kSUTotal];
-    for (int r = blockIdx.x * kBlock + threadIdx.x; r < n; r += gridDim.x * kBlock)
+    for (int r = blockIdx.x * kBlock + threadIdx.x; r < n; r += gridDim.x * kBlock) {
         flush_meta_row(r, sorted_ids, sorted_slots, cnt_of_slot, slot_of, uniq_total, counts_total,
                        counts64_total);
+        if (rank_of_slot) rank_of_slot[sorted_slots[r]] = r;
+    }
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         if (u_total_dev) *u_total_dev = n;
         scal[kSFlushN] = n;
@@ -809,7 +813,8 @@ void flush_export(Ctx* c, int* uniq_total, int* counts_total, long long* counts6
 {
     if (c->steps_done == 0 && !c->window_imported) {       // nothing accumulated since the last flush
         launch(c, KID_FLUSH_META, k_flush_meta, dim3(1), dim3(kBlock), s, c->id_of_slot, (const int*)nullptr,
-               c->cnt_of_slot, c->slot_of, uniq_total, counts_total, counts64_total, c->scal, u_total_dev, 1);
+               c->cnt_of_slot, c->slot_of, uniq_total, counts_total, counts64_total, c->scal, u_total_dev, 1,
+               (int*)nullptr);
         return;
     }
     // After one step the buffer rows are already in ascending ID order (rows are handed out in
@@ -836,8 +841,31 @@ void flush_export(Ctx* c, int* uniq_total, int* counts_total, long long* counts6
         if (blocks > 1024) blocks = 1024;
         launch(c, KID_FLUSH_META, k_flush_meta, dim3((unsigned)blocks), dim3(kBlock), s, sorted_ids,
                sorted_slots, c->cnt_of_slot, c->slot_of, uniq_total, counts_total, counts64_total, c->scal,
-               u_total_dev, 0);
+               u_total_dev, 0, (int*)nullptr);
     }
+}
+
+// The export without the rows: IDs and counts in ascending-ID order, slot map cleared, and the
+// place of every buffer row in that order (returned; NULL: the rows are in that order already).
+// The caller's weight-gradient kernel then writes the rows themselves.  Needs a non-empty window.
+const int* flush_meta_and_ranks(Ctx* c, int* uniq_total, int* counts_total, int* u_total_dev, hipStream_t s)
+{
+    const int* sorted_ids = c->id_of_slot;
+    const int* sorted_slots = nullptr;
+    int* ranks = nullptr;
+    if (c->steps_done > 1 || c->window_imported) {
+        const int r = radix_sort_pairs(c, c->id_of_slot, nullptr, 0, c->scal + kSUTotal, c->cap_total,
+                                       false, 0, s);
+        sorted_ids = c->keys[r];
+        sorted_slots = c->vals[r];
+        ranks = c->chunk_ids;          // [cap_chunk >= cap_total]: free between content-encoder batches
+    }
+    int64_t blocks = (c->cap_total + kBlock - 1) / kBlock;
+    if (blocks > 1024) blocks = 1024;
+    launch(c, KID_FLUSH_META, k_flush_meta, dim3((unsigned)blocks), dim3(kBlock), s, sorted_ids, sorted_slots,
+           c->cnt_of_slot, c->slot_of, uniq_total, counts_total, (long long*)nullptr, c->scal, u_total_dev, 0,
+           ranks);
+    return ranks;
 }
 
 // ---- slot table: a saved window state merged into the buffer ----------------------------

@@ -22,7 +22,7 @@ STATUS_NAMES = {OK: "GRAM_OK", ERR_ARG: "GRAM_ERR_ARG", ERR_CAPACITY: "GRAM_ERR_
 EXPORTS = ("gram_workspace_bytes", "gram_create", "gram_destroy", "gram_unique", "gram_encode_gather",
            "gram_grad_accumulate", "gram_pseudo_target", "gram_gather", "gram_encoder_wgrad",
            "gram_encoder_wgrad_chunk", "gram_pseudo_loss_grad", "gram_flush",
-           "gram_flush64", "gram_window_import", "gram_mlp_encode_gather", "gram_mlp_batch_bytes",
+           "gram_flush64", "gram_window_end", "gram_window_import", "gram_mlp_encode_gather", "gram_mlp_batch_bytes",
            "gram_mlp_backward", "gram_unique_static",
            "gram_check", "gram_last_error",
            "gram_kernel_count", "gram_kernel_name", "gram_light_max", "gram_profile_enable",
@@ -78,6 +78,8 @@ def load():
     L.gram_encoder_wgrad.argtypes = [vp, vp, vp, vp]
     L.gram_flush.restype = C.c_int
     L.gram_flush.argtypes = [vp, vp, vp, vp, vp, i32p, vp]
+    L.gram_window_end.restype = C.c_int
+    L.gram_window_end.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32p, vp]
     L.gram_mlp_encode_gather.restype = C.c_int
     L.gram_mlp_encode_gather.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_int64, vp, vp, vp, vp]
     L.gram_mlp_batch_bytes.restype = C.c_int64
@@ -215,6 +217,14 @@ class Gram:
         self._ck(self._lib.gram_flush(self._h, _ptr(uniq_total), _ptr(counts_total), _ptr(G_total),
                                       _ptr(u_total_dev), C.byref(u_host) if want_host_u else None,
                                       _stream(stream)))
+        return u_host.value if want_host_u else None
+
+    def window_end(self, X, dW, uniq_total=None, counts_total=None, G_total=None, u_total_dev=None,
+                   want_host_u=False, stream=None):
+        u_host = C.c_int32(-1)
+        self._ck(self._lib.gram_window_end(self._h, _ptr(X), _ptr(dW), _ptr(uniq_total), _ptr(counts_total),
+                                           _ptr(G_total), _ptr(u_total_dev),
+                                           C.byref(u_host) if want_host_u else None, _stream(stream)))
         return u_host.value if want_host_u else None
 
     def mlp_encode_gather(self, X, W1, W2, uniq, inverse, u_dev, m, A1, E, H, stream=None):

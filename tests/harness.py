@@ -16,7 +16,7 @@ def to_dev(a, torch):
 def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=None, u_total_cap=0,
                keep_H=True, keep_E=True, want_G=True, gram_obj=None, X_dev=None, W_dev=None,
                pass_E=True, foreign_buffers=False, profile=None, pseudo=False, wgrad_chunks=None,
-               dense=False, resume=None, h_bf16=False):
+               dense=False, resume=None, h_bf16=False, window_end=False):
     """batches: list of (ids int32 [m], dH float32 [m,d]).  Returns dict with per-step
     uniq/inverse/counts/E/H and the window's uniq_total/counts_total/G_total/dW.
     pass_E=False calls gram_encode_gather with E = NULL (no "E" in the result);
@@ -28,7 +28,9 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
     and all of them accumulated into one matrix (key "dW_chunked").  dense=True selects the
     one-row-per-ID buffer and exports through gram_flush64 (counts_total is then int64);
     resume=(ids, counts int64, G rows float32) is merged into the window with gram_window_import
-    before the first step.  h_bf16=True asks for H in bf16 (returned widened to float32)."""
+    before the first step.  h_bf16=True asks for H in bf16 (returned widened to float32).
+    window_end=True ends the window with the one call gram_window_end instead of
+    gram_encoder_wgrad followed by gram_flush."""
     import torch
     from paper_2204_04179_amd import gram
 
@@ -95,13 +97,18 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
         torch.cuda.synchronize()
         chunk_out = dict(dW_chunks=[t.cpu().numpy() for t in singles], dW_chunked=acc.cpu().numpy())
     dW = torch.full((d_in, d), float("nan"), device="cuda")
-    g.encoder_wgrad(Xd, dW)
+    if not window_end:
+        g.encoder_wgrad(Xd, dW)
     cap_total = vocab_n if dense else (u_total_cap or max(1, min(K * M_max, vocab_n)))
     ut = torch.full((cap_total,), -7, dtype=torch.int32, device="cuda")
     ct = torch.full((cap_total,), -7, dtype=torch.int64 if dense else torch.int32, device="cuda")
     Gt = torch.full((cap_total, d), float("nan"), device="cuda") if want_G else None
     utd = torch.zeros(1, dtype=torch.int32, device="cuda")
-    n = (g.flush64 if dense else g.flush)(ut, ct, Gt, utd, want_host_u=True)
+    if window_end:
+        assert not dense
+        n = g.window_end(Xd, dW, ut, ct, Gt, utd, want_host_u=True)
+    else:
+        n = (g.flush64 if dense else g.flush)(ut, ct, Gt, utd, want_host_u=True)
     torch.cuda.synchronize()
     out = dict(steps=steps, dW=dW.cpu().numpy(), U_total=n, **chunk_out, uniq_total=ut[:n].cpu().numpy(),
                counts_total=ct[:n].cpu().numpy(), gram=g, X_dev=Xd, W_dev=Wd)
@@ -111,6 +118,7 @@ def run_window(X, W, batches, *, vocab_n, pad_id=0, k_steps=None, max_positions=
         g.profile_enable([])
     if want_G:
         out["G_total"] = Gt[:n].cpu().numpy()
+        out["G_tail_untouched"] = bool(torch.isnan(Gt[n:]).all().item())
     return out
 
 

@@ -1214,6 +1214,91 @@ def test_flush_variants_and_back_to_back_windows():
     assert d["G_total"].tobytes() == a["G_total"].tobytes() and d["dW"].tobytes() == a["dW"].tobytes()
 
 
+@pytest.mark.parametrize("case", ["multi_step", "one_step", "three_feature_tiles", "resumed", "no_rows_wanted",
+                                  "float32", "dense_falls_back"])
+def test_window_end_in_one_call_equals_weight_gradient_then_flush(case):
+    """gram_window_end against gram_encoder_wgrad followed by gram_flush on the same window: IDs,
+    counts, every row of G_total and every entry of dW bit for bit, rows beyond the export
+    untouched, and the context ready for the next window.  The shapes take the weight-gradient
+    kernel through split ranges of the rows, one to three feature tiles (each buffer row is
+    written by one of them), a window whose rows are already in ID order (one step) and one that
+    needs the sort; float32 features and the dense buffer take the two steps one after the other."""
+    K, n, d_in, d, m, bf16 = 3, 30000, 512, 256, 9000, True
+    kw = {}
+    if case == "one_step":
+        K = 1
+    elif case == "three_feature_tiles":
+        d_in, d, n, m = 640, 264, 9000, 5000
+    elif case == "float32":
+        bf16, d_in, d, n, m = False, 48, 24, 2000, 3000
+    elif case == "no_rows_wanted":
+        kw["want_G"] = False
+    probs = [small_problem(500 + k, m, n, d_in=d_in, d=d, bf16=bf16) for k in range(K)]
+    X, W = probs[0][1], probs[0][2]
+    batches = [(p[0], p[3]) for p in probs]
+    if case == "resumed":
+        rng = np.random.default_rng(3)
+        r_ids = np.sort(rng.choice(n, size=700, replace=False)).astype(np.int32)
+        kw["resume"] = (r_ids, rng.integers(1, 9, size=700).astype(np.int64),
+                        rng.standard_normal((700, d)).astype(np.float32))
+    if case == "dense_falls_back":
+        import torch
+        a = run_window(X, W, batches, vocab_n=n, k_steps=K, dense=True)
+        g = a["gram"]
+        for k, (ids, dH) in enumerate(batches):
+            ids_d, dH_d = torch.from_numpy(ids).cuda(), torch.from_numpy(dH).cuda()
+            uq = torch.empty(min(m, n), dtype=torch.int32, device="cuda")
+            inv = torch.empty(m, dtype=torch.int32, device="cuda")
+            cn, ud = torch.empty_like(uq), torch.zeros(1, dtype=torch.int32, device="cuda")
+            H = torch.empty(m, d, device="cuda")
+            g.unique(ids_d, uq, inv, cn, ud)
+            g.encode_gather(a["X_dev"], a["W_dev"], uq, inv, ud, m, None, H)
+            g.grad_accumulate(dH_d, m, k)
+        dW = torch.full((d_in, d), float("nan"), device="cuda")
+        ut = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+        ct = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+        Gt = torch.full((n, d), float("nan"), device="cuda")
+        nn = g.window_end(a["X_dev"], dW, ut, ct, Gt, None, want_host_u=True)
+        assert nn == a["U_total"]
+        np.testing.assert_array_equal(ut[:nn].cpu().numpy(), a["uniq_total"])
+        np.testing.assert_array_equal(ct[:nn].cpu().numpy().astype(np.int64), a["counts_total"])
+        assert Gt[:nn].cpu().numpy().tobytes() == a["G_total"].tobytes()
+        assert dW.cpu().numpy().tobytes() == a["dW"].tobytes()
+        return
+    prof = ["wgrad_bf16", "wgrad_f32", "flush_rows", "flush_meta"]
+    a = run_window(X, W, batches, vocab_n=n, k_steps=K, **kw)
+    b = run_window(X, W, batches, vocab_n=n, k_steps=K, gram_obj=a["gram"], window_end=True, profile=prof, **kw)
+    launches = {k: v[0] for k, v in b["profile"].items() if v[0]}
+    say(f"{case}: U_total={a['U_total']} launches of the one call: {launches}")
+    if case == "resumed":
+        assert launches.pop("flush_rows") == 1       # gram_window_import's row kernel is counted under this name
+    # bf16: no launch of the export's row copy (with no rows wanted there is none either way)
+    assert launches == ({"wgrad_bf16": 1, "flush_meta": 1} if bf16 else {"wgrad_f32": 1, "flush_rows": 1})
+    assert a["U_total"] == b["U_total"] and a["U_total"] > 0
+    np.testing.assert_array_equal(a["uniq_total"], b["uniq_total"])
+    np.testing.assert_array_equal(a["counts_total"], b["counts_total"])
+    assert a["dW"].tobytes() == b["dW"].tobytes()
+    if case != "no_rows_wanted":
+        assert a["G_total"].tobytes() == b["G_total"].tobytes()
+        assert b["G_tail_untouched"]
+    # against the oracle as well, and the next window on the same context starts clean
+    acc = orc.GramMulti(X, W, pad_id=0)
+    if case == "resumed":
+        acc.resume(*kw["resume"])
+    for ids, dH in batches:
+        acc.step(ids, dH)
+    ids_t, counts_t, G_t = acc.export()
+    np.testing.assert_array_equal(b["uniq_total"], ids_t)
+    np.testing.assert_array_equal(b["counts_total"], counts_t)
+    tol = TOL[wl.BF16 if bf16 else wl.F32]
+    if case != "no_rows_wanted":
+        assert_close(b["G_total"], G_t, TOL_SUM[wl.BF16 if bf16 else wl.F32], "G_total of the one call")
+    assert_close(b["dW"], orc.wgrad(ids_t, X, G_t, 0), tol, "dW of the one call")
+    c = run_window(X, W, batches, vocab_n=n, k_steps=K, gram_obj=a["gram"], **kw)
+    assert c["dW"].tobytes() == a["dW"].tobytes()
+    np.testing.assert_array_equal(c["counts_total"], a["counts_total"])
+
+
 def test_error_paths():
     import torch
     from paper_2204_04179_amd import gram
