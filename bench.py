@@ -3,9 +3,12 @@
 
 A step is one pass of the whole path over one synthetic mini-batch:
 gram_unique -> gram_encode_gather -> gram_grad_accumulate, and at the end of
-every window of K steps gram_encoder_wgrad + gram_flush (so their cost is
+every window of K steps the weight gradient and the export of the buffer
+(gram_window_end, i.e. gram_encoder_wgrad + gram_flush; their cost is
 amortised over K, as in Multi-step GRAM).  Inputs are resident in HBM before
 the timed region; nothing in the timed region synchronises with the host.
+The small workloads rotate over several windows of distinct inputs so that
+no step replays data the caches still hold.
 
 Prints ONE JSON line: throughput in valid item occurrences per second, the
 roofline position of the dominant kernel (its duration measured with HIP
@@ -37,15 +40,19 @@ def log(*a):
 class Runner:
     """Device buffers of one workload plus the step loop."""
 
-    def __init__(self, w, export_G=True):
+    def __init__(self, w, export_G=True, sets=1, one_call_end=True):
+        """sets: windows of distinct inputs the steps rotate over (step j of the run uses the
+        inputs of step j mod (sets * K)).  one_call_end: end a window with gram_window_end instead
+        of gram_encoder_wgrad followed by gram_flush."""
         import torch
         from paper_2204_04179_amd import gram, workloads as wl
         self.torch, self.w, self.K = torch, w, w.K
         self.M, self.d, self.d_in = w.M, w.d, w.d_in
+        self.sets, self.one_call_end = sets, one_call_end
         t0 = time.time()
         X, W = wl.features(w), wl.weights(w)
-        self.ids_np = [wl.ids(w, k).reshape(-1) for k in range(w.K)]
-        dH_np = [wl.upstream_grad(w, k) for k in range(w.K)]
+        self.ids_np = [wl.ids(w, k).reshape(-1) for k in range(sets * w.K)]
+        dH_np = [wl.upstream_grad(w, k) for k in range(sets * w.K)]
         log(f"[bench] {w.name}: inputs drawn in {time.time() - t0:.1f}s")
 
         def dev(a):
@@ -72,28 +79,42 @@ class Runner:
         self.G_t = torch.empty(cap_t, w.d, device="cuda") if export_G else None
         self.u_t = torch.zeros(1, **i32)
         self.pos = 0     # step index inside the current window
+        self.win = 0     # which of the `sets` windows of inputs is running
+        self.window_events = None        # list: an event after every finished window (time_steps)
         # host-side statistics for the algorithmic byte counts
-        seen = np.zeros(w.N, bool)
         self.stats = []
-        for a in self.ids_np:
-            u, cnt = np.unique(a, return_counts=True)
-            heavy = cnt > self.g.light_max()
-            self.stats.append(dict(U=int(u.size), U_old=int(seen[u].sum()), M_valid=int((a != 0).sum()),
-                                   U_heavy=int(heavy.sum()), P_heavy=int(cnt[heavy].sum())))
-            seen[u] = True
-        self.U_total = int(seen.sum())
+        u_totals = []
+        for j in range(sets):
+            seen = np.zeros(w.N, bool)
+            for a in self.ids_np[j * w.K:(j + 1) * w.K]:
+                u, cnt = np.unique(a, return_counts=True)
+                heavy = cnt > self.g.light_max()
+                self.stats.append(dict(U=int(u.size), U_old=int(seen[u].sum()), M_valid=int((a != 0).sum()),
+                                       U_heavy=int(heavy.sum()), P_heavy=int(cnt[heavy].sum())))
+                seen[u] = True
+            u_totals.append(int(seen.sum()))
+        self.U_total = int(round(float(np.mean(u_totals))))     # items of a window (mean over the sets)
         self.M_valid_per_step = float(np.mean([s["M_valid"] for s in self.stats]))
 
     def step(self):
         g, k = self.g, self.pos
-        g.unique(self.ids[k], self.uniq, self.inverse, self.counts, self.u_dev)
+        j = self.win * self.K + k
+        g.unique(self.ids[j], self.uniq, self.inverse, self.counts, self.u_dev)
         g.encode_gather(self.X, self.Wt, self.uniq, self.inverse, self.u_dev, self.M, None, self.H)
-        g.grad_accumulate(self.dH[k], self.M, k)
+        g.grad_accumulate(self.dH[j], self.M, k)
         self.pos += 1
         if self.pos == self.K:
-            g.encoder_wgrad(self.X, self.dW)
-            g.flush(self.uniq_t, self.counts_t, self.G_t, self.u_t)
+            if self.one_call_end:
+                g.window_end(self.X, self.dW, self.uniq_t, self.counts_t, self.G_t, self.u_t)
+            else:
+                g.encoder_wgrad(self.X, self.dW)
+                g.flush(self.uniq_t, self.counts_t, self.G_t, self.u_t)
             self.pos = 0
+            self.win = (self.win + 1) % self.sets
+            if self.window_events is not None:
+                ev = self.torch.cuda.Event(enable_timing=True)
+                ev.record()
+                self.window_events.append(ev)
 
     def finish_window(self):
         while self.pos != 0:
@@ -127,8 +148,10 @@ class Runner:
             "seg_reduce": dict(bound="hbm", bytes=avg(lambda s: 4 * s["M_valid"] * d + 4 * M + 4 * s["U"] * d + 4 * s["U_old"] * d)),
             "encode_f32": dict(bound="alu", flops=avg(lambda s: 2 * s["U"] * d_in * d),
                                bytes=avg(lambda s: s["U"] * d_in * sx + d_in * d * sx + 4 * s["U"] * d)),
+            # (with gram_window_end the kernel also writes the rows of G_total)
             "wgrad_bf16": dict(bound="mfma", flops=2 * self.U_total * d_in * d,
-                               bytes=self.U_total * d_in * sx + 4 * self.U_total * d + 4 * d_in * d),
+                               bytes=self.U_total * d_in * sx + 4 * self.U_total * d + 4 * d_in * d
+                               + (4 * self.U_total * d if self.one_call_end and self.G_t is not None else 0)),
             "wgrad_f32": dict(bound="alu", flops=2 * self.U_total * d_in * d,
                               bytes=self.U_total * d_in * sx + 4 * self.U_total * d + 4 * d_in * d),
             "flush_rows": dict(bound="hbm", bytes=8 * self.U_total * d),
@@ -142,44 +165,60 @@ def time_steps(r, steps, warmup, profile_kernel=None):
     r.finish_window()
     torch.cuda.synchronize()
     r.g.profile_enable([profile_kernel] if profile_kernel else [], max_launches=max(64, 2 * steps))
+    # an event on the stream the library runs on (the default stream, torch's current one) after every
+    # window: the spread of the per-window times beside the wall-clock mean
+    start = torch.cuda.Event(enable_timing=True)
+    r.window_events = []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    start.record()
     for _ in range(steps):
         r.step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    evs, r.window_events = [start] + r.window_events, None
+    per_window = sorted(a.elapsed_time(b) / r.K for a, b in zip(evs[:-1], evs[1:]))
+    spread = None
+    if per_window:
+        spread = dict(windows=len(per_window), median=per_window[len(per_window) // 2], min=per_window[0],
+                      max=per_window[-1], mean=sum(per_window) / len(per_window))
     prof = r.g.profile_read() if profile_kernel else {}
     r.finish_window()
     torch.cuda.synchronize()
     r.g.profile_enable([])
-    return dt, prof
+    return dt, prof, spread
 
 
-def time_windows_graph(r, windows, warmup_windows=5):
-    """One window of K steps captured in a HIP graph (the library's calls only enqueue kernels, so
-    they can be captured) and replayed: removes the host's launch cost from small workloads."""
+def time_windows_graph(r, windows, warmup_replays=5):
+    """The windows of all input sets (sets * K steps) captured in one HIP graph (the library's calls
+    only enqueue kernels, so they can be captured) and replayed: removes the host's launch cost
+    from small workloads.  Returns (seconds, windows actually run)."""
     torch = r.torch
     r.finish_window()
+    while r.win != 0:
+        r.step()
     torch.cuda.synchronize()
+    per_graph = r.sets * r.K
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
-        for _ in range(r.K):
+        for _ in range(per_graph):
             r.step()                      # warm-up on the capture stream
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
-        for _ in range(r.K):
+        for _ in range(per_graph):
             r.step()
-    for _ in range(warmup_windows):
+    for _ in range(warmup_replays):
         graph.replay()
     torch.cuda.synchronize()
+    replays = max(1, windows // r.sets)
     t0 = time.perf_counter()
-    for _ in range(windows):
+    for _ in range(replays):
         graph.replay()
     torch.cuda.synchronize()
-    return time.perf_counter() - t0
+    return time.perf_counter() - t0, replays * r.sets
 
 
 def kernel_breakdown(r, windows=3):
@@ -207,24 +246,32 @@ def roofline_for(kernel, avg_us, alg):
 
 
 def read_traffic(workload, kernel):
-    """HBM bytes per launch from committed rocprofv3 counter runs, if present."""
+    """(HBM bytes per launch, commit of the code the counters were read on) from the committed
+    rocprofv3 counter runs, if present.  The file names its commit in a '# commit <id>' line."""
     path = os.path.join(ROOT, "profiles", "pmc_traffic.txt")
     if not os.path.exists(path):
-        return None
+        return None, None
+    commit, value = None, None
     for line in open(path):
         f = line.split()
-        if len(f) >= 3 and not line.startswith("#") and f[0] == workload and f[1] == kernel:
-            return float(f[2])
-    return None
+        if line.startswith("# commit") and len(f) >= 3:
+            commit = f[2]
+        elif len(f) >= 3 and not line.startswith("#") and f[0] == workload and f[1] == kernel:
+            value = float(f[2])
+    return value, commit
 
 
-def cpu_baseline(r, target_s=12.0):
-    """The CPU oracle (oracle/) on the first rows of every step of one window."""
+def cpu_baseline(r, target_s=10.0):
+    """The CPU oracle (oracle/) as it stands, on the first histories of every step of one window:
+    the GRAM path on all host threads (the headline of this object), the same on one thread, and the
+    end-to-end baseline of Section 3.3 (encoder forward and backward once per interaction) on all
+    threads and on one.  Each leg grows its sample towards its share of `target_s` seconds."""
     from oracle import gram_oracle as orc
     w = r.w
     L = w.L
+    all_threads = orc.num_threads()
 
-    def run(rows):
+    def run_gram(rows):
         mm = orc.GramMulti(r.X_np, r.W_np, pad_id=0)
         t0 = time.perf_counter()
         occ = 0
@@ -235,19 +282,78 @@ def cpu_baseline(r, target_s=12.0):
         mm.finish()
         return time.perf_counter() - t0, occ
 
-    rows = max(1, min(w.B, 8))
-    t, occ = run(rows)
-    # the cost per history falls as the sample grows (more repeats per unique item), so the sample is
-    # grown in up to three rounds towards target_s of oracle time
-    for _ in range(3):
-        if rows >= w.B or t >= 0.8 * target_s:
-            break
-        rows = int(min(w.B, max(rows + 1, rows * target_s / max(t, 1e-3))))
+    def run_e2e(rows):
+        t0 = time.perf_counter()
+        occ = 0
+        for k in range(w.K):
+            ids = r.ids_np[k][: rows * L]
+            orc.e2e(ids, r.X_np, r.W_np, r.dH_np[k][: rows * L], 0)
+            occ += int((ids != 0).sum())
+        return time.perf_counter() - t0, occ
+
+    def leg(run, threads, budget_s, what):
+        # the cost per history falls as the sample grows (more repeats per unique item), so the
+        # sample is grown in up to three rounds towards budget_s of oracle time
+        orc.set_num_threads(threads)
+        rows = 1
         t, occ = run(rows)
-    return dict(value=occ / t, unit="occurrences/s", cores=orc.num_threads(), kind="oracle",
-                sample=f"first {rows} of {w.B} histories of each of the K={w.K} steps of one window "
-                       f"(encode, gather, accumulate, wgrad), {occ} valid occurrences in {t:.2f}s",
-                seconds=t)
+        for _ in range(3):
+            if rows >= w.B or t >= 0.7 * budget_s:
+                break
+            rows = int(min(w.B, max(rows + 1, rows * budget_s / max(t, 1e-3))))
+            t, occ = run(rows)
+        orc.set_num_threads(all_threads)
+        return dict(value=occ / t, unit="occurrences/s", cores=threads, seconds=t, histories=rows,
+                    sample=f"first {rows} of {w.B} histories of each of the K={w.K} steps of one window "
+                           f"({what}), {occ} valid occurrences in {t:.2f}s"), rows
+
+    gram_what = "dedup, encode, gather, accumulate, weight gradient at the window's end"
+    e2e_what = "encoder forward and weight gradient once per interaction, no dedup"
+    head, rows_all = leg(run_gram, all_threads, 0.45 * target_s, gram_what)
+    one, _ = leg(run_gram, 1, 0.15 * target_s, gram_what)
+    e2e_all, _ = leg(run_e2e, all_threads, 0.25 * target_s, e2e_what)
+    e2e_one, _ = leg(run_e2e, 1, 0.15 * target_s, e2e_what)
+    # the two methods on the SAME sample (that of the e2e leg), all threads: the measured speed-up of
+    # the method on the CPU next to the boost ratio R of Eq. 10 of that sample
+    orc.set_num_threads(all_threads)
+    rows = e2e_all["histories"]
+    t_gram, _ = run_gram(rows)
+    t_e2e, _ = run_e2e(rows)
+    R = float(np.mean([orc.boost_ratio(r.ids_np[k][: rows * L], 0) for k in range(w.K)]))
+    seen = set()
+    for k in range(w.K):
+        seen.update(np.unique(r.ids_np[k][: rows * L]).tolist())
+    seen.discard(0)
+    occ_window = sum(int((r.ids_np[k][: rows * L] != 0).sum()) for k in range(w.K))
+    head.update(kind="oracle", single_thread=one, oracle_e2e=e2e_all, oracle_e2e_single_thread=e2e_one,
+                e2e_over_gram=dict(measured=t_e2e / t_gram, histories=rows,
+                                   boost_ratio_R_per_step=R,
+                                   boost_ratio_R_per_window=occ_window / max(1, len(seen)),
+                                   note="same sample for both, all threads; Eq. 10 predicts the ratio of encoder "
+                                        "passes (per step for the forward, per window for the weight gradient)"))
+    return head
+
+
+def e2e_on_gpu_leg(r, reps=3):
+    """Outside the timed steps: the end-to-end baseline of Section 3.3 with this library's own
+    contraction kernels: the encoder forward and the weight gradient once per interaction (M rows
+    instead of U), no dedup, no accumulation.  gram_pseudo_loss_grad over the positions of a step is
+    exactly that pair of contractions (h = X[ids].W written to [M,d], dW = X[ids]^T.R); the upstream
+    gradient stands in for the targets, which does not change the work."""
+    torch, g, w = r.torch, r.g, r.w
+    r.finish_window()
+    R = torch.empty(w.M, w.d, device="cuda")
+    g.pseudo_loss_grad(r.X, r.Wt, r.ids[0], r.dH[0], w.M, R, r.dW, False, None)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        for k in range(w.K):
+            g.pseudo_loss_grad(r.X, r.Wt, r.ids[k], r.dH[k], w.M, R, r.dW, False, None)
+    torch.cuda.synchronize()
+    us = 1e6 * (time.perf_counter() - t0) / (reps * w.K)
+    return {"us_per_step": us, "value": r.M_valid_per_step / (us * 1e-6), "unit": "occurrences/s",
+            "flops_per_step": 4 * w.M * w.d_in * w.d,
+            "tflops": 4 * w.M * w.d_in * w.d / (us * 1e-6) / 1e12}
 
 
 def pseudo_target_leg(r, reps=20):
@@ -509,7 +615,11 @@ def main():
                     help="comma-separated workloads reported under 'also' ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-export-G", action="store_true", help="gram_flush without the G_total copy")
-    ap.add_argument("--legs", default="no_export,pseudo_target,chunked_wgrad,encoder_batches,mlp,bf16_h,long_window",
+    ap.add_argument("--separate-end", action="store_true",
+                    help="end a window with gram_encoder_wgrad + gram_flush instead of gram_window_end")
+    ap.add_argument("--sets", type=int, default=4,
+                    help="windows of distinct inputs the small workloads under 'also' rotate over")
+    ap.add_argument("--legs", default="no_export,e2e_gpu,separate_end,pseudo_target,chunked_wgrad,encoder_batches,mlp,bf16_h,long_window",
                     help="extra measurements outside the timed steps (profiling runs drop chunked_wgrad so that "
                          "the weight-gradient kernel's statistics cover the timed windows only)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -526,7 +636,7 @@ def main():
     torch.cuda.set_device(0)
 
     w = wl.get(args.workload)
-    r = Runner(w, export_G=not args.no_export_G)
+    r = Runner(w, export_G=not args.no_export_G, one_call_end=not args.separate_end)
     if args.copy_probe:
         a = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
         b = torch.empty_like(a)
@@ -540,10 +650,10 @@ def main():
     fused = "gather_heavy" in kernels
     alg = r.algorithmic(fused)
     dominant = max((k for k in kernels if k in alg), key=lambda k: kernels[k]["total_us_per_step"])
-    dt, prof = time_steps(r, args.steps, args.warmup, profile_kernel=dominant)
+    dt, prof, spread = time_steps(r, args.steps, args.warmup, profile_kernel=dominant)
     n, ms = prof[dominant]
     roof = roofline_for(dominant, 1e3 * ms / n, alg)
-    roof["traffic"] = read_traffic(w.name, dominant)
+    roof["traffic"], roof["traffic_measured_at_commit"] = read_traffic(w.name, dominant)
     roof["timed_launches"] = n
     ms_per_step = 1e3 * dt / args.steps
     value = r.M_valid_per_step * args.steps / dt
@@ -560,6 +670,7 @@ def main():
     out = {
         "metric": "item_occurrences_per_sec", "value": value, "unit": "occurrences/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_by_window": spread,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if w.xw_dtype == "f32" else "bf16_in_f32_acc", "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} L={w.L} N={w.N} Zipf(s={w.s}) d_in={w.d_in} d={w.d} "
@@ -568,7 +679,9 @@ def main():
                    "unique_per_step": float(np.mean([s["U"] for s in r.stats])),
                    "unique_per_window": r.U_total,
                    "boost_ratio": r.M_valid_per_step / float(np.mean([s["U"] - (1 if w.padding else 0) for s in r.stats])),
-                   "flush_exports_G": not args.no_export_G, "workspace_bytes": r.ws_bytes},
+                   "flush_exports_G": not args.no_export_G,
+                   "window_end": "gram_encoder_wgrad + gram_flush" if args.separate_end else "gram_window_end",
+                   "input_sets": r.sets, "workspace_bytes": r.ws_bytes},
         "roofline": roof,
         "hbm_kernels": {"kernels": mem_kernels, "algorithmic_bytes": mem_bytes, "us": mem_us,
                         "encode_gather_accumulate_GBs": mem_bytes / (mem_us * 1e-6) / 1e9 if mem_us else None,
@@ -583,11 +696,24 @@ def main():
         # the weight gradient is taken from the buffer itself, so a caller that does not need the
         # rows afterwards can flush without the G_total copy: same steps, that copy left out
         keep, r.G_t = r.G_t, None
-        dt2, _ = time_steps(r, max(w.K, args.steps // 2 // w.K * w.K), w.K)
-        r.G_t = keep
         steps2 = max(w.K, args.steps // 2 // w.K * w.K)
+        dt2, _, _ = time_steps(r, steps2, w.K)
+        r.G_t = keep
         out["flush_without_G_export"] = {"ms_per_step": 1e3 * dt2 / steps2,
                                          "value": r.M_valid_per_step * steps2 / dt2, "unit": "occurrences/s"}
+    if "separate_end" in legs and not args.separate_end:
+        # the same steps with the window ended by the two separate calls
+        steps2 = max(w.K, args.steps // 2 // w.K * w.K)
+        r.one_call_end = False
+        dt2, _, sp2 = time_steps(r, steps2, w.K)
+        r.one_call_end = True
+        out["window_end_in_two_calls"] = {"ms_per_step": 1e3 * dt2 / steps2, "ms_per_step_by_window": sp2,
+                                          "value": r.M_valid_per_step * steps2 / dt2, "unit": "occurrences/s"}
+    if "e2e_gpu" in legs and w.xw_dtype != wl.F32:
+        e2e = e2e_on_gpu_leg(r)
+        e2e["e2e_over_gram_measured"] = e2e["us_per_step"] / (1e3 * ms_per_step)
+        e2e["boost_ratio_R"] = out["config"]["boost_ratio"]
+        out["e2e_on_gpu"] = e2e
     out["next_rows"] = {}
     if "pseudo_target" in legs:
         out["next_rows"]["pseudo_target"] = pseudo_target_leg(r)
@@ -608,18 +734,20 @@ def main():
     also = []
     for name in [a for a in args.also.split(",") if a]:
         w2 = wl.get(name)
-        r2 = Runner(w2, export_G=not args.no_export_G)
+        r2 = Runner(w2, export_G=not args.no_export_G, sets=max(1, args.sets), one_call_end=not args.separate_end)
         for _ in range(w2.K):
             r2.step()
         torch.cuda.synchronize()
-        steps2 = 400
-        dt2, _ = time_steps(r2, steps2, 20)
+        steps2 = 400 // (r2.sets * w2.K) * (r2.sets * w2.K)
+        dt2, _, sp2 = time_steps(r2, steps2, 5 * w2.K)
         windows2 = steps2 // w2.K
-        dt3 = time_windows_graph(r2, windows2)
+        dt3, windows3 = time_windows_graph(r2, windows2)
         also.append({"workload": w2.name, "value": r2.M_valid_per_step * steps2 / dt2,
                      "unit": "occurrences/s", "us_per_step": 1e6 * dt2 / steps2, "steps": steps2,
-                     "hip_graph_replay": {"value": r2.M_valid_per_step * windows2 * w2.K / dt3,
-                                          "us_per_step": 1e6 * dt3 / (windows2 * w2.K)},
+                     "input_sets": r2.sets, "us_per_step_by_window": {k: (1e3 * v if k != "windows" else v)
+                                                                       for k, v in sp2.items()},
+                     "hip_graph_replay": {"value": r2.M_valid_per_step * windows3 * w2.K / dt3,
+                                          "us_per_step": 1e6 * dt3 / (windows3 * w2.K)},
                      "kernels_us": {k: round(v["avg_us"], 1) for k, v in kernel_breakdown(r2, 20).items()},
                      "note": "launch-latency bound: a few microseconds of HBM traffic per step"})
         del r2

@@ -58,6 +58,20 @@ int oracle_num_threads(void)
 #endif
 }
 
+/* Number of OpenMP threads the later calls use (n < 1: left as it is); returns the
+ * number in force.  Thread count only: no arithmetic depends on it (every sum
+ * below is taken by one thread in a fixed order). */
+int oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1)
+        omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+    return oracle_num_threads();
+}
+
 static int cmp_i32(const void *a, const void *b)
 {
     int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;

@@ -47,6 +47,8 @@ def lib():
         i32p, i64p, f32p, f64p, vp = (C.POINTER(C.c_int32), C.POINTER(C.c_int64),
                                       C.POINTER(C.c_float), C.POINTER(C.c_double), C.c_void_p)
         L.oracle_num_threads.restype = C.c_int
+        L.oracle_set_num_threads.restype = C.c_int
+        L.oracle_set_num_threads.argtypes = [C.c_int]
         for name in ("oracle_unique", "oracle_unique_brute"):
             f = getattr(L, name)
             f.restype = C.c_int64
@@ -110,6 +112,11 @@ def _check(rc, what):
 
 def num_threads() -> int:
     return lib().oracle_num_threads()
+
+
+def set_num_threads(n: int) -> int:
+    """OpenMP threads for the calls that follow; returns the number in force."""
+    return lib().oracle_set_num_threads(int(n))
 
 
 def _xw_dtype(a: np.ndarray) -> int:
