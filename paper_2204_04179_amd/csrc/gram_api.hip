@@ -109,7 +109,7 @@ int64_t layout(Ctx* c, const gram_config& cfg, const Derived& dv, char* base)
     int* vals1 = (int*)take(dv.n_sort_max * 4);
     int* table = (int*)take(table_elems_for(dv.n_sort_max) * 4);
     int* gtot = (int*)take((1 << kMaxDigitBits) * 4);
-    int* tile_sums = (int*)take(dv.tiles_scan * 4);
+    int* tile_sums = (int*)take(dv.tiles_scan * 3 * 4);     // three figures per scan tile
     int* offsets = (int*)take((dv.cap_u + 2) * 4);
     int* seg_of_row = (int*)take(cfg.max_positions * 4);
     int* uniq_ws = (int*)take(dv.cap_u * 4);
@@ -201,7 +201,7 @@ constexpr int64_t kStaticOffVals1 = kStaticOffVals0 + static_align(kStaticMax * 
 constexpr int64_t kStaticOffTable = kStaticOffVals1 + static_align(kStaticMax * 4);
 constexpr int64_t kStaticOffGtot = kStaticOffTable + static_align(kStaticTableElems * 4);
 constexpr int64_t kStaticOffTiles = kStaticOffGtot + static_align((1 << kMaxDigitBits) * 4);
-constexpr int64_t kStaticOffOffsets = kStaticOffTiles + static_align((kStaticMax / kScanTile + 2) * 4);
+constexpr int64_t kStaticOffOffsets = kStaticOffTiles + static_align((kStaticMax / kScanTile + 2) * 3 * 4);
 constexpr int64_t kStaticOffSegOfRow = kStaticOffOffsets + static_align((kStaticMax + 2) * 4);
 constexpr int64_t kStaticOffUniqWs = kStaticOffSegOfRow + static_align(kStaticMax * 4);
 constexpr int64_t kStaticBytes = kStaticOffUniqWs + static_align(kStaticMax * 4);
@@ -341,14 +341,19 @@ int gram_unique(gram_ctx* ctx, const int32_t* ids, int64_t m, int32_t* uniq, int
     c->have_unique = false;
     if (m > 0) {
         const int fix = c->cfg.pad_id >= 0 ? c->cfg.pad_id : 0;
-        if (!unique_small(c, ids, (int)m, fix, uniq, inverse, counts, u_dev, s)) {
+        // slot-table contexts: the dedup kernels also work out the buffer rows of the items
+        const bool prospect = !c->dense;
+        const int first_step = (c->steps_done == 0 && !c->window_imported) ? 1 : 0;
+        if (!unique_small(c, ids, (int)m, fix, uniq, inverse, counts, u_dev, s, prospect, first_step)) {
             const int r = radix_sort_pairs(c, ids, nullptr, (int)m, nullptr, m, true, fix, s);
             c->sorted_keys = c->keys[r];
             c->perm = c->vals[r];
-            unique_from_sorted(c, (int)m, uniq, inverse, counts, u_dev, s);
+            unique_from_sorted(c, (int)m, uniq, inverse, counts, u_dev, s, prospect, first_step);
         }
+        c->prospect_epoch = prospect ? c->slot_epoch : 0;
     } else {
         unique_from_sorted(c, 0, uniq, inverse, counts, u_dev, s);
+        c->prospect_epoch = 0;
     }
     if (int rc = launch_status(c, "gram_unique")) return rc;
     c->have_unique = true;
@@ -462,8 +467,12 @@ int gram_grad_accumulate(gram_ctx* ctx, const float* dH, int64_t m, int32_t step
                     step_k, c->steps_done, c->cfg.k_steps);
     if (m > 0 && !dH) return fail(c, GRAM_ERR_ARG, "gram_grad_accumulate: dH is NULL");
     hipStream_t s = static_cast<hipStream_t>(stream);
-    assign_slots(c, s);
-    segment_reduce(c, dH, m, s);
+    // the rows worked out by gram_unique hold if the slot table is still the one it looked at;
+    // the reduction then commits them as it goes, else they are assigned afresh first
+    const bool commit = m > 0 && c->prospect_epoch == c->slot_epoch;
+    if (!commit) assign_slots(c, s);
+    segment_reduce(c, dH, m, s, commit);
+    c->slot_epoch += 1;
     if (int rc = launch_status(c, "gram_grad_accumulate")) return rc;
     c->unique_consumed = true;
     c->steps_done += 1;
@@ -555,6 +564,7 @@ static int flush_any(Ctx* c, int32_t* uniq_total, int32_t* counts_total, int64_t
         flush_export(c, uniq_total, counts_total, reinterpret_cast<long long*>(counts64_total), G_total,
                      u_total_dev, s);
     c->have_unique = false;     // the sort buffers were reused
+    c->slot_epoch += 1;
     c->steps_done = 0;
     c->window_positions = 0;
     c->window_imported = false;
@@ -606,6 +616,7 @@ int gram_window_end(gram_ctx* ctx, const void* X, float* dW, int32_t* uniq_total
     const int* ranks = flush_meta_and_ranks(c, uniq_total, counts_total, u_total_dev, s);
     encoder_wgrad(c, X, dW, s, 0, c->cap_total, false, nullptr, G_total, ranks);
     c->have_unique = false;     // the sort buffers were reused
+    c->slot_epoch += 1;
     c->steps_done = 0;
     c->window_positions = 0;
     c->window_imported = false;
@@ -631,6 +642,7 @@ int gram_window_import(gram_ctx* ctx, const int32_t* ids, const int64_t* counts,
         import_dense(c, ids, reinterpret_cast<const long long*>(counts), G_rows, n, static_cast<hipStream_t>(stream));
     else
         import_slots(c, ids, reinterpret_cast<const long long*>(counts), G_rows, n, static_cast<hipStream_t>(stream));
+    c->slot_epoch += 1;
     if (int rc = launch_status(c, "gram_window_import")) return rc;
     c->window_imported = true;
     c->window_positions += n;      // host bound on the rows in the buffer (sizes the split-K of the weight gradient)
@@ -638,7 +650,7 @@ int gram_window_import(gram_ctx* ctx, const int32_t* ids, const int64_t* counts,
 }
 
 static const char* const kKernelNames[KID_COUNT] = {
-    "radix_hist", "radix_scan", "radix_scatter", "heads_count", "heads_emit", "counts", "unique_empty",
+    "radix_hist", "radix_scan", "radix_scatter", "heads_count", "heads_emit", "unique_empty",
     "transpose_w", "encode_bf16", "encode_f32", "gather_rows", "slot_count", "slot_emit", "seg_reduce",
     "seg_combine", "wgrad_bf16", "wgrad_f32", "wgrad_reduce", "flush_meta",
     "flush_rows", "unique_small", "gather_heavy", "pseudo_target", "pseudo_loss", "chunk_ids",

@@ -41,7 +41,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 }
 
 // Device scalars (ctx->scal[...]).
-enum Scalar { kSU = 0, kSUTotal, kSErr, kSUBase, kSLongCount, kSFlushN, kSChunkN, kSCount };
+enum Scalar { kSU = 0, kSUTotal, kSErr, kSUBase, kSLongCount, kSFlushN, kSChunkN, kSUNext, kSCount };
 
 // Device-latched error bits (scal[kSErr]).
 constexpr int kErrBitRange = 1;
@@ -49,7 +49,7 @@ constexpr int kErrBitCapacity = 2;
 
 // Kernel identifiers for the built-in event timer (gram_profile_*).
 enum KernelId {
-    KID_RADIX_HIST = 0, KID_RADIX_SCAN, KID_RADIX_SCATTER, KID_HEADS_COUNT, KID_HEADS_EMIT, KID_COUNTS,
+    KID_RADIX_HIST = 0, KID_RADIX_SCAN, KID_RADIX_SCATTER, KID_HEADS_COUNT, KID_HEADS_EMIT,
     KID_UNIQUE_EMPTY, KID_TRANSPOSE_U16, KID_ENCODE_BF16, KID_ENCODE_F32, KID_GATHER_ROWS,
     KID_SLOT_COUNT, KID_SLOT_EMIT, KID_SEG_REDUCE, KID_SEG_COMBINE, KID_WGRAD_BF16, KID_WGRAD_F32,
     KID_WGRAD_REDUCE, KID_FLUSH_META, KID_FLUSH_ROWS, KID_UNIQUE_SMALL,
@@ -129,6 +129,11 @@ struct Ctx {
     const int* last_inverse = nullptr;
     bool unique_consumed = false;  // the current batch was already accumulated
     bool window_imported = false;  // a saved state was merged into this window
+    // The dedup of a batch also works out which buffer rows its items will get (seg_slot), from
+    // the slot table as it is at that moment; gram_grad_accumulate commits them if the table has
+    // not changed since (every change of it advances slot_epoch), else assigns rows afresh.
+    uint64_t slot_epoch = 1;
+    uint64_t prospect_epoch = 0;   // slot_epoch at which seg_slot was worked out; 0 = not at all
     int64_t cur_m = 0;
     int32_t steps_done = 0;
     int64_t window_positions = 0;  // positions accumulated in this window: bounds the buffer rows
@@ -185,10 +190,11 @@ SortPlan make_sort_plan(int key_bits, int64_t n_max);
 // ctx->keys[r] / ctx->vals[r]; r is returned.
 int radix_sort_pairs(Ctx* c, const int* keys_in, const int* vals_in, int n_host, const int* n_dev,
                      int64_t n_max, bool check_range, int fix_key, hipStream_t s);
-void unique_from_sorted(Ctx* c, int n, int* uniq, int* inverse, int* counts, int* u_out, hipStream_t s);
+void unique_from_sorted(Ctx* c, int n, int* uniq, int* inverse, int* counts, int* u_out, hipStream_t s,
+                        bool prospect = false, int first_step = 0);
 // One-launch dedup for small batches; returns false if n is too large for it.
 bool unique_small(Ctx* c, const int* ids, int n, int fix_key, int* uniq, int* inverse, int* counts,
-                  int* u_out, hipStream_t s);
+                  int* u_out, hipStream_t s, bool prospect = false, int first_step = 0);
 
 // ---- gram_stream.hip -----------------------------------------------------
 // H has the context's h_dtype (float32, or bf16 rounded to nearest even).
@@ -201,7 +207,7 @@ void chunk_ids_prepare(Ctx* c, const int* ids, int64_t n, hipStream_t s);
 // item); without: R is taken as it is.  With loss_dev, 1/2 of the sum of the squares of R.
 void pseudo_miss(Ctx* c, float* R, const float* Ht, int64_t n, double* loss_dev, hipStream_t s);
 void assign_slots(Ctx* c, hipStream_t s);
-void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s);
+void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s, bool commit = false);
 void flush_export(Ctx* c, int* uniq_total, int* counts_total, long long* counts64_total, float* G_total,
                   int* u_total_dev, hipStream_t s);
 const int* flush_meta_and_ranks(Ctx* c, int* uniq_total, int* counts_total, int* u_total_dev, hipStream_t s);

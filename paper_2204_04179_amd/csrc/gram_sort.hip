@@ -269,47 +269,124 @@ int radix_sort_pairs(Ctx* c, const int* keys_in, const int* vals_in, int n_host,
     return dst ^ 1;
 }
 
-// ---- head flags -> uniq / inverse / offsets / counts ----------------------
+// ---- head flags -> uniq / inverse / offsets / counts / prospective buffer rows ----
 
 __device__ __forceinline__ bool is_head(const int* __restrict__ sk, int r)
 {
     return r == 0 || sk[r] != sk[r - 1];
 }
 
+// Two launches over tiles of kScanTile sorted rows.  The first leaves three figures per tile
+// (tile_info[t], [T + t], [2 T + t] with T tiles): the number of segment heads in the tile, how
+// many of those items have no row in the window's buffer yet, and the row of the tile's first
+// head (-1: none).  The second turns them into everything that is known per unique item:
+// uniq, offsets, counts (a head's segment ends at the next head, which may lie tiles ahead: the
+// third figure finds it), the inverse index, and - when the context keeps a slot table - the
+// buffer row each item WOULD get from the next gram_grad_accumulate (seg_slot: its row, or for
+// an item new to the window the next free row with kSlotNew set, in ascending-ID order, or -1
+// when the buffer is full).  Nothing of the slot table is written here: the accumulate step
+// commits those rows, provided the table has not changed in between.
+__device__ __forceinline__ int block_min(int v, int* sm)
+{
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+        const int t = __shfl_down(v, o);
+        v = t < v ? t : v;
+    }
+    if (lane_id() == 0) sm[wave_id()] = v;
+    __syncthreads();
+    int m = sm[0];
+#pragma unroll
+    for (int w = 1; w < kWavesPerBlock; ++w) m = sm[w] < m ? sm[w] : m;
+    __syncthreads();
+    return m;
+}
+
+constexpr int kNoRow = 0x7fffffff;
+
 __global__ __launch_bounds__(kBlock) void k_heads_count(const int* __restrict__ sk, int n,
-                                                        int* __restrict__ tile_sums)
+                                                        const int* __restrict__ slot_of,
+                                                        int* __restrict__ tile_info)
 {
     __shared__ int sm[kWavesPerBlock];
     const int r0 = blockIdx.x * kScanTile + threadIdx.x * 4;
-    int s = 0;
+    int s = 0, fresh = 0, first = kNoRow;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-        if (r0 + i < n) s += is_head(sk, r0 + i) ? 1 : 0;
+        if (r0 + i < n && is_head(sk, r0 + i)) {
+            ++s;
+            if (first == kNoRow) first = r0 + i;
+            if (slot_of && slot_of[sk[r0 + i]] < 0) ++fresh;
+        }
     const int tot = block_sum(s, sm);
-    if (threadIdx.x == 0) tile_sums[blockIdx.x] = tot;
+    const int tot_fresh = block_sum(fresh, sm);
+    const int row = block_min(first, sm);
+    if (threadIdx.x == 0) {
+        tile_info[blockIdx.x] = tot;
+        tile_info[gridDim.x + blockIdx.x] = tot_fresh;
+        tile_info[2 * gridDim.x + blockIdx.x] = row == kNoRow ? -1 : row;
+    }
 }
 
 __global__ __launch_bounds__(kBlock) void k_heads_emit(
-    const int* __restrict__ sk, const int* __restrict__ sv, int n, const int* __restrict__ tile_sums,
-    int* __restrict__ uniq, int* __restrict__ inverse, int* __restrict__ offsets,
-    int* __restrict__ seg_of_row, int* __restrict__ uniq_ws, int* __restrict__ u_ws,
-    int* __restrict__ u_out)
+    const int* __restrict__ sk, const int* __restrict__ sv, int n, const int* __restrict__ tile_info,
+    int* __restrict__ uniq, int* __restrict__ inverse, int* __restrict__ counts,
+    int* __restrict__ offsets, int* __restrict__ seg_of_row, int* __restrict__ uniq_ws,
+    int* __restrict__ u_out, const int* __restrict__ slot_of, int* __restrict__ seg_slot,
+    int* __restrict__ scal, int first_step, int cap_total)
 {
     __shared__ int sm[kWavesPerBlock];
-    int pre = 0;
-    for (int t = threadIdx.x; t < (int)blockIdx.x; t += kBlock) pre += tile_sums[t];
+    __shared__ int s_rows[kScanTile + 1];     // rows of the tile's heads, then the next head's row
+    __shared__ int s_next;
+    const int T = gridDim.x;
+    int pre = 0, pre_fresh = 0;
+    for (int t = threadIdx.x; t < (int)blockIdx.x; t += kBlock) {
+        pre += tile_info[t];
+        pre_fresh += tile_info[T + t];
+    }
     pre = block_sum(pre, sm);
+    pre_fresh = block_sum(pre_fresh, sm);
+    if (threadIdx.x == 0) s_next = kNoRow;
 
     const int r0 = blockIdx.x * kScanTile + threadIdx.x * 4;
     bool f[4];
-    int s = 0;
+    int old[4];
+    int s = 0, fresh = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         f[i] = (r0 + i < n) && is_head(sk, r0 + i);
+        old[i] = 0;
         s += f[i] ? 1 : 0;
+        if (f[i] && slot_of) {
+            old[i] = slot_of[sk[r0 + i]];
+            fresh += old[i] < 0 ? 1 : 0;
+        }
     }
-    int total;
-    int run = pre + block_excl_scan(s, &total, sm);
+    int total, total_fresh;
+    const int local = block_excl_scan(s, &total, sm);
+    const int local_fresh = block_excl_scan(fresh, &total_fresh, sm);
+    {
+        int li = local;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (f[i]) s_rows[li++] = r0 + i;
+    }
+    // the first head after this tile: the tiles ahead are looked at kBlock at a time (their first
+    // heads ascend with the tile index, so the minimum is the nearest)
+    for (int base = blockIdx.x + 1; base < T; base += kBlock) {
+        const int t = base + threadIdx.x;
+        const int row = t < T ? tile_info[2 * T + t] : -1;
+        if (row >= 0) atomicMin(&s_next, row);
+        __syncthreads();
+        if (s_next != kNoRow) break;           // the same value for every thread
+        __syncthreads();
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) s_rows[total] = s_next == kNoRow ? n : s_next;
+    __syncthreads();
+
+    const int u_base = (slot_of && !first_step) ? scal[kSUTotal] : 0;   // a flush leaves the old count behind
+    int run = pre + local, li = local, next_slot = u_base + pre_fresh + local_fresh;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int r = r0 + i;
@@ -323,23 +400,30 @@ __global__ __launch_bounds__(kBlock) void k_heads_emit(
                 uniq[seg] = key;
                 uniq_ws[seg] = key;
                 offsets[seg] = r;
+                counts[seg] = s_rows[li + 1] - r;
+                ++li;
+                if (slot_of) {
+                    int code = old[i];
+                    if (code < 0) {
+                        const int slot = next_slot++;
+                        code = slot < cap_total ? (slot | kSlotNew) : -1;
+                    }
+                    seg_slot[seg] = code;
+                }
             }
         }
     }
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
         const int u = pre + total;
-        *u_ws = u;
+        scal[kSU] = u;
         if (u_out) *u_out = u;
         offsets[u] = n;
+        if (slot_of) {
+            const int nt = u_base + pre_fresh + total_fresh;
+            scal[kSUNext] = nt < cap_total ? nt : cap_total;
+            scal[kSLongCount] = 0;
+        }
     }
-}
-
-__global__ __launch_bounds__(kBlock) void k_counts(const int* __restrict__ offsets,
-                                                   const int* __restrict__ u_ws,
-                                                   int* __restrict__ counts)
-{
-    const int j = blockIdx.x * kBlock + threadIdx.x;
-    if (j < *u_ws) counts[j] = offsets[j + 1] - offsets[j];
 }
 
 __global__ void k_unique_empty(int* u_ws, int* u_out, int* offsets)
@@ -400,7 +484,8 @@ __global__ __launch_bounds__(kSmallThreads) void k_unique_small(
     int* __restrict__ sorted_keys, int* __restrict__ perm, int* __restrict__ uniq,
     int* __restrict__ inverse, int* __restrict__ counts, int* __restrict__ offsets,
     int* __restrict__ seg_of_row, int* __restrict__ uniq_ws, int* __restrict__ u_ws,
-    int* __restrict__ u_out)
+    int* __restrict__ u_out, const int* __restrict__ slot_of, int* __restrict__ seg_slot,
+    int* __restrict__ scal, int first_step, int cap_total)
 {
     extern __shared__ __attribute__((aligned(16))) int lds[];
     // keys of order `o` at KBUF(o), positions at VBUF(o)
@@ -569,29 +654,62 @@ __global__ __launch_bounds__(kSmallThreads) void k_unique_small(
         offsets[j] = r;
         counts[j] = (j + 1 < total ? loff[j + 1] : n) - r;
     }
+    // the buffer rows the items would get from the next gram_grad_accumulate (see k_heads_emit):
+    // thread t looks up items 8 t .. 8 t + 7, one scan ranks the items new to the window
+    if (slot_of) {
+        const int j0 = tid * 8;
+        int old[8], fresh = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            old[i] = 0;
+            if (j0 + i < total) {
+                old[i] = slot_of[sk[loff[j0 + i]]];
+                fresh += old[i] < 0 ? 1 : 0;
+            }
+        }
+        int total_fresh;
+        const int u_base = first_step ? 0 : scal[kSUTotal];    // a flush leaves the old count behind
+        int next_slot = u_base + block1024_excl_scan(fresh, &total_fresh, wsum);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (j0 + i < total) {
+                int code = old[i];
+                if (code < 0) {
+                    const int slot = next_slot++;
+                    code = slot < cap_total ? (slot | kSlotNew) : -1;
+                }
+                seg_slot[j0 + i] = code;
+            }
+        if (tid == 0) {
+            const int nt = u_base + total_fresh;
+            scal[kSUNext] = nt < cap_total ? nt : cap_total;
+            scal[kSLongCount] = 0;
+        }
+    }
 #undef KBUF
 #undef VBUF
 }
 
+// prospect: also work out the buffer rows the items would get (slot-table contexts only);
+// first_step: the window's buffer holds nothing yet.
 void unique_from_sorted(Ctx* c, int n, int* uniq, int* inverse, int* counts, int* u_out,
-                        hipStream_t s)
+                        hipStream_t s, bool prospect, int first_step)
 {
     if (n == 0) {
         launch(c, KID_UNIQUE_EMPTY, k_unique_empty, dim3(1), dim3(kWave), s, c->scal + kSU, u_out, c->offsets);
         return;
     }
     const int tiles = (n + kScanTile - 1) / kScanTile;
-    launch(c, KID_HEADS_COUNT, k_heads_count, dim3(tiles), dim3(kBlock), s, c->sorted_keys, n, c->tile_sums);
+    const int* slot_of = prospect ? c->slot_of : nullptr;
+    launch(c, KID_HEADS_COUNT, k_heads_count, dim3(tiles), dim3(kBlock), s, c->sorted_keys, n, slot_of,
+           c->tile_sums);
     launch(c, KID_HEADS_EMIT, k_heads_emit, dim3(tiles), dim3(kBlock), s, c->sorted_keys, c->perm, n,
-                       c->tile_sums, uniq, inverse, c->offsets, c->seg_of_row, c->uniq_ws, c->scal + kSU,
-                       u_out);
-    const int64_t cap = n < c->cap_u ? n : c->cap_u;
-    launch(c, KID_COUNTS, k_counts, dim3((unsigned)((cap + kBlock - 1) / kBlock)), dim3(kBlock), s,
-                       c->offsets, c->scal + kSU, counts);
+           c->tile_sums, uniq, inverse, counts, c->offsets, c->seg_of_row, c->uniq_ws, u_out, slot_of,
+           c->seg_slot, c->scal, first_step, (int)c->cap_total);
 }
 
 bool unique_small(Ctx* c, const int* ids, int n, int fix_key, int* uniq, int* inverse, int* counts,
-                  int* u_out, hipStream_t s)
+                  int* u_out, hipStream_t s, bool prospect, int first_step)
 {
     if (n <= 0 || n > kSmallMaxN) return false;
     ensure_dynamic_lds<k_unique_small>((int)kSmallLds);
@@ -599,7 +717,8 @@ bool unique_small(Ctx* c, const int* ids, int n, int fix_key, int* uniq, int* in
     c->perm = c->vals[0];
     launch_smem(c, KID_UNIQUE_SMALL, k_unique_small, dim3(1), dim3(kSmallThreads), kSmallLds, s, ids, n,
                 c->key_bits, c->cfg.vocab_n, fix_key, c->scal + kSErr, c->sorted_keys, c->perm, uniq, inverse,
-                counts, c->offsets, c->seg_of_row, c->uniq_ws, c->scal + kSU, u_out);
+                counts, c->offsets, c->seg_of_row, c->uniq_ws, c->scal + kSU, u_out,
+                prospect ? c->slot_of : nullptr, c->seg_slot, c->scal, first_step, (int)c->cap_total);
     return true;
 }
 

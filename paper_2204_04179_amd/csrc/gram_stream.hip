@@ -584,7 +584,8 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(
     const int* __restrict__ offsets, const int* __restrict__ uniq_ws,
     const int* __restrict__ seg_slot, int n, int cols4, int pad_id, float4* __restrict__ G,
     float4* __restrict__ seg_first, float4* __restrict__ seg_last, int* __restrict__ scal,
-    int* __restrict__ long_list, int seg_long)
+    int* __restrict__ long_list, int seg_long, int* __restrict__ slot_of, int* __restrict__ id_of_slot,
+    long long* __restrict__ cnt_of_slot)
 {
     __shared__ int s_src[kSegMaxRows];    // dH row of each sorted row, -1 = padding (not read)
     __shared__ int s_dst[kSegMaxRows];    // 0 = keep adding; else destination code + 4 (see below)
@@ -593,6 +594,10 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(
     const int t = blockIdx.x;
     const int r0 = t * kSegRows;
     const int r1 = r0 + kSegRows < n ? r0 + kSegRows : n;
+    // slot_of given: the buffer rows in seg_slot were worked out by the dedup and are committed
+    // here, each item by the thread that meets the first row of its segment (one tile holds it)
+    const bool commit = slot_of != nullptr && blockIdx.y == 0;
+    if (commit && t == 0 && threadIdx.x == 0) scal[kSUTotal] = scal[kSUNext];
 
     // first and one-past-last sorted row this tile sums
     int a, b;
@@ -623,6 +628,19 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(
         s_src[i] = is_pad ? -1 : perm[r];
         s_dst[i] = code;
         s_pad[i] = is_pad ? 1 : 0;
+        if (commit && r == o0) {
+            const int row = seg_slot[sg];
+            if (row < 0) {
+                atomicOr(&scal[kSErr], kErrBitCapacity);      // dropped: the buffer is full
+            } else if (row & kSlotNew) {
+                const int id = uniq_ws[sg], slot = row & (kSlotNew - 1);
+                slot_of[id] = slot;
+                id_of_slot[slot] = id;
+                cnt_of_slot[slot] = o1 - o0;
+            } else {
+                cnt_of_slot[row] += o1 - o0;
+            }
+        }
     }
     __syncthreads();
 
@@ -711,7 +729,8 @@ __global__ __launch_bounds__(kBlock) void k_seg_combine(
     }
 }
 
-void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s)
+// commit: seg_slot holds rows worked out by the dedup; the reduction writes them into the slot table
+void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s, bool commit)
 {
     if (m == 0) return;
     const int n = (int)m;
@@ -727,7 +746,8 @@ void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s)
                        reinterpret_cast<const float4*>(dH), c->perm, c->seg_of_row, c->offsets,
                        c->uniq_ws, c->seg_slot, n, cols4, c->cfg.pad_id,
                        reinterpret_cast<float4*>(c->G), reinterpret_cast<float4*>(c->seg_first),
-                       reinterpret_cast<float4*>(c->seg_last), c->scal, c->long_list, seg_long);
+                       reinterpret_cast<float4*>(c->seg_last), c->scal, c->long_list, seg_long,
+                       commit ? c->slot_of : (int*)nullptr, c->id_of_slot, c->cnt_of_slot);
     int fix_blocks = tiles / (seg_long / kSegRows) + 1;   // upper bound of long segments
     if (fix_blocks > 256) fix_blocks = 256;
     launch(c, KID_SEG_COMBINE, k_seg_combine, dim3(fix_blocks, (cols4 + kFixCols4 - 1) / kFixCols4),

@@ -1299,6 +1299,55 @@ def test_window_end_in_one_call_equals_weight_gradient_then_flush(case):
     np.testing.assert_array_equal(c["counts_total"], a["counts_total"])
 
 
+@pytest.mark.parametrize("m", [3000, 30000])
+def test_buffer_rows_are_assigned_afresh_when_the_window_changed_after_the_dedup(m):
+    """gram_unique works out the buffer rows of the batch's items from the slot table as it is;
+    if the table changes before gram_grad_accumulate (here: a saved state is merged in between),
+    the accumulate step must not use them.  Both dedup variants (one block, sorted tiles);
+    checked against the oracle's resumed window."""
+    import torch
+    from paper_2204_04179_amd import gram
+    from harness import to_dev
+    n, d_in, d = 5000, 32, 16
+    ids, X, W, dH = small_problem(77, m, n, d_in=d_in, d=d)
+    ids2, _, _, dH2 = small_problem(78, m, n, d_in=d_in, d=d)
+    rng = np.random.default_rng(5)
+    r_ids = np.sort(rng.choice(n, size=900, replace=False)).astype(np.int32)
+    r_cnt = rng.integers(1, 5, size=900).astype(np.int64)
+    r_G = rng.standard_normal((900, d)).astype(np.float32)
+    g = gram.Gram(gram.make_config(n, d_in, d, m, 2, 0, 0, gram.F32))
+    Xd, Wd = to_dev(X, torch), to_dev(W, torch)
+    cap_u = min(m, n)
+    uq = torch.empty(cap_u, dtype=torch.int32, device="cuda")
+    cn, inv = torch.empty_like(uq), torch.empty(m, dtype=torch.int32, device="cuda")
+    ud = torch.zeros(1, dtype=torch.int32, device="cuda")
+    H = torch.empty(m, d, device="cuda")
+    # step 0: dedup first, THEN the import, then accumulate
+    g.unique(torch.from_numpy(ids).cuda(), uq, inv, cn, ud)
+    g.encode_gather(Xd, Wd, uq, inv, ud, m, None, H)
+    g.window_import(torch.from_numpy(r_ids).cuda(), torch.from_numpy(r_cnt).cuda(), torch.from_numpy(r_G).cuda(), 900)
+    g.grad_accumulate(torch.from_numpy(dH).cuda(), m, 0)
+    # step 1: the ordinary order (rows committed as worked out)
+    g.unique(torch.from_numpy(ids2).cuda(), uq, inv, cn, ud)
+    g.encode_gather(Xd, Wd, uq, inv, ud, m, None, H)
+    g.grad_accumulate(torch.from_numpy(dH2).cuda(), m, 1)
+    dW = torch.empty(d_in, d, device="cuda")
+    ut = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    ct = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    Gt = torch.full((n, d), float("nan"), device="cuda")
+    nn = g.window_end(Xd, dW, ut, ct, Gt, None, want_host_u=True)
+    acc = orc.GramMulti(X, W, pad_id=0)
+    acc.resume(r_ids, r_cnt, r_G)
+    acc.step(ids, dH)
+    acc.step(ids2, dH2)
+    ref = acc.finish()
+    assert nn == ref["uniq"].size
+    np.testing.assert_array_equal(ut[:nn].cpu().numpy(), ref["uniq"])
+    np.testing.assert_array_equal(ct[:nn].cpu().numpy(), ref["counts"])
+    assert_close(Gt[:nn].cpu().numpy(), ref["G"], 1e-5, "G_total")
+    assert_close(dW.cpu().numpy(), ref["dW"], 1e-5, "dW")
+
+
 def test_error_paths():
     import torch
     from paper_2204_04179_amd import gram
