@@ -711,10 +711,21 @@ __global__ __launch_bounds__(kBlock) void k_seg_combine(
         const int parts = 1 + (seg_end - 1) / kSegRows - t;
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         if (!is_pad && col < cols4) {
-            for (int i = rl; i < parts; i += kFixLanes) {
-                const float4* src = i == 0 ? seg_last + (int64_t)t * cols4
-                                           : seg_first + (int64_t)(t + i) * cols4;
-                acc = f4_add(acc, src[col]);
+            // the lane's partials are fetched eight at a time (the adds keep their order): one
+            // load per round trip would make the longest segment's chain the kernel's duration
+            constexpr int kAhead = 8;
+            for (int i0 = rl; i0 < parts; i0 += kFixLanes * kAhead) {
+                float4 v[kAhead];
+#pragma unroll
+                for (int k = 0; k < kAhead; ++k) {
+                    const int i = i0 + k * kFixLanes;
+                    const float4* src = i == 0 ? seg_last + (int64_t)t * cols4
+                                               : seg_first + (int64_t)(t + i) * cols4;
+                    v[k] = i < parts ? src[col] : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int k = 0; k < kAhead; ++k)
+                    if (i0 + k * kFixLanes < parts) acc = f4_add(acc, v[k]);
             }
         }
         sm[rl][cl] = acc;
@@ -749,7 +760,7 @@ void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s, bool comm
                        reinterpret_cast<float4*>(c->seg_last), c->scal, c->long_list, seg_long,
                        commit ? c->slot_of : (int*)nullptr, c->id_of_slot, c->cnt_of_slot);
     int fix_blocks = tiles / (seg_long / kSegRows) + 1;   // upper bound of long segments
-    if (fix_blocks > 256) fix_blocks = 256;
+    if (fix_blocks > 1024) fix_blocks = 1024;        // a block per long segment for all but extreme batches
     launch(c, KID_SEG_COMBINE, k_seg_combine, dim3(fix_blocks, (cols4 + kFixCols4 - 1) / kFixCols4),
                        dim3(kBlock), s, c->seg_of_row, c->offsets, c->uniq_ws, c->seg_slot, n,
                        cols4, c->cfg.pad_id, reinterpret_cast<float4*>(c->G),
