@@ -94,7 +94,9 @@ def test_stress_workload_against_oracle():
         f"{'FULL compare of E (step 0) and dW' if full else 'SAMPLED compare of E and dW (fewer than 8 cores)'}")
     rng = np.random.default_rng(7)
     batches = [(wl.ids(w, k).reshape(-1), wl.upstream_grad(w, k)) for k in range(w.K)]
-    out = run_window(X, W, batches, vocab_n=w.N, k_steps=w.K, keep_H=False, keep_E=False)
+    # the window ends as in the benchmark: weight gradient and export in one call
+    out = run_window(X, W, batches, vocab_n=w.N, k_steps=w.K, keep_H=False, keep_E=False, window_end=True)
+    assert out["G_tail_untouched"]
     say("   GPU window done")
     acc = orc.GramMulti(X, W, pad_id=0)
     for k, (ids, dH) in enumerate(batches):
