@@ -613,8 +613,10 @@ int gram_window_end(gram_ctx* ctx, const void* X, float* dW, int32_t* uniq_total
         return flush_any(c, uniq_total, counts_total, nullptr, G_total, u_total_dev, u_total_host, s,
                          "gram_window_end");
     }
-    const int* ranks = flush_meta_and_ranks(c, uniq_total, counts_total, u_total_dev, s);
-    encoder_wgrad(c, X, dW, s, 0, c->cap_total, false, nullptr, G_total, ranks);
+    bool meta_left = false;
+    const int* ranks = flush_meta_and_ranks(c, uniq_total, counts_total, u_total_dev, s, &meta_left);
+    const WindowMeta meta = {uniq_total, counts_total, u_total_dev};
+    encoder_wgrad(c, X, dW, s, 0, c->cap_total, false, nullptr, G_total, ranks, meta_left ? &meta : nullptr);
     c->have_unique = false;     // the sort buffers were reused
     c->slot_epoch += 1;
     c->steps_done = 0;

@@ -830,6 +830,15 @@ constexpr int kWgradWaves = 8;
 struct WgradExport {
     float* G_total;            // [rows held, d]
     const int* rank_of_slot;   // [rows held] or NULL
+    // one-step windows: the last meta_blocks blocks of the grid export IDs and counts and clear the
+    // slot map (what k_flush_meta does), so the end of such a window is two launches
+    int meta_blocks;
+    const long long* cnt_of_slot;
+    int* slot_of;
+    int* uniq_total;           // nullable
+    int* counts_total;         // nullable
+    int* u_total_dev;          // nullable
+    int* scal;
 };
 template <int NW, bool WIDE = false, bool EXPORT = false>
 __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
@@ -838,6 +847,17 @@ __global__ __launch_bounds__(NW * 64) void k_wgrad_tn_bf16(
     int pad_id, int splits, float* __restrict__ partial, int row_begin, int row_end, WgradExport ex)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    if (EXPORT && ex.meta_blocks > 0 && blockIdx.x >= gridDim.x - ex.meta_blocks) {
+        const int n_ = *rows_dev;
+        const int mb = blockIdx.x - (gridDim.x - ex.meta_blocks);
+        for (int r = mb * (NW * 64) + threadIdx.x; r < n_; r += ex.meta_blocks * (NW * 64))
+            flush_meta_row(r, id_of_slot, nullptr, ex.cnt_of_slot, ex.slot_of, ex.uniq_total, ex.counts_total, nullptr);
+        if (mb == 0 && threadIdx.x == 0) {
+            if (ex.u_total_dev) *ex.u_total_dev = n_;
+            ex.scal[kSFlushN] = n_;
+        }
+        return;
+    }
     const int tiles_c = (d + 255) / 256, tiles = ((d_in + 255) / 256) * tiles_c;
     const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
     const int z = xcd + 8 * (q / tiles);
@@ -1130,7 +1150,8 @@ int wgrad_splits_dims(int d_in, int d, bool bf16)
 }
 
 bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t first_row, int64_t n_rows,
-                   bool accumulate, const WgradRows* other, float* export_G, const int* rank_of_slot)
+                   bool accumulate, const WgradRows* other, float* export_G, const int* rank_of_slot,
+                   const WindowMeta* meta)
 {
     bool exported = false;
     const int d_in = other && other->d_in ? other->d_in : c->cfg.d_in;
@@ -1157,12 +1178,24 @@ bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t firs
         if (want < S) S = (int)want;
         const int64_t x_bytes = x_rows * d_in * 2, g_bytes = cap * d * 4;
         const int tiles = ((d_in + 255) / 256) * ((d + 255) / 256);
-        const WgradExport no_export = {nullptr, nullptr};
+        const WgradExport no_export = {nullptr, nullptr, 0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
         if (x_bytes < kBufferWindow && g_bytes < kBufferWindow && export_G && !other) {
             constexpr auto kern = k_wgrad_tn_bf16<kWgradWaves, false, true>;
             ensure_dynamic_lds<kern>((int)WSMEM);
-            const WgradExport ex = {export_G, rank_of_slot};
-            launch_smem(c, KID_WGRAD_BF16, kern, dim3((unsigned)(tiles * S)), dim3(kWgradWaves * 64), WSMEM, s,
+            WgradExport ex = no_export;
+            ex.G_total = export_G;
+            ex.rank_of_slot = rank_of_slot;
+            if (meta) {
+                int64_t mb = (rows_bound + kWgradWaves * 64 - 1) / (kWgradWaves * 64);
+                ex.meta_blocks = (int)(mb < 1 ? 1 : (mb > 64 ? 64 : mb));
+                ex.cnt_of_slot = c->cnt_of_slot;
+                ex.slot_of = c->slot_of;
+                ex.uniq_total = meta->uniq_total;
+                ex.counts_total = meta->counts_total;
+                ex.u_total_dev = meta->u_total_dev;
+                ex.scal = c->scal;
+            }
+            launch_smem(c, KID_WGRAD_BF16, kern, dim3((unsigned)(tiles * S + ex.meta_blocks)), dim3(kWgradWaves * 64), WSMEM, s,
                         static_cast<const uint16_t*>(X), (uint32_t)x_bytes, ids, rows, (uint32_t)g_bytes,
                         rows_dev, d_in, d, pad_id, S, c->wg_partial, row_begin, row_end, ex);
             exported = true;

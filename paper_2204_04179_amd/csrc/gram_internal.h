@@ -31,6 +31,20 @@ constexpr int kFixLanes = kBlock / kFixCols4;
 // take the kernels' wide-address variants.
 constexpr int64_t kBufferWindow = ((int64_t)1 << 32) - 16;
 
+// Export of one item at the end of a window: ID and count of the r-th item in ascending-ID order
+// (sorted_slots NULL: buffer row r), its entry of the slot map cleared.
+__device__ __forceinline__ void flush_meta_row(int r, const int* sorted_ids, const int* sorted_slots,
+                                               const long long* cnt_of_slot, int* slot_of, int* uniq_total,
+                                               int* counts_total, long long* counts64_total)
+{
+    const int id = sorted_ids[r];
+    const long long cnt = cnt_of_slot[sorted_slots ? sorted_slots[r] : r];
+    if (uniq_total) uniq_total[r] = id;
+    if (counts_total) counts_total[r] = cnt > 0x7fffffffLL ? 0x7fffffff : (int)cnt;     // the 32-bit export saturates
+    if (counts64_total) counts64_total[r] = cnt;
+    slot_of[id] = -1;
+}
+
 // two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
@@ -210,7 +224,8 @@ void assign_slots(Ctx* c, hipStream_t s);
 void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s, bool commit = false);
 void flush_export(Ctx* c, int* uniq_total, int* counts_total, long long* counts64_total, float* G_total,
                   int* u_total_dev, hipStream_t s);
-const int* flush_meta_and_ranks(Ctx* c, int* uniq_total, int* counts_total, int* u_total_dev, hipStream_t s);
+const int* flush_meta_and_ranks(Ctx* c, int* uniq_total, int* counts_total, int* u_total_dev, hipStream_t s,
+                                bool* left_to_caller);
 void import_slots(Ctx* c, const int* ids, const long long* counts, const float* rows, int64_t n,
                   hipStream_t s);
 void flush_dense(Ctx* c, int* uniq_total, int* counts_total, long long* counts64_total, float* G_total,
@@ -248,9 +263,15 @@ struct WgradRows {
 // export_G (buffer rows, bf16, whole window only): the kernel also writes buffer row s to
 // export_G[rank_of_slot[s], :] (rank_of_slot NULL: to row s).  Returns false, and does not export,
 // when that variant does not apply (float32 features, an operand beyond 4 GiB).
+// meta (with export_G, one-step windows): the launch also exports IDs and counts and clears the slot map
+struct WindowMeta {
+    int* uniq_total;
+    int* counts_total;
+    int* u_total_dev;
+};
 bool encoder_wgrad(Ctx* c, const void* X, float* dW, hipStream_t s, int64_t first_row, int64_t n_rows,
                    bool accumulate, const WgradRows* other = nullptr, float* export_G = nullptr,
-                   const int* rank_of_slot = nullptr);
+                   const int* rank_of_slot = nullptr, const WindowMeta* meta = nullptr);
 // ---- gram_mlp.hip --------------------------------------------------------
 // Forward of the two-layer encoder for the unique items of the batch; A1 (nullable) receives the
 // bf16 hidden activations.  Return value as encode_forward.

@@ -775,18 +775,6 @@ void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s, bool comm
 // The count of buffer rows (scal[kSUTotal]) is left as it is: every block reads it here, and
 // the first step of the next window starts from zero by itself.  `n_zero`: the window is empty.
 
-__device__ __forceinline__ void flush_meta_row(int r, const int* sorted_ids, const int* sorted_slots,
-                                               const long long* cnt_of_slot, int* slot_of, int* uniq_total,
-                                               int* counts_total, long long* counts64_total)
-{
-    const int id = sorted_ids[r];
-    const long long cnt = cnt_of_slot[sorted_slots ? sorted_slots[r] : r];
-    if (uniq_total) uniq_total[r] = id;
-    if (counts_total) counts_total[r] = cnt > 0x7fffffffLL ? 0x7fffffff : (int)cnt;     // the 32-bit export saturates
-    if (counts64_total) counts64_total[r] = cnt;
-    slot_of[id] = -1;
-}
-
 // rank_of_slot (nullable, needs sorted_slots): receives, for every buffer row, its place in
 // ascending-ID order, for a weight-gradient kernel that writes the rows out itself.
 __global__ __launch_bounds__(kBlock) void k_flush_meta(
@@ -879,12 +867,21 @@ void flush_export(Ctx* c, int* uniq_total, int* counts_total, long long* counts6
 // The export without the rows: IDs and counts in ascending-ID order, slot map cleared, and the
 // place of every buffer row in that order (returned; NULL: the rows are in that order already).
 // The caller's weight-gradient kernel then writes the rows themselves.  Needs a non-empty window.
-const int* flush_meta_and_ranks(Ctx* c, int* uniq_total, int* counts_total, int* u_total_dev, hipStream_t s)
+// *left_to_caller: nothing was launched (a one-step window); the caller's kernel does this part too.
+const int* flush_meta_and_ranks(Ctx* c, int* uniq_total, int* counts_total, int* u_total_dev, hipStream_t s,
+                                bool* left_to_caller)
 {
     const int* sorted_ids = c->id_of_slot;
     const int* sorted_slots = nullptr;
     int* ranks = nullptr;
-    if (c->steps_done > 1 || c->window_imported) {
+    *left_to_caller = false;
+    if (c->steps_done <= 1 && !c->window_imported) {
+        // one step: the rows are in order already and nothing has to be ranked; a few extra blocks
+        // of the caller's weight-gradient launch export the IDs and counts
+        *left_to_caller = true;
+        return nullptr;
+    }
+    {
         const int r = radix_sort_pairs(c, c->id_of_slot, nullptr, 0, c->scal + kSUTotal, c->cap_total,
                                        false, 0, s);
         sorted_ids = c->keys[r];
