@@ -1127,10 +1127,12 @@ def test_positions_output_in_bf16(case):
     assert out["G_total"].tobytes() == base["G_total"].tobytes() and out["dW"].tobytes() == base["dW"].tobytes()
 
 
-def test_window_captured_in_a_hip_graph_replays_like_eager():
+@pytest.mark.parametrize("end", ["two_calls", "one_call"])
+def test_window_captured_in_a_hip_graph_replays_like_eager(end):
     """The calls only enqueue kernels (no memset nodes, no host read-backs unless asked for), so a
     whole window can be captured once and replayed; every replay, with eager work and
-    synchronisations in between, must reproduce the eager window bit for bit."""
+    synchronisations in between, must reproduce the eager window bit for bit.  The window ends with
+    gram_encoder_wgrad + gram_flush, or with gram_window_end."""
     import torch
     from paper_2204_04179_amd import gram
     from harness import to_dev
@@ -1152,15 +1154,18 @@ def test_window_captured_in_a_hip_graph_replays_like_eager():
             g.unique(ids[k], uniq, inverse, counts, u_dev)
             g.encode_gather(X, W, uniq, inverse, u_dev, m, None, H)
             g.grad_accumulate(dH[k], m, k)
-        g.encoder_wgrad(X, dW)
-        g.flush(ut, ct, Gt, n_t)
+        if end == "one_call":
+            g.window_end(X, dW, ut, ct, Gt, n_t)
+        else:
+            g.encoder_wgrad(X, dW)
+            g.flush(ut, ct, Gt, n_t)
 
     def snapshot():
         torch.cuda.synchronize()
         u = int(n_t.item())
         return [t.clone() if t is not ut and t is not ct and t is not Gt else t[:u].clone() for t in outs]
 
-    say("graph capture of a window")
+    say(f"graph capture of a window ({end})")
     window()
     eager = snapshot()
     side = torch.cuda.Stream()
@@ -1350,6 +1355,52 @@ def test_buffer_rows_are_assigned_afresh_when_the_window_changed_after_the_dedup
     np.testing.assert_array_equal(ct[:nn].cpu().numpy(), ref["counts"])
     assert_close(Gt[:nn].cpu().numpy(), ref["G"], 1e-5, "G_total")
     assert_close(dW.cpu().numpy(), ref["dW"], 1e-5, "dW")
+
+
+@pytest.mark.parametrize("K", [1, 2])
+def test_window_end_with_a_full_buffer_drops_the_same_rows_as_the_two_calls(K):
+    """A buffer smaller than the window's items: the rows beyond its capacity are dropped (never
+    written out of bounds) and the error is latched; gram_window_end exports exactly what
+    gram_encoder_wgrad + gram_flush export, and an empty window is refused by both."""
+    import torch
+    from paper_2204_04179_amd import gram
+    from harness import to_dev
+    n, d_in, d, m, cap = 4000, 64, 32, 3000, 700
+    probs = [small_problem(40 + k, m, n, d_in=d_in, d=d, bf16=True) for k in range(K)]
+    X, W = to_dev(probs[0][1], torch), to_dev(probs[0][2], torch)
+    res = []
+    for one_call in (False, True):
+        g = gram.Gram(gram.make_config(n, d_in, d, m, K, 0, cap, gram.BF16))
+        dW = torch.full((d_in, d), float("nan"), device="cuda")
+        with pytest.raises(gram.GramError) as e:
+            (g.window_end if one_call else g.encoder_wgrad)(X, dW)
+        assert e.value.status == gram.ERR_SEQUENCE
+        uq = torch.empty(min(m, n), dtype=torch.int32, device="cuda")
+        cn, inv = torch.empty_like(uq), torch.empty(m, dtype=torch.int32, device="cuda")
+        ud = torch.zeros(1, dtype=torch.int32, device="cuda")
+        H = torch.empty(m, d, device="cuda")
+        for k, p in enumerate(probs):
+            g.unique(torch.from_numpy(p[0]).cuda(), uq, inv, cn, ud)
+            g.encode_gather(X, W, uq, inv, ud, m, None, H)
+            g.grad_accumulate(torch.from_numpy(p[3]).cuda(), m, k)
+        ut = torch.full((cap + 8,), -7, dtype=torch.int32, device="cuda")
+        ct = torch.full((cap + 8,), -7, dtype=torch.int32, device="cuda")
+        Gt = torch.full((cap + 8, d), float("nan"), device="cuda")
+        nt = torch.zeros(1, dtype=torch.int32, device="cuda")
+        if one_call:
+            g.window_end(X, dW, ut, ct, Gt, nt)
+        else:
+            g.encoder_wgrad(X, dW)
+            g.flush(ut, ct, Gt, nt)
+        torch.cuda.synchronize()
+        with pytest.raises(gram.GramError) as e:
+            g.check()
+        assert e.value.status == gram.ERR_CAPACITY
+        assert int(nt.item()) == cap
+        assert bool((ut[cap:] == -7).all().item()) and bool(torch.isnan(Gt[cap:]).all().item())
+        res.append([t.cpu().numpy().tobytes() for t in (ut[:cap], ct[:cap], Gt[:cap], dW)])
+        g.close()
+    assert res[0] == res[1]
 
 
 def test_error_paths():
