@@ -366,6 +366,10 @@ void pseudo_miss(Ctx* c, float* R, const float* Ht, int64_t n, double* loss_dev,
 // persistent buffer; new items of one batch take consecutive rows in ascending
 // ID order (a scan over "is new" flags), so the row layout, and with it the
 // summation order of the weight gradient, is a function of the data alone.
+// The dedup kernels normally work these rows out themselves (seg_slot) and the segment
+// reduction commits them; the kernels below do the same job in launches of their own when the
+// slot table has changed since the dedup looked at it, for an empty batch, and for the
+// dense layout.
 
 __global__ __launch_bounds__(kBlock) void k_slot_count(const int* __restrict__ uniq_ws,
                                                        const int* __restrict__ slot_of,
