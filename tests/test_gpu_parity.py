@@ -299,6 +299,39 @@ def test_segment_lengths_around_tile_and_long_thresholds():
         check_single(ids_, X, W, dH, n, TOL[wl.BF16 if bf16 else wl.F32], TOL_SUM[wl.BF16 if bf16 else wl.F32], pad_id=-1)
 
 
+def test_one_item_owning_hundreds_of_scan_tiles_over_a_two_step_window():
+    """An item with 300,000 of 640,000 positions: its segment covers about 293 of the 1024-row tiles
+    of the head scan, more than the 256 tiles the count of a segment looks ahead at a time; an
+    item of 70,000 and the padding item with 90,000 positions sit beside it, the rest are items
+    seen once or a few times.  Two steps with different mixes, so that rows worked out by the
+    dedup are committed on top of existing ones; everything against the oracle."""
+    n, d_in, d, m = 200000, 8, 4, 640000
+    batches = []
+    for k, (big, second, pads) in enumerate([(300000, 70000, 90000), (5, 260000, 1000)]):
+        rng = np.random.default_rng(60 + k)
+        rest = m - big - second - pads
+        ids = np.concatenate([np.full(big, 777, np.int32), np.full(second, 150001, np.int32),
+                              np.zeros(pads, np.int32), rng.integers(1, n, size=rest).astype(np.int32)])
+        ids = ids[rng.permutation(m)]
+        batches.append((ids, rng.standard_normal((m, d)).astype(np.float32)))
+    rng = np.random.default_rng(59)
+    X = rng.standard_normal((n, d_in)).astype(np.float32)
+    W = (rng.standard_normal((d_in, d)) / np.sqrt(d_in)).astype(np.float32)
+    say(f"one item over hundreds of scan tiles: m={m}")
+    out = run_window(X, W, batches, vocab_n=n, k_steps=2, keep_H=True, keep_E=False, window_end=True)
+    acc = orc.GramMulti(X, W, pad_id=0)
+    for k, (ids, dH) in enumerate(batches):
+        ref = acc.step(ids, dH)
+        check_step_exact(out["steps"][k], ref)
+        assert_close(out["steps"][k]["H"], ref["H"], 1e-5, f"H step {k}")
+    ref = acc.finish()
+    np.testing.assert_array_equal(out["uniq_total"], ref["uniq"])
+    np.testing.assert_array_equal(out["counts_total"], ref["counts"])
+    # sums of up to 300,000 float32 terms in tile order against float64
+    assert_close(out["G_total"], ref["G"], 1e-4, "G_total")
+    assert_close(out["dW"], ref["dW"], 1e-4, "dW")
+
+
 @pytest.mark.parametrize("d,variant", [(256, "E requested"), (256, "E = NULL"), (320, "E = NULL"),
                                        (256, "foreign uniq/inverse"), (64, "E = NULL, two padding positions")])
 def test_fused_forward_stores_representations_to_positions(d, variant):
