@@ -286,7 +286,13 @@ struct ScatterArgs {
 };
 
 // HB (with SCATTER): H holds bf16, values are rounded to nearest even as they are stored.
-template <bool GATHER, int NW, bool SCATTER, int EPI = kEpiPlain, bool HB = false, bool WIDE = false>
+// BDIRECT: B is not the K-contiguous [n, k] matrix but its transpose as the caller holds it,
+// W [k, n] (n a multiple of 8, ldb = n): a slab of it is parked as 32 rows of k with 256 values
+// of n each (512-byte rows, 16-byte chunk c of row r at position c ^ ((r & 3) << 2)), and the
+// MFMA fragments (8 consecutive k for one n) come from the transposing LDS read, exactly as
+// in k_wgrad_tn_bf16 below.  Saves the transposed copy of the weights and its launch.
+template <bool GATHER, int NW, bool SCATTER, int EPI = kEpiPlain, bool HB = false, bool WIDE = false,
+          bool BDIRECT = false>
 __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
     const uint16_t* __restrict__ A, int64_t lda, uint32_t a_bytes, const int* __restrict__ row_ids,
     const int* __restrict__ m_dev, const uint16_t* __restrict__ B, int64_t ldb, uint32_t b_bytes, int n,
@@ -332,9 +338,21 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
         }
         oa[t] = (uint32_t)((rowA * lda + (int64_t)sl_begin * TK + lchunk * 8) * 2);
         if (WIDE) pa[t] = reinterpret_cast<const unsigned char*>(A) + (rowA * lda + (int64_t)sl_begin * TK + lchunk * 8) * 2;
-        const int nn = n0 + r;
-        ob[t] = (uint32_t)(((int64_t)(nn < n ? nn : n - 1) * ldb + (int64_t)sl_begin * TK + lchunk * 8) * 2);
+        if (BDIRECT) {
+            // chunk cb of the slab: row cb / 32 of k, position cb % 32 of that row in LDS; columns past
+            // n are clamped to the last chunk (their products are never stored)
+            const int cb = (wave * GA + t) * 64 + lane;
+            const int krow = cb >> 5;
+            int ncol = n0 + (((cb & 31) ^ ((krow & 3) << 2)) << 3);
+            if (ncol > n - 8) ncol = n - 8;
+            ob[t] = (uint32_t)(((int64_t)krow * ldb + ncol) * 2);
+        } else {
+            const int nn = n0 + r;
+            ob[t] = (uint32_t)(((int64_t)(nn < n ? nn : n - 1) * ldb + (int64_t)sl_begin * TK + lchunk * 8) * 2);
+        }
     }
+    static_assert(!BDIRECT || NW == 8, "the untransposed second operand is wired for 8 waves");
+    const uint32_t b_slab_bytes = BDIRECT ? (uint32_t)(TK * ldb * 2) : (uint32_t)(TK * 2);
     unsigned char* park = smem + (wave * GA) * 1024 + lane * 16;
 
     // (fused gather) position ranges and position lists of the rows this wave will store in the
@@ -373,13 +391,33 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
     const int c0 = ph0 * 16, c1 = (ph0 ^ 2) * 16;
     bf16x8 fa[2][4], fb[2][NT];
     v4i32 ra[2][GA], rb[2][GA];
-#define GRAM_FRAGS(FS, STAGE, COFF)                                                                 \
+    // (BDIRECT) addresses of the transposing reads: group g = lane / 16, j = lane % 16 (see the header
+    // comment of k_wgrad_tn_bf16); the wave's columns start at chunk NT 4 wn of the 512-byte row
+    int tr_offB[BDIRECT ? NT : 1];
+    if (BDIRECT) {
+        const int j16 = lane & 15, grp = lane >> 4;
+        const int f_row = (grp >> 1) * 8 + (j16 >> 2);               // + 16 ks + 4 h
+        const int f_x = ((j16 >> 2) & 3) << 2;
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+            tr_offB[i] = TM * TROWB + f_row * 512 +
+                         (((wn * (NT * 4) + i * 4 + (grp & 1) * 2 + ((j16 & 3) >> 1)) ^ f_x) * 16) + (j16 & 1) * 8;
+    }
+#define GRAM_FRAGS(FS, STAGE, COFF, KS)                                                             \
     {                                                                                               \
         const unsigned char* sb_ = smem + (STAGE) * TSTAGEB;                                        \
         _Pragma("unroll") for (int i = 0; i < 4; ++i)                                               \
             fa[FS][i] = *reinterpret_cast<const bf16x8*>(sb_ + offA + i * 32 * TROWB + (COFF));     \
-        _Pragma("unroll") for (int i = 0; i < NT; ++i)                                              \
-            fb[FS][i] = *reinterpret_cast<const bf16x8*>(sb_ + offB + i * 32 * TROWB + (COFF));     \
+        _Pragma("unroll") for (int i = 0; i < NT; ++i) {                                            \
+            if (BDIRECT) {                                                                          \
+                const unsigned char* t_ = sb_ + (KS) * 16 * 512 + tr_offB[i];                       \
+                const sv4i16 b0_ = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_sv4i16*)t_);        \
+                const sv4i16 b1_ = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_sv4i16*)(t_ + 4 * 512)); \
+                fb[FS][i] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(b0_, b1_, 0, 1, 2, 3, 4, 5, 6, 7)); \
+            } else {                                                                                \
+                fb[FS][i] = *reinterpret_cast<const bf16x8*>(sb_ + offB + i * 32 * TROWB + (COFF)); \
+            }                                                                                       \
+        }                                                                                           \
     }
 #define GRAM_MMA(FS)                                                                                \
     _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                   \
@@ -389,10 +427,11 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
 #define GRAM_LOAD(SET, SLAB)                                                                        \
     {                                                                                               \
         const uint32_t k_ = (uint32_t)(((SLAB) < last ? (SLAB) : last) * (TK * 2));                 \
+        const uint32_t kb_ = (uint32_t)((SLAB) < last ? (SLAB) : last) * b_slab_bytes;              \
         _Pragma("unroll") for (int t = 0; t < GA; ++t) {                                            \
             if (WIDE) ra[SET][t] = *reinterpret_cast<const v4i32*>(pa[t] + k_);                      \
             else ra[SET][t] = __builtin_amdgcn_raw_buffer_load_b128(rsA, oa[t] + k_, 0, 0);         \
-            rb[SET][t] = __builtin_amdgcn_raw_buffer_load_b128(rsB, ob[t] + k_, 0, 0);              \
+            rb[SET][t] = __builtin_amdgcn_raw_buffer_load_b128(rsB, ob[t] + kb_, 0, 0);             \
         }                                                                                           \
     }
 #define GRAM_PARK(SET, STAGE)                                                                       \
@@ -429,13 +468,13 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
     }
 #define GRAM_ITER(SL, P)                                                                            \
     {                                                                                               \
-        GRAM_FRAGS(1, (SL) & 1, c1)                                                                 \
+        GRAM_FRAGS(1, (SL) & 1, c1, 1)                                                              \
         GRAM_MMA(0)                                                                                 \
         GRAM_PARK(P, ((SL) + 1) & 1)                                                                \
         GRAM_SCHED_FIRST                                                                            \
         __syncthreads();                                                                            \
         GRAM_LOAD(P, (SL) + 3)                                                                      \
-        GRAM_FRAGS(0, ((SL) + 1) & 1, c0)                                                           \
+        GRAM_FRAGS(0, ((SL) + 1) & 1, c0, 0)                                                        \
         GRAM_MMA(1)                                                                                 \
         GRAM_SCHED_SECOND                                                                           \
     }
@@ -447,14 +486,14 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
         GRAM_PARK(0, 0)
         GRAM_LOAD(0, 2)
         __syncthreads();
-        GRAM_FRAGS(0, 0, c0)
+        GRAM_FRAGS(0, 0, c0, 0)
         int sl = 0;
         for (; sl + 1 < last; sl += 2) {
             GRAM_ITER(sl, 1)          // set 1 holds slab sl+1, set 0 holds slab sl+2
             GRAM_ITER(sl + 1, 0)      // set 0 holds slab sl+2, set 1 holds slab sl+3
         }
         if (sl < last) GRAM_ITER(sl, 1)
-        GRAM_FRAGS(1, last & 1, c1)
+        GRAM_FRAGS(1, last & 1, c1, 1)
         GRAM_MMA(0)
         GRAM_MMA(1)
     }
@@ -581,13 +620,13 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_nt_bf16(
 
 constexpr int kGemmWaves = 8;
 
-template <bool SCATTER, int EPI, bool HB, bool WIDE>
+template <bool SCATTER, int EPI, bool HB, bool WIDE, bool BDIRECT = false>
 static void launch_gemm_variant(Ctx* c, int kid, unsigned blocks, hipStream_t s, const uint16_t* A, int64_t lda,
                                 int64_t a_bytes, const int* row_ids, const int* m_dev, const uint16_t* B,
                                 int64_t ldb, int64_t b_bytes, int n, int k, int pad_id, int n_tiles, float* C,
                                 int64_t ldc, const ScatterArgs& sc, const void* aux)
 {
-    constexpr auto kern = k_gemm_nt_bf16<true, kGemmWaves, SCATTER, EPI, HB, WIDE>;
+    constexpr auto kern = k_gemm_nt_bf16<true, kGemmWaves, SCATTER, EPI, HB, WIDE, BDIRECT>;
     constexpr size_t smem = SCATTER ? RSMEM_SC : RSMEM;
     ensure_dynamic_lds<kern>((int)smem);
     // the descriptor of a WIDE operand is not used; any size that fits its field will do
@@ -600,10 +639,12 @@ static void launch_gemm_variant(Ctx* c, int kid, unsigned blocks, hipStream_t s,
 // a_rows / b_rows: rows of the matrices A and B as allocated (A: all rows that row_ids may
 // name).  A may lie beyond 4 GiB for the plain epilogue (with or without the fused gather);
 // the other epilogue modes and B need buffer descriptors (callers check).
+// b_direct: B is the [k, n] matrix as the caller holds it (ldb = n, b_rows = k, n a multiple of 8)
+// instead of its K-contiguous transpose; available for A below 4 GiB and every mode but "gate".
 static void launch_gemm_nt(Ctx* c, const uint16_t* A, int64_t lda, int64_t a_rows, const int* row_ids,
                            const int* m_dev, int64_t m_bound, const uint16_t* B, int64_t ldb, int64_t b_rows,
                            int n, int k, float* C, int64_t ldc, hipStream_t s, const ScatterArgs* scatter,
-                           int pad_id, int epi, const void* aux)
+                           int pad_id, int epi, const void* aux, bool b_direct = false)
 {
     const int n_tiles = (n + TN - 1) / TN;
     const unsigned blocks = (unsigned)((((m_bound + TM - 1) / TM + 7) / 8 * 8) * n_tiles);
@@ -614,7 +655,16 @@ static void launch_gemm_nt(Ctx* c, const uint16_t* A, int64_t lda, int64_t a_row
 #define GRAM_GO(SC, EPI, HB, WIDE, ARGS)                                                            \
     launch_gemm_variant<SC, EPI, HB, WIDE>(c, kid, blocks, s, A, lda, a_bytes, row_ids, m_dev, B, ldb, b_bytes, n, \
                                            k, pad_id, n_tiles, C, ldc, ARGS, aux)
-    if (epi == kEpiReluBf16) GRAM_GO(false, kEpiReluBf16, false, false, none);
+#define GRAM_GO_DIRECT(SC, EPI, HB, ARGS)                                                           \
+    launch_gemm_variant<SC, EPI, HB, false, true>(c, kid, blocks, s, A, lda, a_bytes, row_ids, m_dev, B, ldb, b_bytes, n, \
+                                                  k, pad_id, n_tiles, C, ldc, ARGS, aux)
+    if (b_direct) {
+        if (epi == kEpiReluBf16) GRAM_GO_DIRECT(false, kEpiReluBf16, false, none);
+        else if (epi == kEpiMinus) GRAM_GO_DIRECT(false, kEpiMinus, false, none);
+        else if (scatter && scatter->h_bf16) GRAM_GO_DIRECT(true, kEpiPlain, true, *scatter);
+        else if (scatter) GRAM_GO_DIRECT(true, kEpiPlain, false, *scatter);
+        else GRAM_GO_DIRECT(false, kEpiPlain, false, none);
+    } else if (epi == kEpiReluBf16) GRAM_GO(false, kEpiReluBf16, false, false, none);
     else if (epi == kEpiMinus) GRAM_GO(false, kEpiMinus, false, false, none);
     else if (epi == kEpiGate) GRAM_GO(false, kEpiGate, false, false, none);
     else if (scatter && scatter->h_bf16) {
@@ -628,6 +678,7 @@ static void launch_gemm_nt(Ctx* c, const uint16_t* A, int64_t lda, int64_t a_row
         else GRAM_GO(false, kEpiPlain, false, false, none);
     }
 #undef GRAM_GO
+#undef GRAM_GO_DIRECT
 }
 
 // ---- 64x64 bf16 transpose through LDS (16-byte global accesses both ways) ----------
@@ -713,6 +764,21 @@ static bool takes_big_kernel(const Ctx* c, int64_t rows_max, int n_out, int k, i
     return tile_bound >= c->num_cus && k % TK == 0;
 }
 
+// The 256x256 kernel reads the second operand untransposed for these shapes and modes.
+static bool big_kernel_reads_plain_b(int64_t a_rows, int k, int n_out, int epi)
+{
+    return n_out % 8 == 0 && n_out >= 8 && epi != kEpiGate && a_rows * k * 2 < kBufferWindow &&
+           (int64_t)k * n_out * 2 < kBufferWindow;
+}
+
+// Whether gemm_rows_bf16 will read B_plain (the [k, n_out] matrix as the caller holds it) instead of
+// the transposed copy Bt for this problem: callers skip the transpose launch then.
+bool gemm_reads_plain_b(const Ctx* c, int64_t rows_max, int64_t a_rows, int k, int n_out, int epi)
+{
+    if (takes_big_kernel(c, rows_max, n_out, k, a_rows, epi)) return big_kernel_reads_plain_b(a_rows, k, n_out, epi);
+    return n_out % 8 == 0 && (epi == kEpiPlain || epi == kEpiMinus);
+}
+
 bool gemm_rows_bf16(Ctx* c, const void* A, int64_t a_rows, int k, const int* row_ids, int pad_id,
                     const int* n_dev, int64_t rows_max, const void* Bt, int n_out, float* C, hipStream_t s,
                     void* H_scatter, bool caller_wants_C, int epi, const void* aux, const void* B_plain)
@@ -724,9 +790,14 @@ bool gemm_rows_bf16(Ctx* c, const void* A, int64_t a_rows, int k, const int* row
         const bool fuse = H_scatter && epi == kEpiPlain;
         const ScatterArgs sc = {c->offsets, c->perm, H_scatter, (int64_t)n_out, caller_wants_C ? 1 : 0,
                                c->cfg.h_dtype == GRAM_BF16 ? 1 : 0};
-        launch_gemm_nt(c, static_cast<const uint16_t*>(A), k, a_rows, row_ids, n_dev, rows_max,
-                       static_cast<const uint16_t*>(Bt), k, n_out, n_out, k, C, n_out, s, fuse ? &sc : nullptr,
-                       pad_id, epi, aux);
+        if (big_kernel_reads_plain_b(a_rows, k, n_out, epi) && B_plain)
+            launch_gemm_nt(c, static_cast<const uint16_t*>(A), k, a_rows, row_ids, n_dev, rows_max,
+                           static_cast<const uint16_t*>(B_plain), n_out, k, n_out, k, C, n_out, s,
+                           fuse ? &sc : nullptr, pad_id, epi, aux, true);
+        else
+            launch_gemm_nt(c, static_cast<const uint16_t*>(A), k, a_rows, row_ids, n_dev, rows_max,
+                           static_cast<const uint16_t*>(Bt), k, n_out, n_out, k, C, n_out, s, fuse ? &sc : nullptr,
+                           pad_id, epi, aux);
         return fuse;
     }
     const dim3 grid((n_out + BN - 1) / BN, (unsigned)((rows_max + BM - 1) / BM));
@@ -765,9 +836,8 @@ bool encode_forward(Ctx* c, const void* X, const void* W, const int* uniq, const
     if (rows_max <= 0) return false;
     const int d_in = c->cfg.d_in, d = c->cfg.d;
     if (c->cfg.xw_dtype == GRAM_BF16) {
-        // the small kernel can read W as it is (no transposed copy, one launch less)
-        const bool direct = !takes_big_kernel(c, rows_max, d, d_in, c->cfg.vocab_n, epi) && d % 8 == 0 &&
-                            (epi == kEpiPlain || epi == kEpiMinus);
+        // both kernels can read W as it is for most shapes (no transposed copy, one launch less)
+        const bool direct = gemm_reads_plain_b(c, rows_max, c->cfg.vocab_n, d_in, d, epi);
         if (!direct) transpose_weight(c, W, d_in, d, c->Wt, s);
         return gemm_rows_bf16(c, X, c->cfg.vocab_n, d_in, uniq, c->cfg.pad_id, u_dev, rows_max, c->Wt, d, E, s,
                               H_scatter, caller_wants_E, epi, aux, direct ? W : nullptr);

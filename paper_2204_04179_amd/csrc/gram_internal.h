@@ -291,9 +291,11 @@ void transpose_weight(Ctx* c, const void* W, int rows, int cols, void* Wt, hipSt
 // C[j,:] = epi(A[row_ids[j],:k] . Bt^T) for j < *n_dev (A bf16 [a_rows, k], Bt bf16 [n_out, k], C
 // float32 [., n_out], or bf16 for kEpiReluBf16); a row whose ID equals pad_id is zero.  kEpiMinus
 // subtracts the float32 matrix aux, kEpiGate keeps the value where the bf16 matrix aux is positive
-// (both [., n_out]).  B_plain, if given, is the untransposed second operand [k, n_out]: the small
-// kernel then reads it directly and Bt is not touched (the caller need not have filled it).
+// (both [., n_out]).  B_plain, if given, is the untransposed second operand [k, n_out]: where
+// gemm_reads_plain_b says so, the kernels read it directly and Bt is not touched (the caller need
+// not have filled it).
 // Same return value and fused-gather rule as encode_forward.
+bool gemm_reads_plain_b(const Ctx* c, int64_t rows_max, int64_t a_rows, int k, int n_out, int epi);
 bool gemm_rows_bf16(Ctx* c, const void* A, int64_t a_rows, int k, const int* row_ids, int pad_id,
                     const int* n_dev, int64_t rows_max, const void* Bt, int n_out, float* C, hipStream_t s,
                     void* H_scatter, bool caller_wants_C, int epi = kEpiPlain, const void* aux = nullptr,

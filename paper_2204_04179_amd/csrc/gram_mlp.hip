@@ -37,15 +37,19 @@ bool mlp_forward(Ctx* c, const void* X, const void* W1, const void* W2, const in
     if (rows_max <= 0) return false;
     const int d_in = c->cfg.d_in, dh = c->cfg.d_hidden, d = c->cfg.d;
     void* a1 = A1 ? A1 : c->A1_ws;
-    transpose_weight(c, W1, d_in, dh, c->W1t, s);
+    // the contraction kernels read the weights as the caller holds them where they can; otherwise a
+    // transposed copy is made first
+    const bool plain1 = gemm_reads_plain_b(c, rows_max, c->cfg.vocab_n, d_in, dh, kEpiReluBf16);
+    if (!plain1) transpose_weight(c, W1, d_in, dh, c->W1t, s);
     // the first contraction stores a = bf16(max(z, 0)) directly: z itself is never written
     gemm_rows_bf16(c, X, c->cfg.vocab_n, d_in, uniq, c->cfg.pad_id, u_dev, rows_max, c->W1t, dh,
-                   static_cast<float*>(a1), s, nullptr, true, kEpiReluBf16, nullptr);
-    transpose_weight(c, W2, dh, d, c->W2t, s);
+                   static_cast<float*>(a1), s, nullptr, true, kEpiReluBf16, nullptr, plain1 ? W1 : nullptr);
+    const bool plain2 = gemm_reads_plain_b(c, rows_max, rows_max, dh, d, kEpiPlain);
+    if (!plain2) transpose_weight(c, W2, dh, d, c->W2t, s);
     // rows of A1 are in the order of uniq: the identity list stands in for the gather, and no row is
     // "padding" by its index (the padding item's activation row is zero already)
     return gemm_rows_bf16(c, a1, rows_max, dh, c->iota, -1, u_dev, rows_max, c->W2t, d, E, s, H_scatter,
-                          caller_wants_E);
+                          caller_wants_E, kEpiPlain, nullptr, plain2 ? W2 : nullptr);
 }
 
 int64_t mlp_batch_bytes(const Ctx* c, int64_t n)
@@ -70,16 +74,19 @@ void mlp_backward(Ctx* c, const void* X, const void* W1, const void* W2, const i
 
     chunk_ids_prepare(c, ids, n, s);
     if (n > 0) {
-        transpose_weight(c, W1, d_in, dh, c->W1t, s);
+        const bool plain1 = gemm_reads_plain_b(c, n, c->cfg.vocab_n, d_in, dh, kEpiReluBf16);
+        if (!plain1) transpose_weight(c, W1, d_in, dh, c->W1t, s);
         gemm_rows_bf16(c, X, c->cfg.vocab_n, d_in, c->chunk_ids, c->cfg.pad_id, n_dev, n, c->W1t, dh,
-                       static_cast<float*>(A1), s, nullptr, true, kEpiReluBf16, nullptr);
+                       static_cast<float*>(A1), s, nullptr, true, kEpiReluBf16, nullptr, plain1 ? W1 : nullptr);
     }
     const float* Rsrc = rows;
     if (Ht) {
         // Algorithm 1 step 4 as a regression: output at the current weights minus the stored target
         if (n > 0) {
-            transpose_weight(c, W2, dh, d, c->W2t, s);
-            gemm_rows_bf16(c, A1, n, dh, c->iota, -1, n_dev, n, c->W2t, d, R, s, nullptr, true);
+            const bool plain2 = gemm_reads_plain_b(c, n, n, dh, d, kEpiPlain);
+            if (!plain2) transpose_weight(c, W2, dh, d, c->W2t, s);
+            gemm_rows_bf16(c, A1, n, dh, c->iota, -1, n_dev, n, c->W2t, d, R, s, nullptr, true, kEpiPlain, nullptr,
+                           plain2 ? W2 : nullptr);
         }
         pseudo_miss(c, R, Ht, n, loss_dev, s);
         Rsrc = R;
