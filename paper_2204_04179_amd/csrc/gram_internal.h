@@ -219,7 +219,9 @@ void pseudo_target(Ctx* c, const float* E, float* Ht, double* loss_dev, hipStrea
 void chunk_ids_prepare(Ctx* c, const int* ids, int64_t n, hipStream_t s);
 // With Ht: R[j,:] -= Ht[j,:] for the n rows of the batch in c->chunk_ids (zero for the padding
 // item); without: R is taken as it is.  With loss_dev, 1/2 of the sum of the squares of R.
-void pseudo_miss(Ctx* c, float* R, const float* Ht, int64_t n, double* loss_dev, hipStream_t s);
+// R_bf16 (nullable, [n, d] bf16): also receives the miss rounded to bf16.
+void pseudo_miss(Ctx* c, float* R, const float* Ht, int64_t n, double* loss_dev, hipStream_t s,
+                 void* R_bf16 = nullptr);
 void assign_slots(Ctx* c, hipStream_t s);
 void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s, bool commit = false);
 void flush_export(Ctx* c, int* uniq_total, int* counts_total, long long* counts64_total, float* G_total,

@@ -88,16 +88,19 @@ void mlp_backward(Ctx* c, const void* X, const void* W1, const void* W2, const i
             gemm_rows_bf16(c, A1, n, dh, c->iota, -1, n_dev, n, c->W2t, d, R, s, nullptr, true, kEpiPlain, nullptr,
                            plain2 ? W2 : nullptr);
         }
-        pseudo_miss(c, R, Ht, n, loss_dev, s);
+        // the miss kernel also leaves the bf16 copy of the miss that the dA contraction reads
+        pseudo_miss(c, R, Ht, n, loss_dev, s, Rb);
         Rsrc = R;
     }
     // dW2 = A1^T R: the kept activations play the part of the features, row j with row j
     const WgradRows top = {nullptr, Rsrc, n_dev, n, n > 0 ? n : 1, dh, d, -1};
     encoder_wgrad(c, A1, dW2, s, 0, n, accumulate, &top);
     if (n > 0) {
-        // dA = R . W2^T: W2 [dh, d] is already the K-contiguous second operand of that product
-        launch(c, KID_MLP_TO_BF16, k_to_bf16, dim3(blocks_for(n, d / 4)), dim3(kBlock), s,
-               reinterpret_cast<const f32x4*>(Rsrc), n_dev, d / 4, reinterpret_cast<uint2*>(Rb));
+        // dA = R . W2^T: W2 [dh, d] is already the K-contiguous second operand of that product; gradient
+        // rows handed in by the caller are rounded to bf16 here (with targets the miss kernel did it)
+        if (!Ht)
+            launch(c, KID_MLP_TO_BF16, k_to_bf16, dim3(blocks_for(n, d / 4)), dim3(kBlock), s,
+                   reinterpret_cast<const f32x4*>(Rsrc), n_dev, d / 4, reinterpret_cast<uint2*>(Rb));
         // the gate of the rectifier is applied as the product is stored: dZ = dA where the kept
         // activation is positive, so forward and backward agree on which units are active
         gemm_rows_bf16(c, Rb, n, d, c->iota, -1, n_dev, n, W2, dh, Z, s, nullptr, true, kEpiGate, A1);

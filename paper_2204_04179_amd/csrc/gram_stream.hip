@@ -318,7 +318,8 @@ void chunk_ids_prepare(Ctx* c, const int* ids, int64_t n, hipStream_t s)
 __global__ __launch_bounds__(kBlock) void k_pseudo_miss(f32x4* __restrict__ R,
                                                         const f32x4* __restrict__ Ht,
                                                         const int* __restrict__ ids, int n, int pad_id,
-                                                        int cols4, double* __restrict__ partial)
+                                                        int cols4, double* __restrict__ partial,
+                                                        uint2* __restrict__ R_bf16)
 {
     __shared__ double s_sum[kBlock];
     const int j0 = blockIdx.x * kPseudoRows;
@@ -336,6 +337,8 @@ __global__ __launch_bounds__(kBlock) void k_pseudo_miss(f32x4* __restrict__ R,
         } else {
             m = R[at];
         }
+        // the copy rounded to bf16 (nearest even) that a following contraction takes as its operand
+        if (R_bf16) R_bf16[at] = make_uint2(pack_bf16x2(m.x, m.y), pack_bf16x2(m.z, m.w));
         sum += (double)m.x * m.x + (double)m.y * m.y + (double)m.z * m.z + (double)m.w * m.w;
     }
     s_sum[threadIdx.x] = sum;
@@ -347,14 +350,14 @@ __global__ __launch_bounds__(kBlock) void k_pseudo_miss(f32x4* __restrict__ R,
     if (threadIdx.x == 0) partial[blockIdx.x] = s_sum[0];
 }
 
-void pseudo_miss(Ctx* c, float* R, const float* Ht, int64_t n, double* loss_dev, hipStream_t s)
+void pseudo_miss(Ctx* c, float* R, const float* Ht, int64_t n, double* loss_dev, hipStream_t s, void* R_bf16)
 {
-    if (!Ht && !loss_dev) return;       // nothing to subtract, nothing to sum
+    if (!Ht && !loss_dev && !R_bf16) return;       // nothing to subtract, nothing to sum, nothing to round
     const int64_t blocks = (n + kPseudoRows - 1) / kPseudoRows;
     if (blocks > 0)
         launch(c, KID_PSEUDO_MISS, k_pseudo_miss, dim3((unsigned)blocks), dim3(kBlock), s,
                reinterpret_cast<f32x4*>(R), reinterpret_cast<const f32x4*>(Ht), c->chunk_ids, (int)n,
-               c->cfg.pad_id, c->cfg.d / 4, c->loss_part);
+               c->cfg.pad_id, c->cfg.d / 4, c->loss_part, static_cast<uint2*>(R_bf16));
     if (loss_dev)
         launch(c, KID_PSEUDO_LOSS, k_pseudo_loss, dim3(1), dim3(kBlock), s, c->loss_part,
                c->scal + kSChunkN, loss_dev);
