@@ -52,6 +52,10 @@ def load():
         return _lib
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2204_04179_amd.build`")
+    # PyTorch ships a HIP runtime of its own.  It has to be in the process before this library is
+    # opened, so that the library binds to the same runtime as the tensors it is handed; opened
+    # the other way round, PyTorch finds no device afterwards.
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     vp, i32p = C.c_void_p, C.POINTER(C.c_int32)
     L.gram_workspace_bytes.restype = C.c_int64

@@ -333,12 +333,15 @@ def test_one_item_owning_hundreds_of_scan_tiles_over_a_two_step_window():
 
 
 @pytest.mark.parametrize("d,variant", [(256, "E requested"), (256, "E = NULL"), (320, "E = NULL"),
-                                       (256, "foreign uniq/inverse"), (64, "E = NULL, two padding positions")])
+                                       (260, "E = NULL"), (256, "foreign uniq/inverse"),
+                                       (64, "E = NULL, two padding positions")])
 def test_fused_forward_stores_representations_to_positions(d, variant):
     """Batches with tiles for every CU take the forward whose contraction epilogue stores each
     representation to the positions of its item, and a copy kernel for items with more than
     gram_light_max() positions.  Item multiplicities sit on both sides of that limit; the padding
-    ID is the heaviest item (zero rows); d = 320 leaves a ragged last column tile."""
+    ID is the heaviest item (zero rows); d = 320 leaves a ragged last column tile; d = 260 is not a
+    multiple of 8, so the contraction takes the transposed copy of the weights instead of reading
+    them as they are."""
     from paper_2204_04179_amd import gram
     T = gram.load().gram_light_max()
     n, m = 70000, 70000
