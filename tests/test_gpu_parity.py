@@ -1490,3 +1490,80 @@ def test_error_paths():
     assert g2.flush(want_host_u=True) == 3
     g.close()
     g2.close()
+
+
+# ------------------------------------------------- randomly drawn shapes --
+
+def random_case(seed):
+    """A window of valid inputs with every shape parameter drawn at random: vocabulary, widths,
+    steps, batch sizes (some empty), popularity law, padding ID (0, none, any other ID) and share,
+    buffer layout, how the window is ended, E requested or not, caller buffers own or foreign,
+    output type of H.  The oracle's contraction is kept affordable."""
+    rng = np.random.default_rng(seed)
+    bf16 = rng.random() < 0.8
+    n = int(2 ** rng.uniform(1, 16.5))
+    d_in = int(rng.choice([8, 16, 24, 32, 40, 64, 96, 128, 200, 256, 264, 512])) if bf16 else int(rng.integers(1, 70))
+    d = int(rng.choice([4, 8, 12, 32, 64, 100, 128, 256, 260, 320, 512, 1024]))
+    K = int(rng.choice([1, 1, 2, 3, 5]))
+    big = rng.random() < 0.3
+    m_hi = 150000 if big else 20000
+    pad_mode = rng.choice(["zero", "none", "other"], p=[0.6, 0.2, 0.2])
+    pad_id = 0 if pad_mode == "zero" else (-1 if pad_mode == "none" else int(rng.integers(0, n)))
+    pad_frac = float(rng.choice([0.0, 0.1, 0.5]))
+    s = float(rng.choice([0.0, 0.8, 1.1, 1.5]))
+    dense = rng.random() < 0.15
+    kw = dict(pad_id=pad_id, dense=dense, window_end=(not dense) and rng.random() < 0.6, pass_E=rng.random() < 0.5,
+              foreign_buffers=rng.random() < 0.2, h_bf16=rng.random() < 0.2)
+    ms = [0 if rng.random() < 0.05 else int(2 ** rng.uniform(np.log2(m_hi) - 5 if big else 0, np.log2(m_hi)))
+          for _ in range(K)]
+    if sum(ms) == 0:
+        ms[0] = 5
+    while K * max(ms) * d_in * d > 2e9:
+        ms = [m // 2 for m in ms]
+    p = np.arange(1, n + 1, dtype=np.float64) ** (-s)
+    p /= p.sum()
+    perm = rng.permutation(n)
+    batches = []
+    for m in ms:
+        ids = perm[rng.choice(n, size=m, p=p)].astype(np.int32) if m else np.zeros(0, np.int32)
+        if pad_id >= 0 and m:
+            ids[rng.random(m) < pad_frac] = pad_id
+        batches.append((ids, rng.standard_normal((m, d)).astype(np.float32)))
+    X = rng.standard_normal((n, d_in)).astype(np.float32)
+    W = (rng.standard_normal((d_in, d)) / np.sqrt(d_in)).astype(np.float32)
+    if bf16:
+        X, W = wl.f32_to_bf16_bits(X), wl.f32_to_bf16_bits(W)
+    shape = dict(seed=seed, bf16=bf16, n=n, d_in=d_in, d=d, ms=ms, s=s, pad_frac=pad_frac, **kw)
+    return shape, X, W, batches, n, K, kw
+
+
+@pytest.mark.parametrize("first_seed", [0, 30, 60, 90])
+def test_randomly_drawn_shapes_against_the_oracle(first_seed):
+    """30 windows per case, every parameter of the problem drawn at random (see random_case);
+    integers bit-exact, E / H / G_total / dW within the bars of the fixed-shape tests (H in bf16:
+    its rounding, 2^-9 per element)."""
+    for seed in range(first_seed, first_seed + 30):
+        shape, X, W, batches, n, K, kw = random_case(seed)
+        say("random shape:", shape)
+        dt = wl.BF16 if shape["bf16"] else wl.F32
+        out = run_window(X, W, batches, vocab_n=n, k_steps=K, max_positions=max(1, max(shape["ms"])), **kw)
+        acc = orc.GramMulti(X, W, pad_id=kw["pad_id"])
+        for k, (ids, dH) in enumerate(batches):
+            ref = acc.step(ids, dH)
+            st = out["steps"][k]
+            check_step_exact(st, ref)
+            if ids.size:
+                if "E" in st:
+                    assert_close(st["E"], ref["E"], TOL_SUM[dt], f"E step {k}")
+                assert_close(st["H"], ref["H"], 8e-3 if kw["h_bf16"] else TOL_SUM[dt], f"H step {k}")
+        ref = acc.finish()
+        np.testing.assert_array_equal(out["uniq_total"], ref["uniq"])
+        np.testing.assert_array_equal(out["counts_total"], ref["counts"])
+        if ref["uniq"].size:
+            assert_close(out["G_total"], ref["G"], TOL_SUM[dt], "G_total")
+        assert out["G_tail_untouched"]
+        if np.abs(ref["dW"]).max() > 0:
+            assert_close(out["dW"], ref["dW"], TOL[dt], "dW")
+        else:
+            assert not out["dW"].any()
+        out["gram"].close()
