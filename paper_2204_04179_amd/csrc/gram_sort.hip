@@ -88,24 +88,30 @@ SortPlan make_sort_plan(int key_bits, int64_t n_max)
     return p;
 }
 
-// Applies `f(key, index, u)` to the keys of one wave's chunk, kSortBatch rounds of 64 keys at a
-// time; the keys of a batch are fetched together, because the rounds are short and otherwise each
-// would wait for its own global load.
-#define GRAM_FOR_WAVE_KEYS(BODY)                                                                    \
+// Applies BODY (which sees the key k, its index idx, `valid` and the value vv that travels with
+// the key: the expression VLOAD of the index idx_) to the keys of one wave's chunk, kSortBatch rounds of 64 keys at a time;
+// the keys (and values) of a batch are fetched together, because the rounds are short and
+// otherwise each would wait for its own global load.
+#define GRAM_FOR_WAVE_KEYS_V(VLOAD, BODY)                                                           \
     for (int it0 = 0; it0 < items; it0 += kSortBatch) {                                             \
-        int kb_[kSortBatch];                                                                        \
+        int kb_[kSortBatch], vb_[kSortBatch];                                                       \
         _Pragma("unroll") for (int u = 0; u < kSortBatch; ++u) {                                    \
             const int64_t idx_ = base + (int64_t)(it0 + u) * kWave + lane;                          \
-            kb_[u] = (it0 + u < items && idx_ < n) ? keys_in[idx_] : 0;                             \
+            const bool in_ = it0 + u < items && idx_ < n;                                           \
+            kb_[u] = in_ ? keys_in[idx_] : 0;                                                       \
+            vb_[u] = in_ ? (VLOAD) : 0;                                                             \
         }                                                                                           \
         _Pragma("unroll") for (int u = 0; u < kSortBatch; ++u) {                                    \
             if (it0 + u >= items) break; /* wave-uniform */                                         \
             const int64_t idx = base + (int64_t)(it0 + u) * kWave + lane;                           \
             const bool valid = idx < n;                                                             \
             int k = kb_[u];                                                                         \
+            const int vv = vb_[u];                                                                  \
+            (void)vv;                                                                               \
             BODY                                                                                    \
         }                                                                                           \
     }
+#define GRAM_FOR_WAVE_KEYS(BODY) GRAM_FOR_WAVE_KEYS_V(0, BODY)
 
 // Digit histogram of one pass per block.  table[digit * nb + block] = count.
 template <bool CHECK>
@@ -210,9 +216,9 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(
 
     volatile int* cnt = cnt_s[wave];
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
-    GRAM_FOR_WAVE_KEYS(
+    GRAM_FOR_WAVE_KEYS_V((vals_in ? vals_in[idx_] : (int)idx_),
         if (CHECK && valid && (k < 0 || k >= vocab_n)) k = fix_key;
-        const int v = valid ? (vals_in ? vals_in[idx] : (int)idx) : 0;
+        const int v = vv;
         const int dg = (k >> shift) & (bins - 1);
         unsigned long long peers = __ballot(valid);
         for (int bit = 0; bit < dbits; ++bit) {
@@ -232,6 +238,7 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(
         })
 }
 #undef GRAM_FOR_WAVE_KEYS
+#undef GRAM_FOR_WAVE_KEYS_V
 
 int radix_sort_pairs(Ctx* c, const int* keys_in, const int* vals_in, int n_host, const int* n_dev,
                      int64_t n_max, bool check_range, int fix_key, hipStream_t s)
