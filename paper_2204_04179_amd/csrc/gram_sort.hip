@@ -88,30 +88,47 @@ SortPlan make_sort_plan(int key_bits, int64_t n_max)
     return p;
 }
 
-// Applies BODY (which sees the key k, its index idx, `valid` and the value vv that travels with
-// the key: the expression VLOAD of the index idx_) to the keys of one wave's chunk, kSortBatch rounds of 64 keys at a time;
-// the keys (and values) of a batch are fetched together, because the rounds are short and
-// otherwise each would wait for its own global load.
-#define GRAM_FOR_WAVE_KEYS_V(VLOAD, BODY)                                                           \
+// The keys of one wave's chunk are walked kSortBatch rounds of 64 keys at a time; the keys of a
+// batch (and the values that travel with them: the expression VLOAD of the index idx_) are
+// fetched together, because the rounds are short and otherwise each would wait for its own
+// global load.  BODY sees the key k, its index idx, `valid` and the value vv.
+#define GRAM_LOAD_BATCH(IT0, KB, VB, VLOAD)                                                         \
+    _Pragma("unroll") for (int u = 0; u < kSortBatch; ++u) {                                        \
+        const int64_t idx_ = base + (int64_t)((IT0) + u) * kWave + lane;                            \
+        const bool in_ = (IT0) + u < items && idx_ < n;                                             \
+        KB[u] = in_ ? keys_in[idx_] : 0;                                                            \
+        VB[u] = in_ ? (VLOAD) : 0;                                                                  \
+    }
+#define GRAM_RUN_BATCH(IT0, KB, VB, BODY)                                                           \
+    _Pragma("unroll") for (int u = 0; u < kSortBatch; ++u) {                                        \
+        if ((IT0) + u >= items) break; /* wave-uniform */                                           \
+        const int64_t idx = base + (int64_t)((IT0) + u) * kWave + lane;                             \
+        const bool valid = idx < n;                                                                 \
+        int k = KB[u];                                                                              \
+        const int vv = VB[u];                                                                       \
+        (void)vv;                                                                                   \
+        BODY                                                                                        \
+    }
+#define GRAM_FOR_WAVE_KEYS(BODY)                                                                    \
     for (int it0 = 0; it0 < items; it0 += kSortBatch) {                                             \
         int kb_[kSortBatch], vb_[kSortBatch];                                                       \
-        _Pragma("unroll") for (int u = 0; u < kSortBatch; ++u) {                                    \
-            const int64_t idx_ = base + (int64_t)(it0 + u) * kWave + lane;                          \
-            const bool in_ = it0 + u < items && idx_ < n;                                           \
-            kb_[u] = in_ ? keys_in[idx_] : 0;                                                       \
-            vb_[u] = in_ ? (VLOAD) : 0;                                                             \
-        }                                                                                           \
-        _Pragma("unroll") for (int u = 0; u < kSortBatch; ++u) {                                    \
-            if (it0 + u >= items) break; /* wave-uniform */                                         \
-            const int64_t idx = base + (int64_t)(it0 + u) * kWave + lane;                           \
-            const bool valid = idx < n;                                                             \
-            int k = kb_[u];                                                                         \
-            const int vv = vb_[u];                                                                  \
-            (void)vv;                                                                               \
-            BODY                                                                                    \
-        }                                                                                           \
+        GRAM_LOAD_BATCH(it0, kb_, vb_, 0)                                                           \
+        GRAM_RUN_BATCH(it0, kb_, vb_, BODY)                                                         \
     }
-#define GRAM_FOR_WAVE_KEYS(BODY) GRAM_FOR_WAVE_KEYS_V(0, BODY)
+// The same walk with the first batch already in registers (KB0, VB0).
+#define GRAM_FOR_WAVE_KEYS_FROM(KB0, VB0, VLOAD, BODY)                                              \
+    for (int it0 = 0; it0 < items; it0 += kSortBatch) {                                             \
+        int kb_[kSortBatch], vb_[kSortBatch];                                                       \
+        if (it0 == 0) {                                                                             \
+            _Pragma("unroll") for (int u = 0; u < kSortBatch; ++u) {                                \
+                kb_[u] = KB0[u];                                                                    \
+                vb_[u] = VB0[u];                                                                    \
+            }                                                                                       \
+        } else {                                                                                    \
+            GRAM_LOAD_BATCH(it0, kb_, vb_, VLOAD)                                                   \
+        }                                                                                           \
+        GRAM_RUN_BATCH(it0, kb_, vb_, BODY)                                                         \
+    }
 
 // Digit histogram of one pass per block.  table[digit * nb + block] = count.
 template <bool CHECK>
@@ -148,12 +165,22 @@ __global__ __launch_bounds__(kBlock) void k_radix_scan(int* __restrict__ table, 
     const int lane = lane_id();
     int* row = table + (int64_t)b * nb;
     int carry = 0;
-    for (int base = 0; base < nb; base += kWave) {
-        const int i = base + lane;
-        const int v = i < nb ? row[i] : 0;
-        const int incl = wave_incl_scan(v);
-        if (i < nb) row[i] = carry + incl - v;
-        carry += __shfl(incl, kWave - 1);
+    // four chunks of 64 counts are fetched together: the scan of a chunk is short, and one chunk
+    // per round trip would make the launch as long as its number of chunks
+    for (int base = 0; base < nb; base += 4 * kWave) {
+        int v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = base + u * kWave + lane;
+            v[u] = i < nb ? row[i] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = base + u * kWave + lane;
+            const int incl = wave_incl_scan(v[u]);
+            if (i < nb) row[i] = carry + incl - v[u];
+            carry += __shfl(incl, kWave - 1);
+        }
     }
     if (lane == 0) gtot[b] = carry;
 }
@@ -177,6 +204,19 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(
     const int bins = 1 << dbits;
     const int64_t base = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * items * kWave;
 
+    // Everything this block reads that does not depend on its own work is fetched first, in one
+    // round trip: the first batch of its keys and values (kept for both walks below), its column
+    // of the block table and the digit totals.
+    int kb0[kSortBatch], vb0[kSortBatch];
+    GRAM_LOAD_BATCH(0, kb0, vb0, (vals_in ? vals_in[idx_] : (int)idx_))
+    static_assert((1 << kMaxDigitBits) <= 4 * kBlock, "a thread holds at most 4 digits of the block table");
+    int tb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int b = threadIdx.x + i * kBlock;
+        tb[i] = b < bins ? table[(int64_t)b * gridDim.x + blockIdx.x] : 0;
+    }
+
     for (int b = threadIdx.x; b < bins; b += kBlock)
 #pragma unroll
         for (int w = 0; w < kWavesPerBlock; ++w) cnt_s[w][b] = 0;
@@ -197,26 +237,30 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(
             run += v[i];
         }
     }
-    GRAM_FOR_WAVE_KEYS(
+    GRAM_FOR_WAVE_KEYS_FROM(kb0, vb0, 0,
         if (valid) {
             if (CHECK && (k < 0 || k >= vocab_n)) k = fix_key;
             atomicAdd(&cnt_s[wave][(k >> shift) & (bins - 1)], 1);
         })
     __syncthreads();
-    for (int b = threadIdx.x; b < bins; b += kBlock) {
-        int o = digit_base[b] + table[(int64_t)b * gridDim.x + blockIdx.x];
 #pragma unroll
-        for (int w = 0; w < kWavesPerBlock; ++w) {
-            const int cw = cnt_s[w][b];
-            cnt_s[w][b] = o;
-            o += cw;
+    for (int i = 0; i < 4; ++i) {
+        const int b = threadIdx.x + i * kBlock;
+        if (b < bins) {
+            int o = digit_base[b] + tb[i];
+#pragma unroll
+            for (int w = 0; w < kWavesPerBlock; ++w) {
+                const int cw = cnt_s[w][b];
+                cnt_s[w][b] = o;
+                o += cw;
+            }
         }
     }
     __syncthreads();
 
     volatile int* cnt = cnt_s[wave];
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
-    GRAM_FOR_WAVE_KEYS_V((vals_in ? vals_in[idx_] : (int)idx_),
+    GRAM_FOR_WAVE_KEYS_FROM(kb0, vb0, (vals_in ? vals_in[idx_] : (int)idx_),
         if (CHECK && valid && (k < 0 || k >= vocab_n)) k = fix_key;
         const int v = vv;
         const int dg = (k >> shift) & (bins - 1);
@@ -238,7 +282,9 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(
         })
 }
 #undef GRAM_FOR_WAVE_KEYS
-#undef GRAM_FOR_WAVE_KEYS_V
+#undef GRAM_FOR_WAVE_KEYS_FROM
+#undef GRAM_LOAD_BATCH
+#undef GRAM_RUN_BATCH
 
 int radix_sort_pairs(Ctx* c, const int* keys_in, const int* vals_in, int n_host, const int* n_dev,
                      int64_t n_max, bool check_range, int fix_key, hipStream_t s)
@@ -346,29 +392,48 @@ __global__ __launch_bounds__(kBlock) void k_heads_emit(
     __shared__ int s_rows[kScanTile + 1];     // rows of the tile's heads, then the next head's row
     __shared__ int s_next;
     const int T = gridDim.x;
+    // Everything that does not depend on this block's own work is fetched before the first
+    // barrier, in one round trip: the thread's 4 sorted keys and positions, the key before them,
+    // the figures of the tiles before and (a first look) after this one, the buffer's row count.
+    const int r0 = blockIdx.x * kScanTile + threadIdx.x * 4;
+    int key[4] = {0, 0, 0, 0}, posn[4] = {0, 0, 0, 0};
+    if (r0 + 3 < n) {           // whole groups of 4: 16-byte loads (the arrays are 256-byte aligned)
+        const int4 k4 = *reinterpret_cast<const int4*>(sk + r0);
+        const int4 p4 = *reinterpret_cast<const int4*>(sv + r0);
+        key[0] = k4.x; key[1] = k4.y; key[2] = k4.z; key[3] = k4.w;
+        posn[0] = p4.x; posn[1] = p4.y; posn[2] = p4.z; posn[3] = p4.w;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (r0 + i < n) {
+                key[i] = sk[r0 + i];
+                posn[i] = sv[r0 + i];
+            }
+    }
+    const int prev = (r0 > 0 && r0 < n) ? sk[r0 - 1] : -1;
+    const int u_base = (slot_of && !first_step) ? scal[kSUTotal] : 0;   // a flush leaves the old count behind
+    const int ahead0 = (int)blockIdx.x + 1 + (int)threadIdx.x < T ? tile_info[2 * T + blockIdx.x + 1 + threadIdx.x] : -1;
     int pre = 0, pre_fresh = 0;
     for (int t = threadIdx.x; t < (int)blockIdx.x; t += kBlock) {
         pre += tile_info[t];
         pre_fresh += tile_info[T + t];
     }
-    pre = block_sum(pre, sm);
-    pre_fresh = block_sum(pre_fresh, sm);
-    if (threadIdx.x == 0) s_next = kNoRow;
-
-    const int r0 = blockIdx.x * kScanTile + threadIdx.x * 4;
     bool f[4];
     int old[4];
     int s = 0, fresh = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        f[i] = (r0 + i < n) && is_head(sk, r0 + i);
+        f[i] = (r0 + i < n) && (r0 + i == 0 || key[i] != (i ? key[i - 1] : prev));
         old[i] = 0;
         s += f[i] ? 1 : 0;
         if (f[i] && slot_of) {
-            old[i] = slot_of[sk[r0 + i]];
+            old[i] = slot_of[key[i]];
             fresh += old[i] < 0 ? 1 : 0;
         }
     }
+    pre = block_sum(pre, sm);
+    pre_fresh = block_sum(pre_fresh, sm);
+    if (threadIdx.x == 0) s_next = kNoRow;
     int total, total_fresh;
     const int local = block_excl_scan(s, &total, sm);
     const int local_fresh = block_excl_scan(fresh, &total_fresh, sm);
@@ -382,7 +447,7 @@ __global__ __launch_bounds__(kBlock) void k_heads_emit(
     // heads ascend with the tile index, so the minimum is the nearest)
     for (int base = blockIdx.x + 1; base < T; base += kBlock) {
         const int t = base + threadIdx.x;
-        const int row = t < T ? tile_info[2 * T + t] : -1;
+        const int row = base == (int)blockIdx.x + 1 ? ahead0 : (t < T ? tile_info[2 * T + t] : -1);
         if (row >= 0) atomicMin(&s_next, row);
         __syncthreads();
         if (s_next != kNoRow) break;           // the same value for every thread
@@ -392,7 +457,6 @@ __global__ __launch_bounds__(kBlock) void k_heads_emit(
     if (threadIdx.x == 0) s_rows[total] = s_next == kNoRow ? n : s_next;
     __syncthreads();
 
-    const int u_base = (slot_of && !first_step) ? scal[kSUTotal] : 0;   // a flush leaves the old count behind
     int run = pre + local, li = local, next_slot = u_base + pre_fresh + local_fresh;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -401,11 +465,10 @@ __global__ __launch_bounds__(kBlock) void k_heads_emit(
             run += f[i] ? 1 : 0;
             const int seg = run - 1;
             seg_of_row[r] = seg;
-            inverse[sv[r]] = seg;
+            inverse[posn[i]] = seg;
             if (f[i]) {
-                const int key = sk[r];
-                uniq[seg] = key;
-                uniq_ws[seg] = key;
+                uniq[seg] = key[i];
+                uniq_ws[seg] = key[i];
                 offsets[seg] = r;
                 counts[seg] = s_rows[li + 1] - r;
                 ++li;
