@@ -332,6 +332,36 @@ def test_one_item_owning_hundreds_of_scan_tiles_over_a_two_step_window():
     assert_close(out["dW"], ref["dW"], 1e-4, "dW")
 
 
+def test_batch_of_more_than_a_million_positions():
+    """1,500,000 positions: a wave of the radix passes owns more keys than it fetches ahead at once
+    (several batches of 16 rounds per wave), the head scan has 1,465 tiles.  Two steps with
+    Zipf-like repeats and padding; everything against the oracle."""
+    n, d_in, d, m = 300000, 8, 4, 1_500_000
+    rng = np.random.default_rng(93)
+    X = rng.standard_normal((n, d_in)).astype(np.float32)
+    W = (rng.standard_normal((d_in, d)) / np.sqrt(d_in)).astype(np.float32)
+    p = np.arange(1, n, dtype=np.float64) ** -1.05
+    p /= p.sum()
+    batches = []
+    for k in range(2):
+        ids = (rng.permutation(n - 1)[rng.choice(n - 1, size=m, p=p)] + 1).astype(np.int32)
+        ids[rng.random(m) < 0.1] = 0
+        batches.append((ids, rng.standard_normal((m, d)).astype(np.float32)))
+    say(f"more than a million positions: m={m}")
+    out = run_window(X, W, batches, vocab_n=n, k_steps=2, keep_E=False, window_end=True)
+    acc = orc.GramMulti(X, W, pad_id=0)
+    for k, (ids, dH) in enumerate(batches):
+        ref = acc.step(ids, dH)
+        check_step_exact(out["steps"][k], ref)
+        assert_close(out["steps"][k]["H"], ref["H"], 1e-5, f"H step {k}")
+    ref = acc.finish()
+    np.testing.assert_array_equal(out["uniq_total"], ref["uniq"])
+    np.testing.assert_array_equal(out["counts_total"], ref["counts"])
+    # the most popular item sums 160,000 float32 terms per step in tile order against float64
+    assert_close(out["G_total"], ref["G"], 1e-4, "G_total")
+    assert_close(out["dW"], ref["dW"], 1e-4, "dW")
+
+
 @pytest.mark.parametrize("d,variant", [(256, "E requested"), (256, "E = NULL"), (320, "E = NULL"),
                                        (260, "E = NULL"), (256, "foreign uniq/inverse"),
                                        (64, "E = NULL, two padding positions")])
