@@ -359,7 +359,7 @@ constexpr int kNoRow = 0x7fffffff;
 
 __global__ __launch_bounds__(kBlock) void k_heads_count(const int* __restrict__ sk, int n,
                                                         const int* __restrict__ slot_of,
-                                                        int* __restrict__ tile_info)
+                                                        int* __restrict__ tile_info, int first_step)
 {
     __shared__ int sm[kWavesPerBlock];
     const int r0 = blockIdx.x * kScanTile + threadIdx.x * 4;
@@ -369,7 +369,8 @@ __global__ __launch_bounds__(kBlock) void k_heads_count(const int* __restrict__ 
         if (r0 + i < n && is_head(sk, r0 + i)) {
             ++s;
             if (first == kNoRow) first = r0 + i;
-            if (slot_of && slot_of[sk[r0 + i]] < 0) ++fresh;
+            // (in the first step of a window the buffer holds nothing: every item is new)
+            if (slot_of && (first_step || slot_of[sk[r0 + i]] < 0)) ++fresh;
         }
     const int tot = block_sum(s, sm);
     const int tot_fresh = block_sum(fresh, sm);
@@ -427,7 +428,7 @@ __global__ __launch_bounds__(kBlock) void k_heads_emit(
         old[i] = 0;
         s += f[i] ? 1 : 0;
         if (f[i] && slot_of) {
-            old[i] = slot_of[key[i]];
+            old[i] = first_step ? -1 : slot_of[key[i]];
             fresh += old[i] < 0 ? 1 : 0;
         }
     }
@@ -523,6 +524,7 @@ constexpr int kSmallWaves = kSmallThreads / kWave;
 constexpr int kSmallMaxN = 8192;
 constexpr int kSmallBits = 8;
 constexpr int kSmallBins = 1 << kSmallBits;
+constexpr int kSmallRounds = kSmallMaxN / kSmallWaves / kWave;   // rounds of 64 keys per wave, at most
 // LDS, in ints: keys x2 | positions x2 (16-bit) | per-wave digit counts | per-wave peer masks (64-bit) | wave sums
 constexpr int kSmallOffV = 2 * kSmallMaxN;
 constexpr int kSmallOffCnt = kSmallOffV + kSmallMaxN;
@@ -588,10 +590,20 @@ __global__ __launch_bounds__(kSmallThreads) void k_unique_small(
     for (int shift = 0; shift < key_bits; shift += kSmallBits) {
         for (int b = lane; b < kSmallBins; b += kWave) cnt[b] = 0;
         __syncthreads();
-        for (int i0 = cbeg; i0 < cend; i0 += kWave) {        // wave-uniform trip count
-            const int i = i0 + lane;
-            const bool valid = i < cend;
-            const int dg = valid ? (KBUF(cur)[i] >> shift) & (kSmallBins - 1) : -1;
+        // the keys (and, for the second walk, positions) of all of the wave's rounds are read from
+        // LDS up front: a round is a chain of dependent LDS operations, and the reads of the next
+        // round would otherwise wait behind it
+        int kr[kSmallRounds];
+#pragma unroll
+        for (int r = 0; r < kSmallRounds; ++r) {
+            const int i = cbeg + r * kWave + lane;
+            kr[r] = i < cend ? KBUF(cur)[i] : 0;
+        }
+#pragma unroll
+        for (int r = 0; r < kSmallRounds; ++r) {
+            if (cbeg + r * kWave >= cend) break;             // wave-uniform
+            const bool valid = cbeg + r * kWave + lane < cend;
+            const int dg = valid ? (kr[r] >> shift) & (kSmallBins - 1) : -1;
             // the digit of the round's first key is counted once for all lanes that hold it:
             // padding and very popular items would otherwise pile up on one LDS counter
             const int d0 = __builtin_amdgcn_readfirstlane(dg);
@@ -617,11 +629,18 @@ __global__ __launch_bounds__(kSmallThreads) void k_unique_small(
             }
         }
         __syncthreads();
-        for (int i0 = cbeg; i0 < cend; i0 += kWave) {        // wave-uniform trip count
-            const int i = i0 + lane;
-            const bool valid = i < cend;
-            const int k = valid ? KBUF(cur)[i] : 0;
-            const int v = valid ? VBUF(cur)[i] : 0;
+        int vr[kSmallRounds];
+#pragma unroll
+        for (int r = 0; r < kSmallRounds; ++r) {
+            const int i = cbeg + r * kWave + lane;
+            vr[r] = i < cend ? VBUF(cur)[i] : 0;
+        }
+#pragma unroll
+        for (int r = 0; r < kSmallRounds; ++r) {
+            if (cbeg + r * kWave >= cend) break;             // wave-uniform
+            const bool valid = cbeg + r * kWave + lane < cend;
+            const int k = kr[r];
+            const int v = vr[r];
             const int dg = (k >> shift) & (kSmallBins - 1);
             // Lanes holding the digit of the round's first key know their group from one ballot
             // (padding and very popular items fill most of a round); the others meet through the
@@ -733,7 +752,8 @@ __global__ __launch_bounds__(kSmallThreads) void k_unique_small(
         for (int i = 0; i < 8; ++i) {
             old[i] = 0;
             if (j0 + i < total) {
-                old[i] = slot_of[sk[loff[j0 + i]]];
+                // in the first step of a window the buffer holds nothing: every item is new
+                old[i] = first_step ? -1 : slot_of[sk[loff[j0 + i]]];
                 fresh += old[i] < 0 ? 1 : 0;
             }
         }
@@ -772,7 +792,7 @@ void unique_from_sorted(Ctx* c, int n, int* uniq, int* inverse, int* counts, int
     const int tiles = (n + kScanTile - 1) / kScanTile;
     const int* slot_of = prospect ? c->slot_of : nullptr;
     launch(c, KID_HEADS_COUNT, k_heads_count, dim3(tiles), dim3(kBlock), s, c->sorted_keys, n, slot_of,
-           c->tile_sums);
+           c->tile_sums, first_step);
     launch(c, KID_HEADS_EMIT, k_heads_emit, dim3(tiles), dim3(kBlock), s, c->sorted_keys, c->perm, n,
            c->tile_sums, uniq, inverse, counts, c->offsets, c->seg_of_row, c->uniq_ws, u_out, slot_of,
            c->seg_slot, c->scal, first_step, (int)c->cap_total);
