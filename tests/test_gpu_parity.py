@@ -1599,3 +1599,131 @@ def test_randomly_drawn_shapes_against_the_oracle(first_seed):
         else:
             assert not out["dW"].any()
         out["gram"].close()
+
+
+@pytest.mark.parametrize("first_seed", [0, 30])
+def test_randomly_drawn_windows_with_pseudo_targets_chunks_and_a_resumed_state(first_seed):
+    """30 windows per case with random shapes: pseudo-targets and pseudo-loss after every step, the
+    weight gradient taken in a random partition of the buffer rows (the last chunk runs past the
+    end), some windows resumed from a random saved state, slot table or dense buffer."""
+    for seed in range(first_seed, first_seed + 30):
+        rng = np.random.default_rng(10_000 + seed)
+        bf16 = rng.random() < 0.7
+        n = int(2 ** rng.uniform(3, 16))
+        d_in = int(rng.choice([8, 16, 32, 64, 96, 128, 256, 264])) if bf16 else int(rng.integers(1, 70))
+        d = int(rng.choice([4, 8, 12, 32, 64, 100, 128, 256, 260, 512]))
+        K = int(rng.choice([1, 2, 3, 4]))
+        big = rng.random() < 0.3
+        m_hi = 100000 if big else 10000
+        pad_id = int(rng.choice([0, 0, -1]))
+        pad_frac = float(rng.choice([0.0, 0.2]))
+        s = float(rng.choice([0.0, 0.8, 1.2]))
+        dense = rng.random() < 0.3
+        do_resume = rng.random() < 0.4
+        ms = [max(1, int(2 ** rng.uniform(np.log2(m_hi) - 4 if big else 2, np.log2(m_hi)))) for _ in range(K)]
+        while K * max(ms) * d_in * d > 2e9:
+            ms = [max(1, m // 2) for m in ms]
+        say("random window:", dict(seed=seed, bf16=bf16, n=n, d_in=d_in, d=d, ms=ms, pad_id=pad_id, dense=dense,
+                                   resume=do_resume))
+        p = np.arange(1, n + 1, dtype=np.float64) ** (-s)
+        p /= p.sum()
+        perm = rng.permutation(n)
+        batches = []
+        for m in ms:
+            ids = perm[rng.choice(n, size=m, p=p)].astype(np.int32)
+            if pad_id >= 0:
+                ids[rng.random(m) < pad_frac] = pad_id
+            batches.append((ids, rng.standard_normal((m, d)).astype(np.float32)))
+        X = rng.standard_normal((n, d_in)).astype(np.float32)
+        W = (rng.standard_normal((d_in, d)) / np.sqrt(d_in)).astype(np.float32)
+        if bf16:
+            X, W = wl.f32_to_bf16_bits(X), wl.f32_to_bf16_bits(W)
+        dt = wl.BF16 if bf16 else wl.F32
+        resume, u_cap = None, 0
+        if do_resume:
+            nr = int(rng.integers(1, max(2, min(n, 3000))))
+            r_ids = np.sort(rng.choice(n, size=nr, replace=False)).astype(np.int32)
+            r_G = rng.standard_normal((nr, d)).astype(np.float32)
+            if pad_id >= 0:
+                r_G[r_ids == pad_id] = 0.0
+            resume = (r_ids, rng.integers(1, 9, size=nr).astype(np.int64), r_G)
+            if not dense:
+                u_cap = min(n, K * max(ms) + nr)
+        cap = n if dense else min(n, K * max(ms) + (resume[0].size if resume else 0))
+        cuts = np.unique(np.concatenate([[0], rng.integers(0, cap + 1, size=int(rng.integers(0, 5)))]))
+        chunks = [(int(a), int(b - a)) for a, b in zip(cuts[:-1], cuts[1:])] + [(int(cuts[-1]), 10 ** 9)]
+        out = run_window(X, W, batches, vocab_n=n, pad_id=pad_id, k_steps=K, max_positions=max(ms), pseudo=True,
+                         wgrad_chunks=chunks, dense=dense, resume=resume, u_total_cap=u_cap)
+        acc = orc.GramMulti(X, W, pad_id=pad_id)
+        if resume is not None:
+            acc.resume(*resume)
+        for k, (ids, dH) in enumerate(batches):
+            ref = acc.step(ids, dH)
+            st = out["steps"][k]
+            check_step_exact(st, ref)
+            assert_close(st["E"], ref["E"], TOL_SUM[dt], f"E step {k}")
+            assert_close(st["H"], ref["H"], TOL_SUM[dt], f"H step {k}")
+            Ht_ref, loss_ref = orc.pseudo_target(ref["E"], acc.rows(ref["uniq"]))
+            assert_close(st["Ht"], Ht_ref, TOL_SUM[dt], f"Ht step {k}")
+            assert abs(st["loss"] - loss_ref) <= TOL_SUM[dt] * max(loss_ref, 1e-30)
+            assert st["Ht_tail_untouched"]
+            np.testing.assert_array_equal(st["H_tilde"], st["Ht"][ref["inverse"]])
+        ref = acc.finish()
+        np.testing.assert_array_equal(out["uniq_total"], ref["uniq"])
+        np.testing.assert_array_equal(out["counts_total"], ref["counts"])
+        assert_close(out["G_total"], ref["G"], TOL_SUM[dt], "G_total")
+        if np.abs(ref["dW"]).max() > 0:
+            assert_close(out["dW"], ref["dW"], TOL[dt], "dW")
+            assert_close(out["dW_chunked"], ref["dW"], TOL[dt], "dW in chunks")
+        out["gram"].close()
+
+
+def test_randomly_drawn_steps_of_the_two_layer_encoder():
+    """40 single-step windows of the two-layer encoder with random widths and batch sizes, the
+    backward pass in a random partition of the items; from accumulated gradient rows (against the
+    oracle's per-item run) or towards stored targets at moved weights (against the oracle's
+    regression)."""
+    for seed in range(40):
+        rng = np.random.default_rng(20_000 + seed)
+        n = int(2 ** rng.uniform(4, 16.5))
+        d_in = int(rng.choice([8, 16, 32, 64, 96, 128, 264]))
+        d_hid = int(rng.choice([8, 16, 40, 64, 128, 256, 264, 512]))
+        d = int(rng.choice([8, 16, 24, 64, 128, 256, 264]))
+        big = rng.random() < 0.3
+        m_hi = 100000 if big else 8000
+        m = max(2, int(2 ** rng.uniform(np.log2(m_hi) - 3 if big else 2, np.log2(m_hi))))
+        while m * (d_in * d_hid + d_hid * d) > 1.5e9:
+            m //= 2
+        regress = rng.random() < 0.4
+        s = float(rng.choice([0.0, 1.0]))
+        say("random two-layer step:", dict(seed=seed, n=n, d_in=d_in, d_hid=d_hid, d=d, m=m, regress=regress))
+        X, W1, W2 = mlp_weights(20_000 + seed, n, d_in, d_hid, d)
+        p = np.arange(1, n + 1, dtype=np.float64) ** (-s)
+        p /= p.sum()
+        ids = rng.permutation(n)[rng.choice(n, size=m, p=p)].astype(np.int32)
+        ids[rng.random(m) < 0.1] = 0
+        dH = rng.standard_normal((m, d)).astype(np.float32)
+        uniq = np.unique(ids)
+        U = uniq.size
+        cuts = np.unique(np.concatenate([[0, U], rng.integers(0, U + 1, size=int(rng.integers(0, 4)))]))
+        parts = [int(b - a) for a, b in zip(cuts[:-1], cuts[1:])]
+        if regress:
+            _, V1, V2 = mlp_weights(30_000 + seed, n, d_in, d_hid, d)
+            Ht = rng.standard_normal((U, d)).astype(np.float32)
+            out = run_mlp_step(X, W1, W2, ids, dH, n, parts, targets=Ht, W_now=(V1, V2))
+            miss, loss, dW1, dW2 = orc.mlp_pseudo_loss_grad(uniq, X, V1, V2, Ht.astype(np.float64))
+            assert abs(sum(out["losses"]) - loss) <= TOL[wl.BF16] * loss
+            assert_close(out["dW1"], dW1, TOL[wl.BF16], "dW1")
+            assert_close(out["dW2"], dW2, TOL[wl.BF16], "dW2")
+        else:
+            out = run_mlp_step(X, W1, W2, ids, dH, n, parts)
+            ref = orc.mlp_gram_single(ids, X, W1, W2, dH)
+            np.testing.assert_array_equal(out["uniq"], ref["uniq"])
+            np.testing.assert_array_equal(out["inverse"], ref["inverse"])
+            assert out["A1_tail_untouched"]
+            assert_close(out["A1"], ref["A1"], 2.0 ** -8, "A1 (kept in bf16)")
+            assert_close(out["E"], ref["E"], TOL[wl.BF16], "E")
+            np.testing.assert_array_equal(out["H"], out["E"][out["inverse"]])
+            assert_close(out["G"], ref["G"], TOL_SUM[wl.BF16], "G")
+            assert_close(out["dW1"], ref["dW1"], TOL[wl.BF16], "dW1")
+            assert_close(out["dW2"], ref["dW2"], TOL[wl.BF16], "dW2")
