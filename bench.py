@@ -81,6 +81,7 @@ class Runner:
         self.pos = 0     # step index inside the current window
         self.win = 0     # which of the `sets` windows of inputs is running
         self.window_events = None        # list: an event after every finished window (time_steps)
+        self.event_pool = []             # events created (and recorded once) before the timed region
         # host-side statistics for the algorithmic byte counts
         self.stats = []
         u_totals = []
@@ -112,7 +113,7 @@ class Runner:
             self.pos = 0
             self.win = (self.win + 1) % self.sets
             if self.window_events is not None:
-                ev = self.torch.cuda.Event(enable_timing=True)
+                ev = self.event_pool.pop() if self.event_pool else self.torch.cuda.Event(enable_timing=True)
                 ev.record()
                 self.window_events.append(ev)
 
@@ -168,6 +169,11 @@ def time_steps(r, steps, warmup, profile_kernels=()):
     # an event on the stream the library runs on (the default stream, torch's current one) after every
     # window: the spread of the per-window times beside the wall-clock mean
     start = torch.cuda.Event(enable_timing=True)
+    # the events of the windows exist before the clock starts (an event is created at its first record;
+    # hundreds of creations inside the timed loop of a small workload once cost one window 28 ms)
+    r.event_pool = [torch.cuda.Event(enable_timing=True) for _ in range(steps // r.K + 2)]
+    for ev in r.event_pool:
+        ev.record()
     r.window_events = []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
