@@ -590,6 +590,7 @@ __device__ __forceinline__ void write_final(float4* __restrict__ G, int cols4, i
     }
 }
 
+template <bool PLAIN>      // dH read with plain instead of non-temporal loads
 __global__ __launch_bounds__(kBlock) void k_seg_reduce(
     const float4* __restrict__ dH, const int* __restrict__ perm, const int* __restrict__ seg_of_row,
     const int* __restrict__ offsets, const int* __restrict__ uniq_ws,
@@ -667,11 +668,13 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(
             const int src = i < rows ? s_src[i] : -1;
             // every row of dH is read exactly once: stream it past the caches (batches of a few
             // thousand positions are better off with plain loads: their rows often still sit in a
-            // cache, and what they have to hide is latency; measured 1 to 1.4 us per step)
+            // cache, and what they have to hide is latency; measured 1 to 1.4 us per step).  The
+            // choice is made at compile time: chosen at run time inside this loop it cost the large
+            // shape 10 % of the kernel
             v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (src >= 0) {
                 const f32x4* p = reinterpret_cast<const f32x4*>(dH) + (int64_t)src * cols4 + col;
-                const f32x4 t = n > kSegPlainLoads ? __builtin_nontemporal_load(p) : *p;
+                const f32x4 t = PLAIN ? *p : __builtin_nontemporal_load(p);
                 v[k] = make_float4(t.x, t.y, t.z, t.w);
             }
         }
@@ -766,12 +769,20 @@ void segment_reduce(Ctx* c, const float* dH, int64_t m, hipStream_t s, bool comm
     // the batch has few tiles to hide them behind.
     const int seg_long = n > kSegSmallBatch ? kSegLong : kSegLongSmall;
     const int tiles = (n + kSegRows - 1) / kSegRows;
-    launch(c, KID_SEG_REDUCE, k_seg_reduce, dim3(tiles, slabs), dim3(threads), s,
-                       reinterpret_cast<const float4*>(dH), c->perm, c->seg_of_row, c->offsets,
-                       c->uniq_ws, c->seg_slot, n, cols4, c->cfg.pad_id,
-                       reinterpret_cast<float4*>(c->G), reinterpret_cast<float4*>(c->seg_first),
-                       reinterpret_cast<float4*>(c->seg_last), c->scal, c->long_list, seg_long,
-                       commit ? c->slot_of : (int*)nullptr, c->id_of_slot, c->cnt_of_slot);
+    if (n > kSegPlainLoads)
+        launch(c, KID_SEG_REDUCE, k_seg_reduce<false>, dim3(tiles, slabs), dim3(threads), s,
+                           reinterpret_cast<const float4*>(dH), c->perm, c->seg_of_row, c->offsets,
+                           c->uniq_ws, c->seg_slot, n, cols4, c->cfg.pad_id,
+                           reinterpret_cast<float4*>(c->G), reinterpret_cast<float4*>(c->seg_first),
+                           reinterpret_cast<float4*>(c->seg_last), c->scal, c->long_list, seg_long,
+                           commit ? c->slot_of : (int*)nullptr, c->id_of_slot, c->cnt_of_slot);
+    else
+        launch(c, KID_SEG_REDUCE, k_seg_reduce<true>, dim3(tiles, slabs), dim3(threads), s,
+                           reinterpret_cast<const float4*>(dH), c->perm, c->seg_of_row, c->offsets,
+                           c->uniq_ws, c->seg_slot, n, cols4, c->cfg.pad_id,
+                           reinterpret_cast<float4*>(c->G), reinterpret_cast<float4*>(c->seg_first),
+                           reinterpret_cast<float4*>(c->seg_last), c->scal, c->long_list, seg_long,
+                           commit ? c->slot_of : (int*)nullptr, c->id_of_slot, c->cnt_of_slot);
     int fix_blocks = tiles / (seg_long / kSegRows) + 1;   // upper bound of long segments
     if (fix_blocks > 1024) fix_blocks = 1024;        // a block per long segment for all but extreme batches
     launch(c, KID_SEG_COMBINE, k_seg_combine, dim3(fix_blocks, (cols4 + kFixCols4 - 1) / kFixCols4),
