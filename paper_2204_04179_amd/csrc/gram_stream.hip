@@ -599,8 +599,9 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(
     int* __restrict__ long_list, int seg_long, int* __restrict__ slot_of, int* __restrict__ id_of_slot,
     long long* __restrict__ cnt_of_slot)
 {
-    __shared__ int s_src[kSegMaxRows];    // dH row of each sorted row, -1 = padding (not read)
-    __shared__ int s_dst[kSegMaxRows];    // 0 = keep adding; else destination code + 4 (see below)
+    __shared__ __attribute__((aligned(16))) int s_src[kSegMaxRows];    // dH row of each sorted row, -1 = padding (not read)
+    __shared__ __attribute__((aligned(16))) int s_dst[kSegMaxRows];    // 0 = keep adding; else destination code + 4 (see below)
+    static_assert(kSegMaxRows % kSegUnroll == 0, "a group of rows is read from the tables as whole 16-byte pieces");
     __shared__ int s_pad[kSegMaxRows];
 
     const int t = blockIdx.x;
@@ -662,10 +663,20 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int i0 = 0; i0 < rows; i0 += kSegUnroll) {
         float4 v[kSegUnroll];
+        // the group's table entries first, as 16-byte LDS reads: fetched one by one, each row's load
+        // would be issued an LDS round trip after the one before it
+        int srcs[kSegUnroll], codes[kSegUnroll];
+#pragma unroll
+        for (int q = 0; q < kSegUnroll / 4; ++q) {
+            const int4 a = *reinterpret_cast<const int4*>(&s_src[i0 + 4 * q]);
+            const int4 b = *reinterpret_cast<const int4*>(&s_dst[i0 + 4 * q]);
+            srcs[4 * q] = a.x; srcs[4 * q + 1] = a.y; srcs[4 * q + 2] = a.z; srcs[4 * q + 3] = a.w;
+            codes[4 * q] = b.x; codes[4 * q + 1] = b.y; codes[4 * q + 2] = b.z; codes[4 * q + 3] = b.w;
+        }
 #pragma unroll
         for (int k = 0; k < kSegUnroll; ++k) {
             const int i = i0 + k;
-            const int src = i < rows ? s_src[i] : -1;
+            const int src = i < rows ? srcs[k] : -1;
             // every row of dH is read exactly once: stream it past the caches (batches of a few
             // thousand positions are better off with plain loads: their rows often still sit in a
             // cache, and what they have to hide is latency; measured 1 to 1.4 us per step).  The
@@ -683,7 +694,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(
             const int i = i0 + k;
             if (i < rows) {
                 acc = f4_add(acc, v[k]);
-                const int code = s_dst[i];
+                const int code = codes[k];
                 if (code != 0) {
                     const int dst = code - 4;
                     if (dst == kDstFirst) {
