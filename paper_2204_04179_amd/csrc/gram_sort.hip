@@ -14,6 +14,13 @@
 
 namespace gram {
 
+// Counters that a wave re-reads from LDS after its own lanes have written them are accessed
+// through volatile pointers IN THE LDS ADDRESS SPACE: a volatile pointer without an address
+// space is compiled to flat, system-coherent accesses, each followed by a wait for every
+// outstanding memory operation of the wave (its scattered global stores included).
+typedef __attribute__((address_space(3))) int lds_i32;
+typedef __attribute__((address_space(3))) unsigned long long lds_u64;
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 __device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
 
@@ -258,7 +265,7 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(
     }
     __syncthreads();
 
-    volatile int* cnt = cnt_s[wave];
+    volatile lds_i32* cnt = (volatile lds_i32*)cnt_s[wave];
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
     GRAM_FOR_WAVE_KEYS_FROM(kb0, vb0, (vals_in ? vals_in[idx_] : (int)idx_),
         if (CHECK && valid && (k < 0 || k >= vocab_n)) k = fix_key;
@@ -583,8 +590,8 @@ __global__ __launch_bounds__(kSmallThreads) void k_unique_small(
     const int cw = ((n + kSmallWaves - 1) / kSmallWaves + kWave - 1) / kWave * kWave;
     const int cbeg = wave * cw;
     const int cend = cbeg + cw < n ? cbeg + cw : n;
-    volatile int* cnt = cnt_all + wave * kSmallBins;
-    volatile unsigned long long* peer = peer_all + wave * kSmallBins;
+    volatile lds_i32* cnt = (volatile lds_i32*)(cnt_all + wave * kSmallBins);
+    volatile lds_u64* peer = (volatile lds_u64*)(peer_all + wave * kSmallBins);
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
     int cur = 0;
     for (int shift = 0; shift < key_bits; shift += kSmallBits) {
@@ -650,7 +657,7 @@ __global__ __launch_bounds__(kSmallThreads) void k_unique_small(
             const int d0 = __builtin_amdgcn_readfirstlane(dg);
             const unsigned long long m0 = __ballot(valid && dg == d0);
             const bool in0 = valid && dg == d0;
-            if (valid && !in0) atomicOr(const_cast<unsigned long long*>(&peer[dg]), 1ull << lane);
+            if (valid && !in0) atomicOr(&peer_all[wave * kSmallBins + dg], 1ull << lane);
             __builtin_amdgcn_wave_barrier();
             unsigned long long peers = 0ull;
             int pos = 0;
