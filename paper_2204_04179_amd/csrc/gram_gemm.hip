@@ -220,16 +220,21 @@ __global__ __launch_bounds__(kBlock) void k_encode_bf16(
 
     // accumulator element r of a lane sits at (row, col) = ((r / 4) * 8 + (lane / 32) * 4 + r % 4, lane % 32)
     const int cc = n0 + wn * 32 + (lane & 31);
+    // everything the stores need is fetched first (the aux values and the IDs that tell the padding
+    // row): fetched inside the store loop, each store would wait for its own load and, with it, for
+    // the stores before it
     float av[16];
+    int idr[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int j = m0 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
         av[r] = (j < U && cc < d) ? epi_load<EPI>(aux, (int64_t)j * d + cc) : 0.f;
+        idr[r] = j < U ? uniq[j] : 0;
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int j = m0 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        if (j < U && cc < d) epi_store<EPI>(E, (int64_t)j * d + cc, acc[r], av[r], uniq[j] == pad_id);
+        if (j < U && cc < d) epi_store<EPI>(E, (int64_t)j * d + cc, acc[r], av[r], idr[r] == pad_id);
     }
 }
 

@@ -125,6 +125,25 @@ __global__ __launch_bounds__(kBlock) void k_gather_rows(const f32x4* __restrict_
     const int rows = (int)(p0 + rows_per_block < m ? rows_per_block : m - p0);
     const int total = rows * cols4;
     for (int e0 = 0; e0 < total; e0 += kBlock * kGatherUnroll) {
+        if (e0 + kBlock * kGatherUnroll <= total) {
+            // a whole group: nothing is conditional, so the loads go out together and every store
+            // waits for its own load only (with conditions around them each store waited for all
+            // memory operations before it, the earlier stores included)
+            int64_t src[kGatherUnroll];
+#pragma unroll
+            for (int u = 0; u < kGatherUnroll; ++u) {
+                const int e = e0 + u * kBlock + threadIdx.x;
+                const int row = e / cols4;
+                src[u] = (int64_t)inverse[p0 + row] * cols4 + (e - row * cols4);
+            }
+            f32x4 v[kGatherUnroll];
+#pragma unroll
+            for (int u = 0; u < kGatherUnroll; ++u) v[u] = E[src[u]];
+#pragma unroll
+            for (int u = 0; u < kGatherUnroll; ++u)
+                store_h4<HB>(H, p0 * cols4 + e0 + u * kBlock + threadIdx.x, v[u]);
+            continue;
+        }
         int64_t src[kGatherUnroll];
 #pragma unroll
         for (int u = 0; u < kGatherUnroll; ++u) {
